@@ -1,0 +1,167 @@
+/*
+ * moe_sb — statically batched MoE expert GEMM for AMD MI355X (gfx950).
+ *
+ * C ABI of the hot path of "Static Batching of Irregular Workloads on GPUs:
+ * Framework and Application to Efficient MoE Model Inference": given the
+ * token sequence, the per-expert weights and this step's routing result,
+ * compute for every token its product with each selected expert's weight
+ * (Sec. 2.2, Sec. 4), as ONE kernel whose workgroups find their own
+ * (expert, m-tile, n-tile) from a compressed task map (Sec. 3.1, Sec. 4.1).
+ *
+ * General rules for every call
+ *   - Pointers marked DEVICE are device memory owned by the caller; pointers
+ *     marked HOST are host memory.  The library allocates nothing and keeps
+ *     no state between calls.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work; they do not synchronise unless stated.
+ *   - Return value: MOE_OK (0) or a negative MOE_ERR_* code.  Nothing is
+ *     enqueued when an argument error is returned.  No call throws or aborts.
+ */
+#ifndef MOE_SB_H
+#define MOE_SB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    MOE_OK = 0,
+    MOE_ERR_INVALID_ARG = -1, /* null pointer, negative size, k > E, misaligned pointer */
+    MOE_ERR_UNSUPPORTED = -2, /* tile shape / dtype / divisibility the kernels do not cover */
+    MOE_ERR_ROUTING = -3,     /* a routing id outside [0,E) was found on the device */
+    MOE_ERR_HIP = -4          /* a HIP runtime call failed */
+};
+
+enum { MOE_DTYPE_BF16 = 0, MOE_DTYPE_FP8_E4M3 = 1 };
+
+/*
+ * Task-map blob (all int32 words; E64 = E rounded up to a multiple of 64,
+ * R = T*k routed rows, flat row id r = t*k + j).  Word offsets:
+ *
+ *   header       [MOE_MAP_HDR_WORDS]   see MOE_HDR_* below
+ *   counts       [E64]       tokens per expert, pad 0
+ *   offsets      [E64 + 64]  exclusive scan of counts; entries above E hold R
+ *   sigma        [E64]       non-empty index -> real expert (Sec. 4.1), ascending, pad -1
+ *   tile_prefix  [E64]       inclusive prefix sum of tiles per non-empty expert
+ *                            (Alg. 1, built over non-empty experts only, Sec. 4.1);
+ *                            pad INT32_MAX (Sec. 3.1 allows "the maximum value")
+ *   sorted_rows  [R]         the per-expert token index arrays (Sec. 4.3) back to
+ *                            back: rows of expert e are sorted_rows[offsets[e] ..
+ *                            offsets[e+1]), ascending in r; token = r / k
+ *   scratch      [...]       private to the library
+ *
+ * Tiles of expert e: nu(e) = ceil(counts[e]/tile_m) * ceil(N/tile_n).
+ * Block B (0-based) belongs to non-empty task h = #{ i : tile_prefix[i] <= B }
+ * (Alg. 2), expert sigma[h] (Alg. 4), tile l = B - tile_prefix[h-1], and
+ * m_tile = l % mt_e, n_tile = l / mt_e  (order 0 = "m fastest").
+ */
+#define MOE_MAP_MAGIC 0x3142534D /* "MSB1" */
+#define MOE_MAP_HDR_WORDS 32
+enum {
+    MOE_HDR_MAGIC = 0,
+    MOE_HDR_T = 1,
+    MOE_HDR_K_TOP = 2,
+    MOE_HDR_E = 3,
+    MOE_HDR_N = 4,
+    MOE_HDR_TILE_M = 5,
+    MOE_HDR_TILE_N = 6,
+    MOE_HDR_NT = 7,          /* ceil(N / tile_n) */
+    MOE_HDR_M = 8,           /* number of non-empty experts */
+    MOE_HDR_TOTAL_TILES = 9, /* tile_prefix[M-1], 0 when the map is empty or invalid */
+    MOE_HDR_ORDER = 10,      /* 0: m-tile fastest inside an expert */
+    MOE_HDR_STATUS = 11,     /* 0, or the number of routing ids outside [0,E) */
+    MOE_HDR_R = 12,          /* T*k */
+    MOE_HDR_E64 = 13
+};
+
+/* Word offsets of the blob's fields for a given E (HOST, pure). */
+size_t moe_map_off_counts(int E);
+size_t moe_map_off_offsets(int E);
+size_t moe_map_off_sigma(int E);
+size_t moe_map_off_tile_prefix(int E);
+size_t moe_map_off_sorted_rows(int E);
+
+/*
+ * Bytes the caller must allocate (DEVICE, 256-byte aligned) for a task map
+ * that will hold up to T_max tokens.  HOST, pure.  Returns 0 on invalid
+ * arguments.
+ */
+size_t moe_task_map_bytes(int T_max, int k, int E, int tile_m, int tile_n, int N);
+
+/*
+ * Workgroups moe_grouped_gemm launches for such a map: an upper bound on
+ * total_tiles that needs no device->host copy,
+ *   (floor(R/tile_m) + min(E, R)) * ceil(N/tile_n).   HOST, pure.
+ */
+int64_t moe_grid_upper_bound(int T, int k, int E, int tile_m, int tile_n, int N);
+
+/*
+ * Build the task map for one inference step (Sec. 4.1 "after the token route",
+ * Alg. 1, Sec. 4.3 token index arrays).
+ *   topk_ids  DEVICE int32 [T, k] row-major: expert chosen for token t, slot j.
+ *   T >= 0 tokens (0 gives a valid empty map), 1 <= k <= E, 1 <= E <= 1024,
+ *   T*k <= 2^24, tile_m in {16,32,64,128,256}, tile_n in {64,128,256}, N >= 1.
+ *   task_map  DEVICE, >= moe_task_map_bytes(T,...) bytes, written entirely.
+ * Deterministic: the same input gives the same bytes.  Ids outside [0,E) are
+ * counted in header[MOE_HDR_STATUS] and force total_tiles = 0.
+ */
+int moe_build_task_map(const int32_t* topk_ids, int T, int k, int E, int tile_m, int tile_n, int N,
+                       void* task_map, void* stream);
+
+/*
+ * Synchronises the stream and returns MOE_ERR_ROUTING if the map recorded a
+ * bad routing id, MOE_ERR_INVALID_ARG if the blob is not a map, else MOE_OK.
+ */
+int moe_task_map_status(const void* task_map, void* stream);
+
+/*
+ * Expand the compressed map into the full per-block table (the prior-art
+ * representation of Sec. 2.1 / 3.1), using the same device decode routine the
+ * GEMM kernel uses.  table: DEVICE int32 [grid][4] = {expert, m_tile, n_tile,
+ * rows_in_tile}; entries B >= total_tiles are set to -1.  `grid` is normally
+ * moe_grid_upper_bound(...).
+ */
+int moe_task_map_expand(const void* task_map, int E, int32_t* table, int64_t grid, void* stream);
+
+typedef struct moe_gemm_desc {
+    int32_t dtype;        /* MOE_DTYPE_* : element type of X and W */
+    int32_t T, k, E;      /* must equal what the map was built with */
+    int32_t K, N;         /* reduction length and output width */
+    int32_t tile_m, tile_n; /* must equal what the map was built with */
+    const float* x_scale; /* DEVICE fp32 [T], per-token scale  (fp8 only, else NULL) */
+    const float* w_scale; /* DEVICE fp32 [E], per-expert scale (fp8 only, else NULL) */
+} moe_gemm_desc;
+
+/*
+ * The statically batched expert GEMM (Alg. 3/4 with the GEMM tile as the task
+ * function; Sec. 4.3 gathered token rows; Sec. 4.4 pipeline):
+ *     Y[t, j, :] = X[t, :] . W[e(t,j), :, :]        e(t,j) = topk_ids[t, j]
+ *   X  DEVICE [T, K]    bf16 or e4m3 bytes, K contiguous, 16-byte aligned rows
+ *   W  DEVICE [E, K, N] same element type, N contiguous
+ *   Y  DEVICE [T, k, N] bf16, written once per element; rows of a partial
+ *      m-tile beyond the expert's count write nothing.
+ *   fp8: Y = (sum over e4m3 products in fp32) * x_scale[t] * w_scale[e].
+ * Accumulation is fp32; the store rounds to bf16 (nearest even).
+ * Requires K % 64 == 0 (bf16) / K % 128 == 0 (fp8) and N % tile_n == 0,
+ * else MOE_ERR_UNSUPPORTED.  (tile_m, tile_n, dtype) must be a supported
+ * combination: see moe_tile_supported.  A map whose header does not match
+ * `desc`, or whose status is non-zero, makes the kernel a no-op.
+ * topk_ids is accepted for symmetry with the problem statement and may be
+ * NULL: the kernel reads the routing from the map.
+ */
+int moe_grouped_gemm(const void* X, const void* W, const int32_t* topk_ids, const void* task_map, void* Y,
+                     const moe_gemm_desc* desc, void* stream);
+
+/* 1 if a GEMM kernel exists for this (dtype, tile_m, tile_n), else 0.  HOST, pure. */
+int moe_tile_supported(int dtype, int tile_m, int tile_n);
+
+/* Static string for a return code. */
+const char* moe_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_SB_H */

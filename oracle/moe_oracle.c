@@ -1,0 +1,345 @@
+/*
+ * Oracle for the statically batched MoE expert GEMM.  TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, CPU-only restatement of what the hot path computes, written
+ * from the paper (Static Batching of Irregular Workloads on GPUs, Sec. 3.1,
+ * Sec. 4.1, Sec. 4.3; Alg. 1, 2, 4) so that it can be checked against the
+ * paper by eye.  It shares no code, header, table or helper with the HIP
+ * library.  Only tests, the smoke check and the CPU-baseline leg of the
+ * benchmark may call it; the product path never does.
+ *
+ * Conventions (the paper leaves these open; each is a fixed reading):
+ *   - block index B and all arrays are 0-based: the task of block B is
+ *     h = #{ i : TilePrefix[i] <= B }  (Alg. 2 as printed: p = B >= TilePrefix[t]).
+ *   - nu(expert e) = ceil(c_e / tile_m) * ceil(N / tile_n)   (tiles of its GEMM).
+ *   - sigma lists the non-empty experts in ascending expert index (Sec. 4.1).
+ *   - inside an expert, tile index l runs m-tile fastest:
+ *       m_tile = l % mt_e,  n_tile = l / mt_e.
+ *   - the token index array of an expert (Sec. 4.3) is ordered by flat row id
+ *     r = t*k + j (stable), which makes the map unique.
+ *   - result: Y[r, n] = sum_kappa X[t, kappa] * W[e(r), kappa, n], no sum over
+ *     a token's experts.
+ *
+ * Parity pins (tests, CPU only): hand-worked examples, brute-force full
+ * per-block table vs. the Alg. 2+4 decode, count/permutation invariants, the
+ * paper's balanced/best/worst closed-form counts (Sec. 5), reduction to a
+ * plain matrix product checked against an independent library matmul, bf16 and
+ * e4m3 format definitions checked against an independent implementation.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ---------------------------------------------------------------- formats */
+
+/* bfloat16 = the upper 16 bits of an IEEE-754 binary32. */
+float orc_bf16_to_f32(uint16_t h) {
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+/* binary32 -> bfloat16, round to nearest, ties to even.  NaN stays NaN. */
+uint16_t orc_f32_to_bf16_rne(float f) {
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    uint32_t lower = u & 0xffffu;
+    uint32_t upper = u >> 16;
+    if (lower > 0x8000u || (lower == 0x8000u && (upper & 1u))) upper += 1u;
+    return (uint16_t)upper;
+}
+
+/* double -> bfloat16 with a single rounding (RNE) straight from the double. */
+uint16_t orc_f64_to_bf16_rne(double d) {
+    if (isnan(d)) return 0x7fc0;
+    uint16_t sign = signbit(d) ? 0x8000u : 0u;
+    double a = fabs(d);
+    if (a == 0.0) return sign;
+    if (isinf(a)) return (uint16_t)(sign | 0x7f80u);
+    int ex;
+    double m = frexp(a, &ex); /* a = m * 2^ex, m in [0.5,1) */
+    int e = ex - 1;            /* a = (2m) * 2^e, 2m in [1,2) */
+    if (e < -126) e = -126;    /* subnormal range: fixed exponent */
+    /* quantum of a bf16 at exponent e is 2^(e-7) */
+    double q = ldexp(1.0, e - 7);
+    double n = a / q; /* exact: power-of-two scaling */
+    double fl = floor(n);
+    double frac = n - fl;
+    if (frac > 0.5 || (frac == 0.5 && fmod(fl, 2.0) == 1.0)) fl += 1.0;
+    double r = fl * q;
+    (void)m;
+    float rf = (float)r; /* exactly representable (<= 8 significant bits) or inf */
+    uint32_t u;
+    memcpy(&u, &rf, 4);
+    if (r >= ldexp(1.0, 128)) return (uint16_t)(sign | 0x7f80u);
+    return (uint16_t)(sign | (u >> 16));
+}
+
+/* OCP 8-bit float E4M3 (the "fn" flavour: bias 7, no infinities, only
+ * S.1111.111 is NaN, max finite 448).
+ *   normal:    (-1)^s * 2^(E-7) * (1 + m/8),  E in 1..15
+ *   subnormal: (-1)^s * 2^(-6)  * (m/8),      E = 0                        */
+float orc_e4m3_to_f32(uint8_t b) {
+    int s = b >> 7, E = (b >> 3) & 15, m = b & 7;
+    float v;
+    if (E == 15 && m == 7) return NAN;
+    if (E == 0) v = ldexpf((float)m / 8.0f, -6);
+    else v = ldexpf(1.0f + (float)m / 8.0f, E - 7);
+    return s ? -v : v;
+}
+
+/* ---------------------------------------------------------------- task map */
+
+static int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+/* Alg. 1: inclusive prefix sum of the tile counts nu[0..n).  Written as the
+ * definition (a fresh sum for every i), not as a running scan. */
+void orc_tile_prefix(const int32_t* nu, int n, int32_t* tile_prefix) {
+    for (int i = 0; i < n; ++i) {
+        int64_t s = 0;
+        for (int j = 0; j <= i; ++j) s += nu[j];
+        tile_prefix[i] = (int32_t)s;
+    }
+}
+
+/* Alg. 2: every "thread" t < n votes p = (B >= TilePrefix[t]); h is the
+ * population count of the votes; l = B - TilePrefix[h-1] (or B when h = 0). */
+void orc_mapping(const int32_t* tile_prefix, int n, int B, int32_t* h_out, int32_t* l_out) {
+    int h = 0;
+    for (int t = 0; t < n; ++t) {
+        int p = (B >= tile_prefix[t]);
+        h += p;
+    }
+    int kk = 0;
+    if (h > 0) kk = tile_prefix[h - 1];
+    *h_out = h;
+    *l_out = B - kk;
+}
+
+/* Routing result -> everything the kernel needs (Sec. 4.1, 4.3):
+ *   counts[E], offsets[E+1] (exclusive scan), sorted_rows[T*k] (per-expert
+ *   token index arrays, stored back to back, as flat row ids r = t*k+j; the
+ *   token is r / k), sigma[M] (non-empty -> real expert), tile_prefix[M].
+ * Returns 0, or -1 if an id is outside [0,E).                               */
+int orc_build_task_map(const int32_t* topk_ids, int T, int k, int E, int tile_m, int tile_n, int N,
+                       int32_t* counts, int32_t* offsets, int32_t* sorted_rows, int32_t* sigma,
+                       int32_t* tile_prefix, int32_t* M_out, int32_t* total_tiles_out) {
+    int R = T * k;
+    for (int e = 0; e < E; ++e) counts[e] = 0;
+    for (int r = 0; r < R; ++r) {
+        int e = topk_ids[r];
+        if (e < 0 || e >= E) return -1;
+        counts[e] += 1;
+    }
+    offsets[0] = 0;
+    for (int e = 0; e < E; ++e) offsets[e + 1] = offsets[e] + counts[e];
+    /* token index arrays: for each expert, the rows routed to it, ascending */
+    for (int e = 0; e < E; ++e) {
+        int w = offsets[e];
+        for (int r = 0; r < R; ++r)
+            if (topk_ids[r] == e) sorted_rows[w++] = r;
+    }
+    /* sigma and the tile counts of the non-empty experts */
+    int M = 0;
+    int32_t* nu = (int32_t*)malloc(sizeof(int32_t) * (size_t)(E > 0 ? E : 1));
+    int nt = ceil_div(N, tile_n);
+    for (int e = 0; e < E; ++e) {
+        if (counts[e] > 0) {
+            sigma[M] = e;
+            nu[M] = ceil_div(counts[e], tile_m) * nt;
+            M += 1;
+        }
+    }
+    orc_tile_prefix(nu, M, tile_prefix);
+    free(nu);
+    *M_out = M;
+    *total_tiles_out = M > 0 ? tile_prefix[M - 1] : 0;
+    return 0;
+}
+
+/* Alg. 4 for block B: non-empty task h, real expert sigma(h), then the tile
+ * index l split into (m_tile, n_tile), m fastest.  out = {e, m_tile, n_tile,
+ * rows_in_tile}.                                                           */
+void orc_decode_block(const int32_t* tile_prefix, const int32_t* sigma, int M, const int32_t* counts,
+                      int tile_m, int B, int32_t* out4) {
+    int32_t h, l;
+    orc_mapping(tile_prefix, M, B, &h, &l);
+    int e = sigma[h];
+    int mt = ceil_div(counts[e], tile_m);
+    int m_tile = l % mt, n_tile = l / mt;
+    int rows = counts[e] - m_tile * tile_m;
+    if (rows > tile_m) rows = tile_m;
+    out4[0] = e; out4[1] = m_tile; out4[2] = n_tile; out4[3] = rows;
+}
+
+/* The prior-art full per-block table (Sec. 2.1 / 3.1: one entry per thread
+ * block), by nested loops over (expert, n_tile, m_tile) with no prefix array
+ * at all.  It is an independent definition of the same map.  Returns the
+ * number of entries written (table has room for cap entries of 4 ints).    */
+int orc_full_table(const int32_t* counts, int E, int tile_m, int tile_n, int N, int32_t* table, int cap) {
+    int b = 0;
+    int nt = ceil_div(N, tile_n);
+    for (int e = 0; e < E; ++e) {
+        int mt = ceil_div(counts[e], tile_m);
+        for (int n_tile = 0; n_tile < nt; ++n_tile)
+            for (int m_tile = 0; m_tile < mt; ++m_tile) {
+                if (b >= cap) return -1;
+                int rows = counts[e] - m_tile * tile_m;
+                if (rows > tile_m) rows = tile_m;
+                table[4 * b + 0] = e; table[4 * b + 1] = m_tile;
+                table[4 * b + 2] = n_tile; table[4 * b + 3] = rows;
+                b += 1;
+            }
+    }
+    return b;
+}
+
+/* ---------------------------------------------------------------- result */
+
+/* Y for a list of routed rows (rows == NULL: all T*k rows, in order).
+ * X: [T,K] bf16 bits, W: [E,K,N] bf16 bits (N contiguous).
+ * For row r = t*k+j with e = topk_ids[r], for every n:
+ *     acc32 = ((x_0*w_0 + x_1*w_1) + x_2*w_2) + ...     (fp32, kappa ascending)
+ *     acc64 = the same sum in fp64
+ * Outputs (any may be NULL), each [nrows, N]:
+ *     Y32  fp32 accumulator, Y64 fp64 accumulator,
+ *     Ybf  bf16_rne(acc64)  (one rounding, from the fp64 sum).
+ * The loop nest is (row, kappa, n) so that memory is walked contiguously;
+ * each output element still adds its terms in increasing kappa.            */
+void orc_grouped_gemm_bf16(const uint16_t* X, const uint16_t* W, const int32_t* topk_ids, int T, int k,
+                           int E, int K, int N, const int32_t* rows, int nrows, float* Y32, double* Y64,
+                           uint16_t* Ybf) {
+    (void)E;
+    if (rows == NULL) nrows = T * k;
+#pragma omp parallel
+    {
+        float* a32 = (float*)malloc(sizeof(float) * (size_t)N);
+        double* a64 = (double*)malloc(sizeof(double) * (size_t)N);
+#pragma omp for schedule(dynamic, 1)
+        for (int i = 0; i < nrows; ++i) {
+            int r = rows ? rows[i] : i;
+            int t = r / k;
+            int e = topk_ids[r];
+            const uint16_t* x = X + (size_t)t * K;
+            const uint16_t* w = W + (size_t)e * K * N;
+            for (int n = 0; n < N; ++n) { a32[n] = 0.0f; a64[n] = 0.0; }
+            for (int kap = 0; kap < K; ++kap) {
+                float xv = orc_bf16_to_f32(x[kap]);
+                const uint16_t* wr = w + (size_t)kap * N;
+                for (int n = 0; n < N; ++n) {
+                    float wv = orc_bf16_to_f32(wr[n]);
+                    float p = xv * wv; /* exact: 8-bit x 8-bit significands */
+                    a32[n] += p;
+                    a64[n] += (double)p;
+                }
+            }
+            for (int n = 0; n < N; ++n) {
+                size_t o = (size_t)i * N + n;
+                if (Y32) Y32[o] = a32[n];
+                if (Y64) Y64[o] = a64[n];
+                if (Ybf) Ybf[o] = orc_f64_to_bf16_rne(a64[n]);
+            }
+        }
+        free(a32);
+        free(a64);
+    }
+}
+
+/* fp8 variant: X [T,K] e4m3 bytes with x_scale[T]; W [E,K,N] e4m3 bytes with
+ * w_scale[E].  The sum runs over the decoded bytes; the two scales multiply
+ * the finished sum once:  Y = (sum) * x_scale[t] * w_scale[e].             */
+void orc_grouped_gemm_fp8(const uint8_t* X, const uint8_t* W, const float* x_scale, const float* w_scale,
+                          const int32_t* topk_ids, int T, int k, int E, int K, int N, const int32_t* rows,
+                          int nrows, float* Y32, double* Y64, uint16_t* Ybf) {
+    (void)E;
+    if (rows == NULL) nrows = T * k;
+#pragma omp parallel
+    {
+        float* a32 = (float*)malloc(sizeof(float) * (size_t)N);
+        double* a64 = (double*)malloc(sizeof(double) * (size_t)N);
+#pragma omp for schedule(dynamic, 1)
+        for (int i = 0; i < nrows; ++i) {
+            int r = rows ? rows[i] : i;
+            int t = r / k;
+            int e = topk_ids[r];
+            const uint8_t* x = X + (size_t)t * K;
+            const uint8_t* w = W + (size_t)e * K * N;
+            for (int n = 0; n < N; ++n) { a32[n] = 0.0f; a64[n] = 0.0; }
+            for (int kap = 0; kap < K; ++kap) {
+                float xv = orc_e4m3_to_f32(x[kap]);
+                const uint8_t* wr = w + (size_t)kap * N;
+                for (int n = 0; n < N; ++n) {
+                    float p = xv * orc_e4m3_to_f32(wr[n]); /* exact: 4-bit x 4-bit */
+                    a32[n] += p;
+                    a64[n] += (double)p;
+                }
+            }
+            double s = (double)x_scale[t] * (double)w_scale[e];
+            for (int n = 0; n < N; ++n) {
+                size_t o = (size_t)i * N + n;
+                if (Y32) Y32[o] = (a32[n] * x_scale[t]) * w_scale[e];
+                if (Y64) Y64[o] = a64[n] * s;
+                if (Ybf) Ybf[o] = orc_f64_to_bf16_rne(a64[n] * s);
+            }
+        }
+        free(a32);
+        free(a64);
+    }
+}
+
+/* Single elements (r, n) one by one: used to sample huge problems.
+ * is_fp8 selects the element decoding; scales may be NULL for bf16.        */
+void orc_gemm_elements(const void* X, const void* W, const float* x_scale, const float* w_scale,
+                       const int32_t* topk_ids, int k, int K, int N, int is_fp8, const int32_t* rr,
+                       const int32_t* nn, int count, double* Y64) {
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < count; ++i) {
+        int r = rr[i], n = nn[i];
+        int t = r / k, e = topk_ids[r];
+        double acc = 0.0;
+        for (int kap = 0; kap < K; ++kap) {
+            float xv, wv;
+            if (is_fp8) {
+                xv = orc_e4m3_to_f32(((const uint8_t*)X)[(size_t)t * K + kap]);
+                wv = orc_e4m3_to_f32(((const uint8_t*)W)[((size_t)e * K + kap) * N + n]);
+            } else {
+                xv = orc_bf16_to_f32(((const uint16_t*)X)[(size_t)t * K + kap]);
+                wv = orc_bf16_to_f32(((const uint16_t*)W)[((size_t)e * K + kap) * N + n]);
+            }
+            acc += (double)xv * (double)wv;
+        }
+        if (is_fp8) acc *= (double)x_scale[t] * (double)w_scale[e];
+        Y64[i] = acc;
+    }
+}
+
+/* Norm product ||X[t,:]||_2 * ||W[e,:,n]||_2 for sampled elements: the scale
+ * the error tolerance is stated against (scales folded in for fp8).        */
+void orc_norm_scale_elements(const void* X, const void* W, const float* x_scale, const float* w_scale,
+                             const int32_t* topk_ids, int k, int K, int N, int is_fp8, const int32_t* rr,
+                             const int32_t* nn, int count, double* out) {
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < count; ++i) {
+        int r = rr[i], n = nn[i];
+        int t = r / k, e = topk_ids[r];
+        double sx = 0.0, sw = 0.0;
+        for (int kap = 0; kap < K; ++kap) {
+            double xv, wv;
+            if (is_fp8) {
+                xv = orc_e4m3_to_f32(((const uint8_t*)X)[(size_t)t * K + kap]);
+                wv = orc_e4m3_to_f32(((const uint8_t*)W)[((size_t)e * K + kap) * N + n]);
+            } else {
+                xv = orc_bf16_to_f32(((const uint16_t*)X)[(size_t)t * K + kap]);
+                wv = orc_bf16_to_f32(((const uint16_t*)W)[((size_t)e * K + kap) * N + n]);
+            }
+            sx += xv * xv;
+            sw += wv * wv;
+        }
+        double s = sqrt(sx) * sqrt(sw);
+        if (is_fp8) s *= fabs((double)x_scale[t] * (double)w_scale[e]);
+        out[i] = s;
+    }
+}

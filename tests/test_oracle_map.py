@@ -1,0 +1,181 @@
+"""CPU pins of the oracle's task map (Alg. 1, 2, 4; Sec. 4.1, 4.3; Sec. 5 scenarios).
+
+Each test checks the oracle against something other than itself: hand-worked
+fixtures, a brute-force nested-loop table, invariants that any correct map
+satisfies, or the closed-form expert loads of the paper's scenarios.
+"""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2501_16103_amd import workloads as wk
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _gold(name):
+    with open(os.path.join(GOLD, name)) as f:
+        return json.load(f)
+
+
+def test_alg1_alg2_hand_example(oracle_mod):
+    g = _gold("alg2_prefix_example.json")
+    prefix = oracle_mod.tile_prefix(g["nu"])
+    assert prefix.tolist() == g["tile_prefix"]
+    for B, h, l in g["blocks"]:
+        assert oracle_mod.mapping(prefix, B) == (h, l)
+
+
+def test_alg4_empty_expert_hand_example(oracle_mod):
+    g = _gold("empty_expert_map.json")
+    tm = oracle_mod.build_task_map(g["topk_ids"], g["T"], g["k"], g["E"], g["tile_m"], g["tile_n"], g["N"])
+    assert tm.counts.tolist() == g["counts"]
+    assert tm.offsets.tolist() == g["offsets"]
+    assert tm.sorted_rows.tolist() == g["sorted_rows"]
+    assert tm.sigma.tolist() == g["sigma"] and tm.M == g["M"]
+    assert tm.tile_prefix.tolist() == g["tile_prefix"] and tm.total_tiles == g["total_tiles"]
+    assert oracle_mod.decode_all(tm).tolist() == g["table"]
+
+
+def test_two_expert_map_hand_example(oracle_mod):
+    g = _gold("two_expert_values.json")
+    tm = oracle_mod.build_task_map(g["topk_ids"], g["T"], g["k"], g["E"], g["tile_m"], g["tile_n"], g["N"])
+    assert tm.counts.tolist() == g["counts"]
+    assert tm.offsets.tolist() == g["offsets"]
+    assert tm.sorted_rows.tolist() == g["sorted_rows"]
+    assert tm.sigma.tolist() == g["sigma"]
+    assert tm.tile_prefix.tolist() == g["tile_prefix"]
+    assert oracle_mod.decode_all(tm).tolist() == g["table"]
+
+
+def _random_ids(rng, T, k, E, skew):
+    ids = np.zeros((T, k), dtype=np.int32)
+    p = np.arange(1, E + 1, dtype=np.float64) ** (-skew)
+    p /= p.sum()
+    for t in range(T):
+        ids[t] = rng.choice(E, size=k, replace=False, p=p)
+    return ids
+
+
+CASES = [
+    # T, k, E, tile_m, tile_n, N, skew
+    (1, 1, 1, 16, 64, 64, 0.0),
+    (7, 2, 5, 16, 128, 300, 0.0),
+    (64, 2, 8, 32, 128, 512, 0.0),
+    (33, 3, 70, 16, 64, 200, 2.0),       # E > 64: several voting rounds, many empty experts
+    (200, 8, 256, 16, 128, 256, 1.0),
+    (129, 2, 8, 128, 256, 512, 3.0),     # counts around the tile size
+    (50, 6, 64, 64, 128, 2816, 0.5),
+]
+
+
+@pytest.mark.parametrize("T,k,E,tile_m,tile_n,N,skew", CASES)
+def test_decode_equals_bruteforce_table(oracle_mod, T, k, E, tile_m, tile_n, N, skew):
+    """Alg. 2 + Alg. 4 decode of every block == the prior-art full table by nested loops."""
+    rng = np.random.default_rng(1234 + T + E)
+    ids = _random_ids(rng, T, k, E, skew)
+    tm = oracle_mod.build_task_map(ids, T, k, E, tile_m, tile_n, N)
+    table = oracle_mod.full_table(tm.counts, tile_m, tile_n, N)
+    assert table.shape[0] == tm.total_tiles
+    np.testing.assert_array_equal(oracle_mod.decode_all(tm), table)
+
+
+@pytest.mark.parametrize("T,k,E,tile_m,tile_n,N,skew", CASES)
+def test_map_invariants(oracle_mod, T, k, E, tile_m, tile_n, N, skew):
+    rng = np.random.default_rng(99 + T * 7 + E)
+    ids = _random_ids(rng, T, k, E, skew)
+    tm = oracle_mod.build_task_map(ids, T, k, E, tile_m, tile_n, N)
+    R = T * k
+    flat = ids.reshape(-1)
+    # counts against an independent library histogram
+    np.testing.assert_array_equal(tm.counts, np.bincount(flat, minlength=E))
+    assert tm.counts.sum() == R and tm.offsets[0] == 0 and tm.offsets[E] == R
+    np.testing.assert_array_equal(np.diff(tm.offsets), tm.counts)
+    # token index arrays: a permutation, right expert, ascending inside a segment
+    assert sorted(tm.sorted_rows.tolist()) == list(range(R))
+    # equals a library stable sort of the rows by expert
+    np.testing.assert_array_equal(tm.sorted_rows, np.argsort(flat, kind="stable"))
+    for e in range(E):
+        seg = tm.sorted_rows[tm.offsets[e]:tm.offsets[e + 1]]
+        assert np.all(flat[seg] == e)
+        assert np.all(np.diff(seg) > 0)
+    # sigma: ascending, exactly the non-empty experts
+    assert tm.sigma.tolist() == [e for e in range(E) if tm.counts[e] > 0]
+    assert tm.M == len(tm.sigma)
+    # prefix: strictly increasing, closed form of the last entry
+    nt = -(-N // tile_n)
+    mt = -(-tm.counts // tile_m)
+    assert np.all(np.diff(np.concatenate([[0], tm.tile_prefix])) > 0)
+    assert tm.total_tiles == int(mt.sum()) * nt
+    np.testing.assert_array_equal(tm.tile_prefix, np.cumsum(mt[tm.sigma] * nt))
+    # decode is a bijection onto {(e, m<mt_e, n<nt)} and rows add up per n-tile
+    table = oracle_mod.decode_all(tm)
+    seen = set(map(tuple, table[:, :3].tolist()))
+    assert len(seen) == tm.total_tiles
+    assert seen == {(e, m, n) for e in range(E) for m in range(mt[e]) for n in range(nt)}
+    for n in range(nt):
+        assert table[table[:, 2] == n][:, 3].sum() == R  # every routed row once per n-tile
+
+
+def test_decode_with_zero_tile_tasks_matches_compact(oracle_mod):
+    """Counting prefix entries <= B over the full-E prefix (zeros for empty experts)
+    picks the same expert as the compact prefix followed by sigma."""
+    rng = np.random.default_rng(5)
+    ids = _random_ids(rng, 40, 2, 24, 2.5)
+    tm = oracle_mod.build_task_map(ids, 40, 2, 24, 16, 64, 128)
+    assert tm.M < 24  # some experts empty
+    nt = 2
+    nu_full = (-(-tm.counts // 16)) * nt
+    full_prefix = oracle_mod.tile_prefix(nu_full)
+    for B in range(tm.total_tiles):
+        h_full, l_full = oracle_mod.mapping(full_prefix, B)
+        h, l = oracle_mod.mapping(tm.tile_prefix, B)
+        assert int(tm.sigma[h]) == h_full and l == l_full
+
+
+def test_paper_scenarios_closed_form_counts(oracle_mod):
+    """Sec. 5: balanced = T*k/E rows each; best = k experts with T rows; worst = E-k
+    experts with exactly one row, the k busy experts share the rest."""
+    T, E, k = 4096, 64, 8
+    for scen in ("balanced", "best", "worst"):
+        wl = wk.paper_eval(scen, T)
+        ids = wk.make_routing(wl).numpy()
+        assert all(len(set(row)) == k for row in ids.tolist())  # distinct experts per token
+        tm = oracle_mod.build_task_map(ids, T, k, E, 256, 256, wl.N)
+        c = tm.counts
+        if scen == "balanced":
+            assert np.all(c == T * k // E) and tm.M == E
+            assert tm.total_tiles == E * 2 * 10
+        elif scen == "best":
+            assert np.all(c[:k] == T) and np.all(c[k:] == 0) and tm.M == k
+            assert tm.total_tiles == k * 16 * 10
+        else:
+            assert np.all(c[k:] == 1) and c[:k].sum() == T * k - (E - k) and tm.M == E
+            assert np.all(c[: k - 1] == T) and c[k - 1] == T - (E - k)
+
+
+def test_T0_and_bad_id(oracle_mod):
+    tm = oracle_mod.build_task_map(np.zeros((0, 2), np.int32), 0, 2, 8, 16, 64, 128)
+    assert tm.total_tiles == 0 and tm.M == 0 and tm.counts.sum() == 0
+    with pytest.raises(ValueError):
+        oracle_mod.build_task_map([[0, 8]], 1, 2, 8, 16, 64, 128)
+    with pytest.raises(ValueError):
+        oracle_mod.build_task_map([[-1, 2]], 1, 2, 8, 16, 64, 128)
+
+
+def test_workload_routing_recipes():
+    for wl in (wk.tiny(), wk.mixtral_up(256), wk.mixtral_down_zipf(256), wk.fine_grained(128), wk.decode_fp8(32)):
+        ids = wk.make_routing(wl)
+        assert ids.dtype == torch.int32 and tuple(ids.shape) == (wl.T, wl.k)
+        assert int(ids.min()) >= 0 and int(ids.max()) < wl.E
+        s = torch.sort(ids, dim=1).values
+        assert bool((s[:, 1:] != s[:, :-1]).all())  # without replacement
+        assert torch.equal(ids, wk.make_routing(wl))  # seeded
+    # zipf is skewed, gauss_topk roughly balanced
+    z = np.bincount(wk.make_routing(wk.mixtral_down_zipf(4096)).numpy().ravel(), minlength=8)
+    assert z.max() > 3 * z.min()
+    b = np.bincount(wk.make_routing(wk.mixtral_up(4096)).numpy().ravel(), minlength=8)
+    assert b.max() < 1.2 * b.min()
