@@ -1,0 +1,168 @@
+"""ctypes binding of libmoe_sb: argument marshalling only.
+
+Every function has the name and meaning of the C entry point it forwards to
+(see include/moe_sb.h).  Tensors are torch tensors used purely as device
+buffers; the current torch stream is passed as the hipStream_t.  If the
+compiled library is missing, importing the functions fails: there is no
+fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmoe_sb.so")
+
+MOE_OK = 0
+MOE_ERR_INVALID_ARG = -1
+MOE_ERR_UNSUPPORTED = -2
+MOE_ERR_ROUTING = -3
+MOE_ERR_HIP = -4
+MOE_DTYPE_BF16 = 0
+MOE_DTYPE_FP8_E4M3 = 1
+MOE_MAP_MAGIC = 0x3142534D
+MOE_MAP_HDR_WORDS = 32
+HDR = dict(MAGIC=0, T=1, K_TOP=2, E=3, N=4, TILE_M=5, TILE_N=6, NT=7, M=8, TOTAL_TILES=9, ORDER=10,
+           STATUS=11, R=12, E64=13)
+
+EXPORTS = [
+    "moe_map_off_counts", "moe_map_off_offsets", "moe_map_off_sigma", "moe_map_off_tile_prefix",
+    "moe_map_off_sorted_rows", "moe_task_map_bytes", "moe_grid_upper_bound", "moe_build_task_map",
+    "moe_task_map_status", "moe_task_map_expand", "moe_grouped_gemm", "moe_tile_supported", "moe_strerror",
+]
+
+
+class MoeError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+
+
+class moe_gemm_desc(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("T", ctypes.c_int32), ("k", ctypes.c_int32), ("E", ctypes.c_int32),
+                ("K", ctypes.c_int32), ("N", ctypes.c_int32), ("tile_m", ctypes.c_int32),
+                ("tile_n", ctypes.c_int32), ("x_scale", ctypes.c_void_p), ("w_scale", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2501_16103_amd.build` "
+                              "(or __graft_entry__.build()). There is no fallback implementation.")
+        L = ctypes.CDLL(LIB_PATH)
+        for n in ("moe_map_off_counts", "moe_map_off_offsets", "moe_map_off_sigma", "moe_map_off_tile_prefix",
+                  "moe_map_off_sorted_rows"):
+            getattr(L, n).restype = ctypes.c_size_t
+            getattr(L, n).argtypes = [ctypes.c_int]
+        L.moe_task_map_bytes.restype = ctypes.c_size_t
+        L.moe_task_map_bytes.argtypes = [ctypes.c_int] * 6
+        L.moe_grid_upper_bound.restype = ctypes.c_int64
+        L.moe_grid_upper_bound.argtypes = [ctypes.c_int] * 6
+        L.moe_build_task_map.restype = ctypes.c_int
+        L.moe_build_task_map.argtypes = [ctypes.c_void_p] + [ctypes.c_int] * 6 + [ctypes.c_void_p, ctypes.c_void_p]
+        L.moe_task_map_status.restype = ctypes.c_int
+        L.moe_task_map_status.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        L.moe_task_map_expand.restype = ctypes.c_int
+        L.moe_task_map_expand.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+        L.moe_grouped_gemm.restype = ctypes.c_int
+        L.moe_grouped_gemm.argtypes = [ctypes.c_void_p] * 5 + [ctypes.POINTER(moe_gemm_desc), ctypes.c_void_p]
+        L.moe_tile_supported.restype = ctypes.c_int
+        L.moe_tile_supported.argtypes = [ctypes.c_int] * 3
+        L.moe_strerror.restype = ctypes.c_char_p
+        L.moe_strerror.argtypes = [ctypes.c_int]
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().moe_strerror(code).decode()
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def moe_task_map_bytes(T_max: int, k: int, E: int, tile_m: int, tile_n: int, N: int) -> int:
+    return int(lib().moe_task_map_bytes(T_max, k, E, tile_m, tile_n, N))
+
+
+def moe_grid_upper_bound(T: int, k: int, E: int, tile_m: int, tile_n: int, N: int) -> int:
+    return int(lib().moe_grid_upper_bound(T, k, E, tile_m, tile_n, N))
+
+
+def moe_tile_supported(dtype: int, tile_m: int, tile_n: int) -> bool:
+    return bool(lib().moe_tile_supported(dtype, tile_m, tile_n))
+
+
+def moe_map_offsets(E: int) -> dict:
+    L = lib()
+    return dict(counts=int(L.moe_map_off_counts(E)), offsets=int(L.moe_map_off_offsets(E)),
+                sigma=int(L.moe_map_off_sigma(E)), tile_prefix=int(L.moe_map_off_tile_prefix(E)),
+                sorted_rows=int(L.moe_map_off_sorted_rows(E)))
+
+
+def alloc_task_map(T_max: int, k: int, E: int, tile_m: int, tile_n: int, N: int, device="cuda") -> torch.Tensor:
+    nbytes = moe_task_map_bytes(T_max, k, E, tile_m, tile_n, N)
+    if nbytes == 0:
+        raise MoeError(MOE_ERR_INVALID_ARG, "moe_task_map_bytes")
+    return torch.empty(nbytes // 4, dtype=torch.int32, device=device)
+
+
+def moe_build_task_map(topk_ids: torch.Tensor, T: int, k: int, E: int, tile_m: int, tile_n: int, N: int,
+                       task_map: torch.Tensor, check: bool = True) -> int:
+    rc = lib().moe_build_task_map(_ptr(topk_ids), T, k, E, tile_m, tile_n, N, _ptr(task_map), _stream())
+    if check and rc != MOE_OK:
+        raise MoeError(rc, "moe_build_task_map")
+    return rc
+
+
+def moe_task_map_status(task_map: torch.Tensor) -> int:
+    return int(lib().moe_task_map_status(_ptr(task_map), _stream()))
+
+
+def moe_task_map_expand(task_map: torch.Tensor, E: int, table: torch.Tensor, grid: int, check: bool = True) -> int:
+    rc = lib().moe_task_map_expand(_ptr(task_map), E, _ptr(table), grid, _stream())
+    if check and rc != MOE_OK:
+        raise MoeError(rc, "moe_task_map_expand")
+    return rc
+
+
+@dataclass
+class GemmDesc:
+    dtype: int
+    T: int
+    k: int
+    E: int
+    K: int
+    N: int
+    tile_m: int
+    tile_n: int
+    x_scale: Optional[torch.Tensor] = None
+    w_scale: Optional[torch.Tensor] = None
+
+    def c_struct(self) -> moe_gemm_desc:
+        return moe_gemm_desc(self.dtype, self.T, self.k, self.E, self.K, self.N, self.tile_m, self.tile_n,
+                             None if self.x_scale is None else self.x_scale.data_ptr(),
+                             None if self.w_scale is None else self.w_scale.data_ptr())
+
+
+def moe_grouped_gemm(X: torch.Tensor, W: torch.Tensor, topk_ids: Optional[torch.Tensor], task_map: torch.Tensor,
+                     Y: torch.Tensor, desc: GemmDesc, check: bool = True) -> int:
+    d = desc.c_struct()
+    rc = lib().moe_grouped_gemm(_ptr(X), _ptr(W), _ptr(topk_ids), _ptr(task_map), _ptr(Y), ctypes.byref(d), _stream())
+    if check and rc != MOE_OK:
+        raise MoeError(rc, "moe_grouped_gemm")
+    return rc

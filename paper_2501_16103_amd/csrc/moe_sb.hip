@@ -1,0 +1,214 @@
+// C-ABI entry points of libmoe_sb: argument checks, launch geometry, kernel selection.
+// Everything that computes lives in task_map.hpp / gemm_kernel.hpp.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <type_traits>
+
+#include "../../include/moe_sb.h"
+#include "gemm_kernel.hpp"
+#include "task_map.hpp"
+
+using namespace moe;
+
+namespace {
+
+bool tile_m_ok(int v) { return v == 16 || v == 32 || v == 64 || v == 128 || v == 256; }
+bool tile_n_ok(int v) { return v == 64 || v == 128 || v == 256; }
+
+int check_map_args(int T, int k, int E, int tile_m, int tile_n, int N) {
+    if (T < 0 || k < 1 || E < 1 || k > E || N < 1) return MOE_ERR_INVALID_ARG;
+    if (E > kMaxE) return MOE_ERR_UNSUPPORTED;
+    if ((int64_t)T * k > (1 << 24)) return MOE_ERR_UNSUPPORTED;
+    if (!tile_m_ok(tile_m) || !tile_n_ok(tile_n)) return MOE_ERR_UNSUPPORTED;
+    return MOE_OK;
+}
+
+int nchunks_for(int64_t R) { return (int)((R + kChunkRows - 1) / kChunkRows); }
+
+typedef int (*gemm_launch_fn)(const GemmArgs&, int64_t grid, hipStream_t);
+
+template <class C>
+int launch_gemm(const GemmArgs& a, int64_t grid, hipStream_t s) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&moe_gemm_kernel<C>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES) != hipSuccess)
+            return MOE_ERR_HIP;
+        attr_set = true;
+    }
+    moe_gemm_kernel<C><<<dim3((unsigned)grid), dim3(C::NT), C::LDS_BYTES, s>>>(a);
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
+struct GemmVariant {
+    int dtype, tile_m, tile_n, bk;
+    gemm_launch_fn fn;
+};
+
+//                    BM   BN   BK  WM WN  FP8
+using Bf_256x256 = GemmCfg<256, 256, 64, 2, 2, false>;
+using Bf_128x256 = GemmCfg<128, 256, 64, 2, 2, false>;
+using Bf_128x128 = GemmCfg<128, 128, 64, 2, 2, false>;
+using Bf_64x256 = GemmCfg<64, 256, 64, 1, 4, false>;
+using Bf_64x128 = GemmCfg<64, 128, 64, 1, 4, false>;
+using Bf_32x256 = GemmCfg<32, 256, 64, 1, 4, false>;
+using Bf_32x128 = GemmCfg<32, 128, 64, 1, 4, false>;
+using Bf_16x256 = GemmCfg<16, 256, 64, 1, 4, false>;
+using Bf_16x128 = GemmCfg<16, 128, 64, 1, 4, false>;
+using F8_16x256 = GemmCfg<16, 256, 128, 1, 4, true>;
+using F8_16x128 = GemmCfg<16, 128, 128, 1, 4, true>;
+using F8_16x64 = GemmCfg<16, 64, 128, 1, 4, true>;
+using F8_32x128 = GemmCfg<32, 128, 128, 1, 4, true>;
+
+const GemmVariant kVariants[] = {
+    {MOE_DTYPE_BF16, 256, 256, 64, &launch_gemm<Bf_256x256>},
+    {MOE_DTYPE_BF16, 128, 256, 64, &launch_gemm<Bf_128x256>},
+    {MOE_DTYPE_BF16, 128, 128, 64, &launch_gemm<Bf_128x128>},
+    {MOE_DTYPE_BF16, 64, 256, 64, &launch_gemm<Bf_64x256>},
+    {MOE_DTYPE_BF16, 64, 128, 64, &launch_gemm<Bf_64x128>},
+    {MOE_DTYPE_BF16, 32, 256, 64, &launch_gemm<Bf_32x256>},
+    {MOE_DTYPE_BF16, 32, 128, 64, &launch_gemm<Bf_32x128>},
+    {MOE_DTYPE_BF16, 16, 256, 64, &launch_gemm<Bf_16x256>},
+    {MOE_DTYPE_BF16, 16, 128, 64, &launch_gemm<Bf_16x128>},
+    {MOE_DTYPE_FP8_E4M3, 16, 256, 128, &launch_gemm<F8_16x256>},
+    {MOE_DTYPE_FP8_E4M3, 16, 128, 128, &launch_gemm<F8_16x128>},
+    {MOE_DTYPE_FP8_E4M3, 16, 64, 128, &launch_gemm<F8_16x64>},
+    {MOE_DTYPE_FP8_E4M3, 32, 128, 128, &launch_gemm<F8_32x128>},
+};
+
+const GemmVariant* find_variant(int dtype, int tile_m, int tile_n) {
+    for (const GemmVariant& v : kVariants)
+        if (v.dtype == dtype && v.tile_m == tile_m && v.tile_n == tile_n) return &v;
+    return nullptr;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t moe_map_off_counts(int E) { return map_layout(E).off_counts; }
+size_t moe_map_off_offsets(int E) { return map_layout(E).off_offsets; }
+size_t moe_map_off_sigma(int E) { return map_layout(E).off_sigma; }
+size_t moe_map_off_tile_prefix(int E) { return map_layout(E).off_prefix; }
+size_t moe_map_off_sorted_rows(int E) { return map_layout(E).off_rows; }
+
+size_t moe_task_map_bytes(int T_max, int k, int E, int tile_m, int tile_n, int N) {
+    if (check_map_args(T_max, k, E, tile_m, tile_n, N) != MOE_OK) return 0;
+    const MapLayout L = map_layout(E);
+    const int64_t R = (int64_t)T_max * k;
+    const size_t words = L.off_rows + round_up64((size_t)R) + (size_t)nchunks_for(R) * hist_stride(L.E64) + 64;
+    return words * sizeof(int32_t);
+}
+
+int64_t moe_grid_upper_bound(int T, int k, int E, int tile_m, int tile_n, int N) {
+    if (check_map_args(T, k, E, tile_m, tile_n, N) != MOE_OK) return 0;
+    const int64_t R = (int64_t)T * k;
+    const int64_t nt = (N + tile_n - 1) / tile_n;
+    return (R / tile_m + (E < R ? E : R)) * nt;
+}
+
+int moe_build_task_map(const int32_t* topk_ids, int T, int k, int E, int tile_m, int tile_n, int N, void* task_map,
+                       void* stream) {
+    if (!task_map || (T > 0 && !topk_ids)) return MOE_ERR_INVALID_ARG;
+    if (((uintptr_t)task_map & 15) || ((uintptr_t)topk_ids & 3)) return MOE_ERR_INVALID_ARG;
+    const int rc = check_map_args(T, k, E, tile_m, tile_n, N);
+    if (rc != MOE_OK) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int32_t* map = static_cast<int32_t*>(task_map);
+    const MapLayout L = map_layout(E);
+    const int64_t R = (int64_t)T * k;
+    if (R <= kChunkRows) {
+        const size_t lds = ((size_t)kWaves * L.E64 + L.E64 + 32) * sizeof(int);
+        static bool attr_set = false;
+        if (!attr_set) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&map_build_small),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)(((size_t)kWaves * kMaxE + kMaxE + 32) * sizeof(int))) != hipSuccess)
+                return MOE_ERR_HIP;
+            attr_set = true;
+        }
+        map_build_small<<<1, kMapThreads, lds, s>>>(topk_ids, map, T, k, E, tile_m, tile_n, N);
+    } else {
+        const int nchunks = nchunks_for(R);
+        int32_t* chunk_hist = map + L.off_rows + round_up64((size_t)R);
+        const int hs = hist_stride(L.E64);
+        map_hist<<<nchunks, 256, hs * sizeof(int), s>>>(topk_ids, (int)R, E, L.E64, chunk_hist);
+        map_scan<<<1, kMapThreads, 0, s>>>(map, chunk_hist, nchunks, T, k, E, tile_m, tile_n, N);
+        static bool attr_set2 = false;
+        if (!attr_set2) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&map_scatter),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)((size_t)kWaves * kMaxE * sizeof(int))) != hipSuccess)
+                return MOE_ERR_HIP;
+            attr_set2 = true;
+        }
+        map_scatter<<<nchunks, kMapThreads, (size_t)kWaves * L.E64 * sizeof(int), s>>>(topk_ids, map, chunk_hist,
+                                                                                      (int)R, E);
+    }
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
+int moe_task_map_status(const void* task_map, void* stream) {
+    if (!task_map) return MOE_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int32_t hdr[MOE_MAP_HDR_WORDS];
+    if (hipMemcpyAsync(hdr, task_map, sizeof(hdr), hipMemcpyDeviceToHost, s) != hipSuccess) return MOE_ERR_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return MOE_ERR_HIP;
+    if (hdr[MOE_HDR_MAGIC] != MOE_MAP_MAGIC) return MOE_ERR_INVALID_ARG;
+    return hdr[MOE_HDR_STATUS] ? MOE_ERR_ROUTING : MOE_OK;
+}
+
+int moe_task_map_expand(const void* task_map, int E, int32_t* table, int64_t grid, void* stream) {
+    if (!task_map || grid < 0 || (grid > 0 && !table) || E < 1 || E > kMaxE) return MOE_ERR_INVALID_ARG;
+    if ((uintptr_t)table & 15) return MOE_ERR_INVALID_ARG;
+    if (grid == 0) return MOE_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int64_t blocks = (grid + 3) / 4;
+    if (blocks > 4096) blocks = 4096;
+    map_expand<<<(unsigned)blocks, 256, 0, s>>>(static_cast<const int32_t*>(task_map), E, table, (long long)grid);
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
+int moe_tile_supported(int dtype, int tile_m, int tile_n) { return find_variant(dtype, tile_m, tile_n) != nullptr; }
+
+int moe_grouped_gemm(const void* X, const void* W, const int32_t* topk_ids, const void* task_map, void* Y,
+                     const moe_gemm_desc* d, void* stream) {
+    (void)topk_ids;
+    if (!d || !task_map) return MOE_ERR_INVALID_ARG;
+    const int rc = check_map_args(d->T, d->k, d->E, d->tile_m, d->tile_n, d->N);
+    if (rc != MOE_OK) return rc;
+    if (d->K < 1) return MOE_ERR_INVALID_ARG;
+    if (d->dtype != MOE_DTYPE_BF16 && d->dtype != MOE_DTYPE_FP8_E4M3) return MOE_ERR_UNSUPPORTED;
+    const GemmVariant* v = find_variant(d->dtype, d->tile_m, d->tile_n);
+    if (!v) return MOE_ERR_UNSUPPORTED;
+    if (d->K % v->bk != 0 || d->N % d->tile_n != 0) return MOE_ERR_UNSUPPORTED;
+    const int es = d->dtype == MOE_DTYPE_FP8_E4M3 ? 1 : 2;
+    if ((int64_t)d->T * d->K * es >= (int64_t)1 << 32) return MOE_ERR_UNSUPPORTED;
+    if (d->T == 0) return MOE_OK;
+    if (!X || !W || !Y) return MOE_ERR_INVALID_ARG;
+    if (((uintptr_t)X & 15) || ((uintptr_t)W & 15) || ((uintptr_t)Y & 15) || ((uintptr_t)task_map & 15))
+        return MOE_ERR_INVALID_ARG;
+    if (d->dtype == MOE_DTYPE_FP8_E4M3 && (!d->x_scale || !d->w_scale)) return MOE_ERR_INVALID_ARG;
+    GemmArgs a;
+    a.X = X; a.W = W; a.map = static_cast<const int32_t*>(task_map); a.Y = Y;
+    a.x_scale = d->x_scale; a.w_scale = d->w_scale;
+    a.T = d->T; a.k = d->k; a.E = d->E; a.K = d->K; a.N = d->N;
+    int64_t grid = moe_grid_upper_bound(d->T, d->k, d->E, d->tile_m, d->tile_n, d->N);
+    grid = (grid + 7) / 8 * 8;
+    if (grid == 0) return MOE_OK;
+    if (grid > 0x7fffffff) return MOE_ERR_UNSUPPORTED;
+    return v->fn(a, grid, static_cast<hipStream_t>(stream));
+}
+
+const char* moe_strerror(int code) {
+    switch (code) {
+        case MOE_OK: return "ok";
+        case MOE_ERR_INVALID_ARG: return "invalid argument";
+        case MOE_ERR_UNSUPPORTED: return "unsupported size, tile shape or dtype";
+        case MOE_ERR_ROUTING: return "routing id outside [0, E)";
+        case MOE_ERR_HIP: return "HIP runtime error";
+        default: return "unknown error";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,314 @@
+// Task-map construction and decode for the statically batched MoE GEMM (gfx950).
+//
+// Builds, on the device, what Sec. 4.1 asks for after the token route: the
+// per-expert counts, the list sigma of non-empty experts, the inclusive
+// TilePrefix over the non-empty experts (Alg. 1), and the per-expert token
+// index arrays of Sec. 4.3 (here a stable counting sort of the flat row ids,
+// so the result does not depend on atomic ordering).  `mapping()` is Alg. 2
+// for a 64-lane wavefront; `decode_block()` adds the sigma stage of Alg. 4.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/moe_sb.h"
+
+namespace moe {
+
+constexpr int kChunkRows = 1024;  // routed rows handled by one scatter workgroup
+constexpr int kMapThreads = 1024; // = kChunkRows: one row per thread, 16 wavefronts
+constexpr int kMaxE = 1024;
+constexpr int kWaves = kMapThreads / 64;
+
+struct MapLayout {
+    int E64;
+    size_t off_counts, off_offsets, off_sigma, off_prefix, off_rows;
+};
+
+__host__ __device__ inline MapLayout map_layout(int E) {
+    MapLayout L;
+    L.E64 = (E + 63) / 64 * 64;
+    L.off_counts = MOE_MAP_HDR_WORDS;
+    L.off_offsets = L.off_counts + L.E64;
+    L.off_sigma = L.off_offsets + L.E64 + 64;
+    L.off_prefix = L.off_sigma + L.E64;
+    L.off_rows = L.off_prefix + L.E64;
+    return L;
+}
+
+__host__ __device__ inline size_t round_up64(size_t v) { return (v + 63) / 64 * 64; }
+// per-chunk histogram row: E64 expert columns + 64 spare (column E64 counts bad ids)
+__host__ __device__ inline int hist_stride(int E64) { return E64 + 64; }
+
+// ---------------------------------------------------------------- decode
+
+// Alg. 2 on one wavefront: lane t tests p = (B >= TilePrefix[t]); the ballot is the
+// warp vote, its population count is the task index h.  For more than 64 tasks the
+// vote is repeated over the array (Sec. 3.1); pads are INT32_MAX and never vote.
+__device__ __forceinline__ void mapping(const int32_t* __restrict__ tile_prefix, int E64, int B, int& h, int& l) {
+    const int lane = __lane_id();
+    int cnt = 0;
+    for (int base = 0; base < E64; base += 64) {
+        const int p = B >= tile_prefix[base + lane];
+        const int votes = __popcll(__ballot(p));
+        cnt += votes;
+        if (votes < 64) break;  // the array is non-decreasing: nothing further can vote
+    }
+    h = cnt;
+    int kprev = 0;
+    if (h > 0) kprev = tile_prefix[h - 1];
+    l = B - kprev;
+}
+
+struct TileCoord {
+    int e, m_tile, n_tile, rows, row_base;  // row_base: index into sorted_rows of the tile's first row
+};
+
+// Alg. 4: block -> non-empty task -> real expert, then the tile index split m-fastest.
+__device__ __forceinline__ TileCoord decode_block(const int32_t* __restrict__ map, const MapLayout& L, int tile_m, int B) {
+    int h, l;
+    mapping(map + L.off_prefix, L.E64, B, h, l);
+    TileCoord c;
+    c.e = map[L.off_sigma + h];
+    const int cnt = map[L.off_counts + c.e];
+    const int mt = (cnt + tile_m - 1) / tile_m;
+    c.n_tile = l / mt;
+    c.m_tile = l - c.n_tile * mt;
+    const int left = cnt - c.m_tile * tile_m;
+    c.rows = left < tile_m ? left : tile_m;
+    c.row_base = map[L.off_offsets + c.e] + c.m_tile * tile_m;
+    return c;
+}
+
+// ---------------------------------------------------------------- build
+
+// Among the lanes of a wavefront holding the same key: my rank (lanes below me with
+// my key) and the group size.  Invalid lanes take no part.
+__device__ __forceinline__ void wave_match(int key, bool valid, int nbits, int& rank, int& size) {
+    unsigned long long peers = __ballot(valid);
+    for (int b = 0; b < nbits; ++b) {
+        const int bit = (key >> b) & 1;
+        const unsigned long long m = __ballot(bit);
+        peers &= bit ? m : ~m;
+    }
+    const unsigned long long below = (1ull << __lane_id()) - 1ull;
+    rank = __popcll(peers & below);
+    size = __popcll(peers);
+}
+
+__device__ __forceinline__ int wave_incl_scan(int v) {
+    const int lane = __lane_id();
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int o = __shfl_up(v, d, 64);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+
+// Inclusive scan across the 1024 threads of the block (s_tmp: >= 16 ints of LDS).
+__device__ __forceinline__ int block_incl_scan(int v, int* s_tmp) {
+    const int w = threadIdx.x >> 6, lane = __lane_id();
+    const int incl = wave_incl_scan(v);
+    __syncthreads();
+    if (lane == 63) s_tmp[w] = incl;
+    __syncthreads();
+    int base = 0;
+    for (int i = 0; i < w; ++i) base += s_tmp[i];
+    return incl + base;
+}
+
+// From the per-expert count held by thread e (< E64; 0 beyond E): write counts, offsets,
+// sigma, tile_prefix and the header.  Executed by all kMapThreads threads of one block.
+// Returns this thread's exclusive offset (valid for threadIdx.x < E).
+__device__ __forceinline__ int finish_map(int32_t* __restrict__ map, const MapLayout& L, int cnt, int bad, int T, int k,
+                                          int E, int tile_m, int tile_n, int N, int* s_tmp) {
+    const int tid = threadIdx.x;
+    const int R = T * k;
+    const int nt = (N + tile_n - 1) / tile_n;
+    const int nonempty = cnt > 0;
+    const int tiles = ((cnt + tile_m - 1) / tile_m) * nt;
+    const int off_incl = block_incl_scan(cnt, s_tmp);
+    const int pos_incl = block_incl_scan(nonempty, s_tmp);
+    const int tile_incl = block_incl_scan(tiles, s_tmp);  // Alg. 1 restricted to non-empty experts
+    __syncthreads();
+    if (tid == kMapThreads - 1) { s_tmp[0] = pos_incl; s_tmp[1] = tile_incl; }
+    __syncthreads();
+    const int M = s_tmp[0], total = s_tmp[1];
+    if (tid < L.E64) {
+        map[L.off_counts + tid] = cnt;
+        map[L.off_sigma + tid] = -1;
+        map[L.off_prefix + tid] = 0x7fffffff;
+    }
+    for (int i = tid; i < L.E64 + 64; i += kMapThreads) map[L.off_offsets + i] = i <= E ? 0 : R;
+    __syncthreads();
+    if (tid < E) map[L.off_offsets + tid] = off_incl - cnt;
+    if (tid == 0) map[L.off_offsets + E] = R - bad;
+    if (nonempty) {
+        map[L.off_sigma + pos_incl - 1] = tid;
+        map[L.off_prefix + pos_incl - 1] = tile_incl;
+    }
+    if (tid < MOE_MAP_HDR_WORDS) {
+        int v = 0;
+        switch (tid) {
+            case MOE_HDR_MAGIC: v = MOE_MAP_MAGIC; break;
+            case MOE_HDR_T: v = T; break;
+            case MOE_HDR_K_TOP: v = k; break;
+            case MOE_HDR_E: v = E; break;
+            case MOE_HDR_N: v = N; break;
+            case MOE_HDR_TILE_M: v = tile_m; break;
+            case MOE_HDR_TILE_N: v = tile_n; break;
+            case MOE_HDR_NT: v = nt; break;
+            case MOE_HDR_M: v = M; break;
+            case MOE_HDR_TOTAL_TILES: v = bad ? 0 : total; break;
+            case MOE_HDR_ORDER: v = 0; break;
+            case MOE_HDR_STATUS: v = bad; break;
+            case MOE_HDR_R: v = R; break;
+            case MOE_HDR_E64: v = L.E64; break;
+            default: v = 0;
+        }
+        map[tid] = v;
+    }
+    return off_incl - cnt;
+}
+
+__device__ __forceinline__ int key_bits(int E) {
+    int nb = 1;
+    while ((1 << nb) < E) ++nb;
+    return nb;
+}
+
+// One-workgroup build for R <= kChunkRows: histogram, scans and stable scatter fused.
+// Dynamic LDS: kWaves * E64 ints (per-wavefront counts) + E64 ints (offsets) + 32.
+__global__ __launch_bounds__(kMapThreads) void map_build_small(const int32_t* __restrict__ ids, int32_t* __restrict__ map,
+                                                                int T, int k, int E, int tile_m, int tile_n, int N) {
+    extern __shared__ int s_mem[];
+    const MapLayout L = map_layout(E);
+    int* s_wave = s_mem;                   // [kWaves][E64]
+    int* s_off = s_mem + kWaves * L.E64;   // [E64]
+    int* s_tmp = s_off + L.E64;            // [32]
+    const int tid = threadIdx.x, w = tid >> 6;
+    const int R = T * k;
+    for (int i = tid; i < kWaves * L.E64; i += kMapThreads) s_wave[i] = 0;
+    if (tid == 0) s_tmp[31] = 0;
+    __syncthreads();
+    const bool in_range = tid < R;
+    const int e = in_range ? ids[tid] : 0;
+    const bool valid = in_range && e >= 0 && e < E;
+    int rank, size;
+    wave_match(e, valid, key_bits(E), rank, size);
+    if (valid && rank == 0) s_wave[w * L.E64 + e] = size;
+    const int nbad = __popcll(__ballot(in_range && !valid));
+    if (nbad && __lane_id() == 0) atomicAdd(&s_tmp[31], nbad);
+    __syncthreads();
+    const int bad = s_tmp[31];
+    int cnt = 0;
+    if (tid < L.E64) {
+        for (int i = 0; i < kWaves; ++i) {  // exclusive scan over wavefronts, in row order
+            const int c = s_wave[i * L.E64 + tid];
+            s_wave[i * L.E64 + tid] = cnt;
+            cnt += c;
+        }
+    }
+    const int off = finish_map(map, L, cnt, bad, T, k, E, tile_m, tile_n, N, s_tmp);
+    if (tid < L.E64) s_off[tid] = off;
+    __syncthreads();
+    if (valid) map[L.off_rows + s_off[e] + s_wave[w * L.E64 + e] + rank] = tid;
+}
+
+// Multi-chunk path, step 1: per-chunk histogram (integer LDS atomics: order-free).
+__global__ __launch_bounds__(256) void map_hist(const int32_t* __restrict__ ids, int R, int E, int E64,
+                                                 int32_t* __restrict__ chunk_hist) {
+    extern __shared__ int s_mem[];
+    const int hs = hist_stride(E64);
+    for (int i = threadIdx.x; i < hs; i += 256) s_mem[i] = 0;
+    __syncthreads();
+    const int base = blockIdx.x * kChunkRows;
+    for (int i = threadIdx.x; i < kChunkRows; i += 256) {
+        const int r = base + i;
+        if (r < R) {
+            const int e = ids[r];
+            atomicAdd(&s_mem[(e >= 0 && e < E) ? e : E64], 1);
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < hs; i += 256) chunk_hist[(size_t)blockIdx.x * hs + i] = s_mem[i];
+}
+
+// Step 2 (one workgroup): turn the chunk histograms into per-chunk exclusive bases,
+// then counts / offsets / sigma / TilePrefix / header.
+__global__ __launch_bounds__(kMapThreads) void map_scan(int32_t* __restrict__ map, int32_t* __restrict__ chunk_hist,
+                                                        int nchunks, int T, int k, int E, int tile_m, int tile_n, int N) {
+    __shared__ int s_tmp[32];
+    const MapLayout L = map_layout(E);
+    const int hs = hist_stride(L.E64);
+    const int tid = threadIdx.x;
+    int cnt = 0;
+    if (tid < L.E64) {
+        for (int c = 0; c < nchunks; ++c) {
+            const int v = chunk_hist[(size_t)c * hs + tid];
+            chunk_hist[(size_t)c * hs + tid] = cnt;
+            cnt += v;
+        }
+    }
+    if (tid == 0) {
+        int b = 0;
+        for (int c = 0; c < nchunks; ++c) b += chunk_hist[(size_t)c * hs + L.E64];
+        s_tmp[31] = b;
+    }
+    __syncthreads();
+    const int bad = s_tmp[31];
+    finish_map(map, L, cnt, bad, T, k, E, tile_m, tile_n, N, s_tmp);
+}
+
+// Step 3: stable scatter of one chunk of rows into the token index arrays.
+__global__ __launch_bounds__(kMapThreads) void map_scatter(const int32_t* __restrict__ ids, int32_t* __restrict__ map,
+                                                           const int32_t* __restrict__ chunk_hist, int R, int E) {
+    extern __shared__ int s_mem[];
+    const MapLayout L = map_layout(E);
+    const int hs = hist_stride(L.E64);
+    int* s_wave = s_mem;  // [kWaves][E64]
+    const int tid = threadIdx.x, w = tid >> 6;
+    for (int i = tid; i < kWaves * L.E64; i += kMapThreads) s_wave[i] = 0;
+    __syncthreads();
+    const int r = blockIdx.x * kChunkRows + tid;
+    const bool in_range = r < R;
+    const int e = in_range ? ids[r] : 0;
+    const bool valid = in_range && e >= 0 && e < E;
+    int rank, size;
+    wave_match(e, valid, key_bits(E), rank, size);
+    if (valid && rank == 0) s_wave[w * L.E64 + e] = size;
+    __syncthreads();
+    if (tid < L.E64) {
+        int run = 0;
+        for (int i = 0; i < kWaves; ++i) {
+            const int c = s_wave[i * L.E64 + tid];
+            s_wave[i * L.E64 + tid] = run;
+            run += c;
+        }
+    }
+    __syncthreads();
+    if (valid) {
+        const int pos = map[L.off_offsets + e] + chunk_hist[(size_t)blockIdx.x * hs + e] + s_wave[w * L.E64 + e] + rank;
+        map[L.off_rows + pos] = r;
+    }
+}
+
+// Full per-block table from the compressed map, one wavefront per block index.
+__global__ __launch_bounds__(256) void map_expand(const int32_t* __restrict__ map, int E, int32_t* __restrict__ table,
+                                                   long long grid) {
+    const MapLayout L = map_layout(E);
+    const int total = map[MOE_HDR_TOTAL_TILES];
+    const int tile_m = map[MOE_HDR_TILE_M];
+    const long long wave = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const long long nwaves = (long long)gridDim.x * 4;
+    for (long long B = wave; B < grid; B += nwaves) {
+        int4 out = make_int4(-1, -1, -1, -1);
+        if (B < total) {
+            const TileCoord c = decode_block(map, L, tile_m, (int)B);
+            out = make_int4(c.e, c.m_tile, c.n_tile, c.rows);
+        }
+        if (__lane_id() == 0) reinterpret_cast<int4*>(table)[B] = out;
+    }
+}
+
+}  // namespace moe

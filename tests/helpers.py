@@ -1,0 +1,64 @@
+"""Shared test helpers: expected task-map blob from the oracle, error metrics."""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+import torch
+
+INT32_MAX = 0x7FFFFFFF
+HDR_WORDS = 32
+MAGIC = 0x3142534D
+
+
+def blob_offsets(E: int) -> dict:
+    """Word offsets of the blob's fields as documented in include/moe_sb.h."""
+    E64 = (E + 63) // 64 * 64
+    counts = HDR_WORDS
+    offsets = counts + E64
+    sigma = offsets + E64 + 64
+    prefix = sigma + E64
+    rows = prefix + E64
+    return dict(E64=E64, counts=counts, offsets=offsets, sigma=sigma, tile_prefix=prefix, sorted_rows=rows)
+
+
+def expected_blob(tm) -> np.ndarray:
+    """The compared part of the blob (header .. sorted_rows[R]) from an oracle TaskMap."""
+    o = blob_offsets(tm.E)
+    R = tm.T * tm.k
+    b = np.zeros(o["sorted_rows"] + R, dtype=np.int32)
+    hdr = [MAGIC, tm.T, tm.k, tm.E, tm.N, tm.tile_m, tm.tile_n, tm.nt, tm.M, tm.total_tiles, 0, 0, R, o["E64"]]
+    b[: len(hdr)] = hdr
+    b[o["counts"]: o["counts"] + tm.E] = tm.counts
+    b[o["offsets"]: o["offsets"] + o["E64"] + 64] = R
+    b[o["offsets"]: o["offsets"] + tm.E + 1] = tm.offsets
+    b[o["sigma"]: o["sigma"] + o["E64"]] = -1
+    b[o["sigma"]: o["sigma"] + tm.M] = tm.sigma
+    b[o["tile_prefix"]: o["tile_prefix"] + o["E64"]] = INT32_MAX
+    b[o["tile_prefix"]: o["tile_prefix"] + tm.M] = tm.tile_prefix
+    b[o["sorted_rows"]: o["sorted_rows"] + R] = tm.sorted_rows
+    return b
+
+
+def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def tol_bf16(K: int) -> float:
+    return 2e-2 * math.sqrt(K / 256.0)
+
+
+def tol_fp8(K: int) -> float:
+    return 6e-2 * math.sqrt(K / 256.0)
+
+
+def ulp_distance(a_bits: np.ndarray, b_bits: np.ndarray) -> np.ndarray:
+    """Distance in bf16 units in the last place between two bf16 bit arrays (sign-magnitude aware)."""
+    def key(x):
+        x = x.astype(np.int32)
+        return np.where(x & 0x8000, -(x & 0x7FFF), x & 0x7FFF)
+    return np.abs(key(a_bits) - key(b_bits))
+
+
+def y_bits(Y: torch.Tensor) -> np.ndarray:
+    return Y.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)

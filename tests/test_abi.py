@@ -1,0 +1,72 @@
+"""CPU checks of the boundary: the library loads, exports every declared symbol, and its
+host-only entry points behave as include/moe_sb.h states.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2501_16103_amd import binding as mb
+from tests import helpers as H
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "moe_sb.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = mb.lib()
+    names = _declared_functions()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in include/moe_sb.h but not exported"
+    assert sorted(mb.EXPORTS) == names
+
+
+def test_host_only_entry_points():
+    assert mb.moe_task_map_bytes(-1, 2, 8, 16, 128, 256) == 0
+    assert mb.moe_task_map_bytes(4, 9, 8, 16, 128, 256) == 0        # k > E
+    assert mb.moe_task_map_bytes(4, 2, 8, 48, 128, 256) == 0        # tile_m not supported
+    nbytes = mb.moe_task_map_bytes(4096, 2, 8, 256, 256, 28672)
+    o = H.blob_offsets(8)
+    assert nbytes % 4 == 0 and nbytes // 4 >= o["sorted_rows"] + 8192
+    assert mb.moe_task_map_bytes(8192, 8, 256, 256, 256, 4096) > mb.moe_task_map_bytes(128, 8, 256, 256, 256, 4096)
+    # documented field offsets
+    for E in (1, 8, 64, 70, 256):
+        lo = mb.moe_map_offsets(E)
+        o = H.blob_offsets(E)
+        assert all(lo[f] == o[f] for f in lo)
+    # grid bound = (floor(R/tile_m) + min(E,R)) * ceil(N/tile_n)
+    assert mb.moe_grid_upper_bound(4096, 2, 8, 256, 256, 28672) == (32 + 8) * 112
+    assert mb.moe_grid_upper_bound(1, 6, 64, 16, 64, 2816) == (0 + 6) * 44
+    assert mb.moe_grid_upper_bound(0, 2, 8, 16, 128, 512) == 0
+    assert mb.moe_tile_supported(mb.MOE_DTYPE_BF16, 256, 256)
+    assert mb.moe_tile_supported(mb.MOE_DTYPE_FP8_E4M3, 16, 128)
+    assert not mb.moe_tile_supported(mb.MOE_DTYPE_FP8_E4M3, 256, 256)
+    assert mb.strerror(mb.MOE_ERR_ROUTING).startswith("routing id")
+    assert mb.strerror(0) == "ok"
+
+
+def test_grid_bound_covers_any_routing(oracle_mod):
+    import numpy as np
+    rng = np.random.default_rng(0)
+    for _ in range(200):
+        E = int(rng.integers(1, 40))
+        k = int(rng.integers(1, min(E, 8) + 1))
+        T = int(rng.integers(0, 80))
+        tile_m = int(rng.choice([16, 32, 64]))
+        ids = np.stack([rng.choice(E, size=k, replace=False) for _ in range(T)]) if T else np.zeros((0, k), np.int32)
+        tm = oracle_mod.build_task_map(ids, T, k, E, tile_m, 64, 128)
+        assert tm.total_tiles <= mb.moe_grid_upper_bound(T, k, E, tile_m, 64, 128)
+
+
+def test_null_arguments_rejected_on_host():
+    lib = mb.lib()
+    assert lib.moe_build_task_map(None, 4, 2, 8, 16, 128, 256, None, None) == mb.MOE_ERR_INVALID_ARG
+    assert lib.moe_task_map_status(None, None) == mb.MOE_ERR_INVALID_ARG
+    assert lib.moe_grouped_gemm(None, None, None, None, None, None, None) == mb.MOE_ERR_INVALID_ARG
+    assert lib.moe_task_map_expand(None, 8, None, 0, None) == mb.MOE_ERR_INVALID_ARG

@@ -1,0 +1,226 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Task map, counts, offsets and the expanded table must be bit-exact.  Y must agree within
+max|err| <= 2e-2*sqrt(K/256)*||x||*||w|| (bf16) or 6e-2*(that scale) (fp8); in addition a much
+tighter statistic is asserted (distance to the oracle's bf16 in units in the last place), because
+the stated bound alone is loose enough to pass a wrongly routed row at large K.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2501_16103_amd import binding as mb
+from paper_2501_16103_amd import workloads as wk
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+POISON = 0x7FC1  # a bf16 NaN with a recognisable payload
+
+
+@pytest.fixture(scope="module")
+def dev():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    mb.lib()  # fails loudly when libmoe_sb.so is not built
+    return torch.device("cuda:0")
+
+
+def _build_map(ids_dev, T, k, E, tile_m, tile_n, N):
+    tmap = mb.alloc_task_map(max(T, 1), k, E, tile_m, tile_n, N)
+    tmap.fill_(0x5A5A5A5A)
+    mb.moe_build_task_map(ids_dev, T, k, E, tile_m, tile_n, N, tmap)
+    return tmap
+
+
+MAP_CASES = [
+    # T, k, E, tile_m, tile_n, N, routing
+    (0, 2, 8, 16, 128, 512, "gauss_topk"),
+    (1, 6, 64, 16, 64, 2816, "uniform_topk"),
+    (64, 2, 8, 32, 128, 512, "gauss_topk"),
+    (512, 2, 8, 64, 128, 4096, "zipf"),            # exactly one chunk of 1024 rows
+    (513, 2, 8, 64, 128, 4096, "zipf"),            # one row into the second chunk
+    (128, 8, 256, 16, 128, 4096, "gauss_topk"),    # E > 64: several voting rounds, empty experts
+    (33, 3, 70, 16, 64, 192, "zipf"),              # E not a multiple of 64
+    (4096, 2, 8, 256, 256, 28672, "gauss_topk"),
+    (4096, 2, 8, 256, 256, 4096, "zipf"),
+    (2048, 8, 256, 64, 128, 4096, "gauss_topk"),
+    (8192, 8, 256, 256, 256, 4096, "gauss_topk"),  # 64 chunks
+    (4096, 8, 64, 256, 256, 2560, "worst"),
+    (4096, 8, 64, 256, 256, 2560, "best"),
+    (1000, 1, 1, 128, 128, 128, "best"),
+]
+
+
+@pytest.mark.parametrize("T,k,E,tile_m,tile_n,N,routing", MAP_CASES)
+def test_task_map_bit_exact(dev, oracle_mod, T, k, E, tile_m, tile_n, N, routing):
+    wl = wk.Workload("mapcase", T, E, k, 64, N, "bf16", routing)
+    ids = wk.make_routing(wl)
+    tm = oracle_mod.build_task_map(ids.numpy(), T, k, E, tile_m, tile_n, N)
+    want = H.expected_blob(tm)
+    ids_dev = ids.to(dev)
+    got1 = _build_map(ids_dev, T, k, E, tile_m, tile_n, N)
+    assert mb.moe_task_map_status(got1) == mb.MOE_OK
+    g1 = got1.cpu().numpy()
+    np.testing.assert_array_equal(g1[: len(want)], want)
+    # determinism: a second build gives the same bytes, scratch included
+    got2 = _build_map(ids_dev, T, k, E, tile_m, tile_n, N)
+    torch.cuda.synchronize()
+    assert torch.equal(got1, got2)
+    # documented offsets are the library's offsets
+    lo = mb.moe_map_offsets(E)
+    o = H.blob_offsets(E)
+    assert all(lo[f] == o[f] for f in lo)
+    # expanded full table == oracle's Alg. 4 decode of every block == brute-force table
+    grid = mb.moe_grid_upper_bound(T, k, E, tile_m, tile_n, N)
+    assert grid >= tm.total_tiles
+    table = torch.full((max(grid, 1), 4), 7, dtype=torch.int32, device=dev)
+    mb.moe_task_map_expand(got1, E, table, grid)
+    tab = table.cpu().numpy()[:grid]
+    np.testing.assert_array_equal(tab[: tm.total_tiles], oracle_mod.full_table(tm.counts, tile_m, tile_n, N))
+    assert np.all(tab[tm.total_tiles:] == -1)
+    if tm.total_tiles <= 6000:
+        np.testing.assert_array_equal(tab[: tm.total_tiles], oracle_mod.decode_all(tm))
+
+
+def test_bad_routing_id_reported_and_gemm_noop(dev):
+    T, k, E, K, N = 40, 2, 8, 256, 256
+    ids = torch.randint(0, E, (T, k), dtype=torch.int32)
+    ids[7, 1] = E
+    ids[20, 0] = -3
+    tmap = _build_map(ids.to(dev), T, k, E, 16, 128, N)
+    assert mb.moe_task_map_status(tmap) == mb.MOE_ERR_ROUTING
+    hdr = tmap[:32].cpu().numpy()
+    assert hdr[mb.HDR["STATUS"]] == 2 and hdr[mb.HDR["TOTAL_TILES"]] == 0
+    X = torch.randn(T, K, device=dev).to(torch.bfloat16)
+    W = torch.randn(E, K, N, device=dev).to(torch.bfloat16)
+    Y = torch.full((T * k, N), float("nan"), device=dev, dtype=torch.bfloat16)
+    mb.moe_grouped_gemm(X, W, None, tmap, Y, mb.GemmDesc(mb.MOE_DTYPE_BF16, T, k, E, K, N, 16, 128))
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(Y).all())  # nothing gathered, nothing written
+
+
+def test_argument_errors(dev):
+    ids = torch.zeros((4, 2), dtype=torch.int32, device=dev)
+    tmap = mb.alloc_task_map(4, 2, 8, 16, 128, 256)
+    assert mb.moe_build_task_map(ids, -1, 2, 8, 16, 128, 256, tmap, check=False) == mb.MOE_ERR_INVALID_ARG
+    assert mb.moe_build_task_map(ids, 4, 9, 8, 16, 128, 256, tmap, check=False) == mb.MOE_ERR_INVALID_ARG
+    assert mb.moe_build_task_map(ids, 4, 2, 8, 17, 128, 256, tmap, check=False) == mb.MOE_ERR_UNSUPPORTED
+    assert mb.moe_build_task_map(None, 4, 2, 8, 16, 128, 256, tmap, check=False) == mb.MOE_ERR_INVALID_ARG
+    mb.moe_build_task_map(ids, 4, 2, 8, 16, 128, 256, tmap)
+    X = torch.zeros(4, 256, device=dev, dtype=torch.bfloat16)
+    W = torch.zeros(8, 256, 256, device=dev, dtype=torch.bfloat16)
+    Y = torch.zeros(8, 256, device=dev, dtype=torch.bfloat16)
+    d = mb.GemmDesc(mb.MOE_DTYPE_BF16, 4, 2, 8, 256, 256, 16, 128)
+    assert mb.moe_grouped_gemm(None, W, None, tmap, Y, d, check=False) == mb.MOE_ERR_INVALID_ARG
+    d_bad_k = mb.GemmDesc(mb.MOE_DTYPE_BF16, 4, 2, 8, 200, 256, 16, 128)
+    assert mb.moe_grouped_gemm(X, W, None, tmap, Y, d_bad_k, check=False) == mb.MOE_ERR_UNSUPPORTED
+    d_fp8 = mb.GemmDesc(mb.MOE_DTYPE_FP8_E4M3, 4, 2, 8, 256, 256, 16, 128)
+    assert mb.moe_grouped_gemm(X, W, None, tmap, Y, d_fp8, check=False) == mb.MOE_ERR_INVALID_ARG  # no scales
+    # a map built for other tiles makes the kernel a no-op instead of a wild gather
+    Y.fill_(float("nan"))
+    d_other = mb.GemmDesc(mb.MOE_DTYPE_BF16, 4, 2, 8, 256, 256, 32, 128)
+    assert mb.moe_grouped_gemm(X, W, None, tmap, Y, d_other, check=False) == mb.MOE_OK
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(Y).all())
+
+
+def _run_gemm(dev, wl, ids, X, W, xs=None, ws=None):
+    """Run map build + GEMM with Y embedded between poisoned canary rows; returns Y bits [R,N]."""
+    R, N = wl.R, wl.N
+    pad = 4
+    buf = torch.empty((R + 2 * pad, N), dtype=torch.int16, device=dev)
+    buf.fill_(POISON)
+    Y = buf[pad: pad + R]
+    tmap = _build_map(ids.to(dev), wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, N)
+    dt = mb.MOE_DTYPE_FP8_E4M3 if wl.dtype == "fp8" else mb.MOE_DTYPE_BF16
+    desc = mb.GemmDesc(dt, wl.T, wl.k, wl.E, wl.K, N, wl.tile_m, wl.tile_n,
+                       None if xs is None else xs.to(dev), None if ws is None else ws.to(dev))
+    mb.moe_grouped_gemm(X.to(dev), W.to(dev), ids.to(dev), tmap, Y, desc)
+    torch.cuda.synchronize()
+    assert mb.moe_task_map_status(tmap) == mb.MOE_OK
+    allbits = buf.cpu().numpy().view(np.uint16)
+    assert np.all(allbits[:pad] == POISON) and np.all(allbits[pad + R:] == POISON), "wrote outside Y"
+    return allbits[pad: pad + R]
+
+
+def _check_y(got_bits, res, Xf, Wf, ids, k, K, tol, xs=None, ws=None):
+    """got_bits [R,N] uint16 vs oracle GemmResult; Xf [T,K], Wf [E,K,N] float64 element values."""
+    assert not np.any(got_bits == POISON), "a (token, slot) row or column range was never written"
+    got = H.bf16_bits_to_f64(got_bits)
+    flat = ids.reshape(-1)
+    xn = np.sqrt((Xf ** 2).sum(axis=1))              # [T]
+    wn = np.sqrt((Wf ** 2).sum(axis=1))              # [E,N]
+    scale = xn[np.arange(len(flat)) // k][:, None] * wn[flat]
+    if xs is not None:
+        scale = scale * (xs[np.arange(len(flat)) // k][:, None] * ws[flat][:, None])
+    err = np.abs(got - res.Y64)
+    assert np.all(err <= tol * scale), f"max err/scale = {(err / scale).max():.3e} > {tol:.3e}"
+    # tight, derived bound: any fp32 summation order errs by at most K*2^-24*sum|x_k w_k|, and the
+    # final round-to-nearest bf16 adds at most 2^-8 of the value
+    xi = np.arange(len(flat)) // k
+    A = np.stack([np.abs(Xf[xi[r]]) @ np.abs(Wf[flat[r]]) for r in range(len(flat))])
+    if xs is not None:
+        A = A * (xs[xi][:, None] * ws[flat][:, None])
+    tight = 2.0 ** -8 * np.abs(res.Y64) * 1.001 + 1.01 * K * 2.0 ** -24 * A + 1e-30
+    assert np.all(err <= tight), f"max err/tight = {(err / tight).max():.3f}"
+    # and nearly every stored value is bit-identical to the oracle's single-rounded bf16
+    ulp = H.ulp_distance(got_bits, res.Ybf)
+    assert (ulp == 0).mean() > 0.97
+
+
+BF16_CASES = [
+    # tile_m, tile_n, T, E, k, K, N, routing
+    (16, 128, 64, 8, 2, 256, 512, "gauss_topk"),
+    (16, 256, 100, 8, 2, 256, 512, "zipf"),
+    (32, 128, 64, 8, 2, 256, 512, "gauss_topk"),      # the tiny benchmark config
+    (32, 256, 150, 8, 2, 192, 512, "zipf"),
+    (64, 128, 300, 8, 2, 256, 256, "gauss_topk"),
+    (64, 256, 300, 8, 2, 128, 512, "zipf"),
+    (128, 128, 600, 8, 2, 256, 256, "gauss_topk"),
+    (128, 256, 600, 8, 2, 128, 512, "zipf"),
+    (256, 256, 1200, 8, 2, 256, 512, "gauss_topk"),
+    (256, 256, 700, 16, 2, 128, 256, "zipf"),         # empty experts, one > 2 tiles, ragged tails
+    (16, 128, 40, 256, 8, 128, 256, "gauss_topk"),    # E = 256: four voting rounds
+    (64, 128, 257, 3, 1, 64, 128, "worst"),
+]
+
+
+@pytest.mark.parametrize("tile_m,tile_n,T,E,k,K,N,routing", BF16_CASES)
+def test_gemm_bf16_parity(dev, oracle_mod, tile_m, tile_n, T, E, k, K, N, routing):
+    wl = wk.Workload("parity_bf16", T, E, k, K, N, "bf16", routing, tile_m, tile_n)
+    ids, X, W = wk.make_routing(wl), wk.make_x(wl), wk.make_w(wl)
+    got = _run_gemm(dev, wl, ids, X, W)
+    res = oracle_mod.grouped_gemm_bf16(wk.bits(X), wk.bits(W), ids.numpy())
+    _check_y(got, res, X.double().numpy(), W.double().numpy(), ids.numpy(), k, K, H.tol_bf16(K))
+
+
+FP8_CASES = [
+    (16, 64, 1, 64, 6, 256, 128, "uniform_topk"),
+    (16, 128, 8, 64, 6, 256, 256, "uniform_topk"),
+    (16, 256, 32, 64, 6, 384, 512, "uniform_topk"),
+    (16, 128, 100, 8, 2, 128, 256, "zipf"),           # several m-tiles per expert
+    (32, 128, 100, 8, 2, 256, 256, "zipf"),
+]
+
+
+@pytest.mark.parametrize("tile_m,tile_n,T,E,k,K,N,routing", FP8_CASES)
+def test_gemm_fp8_parity(dev, oracle_mod, tile_m, tile_n, T, E, k, K, N, routing):
+    wl = wk.Workload("parity_fp8", T, E, k, K, N, "fp8", routing, tile_m, tile_n)
+    ids = wk.make_routing(wl)
+    Xq, xs = wk.make_x(wl)
+    Wq, ws = wk.make_w(wl)
+    got = _run_gemm(dev, wl, ids, Xq, Wq, xs, ws)
+    res = oracle_mod.grouped_gemm_fp8(Xq.numpy(), Wq.numpy(), xs.numpy(), ws.numpy(), ids.numpy())
+    Xf = Xq.view(torch.float8_e4m3fn).double().numpy()
+    Wf = Wq.view(torch.float8_e4m3fn).double().numpy()
+    _check_y(got, res, Xf, Wf, ids.numpy(), k, K, H.tol_fp8(K), xs.double().numpy(), ws.double().numpy())
+
+
+def test_identity_weight_returns_tokens_exactly(dev):
+    """W = I: every output row is bit-for-bit the gathered token (a property, no oracle needed)."""
+    T, E, k, K = 300, 8, 2, 256
+    wl = wk.Workload("ident", T, E, k, K, K, "bf16", "zipf", 64, 128)
+    ids, X = wk.make_routing(wl), wk.make_x(wl)
+    W = torch.eye(K).to(torch.bfloat16).expand(E, K, K).contiguous()
+    got = _run_gemm(dev, wl, ids, X, W)
+    np.testing.assert_array_equal(got, wk.bits(X)[np.arange(T * k) // k])
