@@ -1,0 +1,234 @@
+#!/usr/bin/env python3
+"""Benchmark of the statically batched MoE expert GEMM on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input: build the task
+map from the routing (histogram, scans, token index arrays) and run the grouped GEMM kernel.
+Inputs are resident in HBM before the timed region.  The headline workload is the
+Mixtral-8x7B-shaped fused gate+up projection at T=4096 (E=8, top-2, K=4096, N=28672, bf16);
+`--points all` also times the other synthetic configurations and reports them in "points".
+
+Prints ONE JSON line on stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2501_16103_amd import binding as mb  # noqa: E402
+from paper_2501_16103_amd import workloads as wk  # noqa: E402
+
+# Published MI355X peaks the fractions are taken against.
+PEAK_BF16_TFLOPS = 2516.6   # dense bf16 MFMA (256 CUs x 2.4 GHz x 4096 FLOP/clk/CU)
+PEAK_FP8_TFLOPS = 5033.2    # dense fp8 MFMA
+PEAK_HBM_GBS = 8000.0
+
+# HBM bytes per GEMM launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a
+# copy kernel of known size; see profiles/.  None where it has not been measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def algorithmic_bytes(wl: wk.Workload, ids: torch.Tensor) -> int:
+    """Weights of every touched expert once + X once + Y once + the map."""
+    es = 1 if wl.dtype == "fp8" else 2
+    touched = int(torch.unique(ids).numel())
+    b = touched * wl.K * wl.N * es + wl.T * wl.K * es + wl.R * wl.N * 2 + 4 * (wl.R + 3 * wl.E)
+    if wl.dtype == "fp8":
+        b += 4 * (wl.T + wl.E)
+    return b
+
+
+class Point:
+    """Device buffers of one workload (optionally several weight copies to defeat the caches)."""
+
+    def __init__(self, wl: wk.Workload, copies: int = 1, dev="cuda:0"):
+        self.wl = wl
+        self.dev = dev
+        self.ids_cpu = wk.make_routing(wl)
+        self.ids = self.ids_cpu.to(dev)
+        self.xs = self.ws = None
+        if wl.dtype == "fp8":
+            X, xs = wk.make_x(wl, dev)
+            W, ws = wk.make_w(wl, dev)
+            self.X, self.xs, self.ws = X, xs, ws
+        else:
+            self.X = wk.make_x(wl, dev)
+            W = wk.make_w(wl, dev)
+        self.W = [W] + [W.clone() for _ in range(copies - 1)]
+        self.Y = torch.empty((wl.R, wl.N), dtype=torch.bfloat16, device=dev)
+        self.tmap = mb.alloc_task_map(wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N, dev)
+        dt = mb.MOE_DTYPE_FP8_E4M3 if wl.dtype == "fp8" else mb.MOE_DTYPE_BF16
+        self.desc = mb.GemmDesc(dt, wl.T, wl.k, wl.E, wl.K, wl.N, wl.tile_m, wl.tile_n, self.xs, self.ws)
+
+    def build_map(self):
+        wl = self.wl
+        mb.moe_build_task_map(self.ids, wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N, self.tmap)
+
+    def gemm(self, i: int = 0):
+        mb.moe_grouped_gemm(self.X, self.W[i % len(self.W)], self.ids, self.tmap, self.Y, self.desc)
+
+    def time(self, steps: int, warmup: int):
+        """Returns (wall ms per step, mean GEMM-kernel ms, mean map-build ms) over `steps` steps."""
+        for i in range(warmup):
+            self.build_map()
+            self.gemm(i)
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            ev[i][0].record()
+            self.build_map()
+            ev[i][1].record()
+            self.gemm(i)
+            ev[i][2].record()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+        gemm_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+        map_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+        return wall_ms, gemm_ms, map_ms
+
+    def report(self, steps: int, warmup: int) -> dict:
+        wl = self.wl
+        wall_ms, gemm_ms, map_ms = self.time(steps, warmup)
+        peak_t = PEAK_FP8_TFLOPS if wl.dtype == "fp8" else PEAK_BF16_TFLOPS
+        abytes = algorithmic_bytes(wl, self.ids_cpu)
+        tf_step = wl.flops / (wall_ms * 1e-3) / 1e12
+        tf_gemm = wl.flops / (gemm_ms * 1e-3) / 1e12
+        gbs = abytes / (gemm_ms * 1e-3) / 1e9
+        ideal_mfma = wl.flops / (peak_t * 1e12)
+        ideal_hbm = abytes / (PEAK_HBM_GBS * 1e9)
+        bound = "mfma" if ideal_mfma >= ideal_hbm else "hbm"
+        return dict(workload=f"{wl.name}_T{wl.T}", dtype=wl.dtype, T=wl.T, E=wl.E, k=wl.k, K=wl.K, N=wl.N,
+                    tile=[wl.tile_m, wl.tile_n], ms_per_step=round(wall_ms, 4), gemm_ms=round(gemm_ms, 4),
+                    map_ms=round(map_ms, 4), tflops_step=round(tf_step, 2), tflops_gemm=round(tf_gemm, 2),
+                    frac_mfma=round(tf_gemm / peak_t, 4), gbs_gemm=round(gbs, 1),
+                    frac_hbm=round(gbs / PEAK_HBM_GBS, 4), bound=bound, alg_bytes=abytes, flops=wl.flops)
+
+
+def cpu_baseline(pt: Point, target_s: float = 15.0) -> dict:
+    """Time the CPU oracle (as it stands) on a bounded sample of complete routed rows of the same
+    workload, and check the GPU output on those rows against it."""
+    import oracle
+    from tests import helpers as H
+    wl = pt.wl
+    rng = np.random.default_rng(0)
+    Xh = wk.bits(pt.X)
+    ids_h = pt.ids_cpu.numpy()
+    # the oracle reads one expert's weights per row: copy to the host only the experts sampled
+    n_probe = 8
+    rows = rng.choice(wl.R, size=min(wl.R, 512), replace=False).astype(np.int32)
+    experts = sorted(set(int(ids_h.reshape(-1)[r]) for r in rows))
+    remap = {e: i for i, e in enumerate(experts)}
+    Wh = np.stack([wk.bits(pt.W[0][e]) for e in experts])
+    ids_local = np.full(wl.R, 0, dtype=np.int32)
+    for r in rows:
+        ids_local[r] = remap[int(ids_h.reshape(-1)[r])]
+    ids_local = ids_local.reshape(wl.T, wl.k)
+
+    def run(rsel):
+        t0 = time.perf_counter()
+        if wl.dtype == "fp8":
+            res = oracle.grouped_gemm_fp8(Xh, Wh, pt.xs.cpu().numpy(), pt.ws.cpu().numpy()[experts], ids_local, rows=rsel)
+        else:
+            res = oracle.grouped_gemm_bf16(Xh, Wh, ids_local, rows=rsel)
+        return res, time.perf_counter() - t0
+
+    res, dt = run(rows[:n_probe])
+    per_row = dt / n_probe
+    n = int(max(n_probe, min(len(rows), target_s / max(per_row, 1e-9))))
+    res, dt = run(rows[:n])
+    flops = 2.0 * n * wl.K * wl.N
+    # parity of the GPU result on the same rows
+    got = H.y_bits(pt.Y[torch.from_numpy(rows[:n].astype(np.int64)).to(pt.dev)])
+    ulp = H.ulp_distance(got, res.Ybf)
+    err = np.abs(H.bf16_bits_to_f64(got) - res.Y64)
+    return dict(value=round(flops / dt / 1e12, 6), unit="TFLOP/s", cores=oracle.num_threads(), kind="oracle",
+                sample=f"{n} complete routed rows of {wl.name}_T{wl.T} ({flops / 1e9:.1f} GFLOP, {dt:.1f} s)",
+                gpu_vs_oracle=dict(rows=n, max_abs_err=float(err.max()), frac_bit_equal=float((ulp == 0).mean())))
+
+
+HEADLINE = "mixtral_up_T4096"
+
+
+def all_points():
+    pts = [wk.tiny(64)]
+    pts += [wk.mixtral_up(T) for T in (16, 256, 4096)]
+    pts += [wk.mixtral_down_zipf(T) for T in (256, 4096)]
+    pts += [wk.fine_grained(T) for T in (128, 2048, 8192)]
+    pts += [wk.decode_fp8(T) for T in (1, 8, 32)]
+    pts += [wk.paper_eval(s) for s in ("balanced", "best", "worst")]
+    return pts
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--points", default="none", help="'all', 'none', or a comma list of workload names")
+    ap.add_argument("--tile", default="", help="override tile_m,tile_n of the headline workload")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (--gpus 1); no multi-GPU path exists.", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    mb.lib()
+    torch.cuda.set_device(0)
+
+    wl = wk.mixtral_up(4096)
+    if args.tile:
+        tm, tn = (int(v) for v in args.tile.split(","))
+        wl = wl.with_T(wl.T, tile_m=tm, tile_n=tn)
+    pt = Point(wl)
+    head = pt.report(args.steps, args.warmup)
+    out = {
+        "metric": "expert-GEMM TFLOP/s (useful FLOPs 2*T*k*K*N, task-map build + grouped GEMM per step)",
+        "value": head["tflops_step"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": HEADLINE, "T": wl.T, "E": wl.E, "top_k": wl.k, "K": wl.K, "N": wl.N,
+                   "tile_m": wl.tile_m, "tile_n": wl.tile_n, "routing": wl.routing},
+        "roofline": {"bound": "mfma", "achieved": head["tflops_gemm"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(head["tflops_gemm"] / PEAK_BF16_TFLOPS, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(HEADLINE), "kernel": "moe_gemm_kernel",
+                     "kernel_ms": head["gemm_ms"], "map_ms": head["map_ms"], "alg_bytes": head["alg_bytes"]},
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(pt)
+    del pt
+    torch.cuda.empty_cache()
+
+    if args.points != "none":
+        want = None if args.points == "all" else set(args.points.split(","))
+        points = []
+        for w in all_points():
+            name = f"{w.name}_T{w.T}"
+            if want is not None and name not in want and w.name not in want:
+                continue
+            if name == HEADLINE and not args.tile:
+                points.append(head)
+                continue
+            copies = 1
+            if w.dtype == "fp8":  # working set comparable to the 256 MB last-level cache: rotate copies
+                copies = max(4, int(1.5e9 // (w.E * w.K * w.N)) + 1)
+            p = Point(w, copies)
+            points.append(p.report(max(10, args.steps // 2), max(3, args.warmup // 2)))
+            del p
+            torch.cuda.empty_cache()
+        out["points"] = points
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
