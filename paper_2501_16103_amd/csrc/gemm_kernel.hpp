@@ -28,6 +28,8 @@ typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 typedef __attribute__((ext_vector_type(4))) short s16x4_t;
 typedef __attribute__((ext_vector_type(8))) short s16x8_t;
 typedef __attribute__((ext_vector_type(2))) int i32x2_t;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2_t;
 
 #define MOE_LDS(T) __attribute__((address_space(3))) T
 
@@ -141,25 +143,25 @@ __global__ __launch_bounds__(C::NT) void moe_gemm_kernel(GemmArgs a) {
     const size_t w_it_stride = (size_t)(NT / C::CPRW) * w_row_bytes;
     const size_t w_kt_stride = (size_t)BK * w_row_bytes;
 
-    uint4 ra[C::A_IT], rb[C::B_IT];
+    u32x4_t ra[C::A_IT], rb[C::B_IT];
     auto gload = [&](int kt) {
 #pragma unroll
         for (int i = 0; i < C::A_IT; ++i)
             if (C::A_CHUNKS % NT == 0 || tid + i * NT < C::A_CHUNKS)
-                ra[i] = *reinterpret_cast<const uint4*>(Xb + x_off[i] + (size_t)kt * (BK * ES));
+                ra[i] = *reinterpret_cast<const u32x4_t*>(Xb + x_off[i] + (size_t)kt * (BK * ES));
 #pragma unroll
-        for (int i = 0; i < C::B_IT; ++i) rb[i] = *reinterpret_cast<const uint4*>(wp + kt * w_kt_stride + i * w_it_stride);
+        for (int i = 0; i < C::B_IT; ++i) rb[i] = *reinterpret_cast<const u32x4_t*>(wp + kt * w_kt_stride + i * w_it_stride);
     };
     auto lstore = [&](int stage) {
         char* xs = smem + stage * C::STAGE_BYTES;
         char* ws = xs + C::XS_BYTES;
 #pragma unroll
         for (int i = 0; i < C::A_IT; ++i)
-            if (C::A_CHUNKS % NT == 0 || tid + i * NT < C::A_CHUNKS) *reinterpret_cast<uint4*>(xs + x_lds[i]) = ra[i];
+            if (C::A_CHUNKS % NT == 0 || tid + i * NT < C::A_CHUNKS) *reinterpret_cast<u32x4_t*>(xs + x_lds[i]) = ra[i];
 #pragma unroll
         for (int i = 0; i < C::B_IT; ++i) {
             const int krow = krow0 + i * (NT / C::CPRW);
-            *reinterpret_cast<uint4*>(ws + krow * C::WROW + ((wc ^ swz_w<C>(krow)) << 4)) = rb[i];
+            *reinterpret_cast<u32x4_t*>(ws + krow * C::WROW + ((wc ^ swz_w<C>(krow)) << 4)) = rb[i];
         }
     };
 
@@ -279,10 +281,10 @@ __global__ __launch_bounds__(C::NT) void moe_gemm_kernel(GemmArgs a) {
 #pragma unroll
                 for (int jq = 0; jq < 4; ++jq) {
                     const int n_local = wn * C::WTN + nb * 32 + 8 * jq + 4 * (lane >> 5);
-                    uint2 v;
+                    u32x2_t v;
                     v.x = pack_bf16(acc[nb][mb][4 * jq + 0], acc[nb][mb][4 * jq + 1]);
                     v.y = pack_bf16(acc[nb][mb][4 * jq + 2], acc[nb][mb][4 * jq + 3]);
-                    *reinterpret_cast<uint2*>(yrow + n_local * 2) = v;
+                    *reinterpret_cast<u32x2_t*>(yrow + n_local * 2) = v;
                 }
             } else {
                 const int n_local = wn * C::WTN + nb * 16 + 4 * g;
@@ -291,10 +293,10 @@ __global__ __launch_bounds__(C::NT) void moe_gemm_kernel(GemmArgs a) {
                     v0 = (v0 * scale) * wscale; v1 = (v1 * scale) * wscale;
                     v2 = (v2 * scale) * wscale; v3 = (v3 * scale) * wscale;
                 }
-                uint2 v;
+                u32x2_t v;
                 v.x = pack_bf16(v0, v1);
                 v.y = pack_bf16(v2, v3);
-                *reinterpret_cast<uint2*>(yrow + n_local * 2) = v;
+                *reinterpret_cast<u32x2_t*>(yrow + n_local * 2) = v;
             }
         }
     }
