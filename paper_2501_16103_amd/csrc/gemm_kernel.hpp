@@ -3,8 +3,13 @@
 // One launch covers every expert (Alg. 3/4): a workgroup turns its block index
 // into (expert, m-tile, n-tile) with the wavefront vote of Alg. 2, gathers the
 // tile's token rows through the expert's token index array (Sec. 4.3), and runs
-// a double-buffered LDS pipeline feeding MFMA (the CDNA4 counterpart of the
-// pipeline of Sec. 4.4).  The contraction is computed transposed: the weight
+// an LDS pipeline feeding MFMA (the CDNA4 counterpart of the pipeline of
+// Sec. 4.4).  Two kernels share this layout:
+//   moe_gemm_pipe_kernel  tiles of >= 32 token rows, bf16: global->LDS DMA ring
+//                         (no register staging), hand-placed MFMA / LDS-read /
+//                         DMA interleave, per-wavefront skipping of all-padding
+//                         32-row blocks in an expert's last m-tile.
+//   moe_gemm_kernel       16-row tiles and fp8: register-staged double buffer.  The contraction is computed transposed: the weight
 // tile is the MFMA "A" operand (accumulator rows = output columns n) and the
 // token tile the "B" operand (accumulator columns = token rows m), so that each
 // lane ends up with runs of 4 consecutive n for one token row.
@@ -301,5 +306,251 @@ __global__ __launch_bounds__(C::NT) void moe_gemm_kernel(GemmArgs a) {
         }
     }
 }
+
+
+// ---------------------------------------------------------------------------
+// Pipelined kernel (tile_m >= 32, bf16)
+// ---------------------------------------------------------------------------
+
+// The compiler may not move anything across this point.
+#define MOE_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// Global -> LDS copy of 64 lanes x 16 bytes without passing through VGPRs: lane L's 16 bytes land at
+// lds_addr + 16*L (lds_addr is wavefront-uniform and goes through M0).  The instruction counts in
+// vmcnt like any load; the compiler does not see it, so every wait on it below is explicit.
+__device__ __forceinline__ void dma16(uint32_t voff, const void* sbase, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_addr)
+                 : "memory");
+}
+// s_waitcnt vmcnt(N) only (expcnt / lgkmcnt fields left at "no wait").
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
+}
+
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int NS_>
+struct PipeCfg {
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, NS = NS_;
+    static constexpr bool FP8 = false;
+    static constexpr int ES = 2;
+    static constexpr int NT = 64 * WM * WN;
+    static constexpr int WTM = BM / WM, WTN = BN / WN;
+    static constexpr int MF = 32;
+    static constexpr int NBW = WTN / 32, MBW = WTM / 32;
+    static constexpr int XROW = BK * ES, CPR = XROW / 16;
+    static constexpr int WROW = BN * ES, CPRW = WROW / 16;
+    static constexpr int XS_BYTES = BM * XROW, WS_BYTES = BK * WROW;
+    static constexpr int STAGE_BYTES = XS_BYTES + WS_BYTES;
+    static constexpr int LDS_BYTES = NS * STAGE_BYTES + BM * 4;
+    static_assert(XROW == 64 || XROW == 128, "token tile rows are 64 or 128 bytes");
+    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile");
+    static_assert(WROW <= 1024 && CPRW >= 16, "weight tile row");
+    static_assert(XS_BYTES % 1024 == 0 && WS_BYTES % 1024 == 0, "DMA granularity");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS");
+};
+
+template <class C>
+__device__ __forceinline__ int pswz_x(int row) {
+    return C::CPR == 8 ? ((row >> 1) & 7) : ((row >> 2) & 3);
+}
+template <class C>
+__device__ __forceinline__ int pswz_w(int krow) {
+    return ((krow & 3) << 2) & (C::CPRW - 1);
+}
+
+// Main loop, per k-tile kt held in ring stage `cur` (NS stages of [token tile | weight tile]):
+//   k-steps 0 .. KSTEPS-2 : MFMA of the step, interleaved one-for-one with the LDS reads of the next step
+//   wait for tile kt+1's DMA, workgroup barrier  (every wavefront has now read all of stage `cur`)
+//   last k-step           : its MFMAs, interleaved with the first LDS reads of tile kt+1 and with the DMA
+//                           instructions that refill stage `cur` with tile kt+NS
+// so neither the barrier nor the DMA issue leaves the MFMA pipe without queued work.
+template <class C>
+__global__ __launch_bounds__(C::NT) void moe_gemm_pipe_kernel(GemmArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr int BM = C::BM, BN = C::BN, BK = C::BK, ES = C::ES, NT = C::NT, NW = NT / 64, NS = C::NS;
+    const int32_t* __restrict__ map = a.map;
+    const int total = map[MOE_HDR_TOTAL_TILES];
+    const bool hdr_ok = map[MOE_HDR_MAGIC] == MOE_MAP_MAGIC && map[MOE_HDR_T] == a.T && map[MOE_HDR_K_TOP] == a.k &&
+                        map[MOE_HDR_E] == a.E && map[MOE_HDR_N] == a.N && map[MOE_HDR_TILE_M] == BM &&
+                        map[MOE_HDR_TILE_N] == BN && map[MOE_HDR_STATUS] == 0;
+    if (!hdr_ok) return;
+    const int per_xcd = (total + 7) >> 3;
+    const int slot = blockIdx.x >> 3;
+    if (slot >= per_xcd) return;
+    const int B = (blockIdx.x & 7) * per_xcd + slot;
+    if (B >= total) return;
+    const MapLayout L = map_layout(a.E);
+    const TileCoord tc = decode_block(map, L, BM, B);
+    const int n0 = tc.n_tile * BN;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / C::WN, wn = wave % C::WN;
+
+    int* s_row = reinterpret_cast<int*>(smem + NS * C::STAGE_BYTES);
+    for (int i = tid; i < BM; i += NT) s_row[i] = i < tc.rows ? map[L.off_rows + tc.row_base + i] : -1;
+    __syncthreads();
+
+    // ---- DMA geometry: one wave instruction moves 64 x 16 B = 1 KiB, linear in LDS
+    constexpr int XI_TOT = C::XS_BYTES / 1024, WI_TOT = C::WS_BYTES / 1024;
+    static_assert(XI_TOT % NW == 0 && WI_TOT % NW == 0, "every wave issues the same number of DMA instructions");
+    constexpr int XI = XI_TOT / NW, WI = WI_TOT / NW, ND = XI + WI;
+    constexpr int XROWS_PER_INST = 1024 / C::XROW, WROWS_PER_INST = 1024 / C::WROW;
+    uint32_t d_off[ND];
+#pragma unroll
+    for (int j = 0; j < XI; ++j) {
+        const int inst = j * NW + wave;
+        const int row = inst * XROWS_PER_INST + lane / C::CPR, pos = lane % C::CPR;
+        int r = s_row[row];
+        if (r < 0) r = s_row[0];
+        d_off[j] = (uint32_t)(r / a.k) * (uint32_t)(a.K * ES) + ((pos ^ pswz_x<C>(row)) << 4);
+    }
+    const uint32_t w_row_bytes = (uint32_t)a.N * ES;
+#pragma unroll
+    for (int j = 0; j < WI; ++j) {
+        const int inst = j * NW + wave;
+        const int krow = inst * WROWS_PER_INST + lane / C::CPRW, pos = lane % C::CPRW;
+        d_off[XI + j] = (uint32_t)krow * w_row_bytes + ((pos ^ pswz_w<C>(krow)) << 4);
+    }
+    const char* Xb = static_cast<const char*>(a.X);
+    const char* Wt = static_cast<const char*>(a.W) + ((size_t)tc.e * a.K * a.N + n0) * ES;
+    const size_t w_kt_stride = (size_t)BK * w_row_bytes;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(MOE_LDS(char)*)smem;
+
+    auto dma_one = [&](int d, int kt, int stage) {
+        const uint32_t sb = lds0 + stage * C::STAGE_BYTES;
+        if (d < XI) dma16(d_off[d], Xb + (size_t)kt * (BK * ES), sb + (d * NW + wave) * 1024);
+        else dma16(d_off[d], Wt + (size_t)kt * w_kt_stride, sb + C::XS_BYTES + ((d - XI) * NW + wave) * 1024);
+    };
+
+    f32x16_t acc[C::NBW][C::MBW];
+#pragma unroll
+    for (int nb = 0; nb < C::NBW; ++nb)
+#pragma unroll
+        for (int mb = 0; mb < C::MBW; ++mb)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc[nb][mb][j] = 0.f;
+
+    const int g = lane >> 4, li = lane & 15;
+    int mb_live = (tc.rows - wm * C::WTM + 31) / 32;
+    mb_live = mb_live < 0 ? 0 : (mb_live > C::MBW ? C::MBW : mb_live);
+
+    constexpr int KSTEPS = BK / 16;
+    constexpr int NREADS = 2 * C::NBW + C::MBW, NM = C::NBW * C::MBW;
+    s16x4_t wlo[2][C::NBW], whi[2][C::NBW];
+    bf16x8_t xf[2][C::MBW];
+    int w_rd[C::NBW], x_rd[C::MBW];
+    const int kr0 = 8 * (g >> 1) + (li >> 2);
+#pragma unroll
+    for (int nb = 0; nb < C::NBW; ++nb) {
+        const int ncol = wn * C::WTN + nb * 32 + 16 * (g & 1) + 4 * (li & 3);
+        const int c = ncol >> 3, within = (ncol & 7) * 2;
+        w_rd[nb] = kr0 * C::WROW + ((c ^ pswz_w<C>(kr0)) << 4) + within;
+    }
+#pragma unroll
+    for (int mb = 0; mb < C::MBW; ++mb) x_rd[mb] = (wm * C::WTM + mb * 32 + (lane & 31)) * C::XROW;
+
+    // read order follows first use by the MFMA sequence (mb outer, nb inner): X block 0, all W halves, X blocks 1..
+    auto read_one = [&](int r, int stage, int kk, int buf, bool tail) {
+        const char* xs = smem + stage * C::STAGE_BYTES;
+        const char* ws = xs + C::XS_BYTES;
+        if (r >= 1 && r <= 2 * C::NBW) {
+            const int nb = (r - 1) >> 1, half = (r - 1) & 1;
+            const char* p = ws + w_rd[nb] + (kk * 16 + half * 4) * C::WROW;
+            const s16x4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((MOE_LDS(s16x4_t)*)(p));
+            if (half) whi[buf][nb] = v; else wlo[buf][nb] = v;
+        } else {
+            const int mb = r == 0 ? 0 : r - 2 * C::NBW;
+            if (tail && mb >= mb_live) return;
+            const int row = wm * C::WTM + mb * 32 + (lane & 31);
+            const int c = kk * 2 + (lane >> 5);
+            xf[buf][mb] = *reinterpret_cast<const bf16x8_t*>(xs + x_rd[mb] + ((c ^ pswz_x<C>(row)) << 4));
+        }
+    };
+    auto mfma_one = [&](int i, int buf, bool tail) {
+        const int mb = i / C::NBW, nb = i % C::NBW;
+        if (tail && mb >= mb_live) return;
+        const bf16x8_t wf = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(wlo[buf][nb], whi[buf][nb], 0, 1, 2, 3, 4, 5, 6, 7));
+        acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf[buf][mb], acc[nb][mb], 0, 0, 0);
+    };
+
+    const int KT = a.K / BK;
+    // ---- prologue: fill the ring, wait for tile 0, first fragments into registers
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        if (s < KT) {
+#pragma unroll
+            for (int d = 0; d < ND; ++d) dma_one(d, s, s);
+        }
+    }
+    if (NS <= KT) wait_vmcnt<(NS - 1) * ND>(); else wait_vmcnt<0>();
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < NREADS; ++r) read_one(r, 0, 0, 0, false);
+
+    auto main_loop = [&](auto tail_tag) {
+        constexpr bool TAIL = decltype(tail_tag)::value;
+        int cur = 0;
+        auto iteration = [&](int kt, auto steady_tag) {
+            constexpr bool STEADY = decltype(steady_tag)::value;  // kt + NS < KT: every fetch below is in range
+            const int nxt = cur + 1 == NS ? 0 : cur + 1;
+#pragma unroll
+            for (int kk = 0; kk < KSTEPS - 1; ++kk) {
+#pragma unroll
+                for (int i = 0; i < NM; ++i) {
+                    mfma_one(i, kk & 1, TAIL);
+#pragma unroll
+                    for (int r = i * NREADS / NM; r < (i + 1) * NREADS / NM; ++r) read_one(r, cur, kk + 1, (kk + 1) & 1, TAIL);
+                    MOE_SCHED_FENCE();
+                }
+            }
+            // the next tile must have landed; the NS-2 tiles behind it may still be in flight
+            if (STEADY || kt + NS - 1 < KT) wait_vmcnt<(NS - 2) * ND>(); else wait_vmcnt<0>();
+            __syncthreads();
+            MOE_SCHED_FENCE();
+#pragma unroll
+            for (int i = 0; i < NM; ++i) {
+                mfma_one(i, (KSTEPS - 1) & 1, TAIL);
+                if (STEADY || kt + 1 < KT) {
+#pragma unroll
+                    for (int r = i * NREADS / NM; r < (i + 1) * NREADS / NM; ++r) read_one(r, nxt, 0, KSTEPS & 1, TAIL);
+                }
+                if (STEADY || kt + NS < KT) {
+#pragma unroll
+                    for (int d = i * ND / NM; d < (i + 1) * ND / NM; ++d) dma_one(d, kt + NS, cur);
+                }
+                MOE_SCHED_FENCE();
+            }
+            cur = nxt;
+        };
+        int kt = 0;
+        for (; kt + NS < KT; ++kt) iteration(kt, std::true_type{});
+        for (; kt < KT; ++kt) iteration(kt, std::false_type{});
+    };
+    if (mb_live == C::MBW) main_loop(std::false_type{}); else main_loop(std::true_type{});
+    wait_vmcnt<0>();
+
+    char* Yb = static_cast<char*>(a.Y);
+    const size_t y_row_bytes = (size_t)a.N * 2;
+#pragma unroll
+    for (int mb = 0; mb < C::MBW; ++mb) {
+        const int m_local = wm * C::WTM + mb * 32 + (lane & 31);
+        const int r = s_row[m_local];
+        if (r < 0) continue;
+        char* yrow = Yb + (size_t)r * y_row_bytes + (size_t)n0 * 2;
+#pragma unroll
+        for (int nb = 0; nb < C::NBW; ++nb) {
+#pragma unroll
+            for (int jq = 0; jq < 4; ++jq) {
+                const int n_local = wn * C::WTN + nb * 32 + 8 * jq + 4 * (lane >> 5);
+                u32x2_t v;
+                v.x = pack_bf16(acc[nb][mb][4 * jq + 0], acc[nb][mb][4 * jq + 1]);
+                v.y = pack_bf16(acc[nb][mb][4 * jq + 2], acc[nb][mb][4 * jq + 3]);
+                *reinterpret_cast<u32x2_t*>(yrow + n_local * 2) = v;
+            }
+        }
+    }
+}
+
 
 }  // namespace moe

@@ -28,6 +28,19 @@ int nchunks_for(int64_t R) { return (int)((R + kChunkRows - 1) / kChunkRows); }
 typedef int (*gemm_launch_fn)(const GemmArgs&, int64_t grid, hipStream_t);
 
 template <class C>
+int launch_pipe(const GemmArgs& a, int64_t grid, hipStream_t s) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&moe_gemm_pipe_kernel<C>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES) != hipSuccess)
+            return MOE_ERR_HIP;
+        attr_set = true;
+    }
+    moe_gemm_pipe_kernel<C><<<dim3((unsigned)grid), dim3(C::NT), C::LDS_BYTES, s>>>(a);
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
+template <class C>
 int launch_gemm(const GemmArgs& a, int64_t grid, hipStream_t s) {
     static bool attr_set = false;
     if (!attr_set) {
@@ -45,14 +58,15 @@ struct GemmVariant {
     gemm_launch_fn fn;
 };
 
-//                    BM   BN   BK  WM WN  FP8
-using Bf_256x256 = GemmCfg<256, 256, 64, 2, 2, false>;
-using Bf_128x256 = GemmCfg<128, 256, 64, 2, 2, false>;
-using Bf_128x128 = GemmCfg<128, 128, 64, 2, 2, false>;
-using Bf_64x256 = GemmCfg<64, 256, 64, 1, 4, false>;
-using Bf_64x128 = GemmCfg<64, 128, 64, 1, 4, false>;
-using Bf_32x256 = GemmCfg<32, 256, 64, 1, 4, false>;
-using Bf_32x128 = GemmCfg<32, 128, 64, 1, 4, false>;
+// Pipelined bf16 kernels:  BM   BN   BK  WM WN  ring stages
+using Pb_256x256 = PipeCfg<256, 256, 64, 2, 4, 2>;
+using Pb_128x256 = PipeCfg<128, 256, 64, 1, 4, 3>;
+using Pb_128x128 = PipeCfg<128, 128, 64, 2, 2, 4>;
+using Pb_64x256 = PipeCfg<64, 256, 64, 1, 4, 3>;
+using Pb_64x128 = PipeCfg<64, 128, 64, 1, 4, 4>;
+using Pb_32x256 = PipeCfg<32, 256, 64, 1, 4, 4>;
+using Pb_32x128 = PipeCfg<32, 128, 64, 1, 4, 6>;
+// Register-staged kernels (16-row tiles, fp8):  BM  BN   BK  WM WN  FP8
 using Bf_16x256 = GemmCfg<16, 256, 64, 1, 4, false>;
 using Bf_16x128 = GemmCfg<16, 128, 64, 1, 4, false>;
 using F8_16x256 = GemmCfg<16, 256, 128, 1, 4, true>;
@@ -61,13 +75,13 @@ using F8_16x64 = GemmCfg<16, 64, 128, 1, 4, true>;
 using F8_32x128 = GemmCfg<32, 128, 128, 1, 4, true>;
 
 const GemmVariant kVariants[] = {
-    {MOE_DTYPE_BF16, 256, 256, 64, &launch_gemm<Bf_256x256>},
-    {MOE_DTYPE_BF16, 128, 256, 64, &launch_gemm<Bf_128x256>},
-    {MOE_DTYPE_BF16, 128, 128, 64, &launch_gemm<Bf_128x128>},
-    {MOE_DTYPE_BF16, 64, 256, 64, &launch_gemm<Bf_64x256>},
-    {MOE_DTYPE_BF16, 64, 128, 64, &launch_gemm<Bf_64x128>},
-    {MOE_DTYPE_BF16, 32, 256, 64, &launch_gemm<Bf_32x256>},
-    {MOE_DTYPE_BF16, 32, 128, 64, &launch_gemm<Bf_32x128>},
+    {MOE_DTYPE_BF16, 256, 256, 64, &launch_pipe<Pb_256x256>},
+    {MOE_DTYPE_BF16, 128, 256, 64, &launch_pipe<Pb_128x256>},
+    {MOE_DTYPE_BF16, 128, 128, 64, &launch_pipe<Pb_128x128>},
+    {MOE_DTYPE_BF16, 64, 256, 64, &launch_pipe<Pb_64x256>},
+    {MOE_DTYPE_BF16, 64, 128, 64, &launch_pipe<Pb_64x128>},
+    {MOE_DTYPE_BF16, 32, 256, 64, &launch_pipe<Pb_32x256>},
+    {MOE_DTYPE_BF16, 32, 128, 64, &launch_pipe<Pb_32x128>},
     {MOE_DTYPE_BF16, 16, 256, 64, &launch_gemm<Bf_16x256>},
     {MOE_DTYPE_BF16, 16, 128, 64, &launch_gemm<Bf_16x128>},
     {MOE_DTYPE_FP8_E4M3, 16, 256, 128, &launch_gemm<F8_16x256>},

@@ -70,18 +70,18 @@ def tiny(T: int = 64) -> Workload:
 
 
 def mixtral_up(T: int) -> Workload:
-    tm = 256 if T >= 2048 else (64 if T >= 256 else 16)
-    return Workload("mixtral_up", T, 8, 2, 4096, 28672, "bf16", "gauss_topk", tm, 256 if tm == 256 else 128)
+    tm = 256 if T >= 2048 else (128 if T >= 256 else 16)
+    return Workload("mixtral_up", T, 8, 2, 4096, 28672, "bf16", "gauss_topk", tm, 256)
 
 
 def mixtral_down_zipf(T: int) -> Workload:
     tm = 256 if T >= 2048 else 64
-    return Workload("mixtral_down_zipf", T, 8, 2, 14336, 4096, "bf16", "zipf", tm, 256 if tm == 256 else 128)
+    return Workload("mixtral_down_zipf", T, 8, 2, 14336, 4096, "bf16", "zipf", tm, 256)
 
 
 def fine_grained(T: int) -> Workload:
-    tm = 256 if T >= 8192 else (64 if T >= 2048 else 16)
-    return Workload("fine_grained", T, 256, 8, 7168, 4096, "bf16", "gauss_topk", tm, 256 if tm == 256 else 128)
+    tm = 256 if T >= 8192 else (128 if T >= 2048 else 16)
+    return Workload("fine_grained", T, 256, 8, 7168, 4096, "bf16", "gauss_topk", tm, 256)
 
 
 def decode_fp8(T: int) -> Workload:
