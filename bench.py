@@ -176,6 +176,8 @@ def main():
     ap.add_argument("--points", default="none", help="'all', 'none', or a comma list of workload names")
     ap.add_argument("--tile", default="", help="override tile_m,tile_n of the headline workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (a kernel of known traffic to scale profiler byte counters by)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (--gpus 1); no multi-GPU path exists.", file=sys.stderr)
@@ -204,6 +206,13 @@ def main():
                      "traffic": MEASURED_TRAFFIC_BYTES.get(HEADLINE), "kernel": "moe_gemm_kernel",
                      "kernel_ms": head["gemm_ms"], "map_ms": head["map_ms"], "alg_bytes": head["alg_bytes"]},
     }
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(pt)
     del pt

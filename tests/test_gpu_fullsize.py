@@ -1,0 +1,164 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The oracle cannot compute these problems whole (1-4 TFLOP), so: the task map is compared whole
+(bit-exact), and Y is compared on samples the oracle computes one by one -- a few elements in
+EVERY tile of the map (its first and last valid row, random columns), plus complete rows that
+straddle tile boundaries -- and with properties that hold at any size (every element written,
+nothing outside Y touched).
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2501_16103_amd import binding as mb
+from paper_2501_16103_amd import workloads as wk
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+POISON = 0x7FC1
+
+
+def _gather_columns(W, experts, cols):
+    """W [E,K,N] on the device -> host array [S, K] of the columns W[experts[i], :, cols[i]] (storage bits)."""
+    e = torch.as_tensor(experts, dtype=torch.long, device=W.device)
+    n = torch.as_tensor(cols, dtype=torch.long, device=W.device)
+    out = []
+    for lo in range(0, len(e), 4096):
+        out.append(W[e[lo:lo + 4096], :, n[lo:lo + 4096]].contiguous().cpu())
+    return torch.cat(out)
+
+
+def _run_full(wl, dev):
+    ids = wk.make_routing(wl)
+    if wl.dtype == "fp8":
+        X, xs = wk.make_x(wl, dev)
+        W, ws = wk.make_w(wl, dev)
+    else:
+        X, W, xs, ws = wk.make_x(wl, dev), wk.make_w(wl, dev), None, None
+    pad = 2
+    buf = torch.empty((wl.R + 2 * pad, wl.N), dtype=torch.int16, device=dev)
+    buf.fill_(POISON)
+    Y = buf[pad: pad + wl.R]
+    tmap = mb.alloc_task_map(wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N, dev)
+    mb.moe_build_task_map(ids.to(dev), wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N, tmap)
+    dt = mb.MOE_DTYPE_FP8_E4M3 if wl.dtype == "fp8" else mb.MOE_DTYPE_BF16
+    mb.moe_grouped_gemm(X, W, ids.to(dev), tmap, Y, mb.GemmDesc(dt, wl.T, wl.k, wl.E, wl.K, wl.N, wl.tile_m, wl.tile_n, xs, ws))
+    torch.cuda.synchronize()
+    assert mb.moe_task_map_status(tmap) == mb.MOE_OK
+    # properties that hold at any size
+    assert bool((buf[:pad] == POISON).all()) and bool((buf[pad + wl.R:] == POISON).all()), "wrote outside Y"
+    assert not bool((Y == POISON).any()), "some output was never written"
+    return ids, X, W, xs, ws, Y, tmap
+
+
+def _sample_points(tm, table, rng, per_tile):
+    """(r, n) samples: in every tile its first and last valid row at random columns, plus the tile's corners."""
+    rr, nn = [], []
+    for e, m_tile, n_tile, rows in table:
+        base = tm.offsets[e] + m_tile * tm.tile_m
+        n0 = n_tile * tm.tile_n
+        cand_rows = [0, rows - 1]
+        for i in range(per_tile):
+            lr = cand_rows[i % 2] if i < 2 else int(rng.integers(0, rows))
+            lc = (0 if i == 0 else tm.tile_n - 1) if i < 2 else int(rng.integers(0, tm.tile_n))
+            rr.append(int(tm.sorted_rows[base + lr]))
+            nn.append(n0 + lc)
+    return np.array(rr, np.int32), np.array(nn, np.int32)
+
+
+def _check_elements(oracle_mod, wl, ids, X, W, xs, ws, Y, rr, nn):
+    """Compare Y[rr, nn] with the oracle, element by element, through a compact stand-in problem:
+    sample i becomes token i with its own one-column expert, so the oracle does the same sums."""
+    flat = ids.numpy().reshape(-1)
+    toks = rr // wl.k
+    exps = flat[rr]
+    Xs = X[torch.as_tensor(toks, dtype=torch.long, device=X.device)].cpu()
+    Wc = _gather_columns(W, exps, nn)                      # [S, K]
+    S = len(rr)
+    ids_c = np.arange(S, dtype=np.int32).reshape(S, 1)
+    sel = np.arange(S, dtype=np.int32)
+    zero = np.zeros(S, dtype=np.int32)
+    if wl.dtype == "fp8":
+        xsc = xs.cpu().numpy()[toks]
+        wsc = ws.cpu().numpy()[exps]
+        want = oracle_mod.gemm_elements(Xs.numpy(), Wc.numpy().reshape(S, wl.K, 1), ids_c, 1, sel, zero, x_scale=xsc, w_scale=wsc)
+        Xf = Xs.view(torch.float8_e4m3fn).double().numpy()
+        Wf = Wc.view(torch.float8_e4m3fn).double().numpy()
+        sc = xsc.astype(np.float64) * wsc.astype(np.float64)
+        tol = H.tol_fp8(wl.K)
+    else:
+        want = oracle_mod.gemm_elements(wk.bits(Xs), wk.bits(Wc).reshape(S, wl.K, 1), ids_c, 1, sel, zero)
+        Xf, Wf, sc, tol = Xs.double().numpy(), Wc.double().numpy(), 1.0, H.tol_bf16(wl.K)
+    got_bits = H.y_bits(Y[torch.as_tensor(rr, dtype=torch.long, device=Y.device), torch.as_tensor(nn, dtype=torch.long, device=Y.device)])
+    got = H.bf16_bits_to_f64(got_bits)
+    err = np.abs(got - want)
+    scale = np.linalg.norm(Xf, axis=1) * np.linalg.norm(Wf, axis=1) * sc
+    assert np.all(err <= tol * scale), f"max err/scale {(err / scale).max():.3e} > {tol:.3e}"
+    A = (np.abs(Xf) * np.abs(Wf)).sum(axis=1) * sc
+    tight = 2.0 ** -8 * np.abs(want) * 1.001 + 1.01 * wl.K * 2.0 ** -24 * A + 1e-30
+    assert np.all(err <= tight), f"max err/tight {(err / tight).max():.3f}"
+    want_bits = np.array([oracle_mod.f64_to_bf16_rne(float(v)) for v in want], dtype=np.uint16)
+    assert (H.ulp_distance(got_bits, want_bits) == 0).mean() > 0.97
+
+
+FULL = [
+    # workload, samples per tile, complete rows
+    (wk.mixtral_up(4096), 8, 64),
+    (wk.mixtral_up(256), 8, 32),
+    (wk.mixtral_up(16), 8, 32),
+    (wk.mixtral_down_zipf(4096), 8, 64),
+    (wk.mixtral_down_zipf(256), 8, 32),
+    (wk.paper_eval("worst"), 8, 64),
+    (wk.decode_fp8(32), 8, 64),
+    (wk.decode_fp8(8), 8, 48),
+    (wk.decode_fp8(1), 8, 6),
+]
+
+
+@pytest.mark.parametrize("wl,per_tile,nrows", FULL, ids=lambda v: f"{v.name}_T{v.T}" if hasattr(v, "name") else str(v))
+def test_full_size_sampled(oracle_mod, wl, per_tile, nrows):
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(wl.T * 7 + wl.E)
+    ids, X, W, xs, ws, Y, tmap = _run_full(wl, dev)
+    # task map: whole and bit-exact
+    tm = oracle_mod.build_task_map(ids.numpy(), wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N)
+    want = H.expected_blob(tm)
+    np.testing.assert_array_equal(tmap.cpu().numpy()[: len(want)], want)
+    table = oracle_mod.full_table(tm.counts, wl.tile_m, wl.tile_n, wl.N)
+    assert len(table) == tm.total_tiles
+    # (a) samples in every tile
+    rr, nn = _sample_points(tm, table, rng, per_tile)
+    _check_elements(oracle_mod, wl, ids, X, W, xs, ws, Y, rr, nn)
+    # (b) complete rows: first / last row of expert segments and rows next to m-tile boundaries, then random
+    rows = []
+    for e in range(wl.E):
+        c = int(tm.counts[e])
+        if c == 0:
+            continue
+        o = int(tm.offsets[e])
+        for pos in (0, c - 1, min(c - 1, wl.tile_m - 1), min(c - 1, wl.tile_m)):
+            rows.append(int(tm.sorted_rows[o + pos]))
+    rows = list(dict.fromkeys(rows))
+    rng.shuffle(rows)
+    rows = rows[: nrows // 2] + rng.choice(wl.R, size=min(wl.R, nrows - min(len(rows), nrows // 2)), replace=False).tolist()
+    rows = np.array(list(dict.fromkeys(rows)), dtype=np.int32)
+    cols = rng.choice(wl.N, size=min(wl.N, 256), replace=False).astype(np.int32)
+    cols[:2] = (0, wl.N - 1)
+    rr = np.repeat(rows, len(cols))
+    nn = np.tile(cols, len(rows))
+    _check_elements(oracle_mod, wl, ids, X, W, xs, ws, Y, rr, nn)
+
+
+def test_fine_grained_full_size_sampled(oracle_mod):
+    """E=256, top-8, 15 GB of weights resident: T=2048 in the benchmark's tiling, 2 samples per tile."""
+    wl = wk.fine_grained(2048)
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(11)
+    ids, X, W, xs, ws, Y, tmap = _run_full(wl, dev)
+    tm = oracle_mod.build_task_map(ids.numpy(), wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N)
+    want = H.expected_blob(tm)
+    np.testing.assert_array_equal(tmap.cpu().numpy()[: len(want)], want)
+    table = oracle_mod.full_table(tm.counts, wl.tile_m, wl.tile_n, wl.N)
+    rr, nn = _sample_points(tm, table, rng, 2)
+    _check_elements(oracle_mod, wl, ids, X, W, xs, ws, Y, rr, nn)
