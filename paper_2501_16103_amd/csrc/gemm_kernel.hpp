@@ -309,7 +309,7 @@ __global__ __launch_bounds__(C::NT) void moe_gemm_kernel(GemmArgs a) {
 
 
 // ---------------------------------------------------------------------------
-// Pipelined kernel (tile_m >= 32, bf16)
+// Pipelined kernel (all tile shapes, bf16 and fp8)
 // ---------------------------------------------------------------------------
 
 // The compiler may not move anything across this point.
@@ -329,23 +329,30 @@ __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
 }
 
-template <int BM_, int BN_, int BK_, int WM_, int WN_, int NS_>
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int NS_, bool FP8_ = false>
 struct PipeCfg {
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, NS = NS_;
-    static constexpr bool FP8 = false;
-    static constexpr int ES = 2;
+    static constexpr bool FP8 = FP8_;
+    static constexpr int ES = FP8 ? 1 : 2;
     static constexpr int NT = 64 * WM * WN;
     static constexpr int WTM = BM / WM, WTN = BN / WN;
-    static constexpr int MF = 32;
-    static constexpr int NBW = WTN / 32, MBW = WTM / 32;
+    static constexpr int MF = (!FP8 && WTM >= 32) ? 32 : 16;   // MFMA block edge
+    static constexpr int KS = MF == 32 ? 16 : 32;              // k elements per MFMA
+    static constexpr int KSTEPS = BK / KS;
+    static constexpr int NBW = WTN / MF, MBW = WTM / MF;
+    static constexpr int ACC = MF == 32 ? 16 : 4;              // accumulator registers per block
     static constexpr int XROW = BK * ES, CPR = XROW / 16;
     static constexpr int WROW = BN * ES, CPRW = WROW / 16;
     static constexpr int XS_BYTES = BM * XROW, WS_BYTES = BK * WROW;
     static constexpr int STAGE_BYTES = XS_BYTES + WS_BYTES;
     static constexpr int LDS_BYTES = NS * STAGE_BYTES + BM * 4;
+    // LDS reads per k-step: weight fragments (two 4-k halves for bf16, one 8-k piece for fp8), token fragments
+    static constexpr int WREADS = NBW * (FP8 ? 1 : 2), NREADS = WREADS + MBW, NM = NBW * MBW;
+    // memory-bound tiles start the weight stream before the token rows are known
+    static constexpr bool EARLY_W = MF == 16;
     static_assert(XROW == 64 || XROW == 128, "token tile rows are 64 or 128 bytes");
-    static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile");
-    static_assert(WROW <= 1024 && CPRW >= 16, "weight tile row");
+    static_assert(WTM % MF == 0 && WTN % MF == 0 && KSTEPS >= 2 && BK % KS == 0, "wave tile");
+    static_assert(WROW <= 1024, "weight tile row");
     static_assert(XS_BYTES % 1024 == 0 && WS_BYTES % 1024 == 0, "DMA granularity");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS");
 };
@@ -356,19 +363,25 @@ __device__ __forceinline__ int pswz_x(int row) {
 }
 template <class C>
 __device__ __forceinline__ int pswz_w(int krow) {
-    return ((krow & 3) << 2) & (C::CPRW - 1);
+    int s;
+    if constexpr (C::FP8) s = C::CPRW >= 16 ? (krow & 15) : ((krow >> 1) & 7);
+    else if constexpr (C::MF == 32) s = (krow & 3) << 2;
+    else s = ((krow & 3) | ((krow >> 1) & 4)) << 1;
+    return s & (C::CPRW - 1);
 }
 
 // Main loop, per k-tile kt held in ring stage `cur` (NS stages of [token tile | weight tile]):
-//   k-steps 0 .. KSTEPS-2 : MFMA of the step, interleaved one-for-one with the LDS reads of the next step
+//   k-steps 0 .. KSTEPS-2 : MFMA of the step, interleaved with the LDS reads of the next step
 //   wait for tile kt+1's DMA, workgroup barrier  (every wavefront has now read all of stage `cur`)
 //   last k-step           : its MFMAs, interleaved with the first LDS reads of tile kt+1 and with the DMA
 //                           instructions that refill stage `cur` with tile kt+NS
-// so neither the barrier nor the DMA issue leaves the MFMA pipe without queued work.
+// so neither the barrier nor the DMA issue leaves the MFMA pipe without queued work, and NS-1 tiles of
+// weights per workgroup are in flight from HBM at any time.
 template <class C>
 __global__ __launch_bounds__(C::NT) void moe_gemm_pipe_kernel(GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    constexpr int BM = C::BM, BN = C::BN, BK = C::BK, ES = C::ES, NT = C::NT, NW = NT / 64, NS = C::NS;
+    constexpr int BM = C::BM, BN = C::BN, BK = C::BK, ES = C::ES, NT = C::NT, NW = NT / 64, NS = C::NS, MF = C::MF;
+    constexpr int KSTEPS = C::KSTEPS, NREADS = C::NREADS, NM = C::NM, WREADS = C::WREADS;
     const int32_t* __restrict__ map = a.map;
     const int total = map[MOE_HDR_TOTAL_TILES];
     const bool hdr_ok = map[MOE_HDR_MAGIC] == MOE_MAP_MAGIC && map[MOE_HDR_T] == a.T && map[MOE_HDR_K_TOP] == a.k &&
@@ -386,25 +399,15 @@ __global__ __launch_bounds__(C::NT) void moe_gemm_pipe_kernel(GemmArgs a) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / C::WN, wn = wave % C::WN;
-
-    int* s_row = reinterpret_cast<int*>(smem + NS * C::STAGE_BYTES);
-    for (int i = tid; i < BM; i += NT) s_row[i] = i < tc.rows ? map[L.off_rows + tc.row_base + i] : -1;
-    __syncthreads();
+    const int g = lane >> 4, li = lane & 15;
 
     // ---- DMA geometry: one wave instruction moves 64 x 16 B = 1 KiB, linear in LDS
     constexpr int XI_TOT = C::XS_BYTES / 1024, WI_TOT = C::WS_BYTES / 1024;
     static_assert(XI_TOT % NW == 0 && WI_TOT % NW == 0, "every wave issues the same number of DMA instructions");
     constexpr int XI = XI_TOT / NW, WI = WI_TOT / NW, ND = XI + WI;
     constexpr int XROWS_PER_INST = 1024 / C::XROW, WROWS_PER_INST = 1024 / C::WROW;
+    static_assert((NS - 1) * ND < 64, "vmcnt range");
     uint32_t d_off[ND];
-#pragma unroll
-    for (int j = 0; j < XI; ++j) {
-        const int inst = j * NW + wave;
-        const int row = inst * XROWS_PER_INST + lane / C::CPR, pos = lane % C::CPR;
-        int r = s_row[row];
-        if (r < 0) r = s_row[0];
-        d_off[j] = (uint32_t)(r / a.k) * (uint32_t)(a.K * ES) + ((pos ^ pswz_x<C>(row)) << 4);
-    }
     const uint32_t w_row_bytes = (uint32_t)a.N * ES;
 #pragma unroll
     for (int j = 0; j < WI; ++j) {
@@ -416,74 +419,128 @@ __global__ __launch_bounds__(C::NT) void moe_gemm_pipe_kernel(GemmArgs a) {
     const char* Wt = static_cast<const char*>(a.W) + ((size_t)tc.e * a.K * a.N + n0) * ES;
     const size_t w_kt_stride = (size_t)BK * w_row_bytes;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(MOE_LDS(char)*)smem;
+    const int KT = a.K / BK;
 
+    // d-th DMA instruction of this wave for k-tile kt: token rows first (d < XI), then weight rows
     auto dma_one = [&](int d, int kt, int stage) {
         const uint32_t sb = lds0 + stage * C::STAGE_BYTES;
         if (d < XI) dma16(d_off[d], Xb + (size_t)kt * (BK * ES), sb + (d * NW + wave) * 1024);
         else dma16(d_off[d], Wt + (size_t)kt * w_kt_stride, sb + C::XS_BYTES + ((d - XI) * NW + wave) * 1024);
     };
 
-    f32x16_t acc[C::NBW][C::MBW];
+    if (C::EARLY_W) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+            if (s < KT) {
+#pragma unroll
+                for (int d = XI; d < ND; ++d) dma_one(d, s, s);
+            }
+    }
+
+    int* s_row = reinterpret_cast<int*>(smem + NS * C::STAGE_BYTES);
+    for (int i = tid; i < BM; i += NT) s_row[i] = i < tc.rows ? map[L.off_rows + tc.row_base + i] : -1;
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < XI; ++j) {
+        const int inst = j * NW + wave;
+        const int row = inst * XROWS_PER_INST + lane / C::CPR, pos = lane % C::CPR;
+        int r = s_row[row];
+        if (r < 0) r = s_row[0];  // rows past the expert's count: fetch a valid row, never store it
+        d_off[j] = (uint32_t)(r / a.k) * (uint32_t)(a.K * ES) + ((pos ^ pswz_x<C>(row)) << 4);
+    }
+
+    using acc_t = typename std::conditional<MF == 32, f32x16_t, f32x4_t>::type;
+    acc_t acc[C::NBW][C::MBW];
 #pragma unroll
     for (int nb = 0; nb < C::NBW; ++nb)
 #pragma unroll
         for (int mb = 0; mb < C::MBW; ++mb)
 #pragma unroll
-            for (int j = 0; j < 16; ++j) acc[nb][mb][j] = 0.f;
+            for (int j = 0; j < C::ACC; ++j) acc[nb][mb][j] = 0.f;
 
-    const int g = lane >> 4, li = lane & 15;
-    int mb_live = (tc.rows - wm * C::WTM + 31) / 32;
+    // whole MF-row blocks of this wave's token sub-tile that hold at least one real row
+    int mb_live = (tc.rows - wm * C::WTM + MF - 1) / MF;
     mb_live = mb_live < 0 ? 0 : (mb_live > C::MBW ? C::MBW : mb_live);
 
-    constexpr int KSTEPS = BK / 16;
-    constexpr int NREADS = 2 * C::NBW + C::MBW, NM = C::NBW * C::MBW;
-    s16x4_t wlo[2][C::NBW], whi[2][C::NBW];
-    bf16x8_t xf[2][C::MBW];
+    // ---- fragment registers, double-buffered across k-steps; per-lane LDS offsets of k-step 0
+    u32x2_t wq[2][C::NBW][2];
+    u32x4_t xq[2][C::MBW];
     int w_rd[C::NBW], x_rd[C::MBW];
-    const int kr0 = 8 * (g >> 1) + (li >> 2);
 #pragma unroll
     for (int nb = 0; nb < C::NBW; ++nb) {
-        const int ncol = wn * C::WTN + nb * 32 + 16 * (g & 1) + 4 * (li & 3);
-        const int c = ncol >> 3, within = (ncol & 7) * 2;
+        int kr0, ncol, c, within;
+        if constexpr (C::FP8) {
+            kr0 = 8 * g + (li >> 1);
+            ncol = wn * C::WTN + nb * 16 + 8 * (li & 1);
+            c = ncol >> 4; within = ncol & 15;
+        } else if constexpr (MF == 32) {
+            kr0 = 8 * (g >> 1) + (li >> 2);
+            ncol = wn * C::WTN + nb * 32 + 16 * (g & 1) + 4 * (li & 3);
+            c = ncol >> 3; within = (ncol & 7) * 2;
+        } else {
+            kr0 = 8 * g + (li >> 2);
+            ncol = wn * C::WTN + nb * 16 + 4 * (li & 3);
+            c = ncol >> 3; within = (ncol & 7) * 2;
+        }
+        // the swizzle of row kr0 also holds for kr0 + 4 and kr0 + KS*kk (see pswz_w), so later k-steps add a constant
         w_rd[nb] = kr0 * C::WROW + ((c ^ pswz_w<C>(kr0)) << 4) + within;
     }
 #pragma unroll
-    for (int mb = 0; mb < C::MBW; ++mb) x_rd[mb] = (wm * C::WTM + mb * 32 + (lane & 31)) * C::XROW;
+    for (int mb = 0; mb < C::MBW; ++mb) x_rd[mb] = (wm * C::WTM + mb * MF + (MF == 32 ? (lane & 31) : li)) * C::XROW;
 
-    // read order follows first use by the MFMA sequence (mb outer, nb inner): X block 0, all W halves, X blocks 1..
+    // r-th LDS read of k-step kk, ordered by first use in the MFMA sequence (token block 0, weights, token blocks 1..)
     auto read_one = [&](int r, int stage, int kk, int buf, bool tail) {
         const char* xs = smem + stage * C::STAGE_BYTES;
         const char* ws = xs + C::XS_BYTES;
-        if (r >= 1 && r <= 2 * C::NBW) {
-            const int nb = (r - 1) >> 1, half = (r - 1) & 1;
-            const char* p = ws + w_rd[nb] + (kk * 16 + half * 4) * C::WROW;
-            const s16x4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((MOE_LDS(s16x4_t)*)(p));
-            if (half) whi[buf][nb] = v; else wlo[buf][nb] = v;
+        if (r >= 1 && r <= WREADS) {
+            if constexpr (C::FP8) {
+                const int nb = r - 1;
+                const char* p = ws + w_rd[nb] + (kk * 32) * C::WROW;
+                wq[buf][nb][0] = __builtin_bit_cast(u32x2_t, __builtin_amdgcn_ds_read_tr8_b64_v2i32((MOE_LDS(i32x2_t)*)(p)));
+            } else {
+                const int nb = (r - 1) >> 1, half = (r - 1) & 1;
+                const char* p = ws + w_rd[nb] + (kk * C::KS + half * 4) * C::WROW;
+                wq[buf][nb][half] = __builtin_bit_cast(u32x2_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16((MOE_LDS(s16x4_t)*)(p)));
+            }
         } else {
-            const int mb = r == 0 ? 0 : r - 2 * C::NBW;
+            const int mb = r == 0 ? 0 : r - WREADS;
             if (tail && mb >= mb_live) return;
-            const int row = wm * C::WTM + mb * 32 + (lane & 31);
-            const int c = kk * 2 + (lane >> 5);
-            xf[buf][mb] = *reinterpret_cast<const bf16x8_t*>(xs + x_rd[mb] + ((c ^ pswz_x<C>(row)) << 4));
+            const int row = wm * C::WTM + mb * MF + (MF == 32 ? (lane & 31) : li);
+            if constexpr (C::FP8) {
+                const int c = kk * 2 + (g >> 1);
+                const u32x2_t v = *reinterpret_cast<const u32x2_t*>(xs + x_rd[mb] + ((c ^ pswz_x<C>(row)) << 4) + (g & 1) * 8);
+                xq[buf][mb].x = v.x; xq[buf][mb].y = v.y;
+            } else {
+                const int c = MF == 32 ? kk * 2 + (lane >> 5) : kk * 4 + g;
+                xq[buf][mb] = *reinterpret_cast<const u32x4_t*>(xs + x_rd[mb] + ((c ^ pswz_x<C>(row)) << 4));
+            }
         }
     };
     auto mfma_one = [&](int i, int buf, bool tail) {
         const int mb = i / C::NBW, nb = i % C::NBW;
         if (tail && mb >= mb_live) return;
-        const bf16x8_t wf = __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(wlo[buf][nb], whi[buf][nb], 0, 1, 2, 3, 4, 5, 6, 7));
-        acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf[buf][mb], acc[nb][mb], 0, 0, 0);
+        if constexpr (C::FP8) {
+            const u32x2_t xv = {xq[buf][mb].x, xq[buf][mb].y};
+            acc[nb][mb] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(__builtin_bit_cast(long, wq[buf][nb][0]),
+                                                                     __builtin_bit_cast(long, xv), acc[nb][mb], 0, 0, 0);
+        } else {
+            const u32x4_t wv = {wq[buf][nb][0].x, wq[buf][nb][0].y, wq[buf][nb][1].x, wq[buf][nb][1].y};
+            const bf16x8_t wf = __builtin_bit_cast(bf16x8_t, wv), xf = __builtin_bit_cast(bf16x8_t, xq[buf][mb]);
+            if constexpr (MF == 32) acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[nb][mb], 0, 0, 0);
+            else acc[nb][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xf, acc[nb][mb], 0, 0, 0);
+        }
     };
 
-    const int KT = a.K / BK;
-    // ---- prologue: fill the ring, wait for tile 0, first fragments into registers
+    // ---- prologue: fill the ring, first fragments into registers
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
         if (s < KT) {
 #pragma unroll
-            for (int d = 0; d < ND; ++d) dma_one(d, s, s);
+            for (int d = 0; d < (C::EARLY_W ? XI : ND); ++d) dma_one(d, s, s);
         }
     }
-    if (NS <= KT) wait_vmcnt<(NS - 1) * ND>(); else wait_vmcnt<0>();
+    // EARLY_W issued weights and token rows in two batches: wait for all of it; else only tile 0 is needed
+    if (!C::EARLY_W && NS <= KT) wait_vmcnt<(NS - 1) * ND>(); else wait_vmcnt<0>();
     __syncthreads();
 #pragma unroll
     for (int r = 0; r < NREADS; ++r) read_one(r, 0, 0, 0, false);
@@ -530,27 +587,34 @@ __global__ __launch_bounds__(C::NT) void moe_gemm_pipe_kernel(GemmArgs a) {
     if (mb_live == C::MBW) main_loop(std::false_type{}); else main_loop(std::true_type{});
     wait_vmcnt<0>();
 
+    // ---- epilogue: fp32 -> bf16 (RNE), scatter to Y[r, n]; fp8 applies the two scales first
     char* Yb = static_cast<char*>(a.Y);
     const size_t y_row_bytes = (size_t)a.N * 2;
 #pragma unroll
     for (int mb = 0; mb < C::MBW; ++mb) {
-        const int m_local = wm * C::WTM + mb * 32 + (lane & 31);
+        const int m_local = wm * C::WTM + mb * MF + (MF == 32 ? (lane & 31) : li);
         const int r = s_row[m_local];
         if (r < 0) continue;
+        float xsc = 1.f, wsc = 1.f;
+        if constexpr (C::FP8) { xsc = a.x_scale[r / a.k]; wsc = a.w_scale[tc.e]; }
         char* yrow = Yb + (size_t)r * y_row_bytes + (size_t)n0 * 2;
 #pragma unroll
         for (int nb = 0; nb < C::NBW; ++nb) {
 #pragma unroll
-            for (int jq = 0; jq < 4; ++jq) {
-                const int n_local = wn * C::WTN + nb * 32 + 8 * jq + 4 * (lane >> 5);
+            for (int jq = 0; jq < C::ACC / 4; ++jq) {
+                const int n_local = MF == 32 ? wn * C::WTN + nb * 32 + 8 * jq + 4 * (lane >> 5) : wn * C::WTN + nb * 16 + 4 * g;
+                float v0 = acc[nb][mb][4 * jq + 0], v1 = acc[nb][mb][4 * jq + 1];
+                float v2 = acc[nb][mb][4 * jq + 2], v3 = acc[nb][mb][4 * jq + 3];
+                if constexpr (C::FP8) {
+                    v0 = (v0 * xsc) * wsc; v1 = (v1 * xsc) * wsc; v2 = (v2 * xsc) * wsc; v3 = (v3 * xsc) * wsc;
+                }
                 u32x2_t v;
-                v.x = pack_bf16(acc[nb][mb][4 * jq + 0], acc[nb][mb][4 * jq + 1]);
-                v.y = pack_bf16(acc[nb][mb][4 * jq + 2], acc[nb][mb][4 * jq + 3]);
+                v.x = pack_bf16(v0, v1);
+                v.y = pack_bf16(v2, v3);
                 *reinterpret_cast<u32x2_t*>(yrow + n_local * 2) = v;
             }
         }
     }
 }
-
 
 }  // namespace moe

@@ -66,13 +66,13 @@ using Pb_64x256 = PipeCfg<64, 256, 64, 1, 4, 3>;
 using Pb_64x128 = PipeCfg<64, 128, 64, 1, 4, 4>;
 using Pb_32x256 = PipeCfg<32, 256, 64, 1, 4, 4>;
 using Pb_32x128 = PipeCfg<32, 128, 64, 1, 4, 6>;
-// Register-staged kernels (16-row tiles, fp8):  BM  BN   BK  WM WN  FP8
-using Bf_16x256 = GemmCfg<16, 256, 64, 1, 4, false>;
-using Bf_16x128 = GemmCfg<16, 128, 64, 1, 4, false>;
-using F8_16x256 = GemmCfg<16, 256, 128, 1, 4, true>;
-using F8_16x128 = GemmCfg<16, 128, 128, 1, 4, true>;
-using F8_16x64 = GemmCfg<16, 64, 128, 1, 4, true>;
-using F8_32x128 = GemmCfg<32, 128, 128, 1, 4, true>;
+// 16-row tiles (two wavefronts) and fp8: the weight stream starts before the token rows are known
+using Pb_16x256 = PipeCfg<16, 256, 64, 1, 2, 4>;
+using Pb_16x128 = PipeCfg<16, 128, 64, 1, 2, 6>;
+using P8_16x256 = PipeCfg<16, 256, 128, 1, 2, 3, true>;
+using P8_16x128 = PipeCfg<16, 128, 128, 1, 2, 4, true>;
+using P8_16x64 = PipeCfg<16, 64, 128, 1, 2, 8, true>;
+using P8_32x128 = PipeCfg<32, 128, 128, 1, 2, 4, true>;
 
 const GemmVariant kVariants[] = {
     {MOE_DTYPE_BF16, 256, 256, 64, &launch_pipe<Pb_256x256>},
@@ -82,12 +82,12 @@ const GemmVariant kVariants[] = {
     {MOE_DTYPE_BF16, 64, 128, 64, &launch_pipe<Pb_64x128>},
     {MOE_DTYPE_BF16, 32, 256, 64, &launch_pipe<Pb_32x256>},
     {MOE_DTYPE_BF16, 32, 128, 64, &launch_pipe<Pb_32x128>},
-    {MOE_DTYPE_BF16, 16, 256, 64, &launch_gemm<Bf_16x256>},
-    {MOE_DTYPE_BF16, 16, 128, 64, &launch_gemm<Bf_16x128>},
-    {MOE_DTYPE_FP8_E4M3, 16, 256, 128, &launch_gemm<F8_16x256>},
-    {MOE_DTYPE_FP8_E4M3, 16, 128, 128, &launch_gemm<F8_16x128>},
-    {MOE_DTYPE_FP8_E4M3, 16, 64, 128, &launch_gemm<F8_16x64>},
-    {MOE_DTYPE_FP8_E4M3, 32, 128, 128, &launch_gemm<F8_32x128>},
+    {MOE_DTYPE_BF16, 16, 256, 64, &launch_pipe<Pb_16x256>},
+    {MOE_DTYPE_BF16, 16, 128, 64, &launch_pipe<Pb_16x128>},
+    {MOE_DTYPE_FP8_E4M3, 16, 256, 128, &launch_pipe<P8_16x256>},
+    {MOE_DTYPE_FP8_E4M3, 16, 128, 128, &launch_pipe<P8_16x128>},
+    {MOE_DTYPE_FP8_E4M3, 16, 64, 128, &launch_pipe<P8_16x64>},
+    {MOE_DTYPE_FP8_E4M3, 32, 128, 128, &launch_pipe<P8_32x128>},
 };
 
 const GemmVariant* find_variant(int dtype, int tile_m, int tile_n) {
