@@ -67,11 +67,11 @@ using Pb_64x128 = PipeCfg<64, 128, 64, 1, 4, 4>;
 using Pb_32x256 = PipeCfg<32, 256, 64, 1, 4, 4>;
 using Pb_32x128 = PipeCfg<32, 128, 64, 1, 4, 6>;
 // 16-row tiles (two wavefronts) and fp8: the weight stream starts before the token rows are known
-using Pb_16x256 = PipeCfg<16, 256, 64, 1, 2, 4>;
-using Pb_16x128 = PipeCfg<16, 128, 64, 1, 2, 6>;
-using P8_16x256 = PipeCfg<16, 256, 128, 1, 2, 3, true>;
+using Pb_16x256 = PipeCfg<16, 256, 64, 1, 2, 2>;
+using Pb_16x128 = PipeCfg<16, 128, 64, 1, 2, 4>;
+using P8_16x256 = PipeCfg<16, 256, 128, 1, 2, 2, true>;
 using P8_16x128 = PipeCfg<16, 128, 128, 1, 2, 4, true>;
-using P8_16x64 = PipeCfg<16, 64, 128, 1, 2, 8, true>;
+using P8_16x64 = PipeCfg<16, 64, 128, 1, 2, 4, true>;
 using P8_32x128 = PipeCfg<32, 128, 128, 1, 2, 4, true>;
 
 const GemmVariant kVariants[] = {

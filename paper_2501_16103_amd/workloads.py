@@ -85,7 +85,7 @@ def fine_grained(T: int) -> Workload:
 
 
 def decode_fp8(T: int) -> Workload:
-    return Workload("decode_fp8", T, 64, 6, 2048, 2816, "fp8", "uniform_topk", 16, 128 if T > 1 else 64)
+    return Workload("decode_fp8", T, 64, 6, 2048, 2816, "fp8", "uniform_topk", 16, 256 if T == 8 else 128)
 
 
 def paper_eval(scenario: str = "balanced", T: int = 4096) -> Workload:
