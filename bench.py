@@ -49,8 +49,9 @@ def algorithmic_bytes(wl: wk.Workload, ids: torch.Tensor) -> int:
 class Point:
     """Device buffers of one workload (optionally several weight copies to defeat the caches)."""
 
-    def __init__(self, wl: wk.Workload, copies: int = 1, dev="cuda:0"):
+    def __init__(self, wl: wk.Workload, copies: int = 1, dev="cuda:0", order: int = 0):
         self.wl = wl
+        self.order = order
         self.dev = dev
         self.ids_cpu = wk.make_routing(wl)
         self.ids = self.ids_cpu.to(dev)
@@ -70,7 +71,7 @@ class Point:
 
     def build_map(self):
         wl = self.wl
-        mb.moe_build_task_map(self.ids, wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N, self.tmap)
+        mb.moe_build_task_map_ordered(self.ids, wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N, self.order, self.tmap)
 
     def gemm(self, i: int = 0):
         mb.moe_grouped_gemm(self.X, self.W[i % len(self.W)], self.ids, self.tmap, self.Y, self.desc)
@@ -117,7 +118,7 @@ class Point:
         ideal_hbm = abytes / (PEAK_HBM_GBS * 1e9)
         bound = "mfma" if ideal_mfma >= ideal_hbm else "hbm"
         return dict(workload=f"{wl.name}_T{wl.T}", dtype=wl.dtype, T=wl.T, E=wl.E, k=wl.k, K=wl.K, N=wl.N,
-                    tile=[wl.tile_m, wl.tile_n], ms_per_step=round(wall_ms, 4), gemm_ms=round(gemm_ms, 4),
+                    tile=[wl.tile_m, wl.tile_n], sigma_order=("spread" if self.order else "ascending"), ms_per_step=round(wall_ms, 4), gemm_ms=round(gemm_ms, 4),
                     map_ms=round(map_ms, 4), tflops_step=round(tf_step, 2), tflops_gemm=round(tf_gemm, 2),
                     frac_mfma=round(tf_gemm / peak_t, 4), gbs_gemm=round(gbs, 1),
                     frac_hbm=round(gbs / PEAK_HBM_GBS, 4), bound=bound, alg_bytes=abytes, flops=wl.flops)
@@ -185,6 +186,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--points", default="none", help="'all', 'none', or a comma list of workload names")
     ap.add_argument("--tile", default="", help="override tile_m,tile_n of the headline workload")
+    ap.add_argument("--order", default="ascending", choices=["ascending", "spread", "both"],
+                    help="expert order in sigma for the extra points (the headline always uses ascending)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (a kernel of known traffic to scale profiler byte counters by)")
@@ -244,10 +247,11 @@ def main():
                 # enough full copies that an iteration never finds its experts cached by an earlier one
                 touched = int(torch.unique(wk.make_routing(w)).numel()) * w.K * w.N
                 copies = min(16, max(4, -(-int(1.2e9) // touched)))
-            p = Point(w, copies)
-            points.append(p.report(max(10, args.steps // 2), max(3, args.warmup // 2)))
-            del p
-            torch.cuda.empty_cache()
+            for order in ([0, 1] if args.order == "both" else [1 if args.order == "spread" else 0]):
+                p = Point(w, copies, order=order)
+                points.append(p.report(max(10, args.steps // 2), max(3, args.warmup // 2)))
+                del p
+                torch.cuda.empty_cache()
         out["points"] = points
     print(json.dumps(out))
 

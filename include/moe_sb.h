@@ -37,6 +37,9 @@ enum {
 
 enum { MOE_DTYPE_BF16 = 0, MOE_DTYPE_FP8_E4M3 = 1 };
 
+/* Order of the non-empty experts in sigma (Sec. 4.1, Sec. 4.2). */
+enum { MOE_ORDER_ASCENDING = 0, MOE_ORDER_SPREAD = 1 };
+
 /*
  * Task-map blob (all int32 words; E64 = E rounded up to a multiple of 64,
  * R = T*k routed rows, flat row id r = t*k + j).  Word offsets:
@@ -74,7 +77,8 @@ enum {
     MOE_HDR_ORDER = 10,      /* 0: m-tile fastest inside an expert */
     MOE_HDR_STATUS = 11,     /* 0, or the number of routing ids outside [0,E) */
     MOE_HDR_R = 12,          /* T*k */
-    MOE_HDR_E64 = 13
+    MOE_HDR_E64 = 13,
+    MOE_HDR_SIGMA_ORDER = 14 /* MOE_ORDER_* the map was built with */
 };
 
 /* Word offsets of the blob's fields for a given E (HOST, pure). */
@@ -110,6 +114,22 @@ int64_t moe_grid_upper_bound(int T, int k, int E, int tile_m, int tile_n, int N)
  */
 int moe_build_task_map(const int32_t* topk_ids, int T, int k, int E, int tile_m, int tile_n, int N,
                        void* task_map, void* stream);
+
+/*
+ * Same, with the expert ordering of Sec. 4.2 made explicit.  The paper interleaves busy
+ * (compute-bound) and non-busy (memory-bound) experts and reports that arranging the busy
+ * experts "in a half-interval manner" works best, without giving the algorithm; here:
+ *   MOE_ORDER_ASCENDING  sigma lists non-empty experts by increasing index (moe_build_task_map).
+ *   MOE_ORDER_SPREAD     non-empty experts are ranked by tile count (largest first, ties by
+ *                        lower index); rank r gets the key bitrev(r) over ceil(log2 M) bits;
+ *                        sigma lists them by increasing key: busiest first, second busiest in
+ *                        the middle, the next two at the quarter points, ... so every
+ *                        contiguous run of blocks (one per XCD) mixes busy and small experts.
+ * Only sigma and tile_prefix depend on the order; counts, offsets and sorted_rows do not.
+ * Any other `order` returns MOE_ERR_INVALID_ARG.
+ */
+int moe_build_task_map_ordered(const int32_t* topk_ids, int T, int k, int E, int tile_m, int tile_n, int N,
+                               int order, void* task_map, void* stream);
 
 /*
  * Synchronises the stream and returns MOE_ERR_ROUTING if the map recorded a

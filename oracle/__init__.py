@@ -104,6 +104,7 @@ class TaskMap:
     tile_prefix: np.ndarray   # [M] inclusive prefix of tiles per non-empty expert
     M: int
     total_tiles: int
+    order: int = 0            # 0: sigma ascending, 1: spread (Sec. 4.2)
 
     @property
     def nt(self) -> int:
@@ -127,7 +128,7 @@ def mapping(prefix, B: int):
     return h.value, l.value
 
 
-def build_task_map(topk_ids, T: int, k: int, E: int, tile_m: int, tile_n: int, N: int) -> TaskMap:
+def build_task_map(topk_ids, T: int, k: int, E: int, tile_m: int, tile_n: int, N: int, order: int = 0) -> TaskMap:
     ids = _i32(topk_ids).reshape(-1)
     assert ids.size == T * k
     counts = np.zeros(E, dtype=np.int32)
@@ -138,13 +139,13 @@ def build_task_map(topk_ids, T: int, k: int, E: int, tile_m: int, tile_n: int, N
     M = ctypes.c_int32(0)
     total = ctypes.c_int32(0)
     rc = _load().orc_build_task_map(_p(ids), ctypes.c_int(T), ctypes.c_int(k), ctypes.c_int(E),
-                                    ctypes.c_int(tile_m), ctypes.c_int(tile_n), ctypes.c_int(N),
+                                    ctypes.c_int(tile_m), ctypes.c_int(tile_n), ctypes.c_int(N), ctypes.c_int(order),
                                     _p(counts), _p(offsets), _p(sorted_rows), _p(sigma), _p(prefix),
                                     ctypes.byref(M), ctypes.byref(total))
     if rc != 0:
         raise ValueError("routing id outside [0, E)")
     return TaskMap(T, k, E, N, tile_m, tile_n, counts, offsets, sorted_rows[: T * k].copy(),
-                   sigma[: M.value].copy(), prefix[: M.value].copy(), M.value, total.value)
+                   sigma[: M.value].copy(), prefix[: M.value].copy(), M.value, total.value, order)
 
 
 def decode_block(tm: TaskMap, B: int):
@@ -167,13 +168,18 @@ def decode_all(tm: TaskMap) -> np.ndarray:
     return out
 
 
-def full_table(counts, tile_m: int, tile_n: int, N: int) -> np.ndarray:
-    """Prior-art full per-block table by nested loops -> [total, 4]."""
+def full_table(counts, tile_m: int, tile_n: int, N: int, sigma=None) -> np.ndarray:
+    """Prior-art full per-block table by nested loops -> [total, 4].  `sigma` (non-empty experts in
+    visiting order) defaults to ascending expert index."""
     counts = _i32(counts)
+    order = None
+    if sigma is not None:
+        sig = [int(e) for e in sigma]
+        order = _i32(sig + [e for e in range(len(counts)) if e not in set(sig)])
     nt = -(-N // tile_n)
     cap = int(sum(-(-int(c) // tile_m) for c in counts) * nt)
     table = np.zeros((max(cap, 1), 4), dtype=np.int32)
-    n = _load().orc_full_table(_p(counts), ctypes.c_int(len(counts)), ctypes.c_int(tile_m),
+    n = _load().orc_full_table(_p(counts), ctypes.c_int(len(counts)), _p(order), ctypes.c_int(tile_m),
                                ctypes.c_int(tile_n), ctypes.c_int(N), _p(table), ctypes.c_int(cap))
     assert n == cap
     return table[:cap]

@@ -12,7 +12,12 @@
  *   - block index B and all arrays are 0-based: the task of block B is
  *     h = #{ i : TilePrefix[i] <= B }  (Alg. 2 as printed: p = B >= TilePrefix[t]).
  *   - nu(expert e) = ceil(c_e / tile_m) * ceil(N / tile_n)   (tiles of its GEMM).
- *   - sigma lists the non-empty experts in ascending expert index (Sec. 4.1).
+ *   - sigma lists the non-empty experts in ascending expert index (Sec. 4.1), or, with
+ *     order = 1, "spread" in the half-interval manner of Sec. 4.2: the non-empty experts
+ *     are ranked by tile count (largest first, ties by lower index), rank r gets the key
+ *     bitrev(r) over ceil(log2 M) bits, and sigma lists them by increasing key -- the
+ *     busiest expert first, the second busiest in the middle, the next two at the
+ *     quarter points, and so on, with the small experts filling the gaps.
  *   - inside an expert, tile index l runs m-tile fastest:
  *       m_tile = l % mt_e,  n_tile = l / mt_e.
  *   - the token index array of an expert (Sec. 4.3) is ordered by flat row id
@@ -119,12 +124,42 @@ void orc_mapping(const int32_t* tile_prefix, int n, int B, int32_t* h_out, int32
     *l_out = B - kk;
 }
 
+/* Bit reversal of r over nbits bits. */
+static int bit_reverse(int r, int nbits) {
+    int v = 0;
+    for (int b = 0; b < nbits; ++b)
+        if (r & (1 << b)) v |= 1 << (nbits - 1 - b);
+    return v;
+}
+
+/* Sec. 4.2 "half-interval" order (reading stated at the top of this file).
+ * experts[0..M) ascending non-empty experts with tile counts nu[0..M): writes sigma[0..M). */
+static void spread_order(const int32_t* experts, const int32_t* nu, int M, int32_t* sigma) {
+    int nbits = 0;
+    while ((1 << nbits) < M) ++nbits;
+    int32_t* key = (int32_t*)malloc(sizeof(int32_t) * (size_t)(M > 0 ? M : 1));
+    for (int i = 0; i < M; ++i) {
+        int rank = 0; /* how many experts are busier (or equally busy with a lower index) */
+        for (int j = 0; j < M; ++j)
+            if (nu[j] > nu[i] || (nu[j] == nu[i] && j < i)) rank += 1;
+        key[i] = bit_reverse(rank, nbits);
+    }
+    for (int i = 0; i < M; ++i) {
+        int pos = 0;
+        for (int j = 0; j < M; ++j)
+            if (key[j] < key[i]) pos += 1;
+        sigma[pos] = experts[i];
+    }
+    free(key);
+}
+
 /* Routing result -> everything the kernel needs (Sec. 4.1, 4.3):
  *   counts[E], offsets[E+1] (exclusive scan), sorted_rows[T*k] (per-expert
  *   token index arrays, stored back to back, as flat row ids r = t*k+j; the
  *   token is r / k), sigma[M] (non-empty -> real expert), tile_prefix[M].
+ *   order: 0 = sigma ascending, 1 = spread (Sec. 4.2).
  * Returns 0, or -1 if an id is outside [0,E).                               */
-int orc_build_task_map(const int32_t* topk_ids, int T, int k, int E, int tile_m, int tile_n, int N,
+int orc_build_task_map(const int32_t* topk_ids, int T, int k, int E, int tile_m, int tile_n, int N, int order,
                        int32_t* counts, int32_t* offsets, int32_t* sorted_rows, int32_t* sigma,
                        int32_t* tile_prefix, int32_t* M_out, int32_t* total_tiles_out) {
     int R = T * k;
@@ -142,19 +177,25 @@ int orc_build_task_map(const int32_t* topk_ids, int T, int k, int E, int tile_m,
         for (int r = 0; r < R; ++r)
             if (topk_ids[r] == e) sorted_rows[w++] = r;
     }
-    /* sigma and the tile counts of the non-empty experts */
+    /* the non-empty experts and their tile counts */
     int M = 0;
     int32_t* nu = (int32_t*)malloc(sizeof(int32_t) * (size_t)(E > 0 ? E : 1));
+    int32_t* ne = (int32_t*)malloc(sizeof(int32_t) * (size_t)(E > 0 ? E : 1));
     int nt = ceil_div(N, tile_n);
     for (int e = 0; e < E; ++e) {
         if (counts[e] > 0) {
-            sigma[M] = e;
+            ne[M] = e;
             nu[M] = ceil_div(counts[e], tile_m) * nt;
             M += 1;
         }
     }
+    if (order == 1) spread_order(ne, nu, M, sigma);
+    else for (int i = 0; i < M; ++i) sigma[i] = ne[i];
+    /* tile counts in sigma order, then Alg. 1 */
+    for (int i = 0; i < M; ++i) nu[i] = ceil_div(counts[sigma[i]], tile_m) * nt;
     orc_tile_prefix(nu, M, tile_prefix);
     free(nu);
+    free(ne);
     *M_out = M;
     *total_tiles_out = M > 0 ? tile_prefix[M - 1] : 0;
     return 0;
@@ -177,12 +218,15 @@ void orc_decode_block(const int32_t* tile_prefix, const int32_t* sigma, int M, c
 
 /* The prior-art full per-block table (Sec. 2.1 / 3.1: one entry per thread
  * block), by nested loops over (expert, n_tile, m_tile) with no prefix array
- * at all.  It is an independent definition of the same map.  Returns the
- * number of entries written (table has room for cap entries of 4 ints).    */
-int orc_full_table(const int32_t* counts, int E, int tile_m, int tile_n, int N, int32_t* table, int cap) {
+ * at all.  It is an independent definition of the same map.  expert_order
+ * lists all E experts in visiting order (empty ones contribute no entry).
+ * Returns the number of entries written (room for cap entries of 4 ints).  */
+int orc_full_table(const int32_t* counts, int E, const int32_t* expert_order, int tile_m, int tile_n, int N,
+                   int32_t* table, int cap) {
     int b = 0;
     int nt = ceil_div(N, tile_n);
-    for (int e = 0; e < E; ++e) {
+    for (int i = 0; i < E; ++i) {
+        int e = expert_order ? expert_order[i] : i; /* experts are visited in this order; NULL = 0,1,2,... */
         int mt = ceil_div(counts[e], tile_m);
         for (int n_tile = 0; n_tile < nt; ++n_tile)
             for (int m_tile = 0; m_tile < mt; ++m_tile) {

@@ -25,14 +25,17 @@ MOE_ERR_ROUTING = -3
 MOE_ERR_HIP = -4
 MOE_DTYPE_BF16 = 0
 MOE_DTYPE_FP8_E4M3 = 1
+MOE_ORDER_ASCENDING = 0
+MOE_ORDER_SPREAD = 1
 MOE_MAP_MAGIC = 0x3142534D
 MOE_MAP_HDR_WORDS = 32
 HDR = dict(MAGIC=0, T=1, K_TOP=2, E=3, N=4, TILE_M=5, TILE_N=6, NT=7, M=8, TOTAL_TILES=9, ORDER=10,
-           STATUS=11, R=12, E64=13)
+           STATUS=11, R=12, E64=13, SIGMA_ORDER=14)
 
 EXPORTS = [
     "moe_map_off_counts", "moe_map_off_offsets", "moe_map_off_sigma", "moe_map_off_tile_prefix",
     "moe_map_off_sorted_rows", "moe_task_map_bytes", "moe_grid_upper_bound", "moe_build_task_map",
+    "moe_build_task_map_ordered",
     "moe_task_map_status", "moe_task_map_expand", "moe_grouped_gemm", "moe_tile_supported", "moe_strerror",
 ]
 
@@ -69,6 +72,8 @@ def lib() -> ctypes.CDLL:
         L.moe_grid_upper_bound.argtypes = [ctypes.c_int] * 6
         L.moe_build_task_map.restype = ctypes.c_int
         L.moe_build_task_map.argtypes = [ctypes.c_void_p] + [ctypes.c_int] * 6 + [ctypes.c_void_p, ctypes.c_void_p]
+        L.moe_build_task_map_ordered.restype = ctypes.c_int
+        L.moe_build_task_map_ordered.argtypes = [ctypes.c_void_p] + [ctypes.c_int] * 7 + [ctypes.c_void_p, ctypes.c_void_p]
         L.moe_task_map_status.restype = ctypes.c_int
         L.moe_task_map_status.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
         L.moe_task_map_expand.restype = ctypes.c_int
@@ -126,6 +131,14 @@ def moe_build_task_map(topk_ids: torch.Tensor, T: int, k: int, E: int, tile_m: i
     rc = lib().moe_build_task_map(_ptr(topk_ids), T, k, E, tile_m, tile_n, N, _ptr(task_map), _stream())
     if check and rc != MOE_OK:
         raise MoeError(rc, "moe_build_task_map")
+    return rc
+
+
+def moe_build_task_map_ordered(topk_ids: torch.Tensor, T: int, k: int, E: int, tile_m: int, tile_n: int, N: int,
+                               order: int, task_map: torch.Tensor, check: bool = True) -> int:
+    rc = lib().moe_build_task_map_ordered(_ptr(topk_ids), T, k, E, tile_m, tile_n, N, order, _ptr(task_map), _stream())
+    if check and rc != MOE_OK:
+        raise MoeError(rc, "moe_build_task_map_ordered")
     return rc
 
 

@@ -123,7 +123,13 @@ int64_t moe_grid_upper_bound(int T, int k, int E, int tile_m, int tile_n, int N)
 
 int moe_build_task_map(const int32_t* topk_ids, int T, int k, int E, int tile_m, int tile_n, int N, void* task_map,
                        void* stream) {
+    return moe_build_task_map_ordered(topk_ids, T, k, E, tile_m, tile_n, N, MOE_ORDER_ASCENDING, task_map, stream);
+}
+
+int moe_build_task_map_ordered(const int32_t* topk_ids, int T, int k, int E, int tile_m, int tile_n, int N, int order,
+                               void* task_map, void* stream) {
     if (!task_map || (T > 0 && !topk_ids)) return MOE_ERR_INVALID_ARG;
+    if (order != MOE_ORDER_ASCENDING && order != MOE_ORDER_SPREAD) return MOE_ERR_INVALID_ARG;
     if (((uintptr_t)task_map & 15) || ((uintptr_t)topk_ids & 3)) return MOE_ERR_INVALID_ARG;
     const int rc = check_map_args(T, k, E, tile_m, tile_n, N);
     if (rc != MOE_OK) return rc;
@@ -132,22 +138,22 @@ int moe_build_task_map(const int32_t* topk_ids, int T, int k, int E, int tile_m,
     const MapLayout L = map_layout(E);
     const int64_t R = (int64_t)T * k;
     if (R <= kChunkRows) {
-        const size_t lds = ((size_t)kWaves * L.E64 + L.E64 + 32) * sizeof(int);
+        const size_t lds = ((size_t)kWaves * L.E64 + L.E64 + 32 + 2 * (size_t)L.E64) * sizeof(int);
         static bool attr_set = false;
         if (!attr_set) {
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(&map_build_small),
                                     hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)(((size_t)kWaves * kMaxE + kMaxE + 32) * sizeof(int))) != hipSuccess)
+                                    (int)(((size_t)kWaves * kMaxE + 3 * (size_t)kMaxE + 32) * sizeof(int))) != hipSuccess)
                 return MOE_ERR_HIP;
             attr_set = true;
         }
-        map_build_small<<<1, kMapThreads, lds, s>>>(topk_ids, map, T, k, E, tile_m, tile_n, N);
+        map_build_small<<<1, kMapThreads, lds, s>>>(topk_ids, map, T, k, E, tile_m, tile_n, N, order);
     } else {
         const int nchunks = nchunks_for(R);
         int32_t* chunk_hist = map + L.off_rows + round_up64((size_t)R);
         const int hs = hist_stride(L.E64);
         map_hist<<<nchunks, 256, hs * sizeof(int), s>>>(topk_ids, (int)R, E, L.E64, chunk_hist);
-        map_scan<<<1, kMapThreads, 0, s>>>(map, chunk_hist, nchunks, T, k, E, tile_m, tile_n, N);
+        map_scan<<<1, kMapThreads, 0, s>>>(map, chunk_hist, nchunks, T, k, E, tile_m, tile_n, N, order);
         static bool attr_set2 = false;
         if (!attr_set2) {
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(&map_scatter),

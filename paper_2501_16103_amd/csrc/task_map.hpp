@@ -117,36 +117,69 @@ __device__ __forceinline__ int block_incl_scan(int v, int* s_tmp) {
     return incl + base;
 }
 
+__device__ __forceinline__ int bit_reverse(int r, int nbits) { return nbits ? (int)(__brev((unsigned)r) >> (32 - nbits)) : 0; }
+
 // From the per-expert count held by thread e (< E64; 0 beyond E): write counts, offsets,
 // sigma, tile_prefix and the header.  Executed by all kMapThreads threads of one block.
-// Returns this thread's exclusive offset (valid for threadIdx.x < E).
+// order 0: sigma ascending in expert index.  order 1 ("spread", the half-interval placement of
+// Sec. 4.2): non-empty experts ranked by tile count (largest first, ties by lower index), rank r
+// keyed by bitrev(r) over ceil(log2 M) bits, sigma by increasing key.
+// s_work: >= 2*E64 ints of LDS.  Returns this thread's exclusive row offset (valid for tid < E).
 __device__ __forceinline__ int finish_map(int32_t* __restrict__ map, const MapLayout& L, int cnt, int bad, int T, int k,
-                                          int E, int tile_m, int tile_n, int N, int* s_tmp) {
+                                          int E, int tile_m, int tile_n, int N, int order, int* s_tmp, int* s_work) {
     const int tid = threadIdx.x;
     const int R = T * k;
     const int nt = (N + tile_n - 1) / tile_n;
     const int nonempty = cnt > 0;
     const int tiles = ((cnt + tile_m - 1) / tile_m) * nt;
     const int off_incl = block_incl_scan(cnt, s_tmp);
-    const int pos_incl = block_incl_scan(nonempty, s_tmp);
-    const int tile_incl = block_incl_scan(tiles, s_tmp);  // Alg. 1 restricted to non-empty experts
+    const int ne_incl = block_incl_scan(nonempty, s_tmp);
     __syncthreads();
-    if (tid == kMapThreads - 1) { s_tmp[0] = pos_incl; s_tmp[1] = tile_incl; }
+    if (tid == kMapThreads - 1) s_tmp[16] = ne_incl;
     __syncthreads();
-    const int M = s_tmp[0], total = s_tmp[1];
+    const int M = s_tmp[16];
+    // position of this expert in sigma
+    int pos = ne_incl - 1;
+    if (order == 1) {
+        if (tid < L.E64) s_work[tid] = nonempty ? tiles : -1;
+        __syncthreads();
+        int rank = 0;
+        if (nonempty)
+            for (int j = 0; j < L.E64; ++j) {
+                const int tj = s_work[j];
+                rank += (tj > tiles) || (tj == tiles && j < tid);
+            }
+        int nbits = 0;
+        while ((1 << nbits) < M) ++nbits;
+        const int key = bit_reverse(rank, nbits);
+        if (tid < L.E64) s_work[L.E64 + tid] = nonempty ? key : 0x7fffffff;
+        __syncthreads();
+        pos = 0;
+        if (nonempty)
+            for (int j = 0; j < L.E64; ++j) pos += s_work[L.E64 + j] < key;
+        __syncthreads();
+    }
     if (tid < L.E64) {
         map[L.off_counts + tid] = cnt;
         map[L.off_sigma + tid] = -1;
-        map[L.off_prefix + tid] = 0x7fffffff;
+        s_work[tid] = 0;
     }
     for (int i = tid; i < L.E64 + 64; i += kMapThreads) map[L.off_offsets + i] = i <= E ? 0 : R;
     __syncthreads();
     if (tid < E) map[L.off_offsets + tid] = off_incl - cnt;
     if (tid == 0) map[L.off_offsets + E] = R - bad;
     if (nonempty) {
-        map[L.off_sigma + pos_incl - 1] = tid;
-        map[L.off_prefix + pos_incl - 1] = tile_incl;
+        map[L.off_sigma + pos] = tid;
+        s_work[pos] = tiles;
     }
+    __syncthreads();
+    // Alg. 1 over the non-empty experts in sigma order
+    const int tile_incl = block_incl_scan(tid < M ? s_work[tid] : 0, s_tmp);
+    if (tid < L.E64) map[L.off_prefix + tid] = tid < M ? tile_incl : 0x7fffffff;
+    __syncthreads();
+    if (tid == kMapThreads - 1) s_tmp[17] = tile_incl;
+    __syncthreads();
+    const int total = s_tmp[17];
     if (tid < MOE_MAP_HDR_WORDS) {
         int v = 0;
         switch (tid) {
@@ -164,6 +197,7 @@ __device__ __forceinline__ int finish_map(int32_t* __restrict__ map, const MapLa
             case MOE_HDR_STATUS: v = bad; break;
             case MOE_HDR_R: v = R; break;
             case MOE_HDR_E64: v = L.E64; break;
+            case MOE_HDR_SIGMA_ORDER: v = order; break;
             default: v = 0;
         }
         map[tid] = v;
@@ -178,14 +212,15 @@ __device__ __forceinline__ int key_bits(int E) {
 }
 
 // One-workgroup build for R <= kChunkRows: histogram, scans and stable scatter fused.
-// Dynamic LDS: kWaves * E64 ints (per-wavefront counts) + E64 ints (offsets) + 32.
+// Dynamic LDS: kWaves * E64 ints (per-wavefront counts) + E64 ints (offsets) + 32 + 2 * E64 (ordering).
 __global__ __launch_bounds__(kMapThreads) void map_build_small(const int32_t* __restrict__ ids, int32_t* __restrict__ map,
-                                                                int T, int k, int E, int tile_m, int tile_n, int N) {
+                                                                int T, int k, int E, int tile_m, int tile_n, int N, int order) {
     extern __shared__ int s_mem[];
     const MapLayout L = map_layout(E);
     int* s_wave = s_mem;                   // [kWaves][E64]
     int* s_off = s_mem + kWaves * L.E64;   // [E64]
     int* s_tmp = s_off + L.E64;            // [32]
+    int* s_work = s_tmp + 32;              // [2*E64]
     const int tid = threadIdx.x, w = tid >> 6;
     const int R = T * k;
     for (int i = tid; i < kWaves * L.E64; i += kMapThreads) s_wave[i] = 0;
@@ -209,7 +244,7 @@ __global__ __launch_bounds__(kMapThreads) void map_build_small(const int32_t* __
             cnt += c;
         }
     }
-    const int off = finish_map(map, L, cnt, bad, T, k, E, tile_m, tile_n, N, s_tmp);
+    const int off = finish_map(map, L, cnt, bad, T, k, E, tile_m, tile_n, N, order, s_tmp, s_work);
     if (tid < L.E64) s_off[tid] = off;
     __syncthreads();
     if (valid) map[L.off_rows + s_off[e] + s_wave[w * L.E64 + e] + rank] = tid;
@@ -237,8 +272,10 @@ __global__ __launch_bounds__(256) void map_hist(const int32_t* __restrict__ ids,
 // Step 2 (one workgroup): turn the chunk histograms into per-chunk exclusive bases,
 // then counts / offsets / sigma / TilePrefix / header.
 __global__ __launch_bounds__(kMapThreads) void map_scan(int32_t* __restrict__ map, int32_t* __restrict__ chunk_hist,
-                                                        int nchunks, int T, int k, int E, int tile_m, int tile_n, int N) {
+                                                        int nchunks, int T, int k, int E, int tile_m, int tile_n, int N,
+                                                        int order) {
     __shared__ int s_tmp[32];
+    __shared__ int s_work[2 * kMaxE];
     const MapLayout L = map_layout(E);
     const int hs = hist_stride(L.E64);
     const int tid = threadIdx.x;
@@ -257,7 +294,7 @@ __global__ __launch_bounds__(kMapThreads) void map_scan(int32_t* __restrict__ ma
     }
     __syncthreads();
     const int bad = s_tmp[31];
-    finish_map(map, L, cnt, bad, T, k, E, tile_m, tile_n, N, s_tmp);
+    finish_map(map, L, cnt, bad, T, k, E, tile_m, tile_n, N, order, s_tmp, s_work);
 }
 
 // Step 3: stable scatter of one chunk of rows into the token index arrays.

@@ -29,7 +29,7 @@ def _gather_columns(W, experts, cols):
     return torch.cat(out)
 
 
-def _run_full(wl, dev):
+def _run_full(wl, dev, order=0):
     ids = wk.make_routing(wl)
     if wl.dtype == "fp8":
         X, xs = wk.make_x(wl, dev)
@@ -41,7 +41,7 @@ def _run_full(wl, dev):
     buf.fill_(POISON)
     Y = buf[pad: pad + wl.R]
     tmap = mb.alloc_task_map(wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N, dev)
-    mb.moe_build_task_map(ids.to(dev), wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N, tmap)
+    mb.moe_build_task_map_ordered(ids.to(dev), wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N, order, tmap)
     dt = mb.MOE_DTYPE_FP8_E4M3 if wl.dtype == "fp8" else mb.MOE_DTYPE_BF16
     mb.moe_grouped_gemm(X, W, ids.to(dev), tmap, Y, mb.GemmDesc(dt, wl.T, wl.k, wl.E, wl.K, wl.N, wl.tile_m, wl.tile_n, xs, ws))
     torch.cuda.synchronize()
@@ -103,29 +103,31 @@ def _check_elements(oracle_mod, wl, ids, X, W, xs, ws, Y, rr, nn):
 
 
 FULL = [
-    # workload, samples per tile, complete rows
-    (wk.mixtral_up(4096), 8, 64),
-    (wk.mixtral_up(256), 8, 32),
-    (wk.mixtral_up(16), 8, 32),
-    (wk.mixtral_down_zipf(4096), 8, 64),
-    (wk.mixtral_down_zipf(256), 8, 32),
-    (wk.paper_eval("worst"), 8, 64),
-    (wk.decode_fp8(32), 8, 64),
-    (wk.decode_fp8(8), 8, 48),
-    (wk.decode_fp8(1), 8, 6),
+    # workload, samples per tile, complete rows, sigma order
+    (wk.mixtral_up(4096), 8, 64, 0),
+    (wk.mixtral_up(256), 8, 32, 0),
+    (wk.mixtral_up(16), 8, 32, 0),
+    (wk.mixtral_down_zipf(4096), 8, 64, 0),
+    (wk.mixtral_down_zipf(256), 8, 32, 0),
+    (wk.paper_eval("worst"), 8, 64, 0),
+    (wk.paper_eval("worst"), 8, 64, 1),
+    (wk.mixtral_down_zipf(4096), 8, 64, 1),
+    (wk.decode_fp8(32), 8, 64, 0),
+    (wk.decode_fp8(8), 8, 48, 0),
+    (wk.decode_fp8(1), 8, 6, 0),
 ]
 
 
-@pytest.mark.parametrize("wl,per_tile,nrows", FULL, ids=lambda v: f"{v.name}_T{v.T}" if hasattr(v, "name") else str(v))
-def test_full_size_sampled(oracle_mod, wl, per_tile, nrows):
+@pytest.mark.parametrize("wl,per_tile,nrows,order", FULL, ids=lambda v: f"{v.name}_T{v.T}" if hasattr(v, "name") else str(v))
+def test_full_size_sampled(oracle_mod, wl, per_tile, nrows, order):
     dev = torch.device("cuda:0")
     rng = np.random.default_rng(wl.T * 7 + wl.E)
-    ids, X, W, xs, ws, Y, tmap = _run_full(wl, dev)
+    ids, X, W, xs, ws, Y, tmap = _run_full(wl, dev, order)
     # task map: whole and bit-exact
-    tm = oracle_mod.build_task_map(ids.numpy(), wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N)
+    tm = oracle_mod.build_task_map(ids.numpy(), wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N, order=order)
     want = H.expected_blob(tm)
     np.testing.assert_array_equal(tmap.cpu().numpy()[: len(want)], want)
-    table = oracle_mod.full_table(tm.counts, wl.tile_m, wl.tile_n, wl.N)
+    table = oracle_mod.full_table(tm.counts, wl.tile_m, wl.tile_n, wl.N, sigma=tm.sigma)
     assert len(table) == tm.total_tiles
     # (a) samples in every tile
     rr, nn = _sample_points(tm, table, rng, per_tile)

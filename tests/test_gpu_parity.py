@@ -25,10 +25,13 @@ def dev():
     return torch.device("cuda:0")
 
 
-def _build_map(ids_dev, T, k, E, tile_m, tile_n, N):
+def _build_map(ids_dev, T, k, E, tile_m, tile_n, N, order=0):
     tmap = mb.alloc_task_map(max(T, 1), k, E, tile_m, tile_n, N)
     tmap.fill_(0x5A5A5A5A)
-    mb.moe_build_task_map(ids_dev, T, k, E, tile_m, tile_n, N, tmap)
+    if order == 0:
+        mb.moe_build_task_map(ids_dev, T, k, E, tile_m, tile_n, N, tmap)
+    else:
+        mb.moe_build_task_map_ordered(ids_dev, T, k, E, tile_m, tile_n, N, order, tmap)
     return tmap
 
 
@@ -51,19 +54,20 @@ MAP_CASES = [
 ]
 
 
+@pytest.mark.parametrize("order", [0, 1], ids=["ascending", "spread"])
 @pytest.mark.parametrize("T,k,E,tile_m,tile_n,N,routing", MAP_CASES)
-def test_task_map_bit_exact(dev, oracle_mod, T, k, E, tile_m, tile_n, N, routing):
+def test_task_map_bit_exact(dev, oracle_mod, T, k, E, tile_m, tile_n, N, routing, order):
     wl = wk.Workload("mapcase", T, E, k, 64, N, "bf16", routing)
     ids = wk.make_routing(wl)
-    tm = oracle_mod.build_task_map(ids.numpy(), T, k, E, tile_m, tile_n, N)
+    tm = oracle_mod.build_task_map(ids.numpy(), T, k, E, tile_m, tile_n, N, order=order)
     want = H.expected_blob(tm)
     ids_dev = ids.to(dev)
-    got1 = _build_map(ids_dev, T, k, E, tile_m, tile_n, N)
+    got1 = _build_map(ids_dev, T, k, E, tile_m, tile_n, N, order)
     assert mb.moe_task_map_status(got1) == mb.MOE_OK
     g1 = got1.cpu().numpy()
     np.testing.assert_array_equal(g1[: len(want)], want)
     # determinism: a second build gives the same bytes, scratch included
-    got2 = _build_map(ids_dev, T, k, E, tile_m, tile_n, N)
+    got2 = _build_map(ids_dev, T, k, E, tile_m, tile_n, N, order)
     torch.cuda.synchronize()
     assert torch.equal(got1, got2)
     # documented offsets are the library's offsets
@@ -76,7 +80,7 @@ def test_task_map_bit_exact(dev, oracle_mod, T, k, E, tile_m, tile_n, N, routing
     table = torch.full((max(grid, 1), 4), 7, dtype=torch.int32, device=dev)
     mb.moe_task_map_expand(got1, E, table, grid)
     tab = table.cpu().numpy()[:grid]
-    np.testing.assert_array_equal(tab[: tm.total_tiles], oracle_mod.full_table(tm.counts, tile_m, tile_n, N))
+    np.testing.assert_array_equal(tab[: tm.total_tiles], oracle_mod.full_table(tm.counts, tile_m, tile_n, N, sigma=tm.sigma))
     assert np.all(tab[tm.total_tiles:] == -1)
     if tm.total_tiles <= 6000:
         np.testing.assert_array_equal(tab[: tm.total_tiles], oracle_mod.decode_all(tm))
@@ -106,6 +110,7 @@ def test_argument_errors(dev):
     assert mb.moe_build_task_map(ids, 4, 9, 8, 16, 128, 256, tmap, check=False) == mb.MOE_ERR_INVALID_ARG
     assert mb.moe_build_task_map(ids, 4, 2, 8, 17, 128, 256, tmap, check=False) == mb.MOE_ERR_UNSUPPORTED
     assert mb.moe_build_task_map(None, 4, 2, 8, 16, 128, 256, tmap, check=False) == mb.MOE_ERR_INVALID_ARG
+    assert mb.moe_build_task_map_ordered(ids, 4, 2, 8, 16, 128, 256, 7, tmap, check=False) == mb.MOE_ERR_INVALID_ARG
     mb.moe_build_task_map(ids, 4, 2, 8, 16, 128, 256, tmap)
     X = torch.zeros(4, 256, device=dev, dtype=torch.bfloat16)
     W = torch.zeros(8, 256, 256, device=dev, dtype=torch.bfloat16)
@@ -124,14 +129,14 @@ def test_argument_errors(dev):
     assert bool(torch.isnan(Y).all())
 
 
-def _run_gemm(dev, wl, ids, X, W, xs=None, ws=None):
+def _run_gemm(dev, wl, ids, X, W, xs=None, ws=None, order=0):
     """Run map build + GEMM with Y embedded between poisoned canary rows; returns Y bits [R,N]."""
     R, N = wl.R, wl.N
     pad = 4
     buf = torch.empty((R + 2 * pad, N), dtype=torch.int16, device=dev)
     buf.fill_(POISON)
     Y = buf[pad: pad + R]
-    tmap = _build_map(ids.to(dev), wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, N)
+    tmap = _build_map(ids.to(dev), wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, N, order)
     dt = mb.MOE_DTYPE_FP8_E4M3 if wl.dtype == "fp8" else mb.MOE_DTYPE_BF16
     desc = mb.GemmDesc(dt, wl.T, wl.k, wl.E, wl.K, N, wl.tile_m, wl.tile_n,
                        None if xs is None else xs.to(dev), None if ws is None else ws.to(dev))
@@ -185,11 +190,12 @@ BF16_CASES = [
 ]
 
 
+@pytest.mark.parametrize("order", [0, 1], ids=["ascending", "spread"])
 @pytest.mark.parametrize("tile_m,tile_n,T,E,k,K,N,routing", BF16_CASES)
-def test_gemm_bf16_parity(dev, oracle_mod, tile_m, tile_n, T, E, k, K, N, routing):
+def test_gemm_bf16_parity(dev, oracle_mod, tile_m, tile_n, T, E, k, K, N, routing, order):
     wl = wk.Workload("parity_bf16", T, E, k, K, N, "bf16", routing, tile_m, tile_n)
     ids, X, W = wk.make_routing(wl), wk.make_x(wl), wk.make_w(wl)
-    got = _run_gemm(dev, wl, ids, X, W)
+    got = _run_gemm(dev, wl, ids, X, W, order=order)
     res = oracle_mod.grouped_gemm_bf16(wk.bits(X), wk.bits(W), ids.numpy())
     _check_y(got, res, X.double().numpy(), W.double().numpy(), ids.numpy(), k, K, H.tol_bf16(K))
 

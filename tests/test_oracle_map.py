@@ -179,3 +179,54 @@ def test_workload_routing_recipes():
     assert z.max() > 3 * z.min()
     b = np.bincount(wk.make_routing(wk.mixtral_up(4096)).numpy().ravel(), minlength=8)
     assert b.max() < 1.2 * b.min()
+
+
+# ------------------------------------------------------------------ expert ordering (Sec. 4.2)
+def test_spread_order_hand_example(oracle_mod):
+    g = _gold("spread_order_example.json")
+    ids = np.concatenate([np.full(c, e, np.int32) for e, c in enumerate(g["counts"])]).reshape(-1, 1)
+    T = len(ids)
+    tm = oracle_mod.build_task_map(ids, T, 1, g["E"], g["tile_m"], g["tile_n"], g["N"], order=1)
+    assert tm.counts.tolist() == g["counts"]
+    assert tm.sigma.tolist() == g["sigma"]
+    assert tm.tile_prefix.tolist() == g["tile_prefix"]
+    # the fixture is self-consistent with its own stated rule
+    rev3 = lambda r: int(f"{r:03b}"[::-1], 2)
+    assert [rev3(r) for r in g["rank"]] == g["key_bitrev3"]
+    assert [g["key_bitrev3"].index(kk) for kk in range(8)] == g["sigma"]
+
+
+@pytest.mark.parametrize("T,k,E,tile_m,tile_n,N,skew", CASES)
+def test_spread_order_properties(oracle_mod, T, k, E, tile_m, tile_n, N, skew):
+    rng = np.random.default_rng(4321 + T + E)
+    ids = _random_ids(rng, T, k, E, skew)
+    asc = oracle_mod.build_task_map(ids, T, k, E, tile_m, tile_n, N, order=0)
+    spr = oracle_mod.build_task_map(ids, T, k, E, tile_m, tile_n, N, order=1)
+    # only sigma and the prefix may differ
+    np.testing.assert_array_equal(asc.counts, spr.counts)
+    np.testing.assert_array_equal(asc.offsets, spr.offsets)
+    np.testing.assert_array_equal(asc.sorted_rows, spr.sorted_rows)
+    assert sorted(spr.sigma.tolist()) == asc.sigma.tolist() and spr.total_tiles == asc.total_tiles
+    nt = -(-N // tile_n)
+    tiles = (-(-spr.counts // tile_m)) * nt
+    np.testing.assert_array_equal(spr.tile_prefix, np.cumsum(tiles[spr.sigma]))
+    # the busiest expert comes first; the second busiest sits at the half point of the key space
+    M = spr.M
+    by_load = sorted(range(E), key=lambda e: (-tiles[e], e))
+    by_load = [e for e in by_load if spr.counts[e] > 0]
+    assert spr.sigma[0] == by_load[0]
+    if M >= 2:
+        P = 1 << (M - 1).bit_length()
+        n_before_half = sum(1 for r in range(M) if int(f"{r:0{max(P.bit_length() - 1, 1)}b}"[::-1], 2) < P // 2) if P > 1 else 0
+        assert spr.sigma[n_before_half] == by_load[1]
+    # decode of every block == nested-loop table visiting experts in sigma order
+    np.testing.assert_array_equal(oracle_mod.decode_all(spr), oracle_mod.full_table(spr.counts, tile_m, tile_n, N, sigma=spr.sigma))
+
+
+def test_spread_order_on_paper_worst_case(oracle_mod):
+    """Sec. 5 worst case: the k busy experts end up evenly spaced among the 56 one-token experts."""
+    wl = wk.paper_eval("worst")
+    ids = wk.make_routing(wl).numpy()
+    tm = oracle_mod.build_task_map(ids, wl.T, wl.k, wl.E, 256, 256, wl.N, order=1)
+    pos = sorted(int(np.where(tm.sigma == e)[0][0]) for e in range(wl.k))
+    assert pos == [0, 8, 16, 24, 32, 40, 48, 56]
