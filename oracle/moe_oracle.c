@@ -11,7 +11,11 @@
  * Conventions (the paper leaves these open; each is a fixed reading):
  *   - block index B and all arrays are 0-based: the task of block B is
  *     h = #{ i : TilePrefix[i] <= B }  (Alg. 2 as printed: p = B >= TilePrefix[t]).
- *   - nu(expert e) = ceil(c_e / tile_m) * ceil(N / tile_n)   (tiles of its GEMM).
+ *   - nu(expert e) = ceil(c_e / tile_m(e)) * ceil(N / tile_n)   (tiles of its GEMM), where
+ *     tile_m(e) is the task's tiling strategy (Sec. 3.2, Sec. 4: tasks "categorized into
+ *     several pre-defined tiling strategies"; thresholds are not given in the paper).  Two
+ *     strategies here: experts with at most small_max_rows rows use tile_m_small, all
+ *     others tile_m; small_max_rows = 0 means one strategy for every expert.
  *   - sigma lists the non-empty experts in ascending expert index (Sec. 4.1), or, with
  *     order = 1, "spread" in the half-interval manner of Sec. 4.2: the non-empty experts
  *     are ranked by tile count (largest first, ties by lower index), rank r gets the key
@@ -124,6 +128,11 @@ void orc_mapping(const int32_t* tile_prefix, int n, int B, int32_t* h_out, int32
     *l_out = B - kk;
 }
 
+/* Tiling strategy of an expert with c rows (see the conventions at the top). */
+static int expert_tile_m(int c, int tile_m, int tile_m_small, int small_max_rows) {
+    return (small_max_rows > 0 && c <= small_max_rows) ? tile_m_small : tile_m;
+}
+
 /* Bit reversal of r over nbits bits. */
 static int bit_reverse(int r, int nbits) {
     int v = 0;
@@ -158,9 +167,10 @@ static void spread_order(const int32_t* experts, const int32_t* nu, int M, int32
  *   token index arrays, stored back to back, as flat row ids r = t*k+j; the
  *   token is r / k), sigma[M] (non-empty -> real expert), tile_prefix[M].
  *   order: 0 = sigma ascending, 1 = spread (Sec. 4.2).
+ *   tile_m_small, small_max_rows: the second tiling strategy (0, 0 = none).
  * Returns 0, or -1 if an id is outside [0,E).                               */
 int orc_build_task_map(const int32_t* topk_ids, int T, int k, int E, int tile_m, int tile_n, int N, int order,
-                       int32_t* counts, int32_t* offsets, int32_t* sorted_rows, int32_t* sigma,
+                       int tile_m_small, int small_max_rows, int32_t* counts, int32_t* offsets, int32_t* sorted_rows, int32_t* sigma,
                        int32_t* tile_prefix, int32_t* M_out, int32_t* total_tiles_out) {
     int R = T * k;
     for (int e = 0; e < E; ++e) counts[e] = 0;
@@ -185,14 +195,15 @@ int orc_build_task_map(const int32_t* topk_ids, int T, int k, int E, int tile_m,
     for (int e = 0; e < E; ++e) {
         if (counts[e] > 0) {
             ne[M] = e;
-            nu[M] = ceil_div(counts[e], tile_m) * nt;
+            nu[M] = ceil_div(counts[e], expert_tile_m(counts[e], tile_m, tile_m_small, small_max_rows)) * nt;
             M += 1;
         }
     }
     if (order == 1) spread_order(ne, nu, M, sigma);
     else for (int i = 0; i < M; ++i) sigma[i] = ne[i];
     /* tile counts in sigma order, then Alg. 1 */
-    for (int i = 0; i < M; ++i) nu[i] = ceil_div(counts[sigma[i]], tile_m) * nt;
+    for (int i = 0; i < M; ++i)
+        nu[i] = ceil_div(counts[sigma[i]], expert_tile_m(counts[sigma[i]], tile_m, tile_m_small, small_max_rows)) * nt;
     orc_tile_prefix(nu, M, tile_prefix);
     free(nu);
     free(ne);
@@ -205,14 +216,15 @@ int orc_build_task_map(const int32_t* topk_ids, int T, int k, int E, int tile_m,
  * index l split into (m_tile, n_tile), m fastest.  out = {e, m_tile, n_tile,
  * rows_in_tile}.                                                           */
 void orc_decode_block(const int32_t* tile_prefix, const int32_t* sigma, int M, const int32_t* counts,
-                      int tile_m, int B, int32_t* out4) {
+                      int tile_m, int tile_m_small, int small_max_rows, int B, int32_t* out4) {
     int32_t h, l;
     orc_mapping(tile_prefix, M, B, &h, &l);
     int e = sigma[h];
-    int mt = ceil_div(counts[e], tile_m);
+    int tm = expert_tile_m(counts[e], tile_m, tile_m_small, small_max_rows); /* Alg. 3: the task's type */
+    int mt = ceil_div(counts[e], tm);
     int m_tile = l % mt, n_tile = l / mt;
-    int rows = counts[e] - m_tile * tile_m;
-    if (rows > tile_m) rows = tile_m;
+    int rows = counts[e] - m_tile * tm;
+    if (rows > tm) rows = tm;
     out4[0] = e; out4[1] = m_tile; out4[2] = n_tile; out4[3] = rows;
 }
 
@@ -221,18 +233,19 @@ void orc_decode_block(const int32_t* tile_prefix, const int32_t* sigma, int M, c
  * at all.  It is an independent definition of the same map.  expert_order
  * lists all E experts in visiting order (empty ones contribute no entry).
  * Returns the number of entries written (room for cap entries of 4 ints).  */
-int orc_full_table(const int32_t* counts, int E, const int32_t* expert_order, int tile_m, int tile_n, int N,
-                   int32_t* table, int cap) {
+int orc_full_table(const int32_t* counts, int E, const int32_t* expert_order, int tile_m, int tile_m_small,
+                   int small_max_rows, int tile_n, int N, int32_t* table, int cap) {
     int b = 0;
     int nt = ceil_div(N, tile_n);
     for (int i = 0; i < E; ++i) {
         int e = expert_order ? expert_order[i] : i; /* experts are visited in this order; NULL = 0,1,2,... */
-        int mt = ceil_div(counts[e], tile_m);
+        int tm = expert_tile_m(counts[e], tile_m, tile_m_small, small_max_rows);
+        int mt = ceil_div(counts[e], tm);
         for (int n_tile = 0; n_tile < nt; ++n_tile)
             for (int m_tile = 0; m_tile < mt; ++m_tile) {
                 if (b >= cap) return -1;
-                int rows = counts[e] - m_tile * tile_m;
-                if (rows > tile_m) rows = tile_m;
+                int rows = counts[e] - m_tile * tm;
+                if (rows > tm) rows = tm;
                 table[4 * b + 0] = e; table[4 * b + 1] = m_tile;
                 table[4 * b + 2] = n_tile; table[4 * b + 3] = rows;
                 b += 1;

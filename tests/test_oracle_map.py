@@ -230,3 +230,40 @@ def test_spread_order_on_paper_worst_case(oracle_mod):
     tm = oracle_mod.build_task_map(ids, wl.T, wl.k, wl.E, 256, 256, wl.N, order=1)
     pos = sorted(int(np.where(tm.sigma == e)[0][0]) for e in range(wl.k))
     assert pos == [0, 8, 16, 24, 32, 40, 48, 56]
+
+
+# ------------------------------------------------------------------ two tiling strategies (Alg. 3)
+def test_two_tilings_hand_example(oracle_mod):
+    g = _gold("two_tilings_example.json")
+    ids = np.concatenate([np.full(c, e, np.int32) for e, c in enumerate(g["counts"])]).reshape(-1, 1)
+    tm = oracle_mod.build_task_map(ids, len(ids), 1, g["E"], g["tile_m"], g["tile_n"], g["N"],
+                                   tile_m_small=g["tile_m_small"], small_max_rows=g["small_max_rows"])
+    assert [tm.expert_tile_m(e) for e in range(g["E"])] == g["expert_tile_m"]
+    assert tm.sigma.tolist() == g["sigma"]
+    assert tm.tile_prefix.tolist() == g["tile_prefix"]
+    assert oracle_mod.decode_all(tm).tolist() == g["table"]
+    assert oracle_mod.full_table(tm.counts, g["tile_m"], g["tile_n"], g["N"], tile_m_small=g["tile_m_small"],
+                                 small_max_rows=g["small_max_rows"]).tolist() == g["table"]
+
+
+@pytest.mark.parametrize("order", [0, 1])
+@pytest.mark.parametrize("T,k,E,tile_m,tile_n,N,skew", CASES)
+def test_two_tilings_properties(oracle_mod, T, k, E, tile_m, tile_n, N, skew, order):
+    rng = np.random.default_rng(777 + T + E)
+    ids = _random_ids(rng, T, k, E, skew)
+    small, thr = 16, 24
+    tm = oracle_mod.build_task_map(ids, T, k, E, max(tile_m, 32), tile_n, N, order=order, tile_m_small=small, small_max_rows=thr)
+    big = max(tile_m, 32)
+    nt = -(-N // tile_n)
+    etm = np.array([small if 0 < c <= thr else big for c in tm.counts])
+    mt = np.where(tm.counts > 0, -(-tm.counts // etm), 0)
+    np.testing.assert_array_equal(tm.tile_prefix, np.cumsum(mt[tm.sigma] * nt))
+    table = oracle_mod.decode_all(tm)
+    np.testing.assert_array_equal(table, oracle_mod.full_table(tm.counts, big, tile_n, N, sigma=tm.sigma,
+                                                                tile_m_small=small, small_max_rows=thr))
+    # every routed row is covered exactly once per n-tile, with the tile height of its expert's strategy
+    for n in range(nt):
+        sub = table[table[:, 2] == n]
+        assert sub[:, 3].sum() == T * k
+    for e, m_tile, n_tile, rows in table.tolist():
+        assert rows == min(etm[e], tm.counts[e] - m_tile * etm[e]) and rows >= 1
