@@ -49,9 +49,10 @@ def algorithmic_bytes(wl: wk.Workload, ids: torch.Tensor) -> int:
 class Point:
     """Device buffers of one workload (optionally several weight copies to defeat the caches)."""
 
-    def __init__(self, wl: wk.Workload, copies: int = 1, dev="cuda:0", order: int = 0):
+    def __init__(self, wl: wk.Workload, copies: int = 1, dev="cuda:0", order: int = 0, small=(0, 0)):
         self.wl = wl
         self.order = order
+        self.small = small  # (tile_m_small, small_max_rows) of the second tiling strategy, or (0, 0)
         self.dev = dev
         self.ids_cpu = wk.make_routing(wl)
         self.ids = self.ids_cpu.to(dev)
@@ -67,11 +68,12 @@ class Point:
         self.Y = torch.empty((wl.R, wl.N), dtype=torch.bfloat16, device=dev)
         self.tmap = mb.alloc_task_map(wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N, dev)
         dt = mb.MOE_DTYPE_FP8_E4M3 if wl.dtype == "fp8" else mb.MOE_DTYPE_BF16
-        self.desc = mb.GemmDesc(dt, wl.T, wl.k, wl.E, wl.K, wl.N, wl.tile_m, wl.tile_n, self.xs, self.ws)
+        self.desc = mb.GemmDesc(dt, wl.T, wl.k, wl.E, wl.K, wl.N, wl.tile_m, wl.tile_n, self.xs, self.ws, *small)
 
     def build_map(self):
         wl = self.wl
-        mb.moe_build_task_map_ordered(self.ids, wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N, self.order, self.tmap)
+        mb.moe_build_task_map_tiled(self.ids, wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N, self.order,
+                                    self.small[0], self.small[1], self.tmap)
 
     def gemm(self, i: int = 0):
         mb.moe_grouped_gemm(self.X, self.W[i % len(self.W)], self.ids, self.tmap, self.Y, self.desc)
@@ -118,7 +120,7 @@ class Point:
         ideal_hbm = abytes / (PEAK_HBM_GBS * 1e9)
         bound = "mfma" if ideal_mfma >= ideal_hbm else "hbm"
         return dict(workload=f"{wl.name}_T{wl.T}", dtype=wl.dtype, T=wl.T, E=wl.E, k=wl.k, K=wl.K, N=wl.N,
-                    tile=[wl.tile_m, wl.tile_n], sigma_order=("spread" if self.order else "ascending"), ms_per_step=round(wall_ms, 4), gemm_ms=round(gemm_ms, 4),
+                    tile=[wl.tile_m, wl.tile_n], sigma_order=("spread" if self.order else "ascending"), small_strategy=list(self.small), ms_per_step=round(wall_ms, 4), gemm_ms=round(gemm_ms, 4),
                     map_ms=round(map_ms, 4), tflops_step=round(tf_step, 2), tflops_gemm=round(tf_gemm, 2),
                     frac_mfma=round(tf_gemm / peak_t, 4), gbs_gemm=round(gbs, 1),
                     frac_hbm=round(gbs / PEAK_HBM_GBS, 4), bound=bound, alg_bytes=abytes, flops=wl.flops)
@@ -188,6 +190,8 @@ def main():
     ap.add_argument("--tile", default="", help="override tile_m,tile_n of the headline workload")
     ap.add_argument("--order", default="ascending", choices=["ascending", "spread", "both"],
                     help="expert order in sigma for the extra points (the headline always uses ascending)")
+    ap.add_argument("--small", default="0,0",
+                    help="tile_m_small,small_max_rows: second tiling strategy for the extra points with 256x256 tiles")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (a kernel of known traffic to scale profiler byte counters by)")
@@ -247,8 +251,11 @@ def main():
                 # enough full copies that an iteration never finds its experts cached by an earlier one
                 touched = int(torch.unique(wk.make_routing(w)).numel()) * w.K * w.N
                 copies = min(16, max(4, -(-int(1.2e9) // touched)))
+            small = tuple(int(v) for v in args.small.split(","))
+            if small[0] and not (w.dtype == "bf16" and mb.moe_tile_pair_supported(mb.MOE_DTYPE_BF16, w.tile_m, w.tile_n, small[0])):
+                small = (0, 0)
             for order in ([0, 1] if args.order == "both" else [1 if args.order == "spread" else 0]):
-                p = Point(w, copies, order=order)
+                p = Point(w, copies, order=order, small=small)
                 points.append(p.report(max(10, args.steps // 2), max(3, args.warmup // 2)))
                 del p
                 torch.cuda.empty_cache()

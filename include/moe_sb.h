@@ -56,7 +56,8 @@ enum { MOE_ORDER_ASCENDING = 0, MOE_ORDER_SPREAD = 1 };
  *                            offsets[e+1]), ascending in r; token = r / k
  *   scratch      [...]       private to the library
  *
- * Tiles of expert e: nu(e) = ceil(counts[e]/tile_m) * ceil(N/tile_n).
+ * Tiles of expert e: nu(e) = ceil(counts[e]/tile_m(e)) * ceil(N/tile_n), tile_m(e) = tile_m unless a
+ * second tiling strategy is in use (moe_build_task_map_tiled).
  * Block B (0-based) belongs to non-empty task h = #{ i : tile_prefix[i] <= B }
  * (Alg. 2), expert sigma[h] (Alg. 4), tile l = B - tile_prefix[h-1], and
  * m_tile = l % mt_e, n_tile = l / mt_e  (order 0 = "m fastest").
@@ -78,7 +79,9 @@ enum {
     MOE_HDR_STATUS = 11,     /* 0, or the number of routing ids outside [0,E) */
     MOE_HDR_R = 12,          /* T*k */
     MOE_HDR_E64 = 13,
-    MOE_HDR_SIGMA_ORDER = 14 /* MOE_ORDER_* the map was built with */
+    MOE_HDR_SIGMA_ORDER = 14,    /* MOE_ORDER_* the map was built with */
+    MOE_HDR_TILE_M_SMALL = 15,   /* second tiling strategy (0 = none), see moe_build_task_map_tiled */
+    MOE_HDR_SMALL_MAX_ROWS = 16
 };
 
 /* Word offsets of the blob's fields for a given E (HOST, pure). */
@@ -132,6 +135,24 @@ int moe_build_task_map_ordered(const int32_t* topk_ids, int T, int k, int E, int
                                int order, void* task_map, void* stream);
 
 /*
+ * Same, with two tiling strategies in one batch (Alg. 3: tasks of different types / tiling
+ * strategies dispatched inside one kernel; Sec. 4: "GEMMs with large input and output sizes prefer
+ * large tiles").  The paper gives neither shapes nor thresholds; here an expert with at most
+ * small_max_rows rows is tiled with tile_m_small rows per tile, every other expert with tile_m:
+ *     nu(e) = ceil(counts[e] / tile_m(e)) * ceil(N / tile_n).
+ * tile_m_small in {16,32,64,128}, tile_m_small < tile_m, 1 <= small_max_rows <= 4*tile_m_small;
+ * tile_m_small = small_max_rows = 0 gives moe_build_task_map_ordered.  The pair must be passed
+ * unchanged to moe_grouped_gemm (desc->tile_m_small, desc->small_max_rows).
+ */
+int moe_build_task_map_tiled(const int32_t* topk_ids, int T, int k, int E, int tile_m, int tile_n, int N, int order,
+                             int tile_m_small, int small_max_rows, void* task_map, void* stream);
+
+/* Grid bound for a two-strategy map (HOST, pure):
+ *   (floor(R/tile_m) + min(E,R) * max(1, ceil(small_max_rows/tile_m_small))) * ceil(N/tile_n). */
+int64_t moe_grid_upper_bound_tiled(int T, int k, int E, int tile_m, int tile_n, int N, int tile_m_small,
+                                   int small_max_rows);
+
+/*
  * Synchronises the stream and returns MOE_ERR_ROUTING if the map recorded a
  * bad routing id, MOE_ERR_INVALID_ARG if the blob is not a map, else MOE_OK.
  */
@@ -153,6 +174,7 @@ typedef struct moe_gemm_desc {
     int32_t tile_m, tile_n; /* must equal what the map was built with */
     const float* x_scale; /* DEVICE fp32 [T], per-token scale  (fp8 only, else NULL) */
     const float* w_scale; /* DEVICE fp32 [E], per-expert scale (fp8 only, else NULL) */
+    int32_t tile_m_small, small_max_rows; /* second tiling strategy of the map, or 0, 0 */
 } moe_gemm_desc;
 
 /*
@@ -177,6 +199,8 @@ int moe_grouped_gemm(const void* X, const void* W, const int32_t* topk_ids, cons
 
 /* 1 if a GEMM kernel exists for this (dtype, tile_m, tile_n), else 0.  HOST, pure. */
 int moe_tile_supported(int dtype, int tile_m, int tile_n);
+/* 1 if a two-strategy GEMM kernel exists for (dtype, tile_m, tile_n) + tile_m_small.  HOST, pure. */
+int moe_tile_pair_supported(int dtype, int tile_m, int tile_n, int tile_m_small);
 
 /* Static string for a return code. */
 const char* moe_strerror(int code);

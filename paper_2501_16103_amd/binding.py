@@ -30,12 +30,13 @@ MOE_ORDER_SPREAD = 1
 MOE_MAP_MAGIC = 0x3142534D
 MOE_MAP_HDR_WORDS = 32
 HDR = dict(MAGIC=0, T=1, K_TOP=2, E=3, N=4, TILE_M=5, TILE_N=6, NT=7, M=8, TOTAL_TILES=9, ORDER=10,
-           STATUS=11, R=12, E64=13, SIGMA_ORDER=14)
+           STATUS=11, R=12, E64=13, SIGMA_ORDER=14, TILE_M_SMALL=15,
+           SMALL_MAX_ROWS=16)
 
 EXPORTS = [
     "moe_map_off_counts", "moe_map_off_offsets", "moe_map_off_sigma", "moe_map_off_tile_prefix",
     "moe_map_off_sorted_rows", "moe_task_map_bytes", "moe_grid_upper_bound", "moe_build_task_map",
-    "moe_build_task_map_ordered",
+    "moe_build_task_map_ordered", "moe_build_task_map_tiled", "moe_grid_upper_bound_tiled", "moe_tile_pair_supported",
     "moe_task_map_status", "moe_task_map_expand", "moe_grouped_gemm", "moe_tile_supported", "moe_strerror",
 ]
 
@@ -49,7 +50,8 @@ class MoeError(RuntimeError):
 class moe_gemm_desc(ctypes.Structure):
     _fields_ = [("dtype", ctypes.c_int32), ("T", ctypes.c_int32), ("k", ctypes.c_int32), ("E", ctypes.c_int32),
                 ("K", ctypes.c_int32), ("N", ctypes.c_int32), ("tile_m", ctypes.c_int32),
-                ("tile_n", ctypes.c_int32), ("x_scale", ctypes.c_void_p), ("w_scale", ctypes.c_void_p)]
+                ("tile_n", ctypes.c_int32), ("x_scale", ctypes.c_void_p), ("w_scale", ctypes.c_void_p),
+                ("tile_m_small", ctypes.c_int32), ("small_max_rows", ctypes.c_int32)]
 
 
 _lib = None
@@ -74,6 +76,12 @@ def lib() -> ctypes.CDLL:
         L.moe_build_task_map.argtypes = [ctypes.c_void_p] + [ctypes.c_int] * 6 + [ctypes.c_void_p, ctypes.c_void_p]
         L.moe_build_task_map_ordered.restype = ctypes.c_int
         L.moe_build_task_map_ordered.argtypes = [ctypes.c_void_p] + [ctypes.c_int] * 7 + [ctypes.c_void_p, ctypes.c_void_p]
+        L.moe_build_task_map_tiled.restype = ctypes.c_int
+        L.moe_build_task_map_tiled.argtypes = [ctypes.c_void_p] + [ctypes.c_int] * 9 + [ctypes.c_void_p, ctypes.c_void_p]
+        L.moe_grid_upper_bound_tiled.restype = ctypes.c_int64
+        L.moe_grid_upper_bound_tiled.argtypes = [ctypes.c_int] * 8
+        L.moe_tile_pair_supported.restype = ctypes.c_int
+        L.moe_tile_pair_supported.argtypes = [ctypes.c_int] * 4
         L.moe_task_map_status.restype = ctypes.c_int
         L.moe_task_map_status.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
         L.moe_task_map_expand.restype = ctypes.c_int
@@ -142,6 +150,25 @@ def moe_build_task_map_ordered(topk_ids: torch.Tensor, T: int, k: int, E: int, t
     return rc
 
 
+def moe_build_task_map_tiled(topk_ids: torch.Tensor, T: int, k: int, E: int, tile_m: int, tile_n: int, N: int,
+                             order: int, tile_m_small: int, small_max_rows: int, task_map: torch.Tensor,
+                             check: bool = True) -> int:
+    rc = lib().moe_build_task_map_tiled(_ptr(topk_ids), T, k, E, tile_m, tile_n, N, order, tile_m_small,
+                                        small_max_rows, _ptr(task_map), _stream())
+    if check and rc != MOE_OK:
+        raise MoeError(rc, "moe_build_task_map_tiled")
+    return rc
+
+
+def moe_grid_upper_bound_tiled(T: int, k: int, E: int, tile_m: int, tile_n: int, N: int, tile_m_small: int,
+                               small_max_rows: int) -> int:
+    return int(lib().moe_grid_upper_bound_tiled(T, k, E, tile_m, tile_n, N, tile_m_small, small_max_rows))
+
+
+def moe_tile_pair_supported(dtype: int, tile_m: int, tile_n: int, tile_m_small: int) -> bool:
+    return bool(lib().moe_tile_pair_supported(dtype, tile_m, tile_n, tile_m_small))
+
+
 def moe_task_map_status(task_map: torch.Tensor) -> int:
     return int(lib().moe_task_map_status(_ptr(task_map), _stream()))
 
@@ -165,11 +192,14 @@ class GemmDesc:
     tile_n: int
     x_scale: Optional[torch.Tensor] = None
     w_scale: Optional[torch.Tensor] = None
+    tile_m_small: int = 0
+    small_max_rows: int = 0
 
     def c_struct(self) -> moe_gemm_desc:
         return moe_gemm_desc(self.dtype, self.T, self.k, self.E, self.K, self.N, self.tile_m, self.tile_n,
                              None if self.x_scale is None else self.x_scale.data_ptr(),
-                             None if self.w_scale is None else self.w_scale.data_ptr())
+                             None if self.w_scale is None else self.w_scale.data_ptr(),
+                             self.tile_m_small, self.small_max_rows)
 
 
 def moe_grouped_gemm(X: torch.Tensor, W: torch.Tensor, topk_ids: Optional[torch.Tensor], task_map: torch.Tensor,

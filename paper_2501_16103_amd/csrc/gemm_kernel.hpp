@@ -4,12 +4,10 @@
 // into (expert, m-tile, n-tile) with the wavefront vote of Alg. 2, gathers the
 // tile's token rows through the expert's token index array (Sec. 4.3), and runs
 // an LDS pipeline feeding MFMA (the CDNA4 counterpart of the pipeline of
-// Sec. 4.4).  Two kernels share this layout:
-//   moe_gemm_pipe_kernel  tiles of >= 32 token rows, bf16: global->LDS DMA ring
-//                         (no register staging), hand-placed MFMA / LDS-read /
-//                         DMA interleave, per-wavefront skipping of all-padding
-//                         32-row blocks in an expert's last m-tile.
-//   moe_gemm_kernel       16-row tiles and fp8: register-staged double buffer.  The contraction is computed transposed: the weight
+// Sec. 4.4): a global->LDS DMA ring (no register staging), hand-placed MFMA /
+// LDS-read / DMA interleave, per-wavefront skipping of all-padding row blocks in
+// an expert's last m-tile.  moe_gemm_pipe_kernel runs one tiling strategy,
+// moe_gemm_pipe2_kernel two (Alg. 3 with two task types).  The contraction is computed transposed: the weight
 // tile is the MFMA "A" operand (accumulator rows = output columns n) and the
 // token tile the "B" operand (accumulator columns = token rows m), so that each
 // lane ends up with runs of 4 consecutive n for one token row.
@@ -46,270 +44,16 @@ struct GemmArgs {
     const float* x_scale;
     const float* w_scale;
     int T, k, E, K, N;
+    int tile_m_small, small_max_rows;  // second tiling strategy of the map (0, 0 = none)
 };
-
-template <int BM_, int BN_, int BK_, int WM_, int WN_, bool FP8_, int SWX_SHIFT_ = 1>
-struct GemmCfg {
-    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_;
-    static constexpr bool FP8 = FP8_;
-    static constexpr int SWX_SHIFT = SWX_SHIFT_;
-    static constexpr int ES = FP8 ? 1 : 2;            // bytes per element
-    static constexpr int NT = 64 * WM * WN;           // threads per workgroup
-    static constexpr int WTM = BM / WM, WTN = BN / WN; // per-wavefront extents
-    static constexpr int MF = (!FP8 && WTM >= 32) ? 32 : 16;  // MFMA block edge
-    static constexpr int KS = MF == 32 ? 16 : 32;     // k elements per MFMA
-    static constexpr int NBW = WTN / MF, MBW = WTM / MF;
-    static constexpr int XROW = BK * ES;              // bytes per token row in LDS
-    static constexpr int CPR = XROW / 16;             // 16-byte chunks per token row
-    static constexpr int WROW = BN * ES;              // bytes per k-row of the weight tile
-    static constexpr int CPRW = WROW / 16;
-    static constexpr int XS_BYTES = BM * XROW, WS_BYTES = BK * WROW;
-    static constexpr int STAGE_BYTES = XS_BYTES + WS_BYTES;
-    static constexpr int LDS_BYTES = 2 * STAGE_BYTES + BM * 4;
-    static constexpr int A_CHUNKS = BM * CPR, B_CHUNKS = BK * CPRW;
-    static constexpr int A_IT = (A_CHUNKS + NT - 1) / NT, B_IT = B_CHUNKS / NT;
-    static_assert(XROW == 128, "token tile rows are 128 bytes");
-    static_assert(WTM % MF == 0 && WTN % MF == 0, "wave tile must be a multiple of the MFMA block");
-    static_assert(B_CHUNKS % NT == 0 && NT % CPRW == 0, "weight tile load must divide evenly");
-    static_assert(BK % KS == 0, "BK");
-};
-
-// XOR swizzles on the 16-byte chunk index, chosen so that the lanes one LDS
-// instruction serves together fall on different banks.
-template <class C>
-__device__ __forceinline__ int swz_x(int row) {
-    return (row >> C::SWX_SHIFT) & 7;
-}
-template <class C>
-__device__ __forceinline__ int swz_w(int krow) {
-    int s;
-    if constexpr (C::FP8) {
-        s = C::CPRW >= 16 ? (krow & 15) : ((krow >> 1) & 7);
-    } else if constexpr (C::MF == 32) {
-        s = (krow & 3) << 2;
-    } else {
-        s = ((krow & 3) | ((krow >> 1) & 4)) << 1;
-    }
-    return s & (C::CPRW - 1);
-}
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
     bf16x2_t p = {(__bf16)a, (__bf16)b};  // hardware round-to-nearest-even
     return __builtin_bit_cast(uint32_t, p);
 }
 
-template <class C>
-__global__ __launch_bounds__(C::NT) void moe_gemm_kernel(GemmArgs a) {
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    constexpr int BM = C::BM, BN = C::BN, BK = C::BK, ES = C::ES, NT = C::NT;
-    const int32_t* __restrict__ map = a.map;
-
-    // ---- which tile am I?  (Alg. 2 + Alg. 4; every wavefront decodes for itself)
-    const int total = map[MOE_HDR_TOTAL_TILES];
-    const bool hdr_ok = map[MOE_HDR_MAGIC] == MOE_MAP_MAGIC && map[MOE_HDR_T] == a.T && map[MOE_HDR_K_TOP] == a.k &&
-                        map[MOE_HDR_E] == a.E && map[MOE_HDR_N] == a.N && map[MOE_HDR_TILE_M] == BM &&
-                        map[MOE_HDR_TILE_N] == BN && map[MOE_HDR_STATUS] == 0;
-    if (!hdr_ok) return;
-    // Workgroup ids are dealt round-robin to the 8 XCDs; give each XCD one contiguous
-    // run of block indices so that neighbours in the map share an L2.
-    const int per_xcd = (total + 7) >> 3;
-    const int slot = blockIdx.x >> 3;
-    if (slot >= per_xcd) return;
-    const int B = (blockIdx.x & 7) * per_xcd + slot;
-    if (B >= total) return;
-    const MapLayout L = map_layout(a.E);
-    const TileCoord tc = decode_block(map, L, BM, B);
-    const int n0 = tc.n_tile * BN;
-
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / C::WN, wn = wave % C::WN;
-
-    int* s_row = reinterpret_cast<int*>(smem + 2 * C::STAGE_BYTES);
-    for (int i = tid; i < BM; i += NT) s_row[i] = i < tc.rows ? map[L.off_rows + tc.row_base + i] : -1;
-    __syncthreads();
-
-    // ---- per-thread global source offsets
-    const char* Xb = static_cast<const char*>(a.X);
-    uint32_t x_off[C::A_IT];
-    int x_lds[C::A_IT];
-#pragma unroll
-    for (int i = 0; i < C::A_IT; ++i) {
-        const int q = tid + i * NT;
-        const int row = (q / C::CPR) % BM, c = q % C::CPR;
-        int r = s_row[row];
-        if (r < 0) r = s_row[0];  // rows past the expert's count: load a valid row, never store it
-        const int tok = r / a.k;
-        x_off[i] = (uint32_t)tok * (uint32_t)(a.K * ES) + c * 16;
-        x_lds[i] = row * C::XROW + ((c ^ swz_x<C>(row)) << 4);
-    }
-    const size_t w_row_bytes = (size_t)a.N * ES;
-    const int krow0 = tid / C::CPRW, wc = tid % C::CPRW;
-    const char* wp = static_cast<const char*>(a.W) + ((size_t)tc.e * a.K * a.N + n0) * ES + krow0 * w_row_bytes + wc * 16;
-    const size_t w_it_stride = (size_t)(NT / C::CPRW) * w_row_bytes;
-    const size_t w_kt_stride = (size_t)BK * w_row_bytes;
-
-    u32x4_t ra[C::A_IT], rb[C::B_IT];
-    auto gload = [&](int kt) {
-#pragma unroll
-        for (int i = 0; i < C::A_IT; ++i)
-            if (C::A_CHUNKS % NT == 0 || tid + i * NT < C::A_CHUNKS)
-                ra[i] = *reinterpret_cast<const u32x4_t*>(Xb + x_off[i] + (size_t)kt * (BK * ES));
-#pragma unroll
-        for (int i = 0; i < C::B_IT; ++i) rb[i] = *reinterpret_cast<const u32x4_t*>(wp + kt * w_kt_stride + i * w_it_stride);
-    };
-    auto lstore = [&](int stage) {
-        char* xs = smem + stage * C::STAGE_BYTES;
-        char* ws = xs + C::XS_BYTES;
-#pragma unroll
-        for (int i = 0; i < C::A_IT; ++i)
-            if (C::A_CHUNKS % NT == 0 || tid + i * NT < C::A_CHUNKS) *reinterpret_cast<u32x4_t*>(xs + x_lds[i]) = ra[i];
-#pragma unroll
-        for (int i = 0; i < C::B_IT; ++i) {
-            const int krow = krow0 + i * (NT / C::CPRW);
-            *reinterpret_cast<u32x4_t*>(ws + krow * C::WROW + ((wc ^ swz_w<C>(krow)) << 4)) = rb[i];
-        }
-    };
-
-    // ---- accumulators
-    using acc_t = typename std::conditional<C::MF == 32, f32x16_t, f32x4_t>::type;
-    acc_t acc[C::NBW][C::MBW];
-#pragma unroll
-    for (int nb = 0; nb < C::NBW; ++nb)
-#pragma unroll
-        for (int mb = 0; mb < C::MBW; ++mb)
-#pragma unroll
-            for (int j = 0; j < (C::MF == 32 ? 16 : 4); ++j) acc[nb][mb][j] = 0.f;
-
-    const int g = lane >> 4, li = lane & 15;
-
-    auto compute = [&](int stage) {
-        const char* xs = smem + stage * C::STAGE_BYTES;
-        const char* ws = xs + C::XS_BYTES;
-#pragma unroll
-        for (int kk = 0; kk < BK / C::KS; ++kk) {
-            if constexpr (!C::FP8) {
-                bf16x8_t wf[C::NBW], xf[C::MBW];
-#pragma unroll
-                for (int nb = 0; nb < C::NBW; ++nb) {
-                    int krow, ncol;
-                    if constexpr (C::MF == 32) {
-                        krow = kk * 16 + 8 * (g >> 1) + (li >> 2);
-                        ncol = wn * C::WTN + nb * 32 + 16 * (g & 1) + 4 * (li & 3);
-                    } else {
-                        krow = kk * 32 + 8 * g + (li >> 2);
-                        ncol = wn * C::WTN + nb * 16 + 4 * (li & 3);
-                    }
-                    const int c = ncol >> 3, within = (ncol & 7) * 2;
-                    const char* p0 = ws + krow * C::WROW + ((c ^ swz_w<C>(krow)) << 4) + within;
-                    const char* p1 = ws + (krow + 4) * C::WROW + ((c ^ swz_w<C>(krow + 4)) << 4) + within;
-                    const s16x4_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((MOE_LDS(s16x4_t)*)(p0));
-                    const s16x4_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((MOE_LDS(s16x4_t)*)(p1));
-                    const s16x8_t both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    wf[nb] = __builtin_bit_cast(bf16x8_t, both);
-                }
-#pragma unroll
-                for (int mb = 0; mb < C::MBW; ++mb) {
-                    int row, c;
-                    if constexpr (C::MF == 32) {
-                        row = wm * C::WTM + mb * 32 + (lane & 31);
-                        c = kk * 2 + (lane >> 5);
-                    } else {
-                        row = wm * C::WTM + mb * 16 + li;
-                        c = kk * 4 + g;
-                    }
-                    xf[mb] = *reinterpret_cast<const bf16x8_t*>(xs + row * C::XROW + ((c ^ swz_x<C>(row)) << 4));
-                }
-#pragma unroll
-                for (int nb = 0; nb < C::NBW; ++nb)
-#pragma unroll
-                    for (int mb = 0; mb < C::MBW; ++mb) {
-                        if constexpr (C::MF == 32)
-                            acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[nb], xf[mb], acc[nb][mb], 0, 0, 0);
-                        else
-                            acc[nb][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[nb], xf[mb], acc[nb][mb], 0, 0, 0);
-                    }
-            } else {
-                long wf[C::NBW], xf[C::MBW];
-#pragma unroll
-                for (int nb = 0; nb < C::NBW; ++nb) {
-                    const int krow = kk * 32 + 8 * g + (li >> 1);
-                    const int ncol = wn * C::WTN + nb * 16 + 8 * (li & 1);
-                    const int c = ncol >> 4, within = ncol & 15;
-                    const char* p0 = ws + krow * C::WROW + ((c ^ swz_w<C>(krow)) << 4) + within;
-                    const i32x2_t v = __builtin_amdgcn_ds_read_tr8_b64_v2i32((MOE_LDS(i32x2_t)*)(p0));
-                    wf[nb] = __builtin_bit_cast(long, v);
-                }
-#pragma unroll
-                for (int mb = 0; mb < C::MBW; ++mb) {
-                    const int row = wm * C::WTM + mb * 16 + li;
-                    const int c = kk * 2 + (g >> 1);
-                    xf[mb] = *reinterpret_cast<const long*>(xs + row * C::XROW + ((c ^ swz_x<C>(row)) << 4) + (g & 1) * 8);
-                }
-#pragma unroll
-                for (int nb = 0; nb < C::NBW; ++nb)
-#pragma unroll
-                    for (int mb = 0; mb < C::MBW; ++mb)
-                        acc[nb][mb] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(wf[nb], xf[mb], acc[nb][mb], 0, 0, 0);
-            }
-        }
-    };
-
-    // ---- main loop: global loads for tile kt+1 fly while tile kt is multiplied
-    const int KT = a.K / BK;
-    gload(0);
-    lstore(0);
-    __syncthreads();
-    for (int kt = 0; kt < KT; ++kt) {
-        const bool more = kt + 1 < KT;
-        if (more) gload(kt + 1);
-        compute(kt & 1);
-        if (more) lstore((kt + 1) & 1);
-        __syncthreads();
-    }
-
-    // ---- epilogue: fp32 -> bf16 (RNE), scatter to Y[r, n]
-    char* Yb = static_cast<char*>(a.Y);
-    const size_t y_row_bytes = (size_t)a.N * 2;
-#pragma unroll
-    for (int mb = 0; mb < C::MBW; ++mb) {
-        const int m_local = wm * C::WTM + mb * C::MF + (C::MF == 32 ? (lane & 31) : li);
-        const int r = s_row[m_local];
-        if (r < 0) continue;
-        float scale = 1.f;
-        if constexpr (C::FP8) scale = a.x_scale[r / a.k];
-        float wscale = 1.f;
-        if constexpr (C::FP8) wscale = a.w_scale[tc.e];
-        char* yrow = Yb + (size_t)r * y_row_bytes + (size_t)n0 * 2;
-#pragma unroll
-        for (int nb = 0; nb < C::NBW; ++nb) {
-            if constexpr (C::MF == 32) {
-#pragma unroll
-                for (int jq = 0; jq < 4; ++jq) {
-                    const int n_local = wn * C::WTN + nb * 32 + 8 * jq + 4 * (lane >> 5);
-                    u32x2_t v;
-                    v.x = pack_bf16(acc[nb][mb][4 * jq + 0], acc[nb][mb][4 * jq + 1]);
-                    v.y = pack_bf16(acc[nb][mb][4 * jq + 2], acc[nb][mb][4 * jq + 3]);
-                    *reinterpret_cast<u32x2_t*>(yrow + n_local * 2) = v;
-                }
-            } else {
-                const int n_local = wn * C::WTN + nb * 16 + 4 * g;
-                float v0 = acc[nb][mb][0], v1 = acc[nb][mb][1], v2 = acc[nb][mb][2], v3 = acc[nb][mb][3];
-                if constexpr (C::FP8) {
-                    v0 = (v0 * scale) * wscale; v1 = (v1 * scale) * wscale;
-                    v2 = (v2 * scale) * wscale; v3 = (v3 * scale) * wscale;
-                }
-                u32x2_t v;
-                v.x = pack_bf16(v0, v1);
-                v.y = pack_bf16(v2, v3);
-                *reinterpret_cast<u32x2_t*>(yrow + n_local * 2) = v;
-            }
-        }
-    }
-}
-
-
 // ---------------------------------------------------------------------------
-// Pipelined kernel (all tile shapes, bf16 and fp8)
+// The tile function (all tile shapes, bf16 and fp8)
 // ---------------------------------------------------------------------------
 
 // The compiler may not move anything across this point.
@@ -377,24 +121,12 @@ __device__ __forceinline__ int pswz_w(int krow) {
 //                           instructions that refill stage `cur` with tile kt+NS
 // so neither the barrier nor the DMA issue leaves the MFMA pipe without queued work, and NS-1 tiles of
 // weights per workgroup are in flight from HBM at any time.
+// One tile of the batch: everything after the task-map decode.  A task function in the sense of Alg. 3.
 template <class C>
-__global__ __launch_bounds__(C::NT) void moe_gemm_pipe_kernel(GemmArgs a) {
-    extern __shared__ __attribute__((aligned(16))) char smem[];
+__device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __restrict__ map, const MapLayout& L,
+                                          const TileCoord& tc, char* smem) {
     constexpr int BM = C::BM, BN = C::BN, BK = C::BK, ES = C::ES, NT = C::NT, NW = NT / 64, NS = C::NS, MF = C::MF;
     constexpr int KSTEPS = C::KSTEPS, NREADS = C::NREADS, NM = C::NM, WREADS = C::WREADS;
-    const int32_t* __restrict__ map = a.map;
-    const int total = map[MOE_HDR_TOTAL_TILES];
-    const bool hdr_ok = map[MOE_HDR_MAGIC] == MOE_MAP_MAGIC && map[MOE_HDR_T] == a.T && map[MOE_HDR_K_TOP] == a.k &&
-                        map[MOE_HDR_E] == a.E && map[MOE_HDR_N] == a.N && map[MOE_HDR_TILE_M] == BM &&
-                        map[MOE_HDR_TILE_N] == BN && map[MOE_HDR_STATUS] == 0;
-    if (!hdr_ok) return;
-    const int per_xcd = (total + 7) >> 3;
-    const int slot = blockIdx.x >> 3;
-    if (slot >= per_xcd) return;
-    const int B = (blockIdx.x & 7) * per_xcd + slot;
-    if (B >= total) return;
-    const MapLayout L = map_layout(a.E);
-    const TileCoord tc = decode_block(map, L, BM, B);
     const int n0 = tc.n_tile * BN;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -615,6 +347,52 @@ __global__ __launch_bounds__(C::NT) void moe_gemm_pipe_kernel(GemmArgs a) {
             }
         }
     }
+}
+
+// Block index -> tile (Alg. 2 + 4), shared by the kernels below.  Returns false for surplus workgroups and for
+// a map that does not belong to this launch (wrong shape, tiling or status): those do nothing.
+template <int BM_BIG, int BN, int BM_SMALL>
+__device__ __forceinline__ bool locate_tile(const GemmArgs& a, const int32_t* __restrict__ map, MapLayout& L, TileCoord& tc) {
+    const int total = map[MOE_HDR_TOTAL_TILES];
+    const bool hdr_ok = map[MOE_HDR_MAGIC] == MOE_MAP_MAGIC && map[MOE_HDR_T] == a.T && map[MOE_HDR_K_TOP] == a.k &&
+                        map[MOE_HDR_E] == a.E && map[MOE_HDR_N] == a.N && map[MOE_HDR_TILE_M] == BM_BIG &&
+                        map[MOE_HDR_TILE_N] == BN && map[MOE_HDR_STATUS] == 0 &&
+                        map[MOE_HDR_TILE_M_SMALL] == BM_SMALL && map[MOE_HDR_SMALL_MAX_ROWS] == a.small_max_rows &&
+                        a.tile_m_small == BM_SMALL;
+    if (!hdr_ok) return false;
+    // Workgroup ids are dealt round-robin to the 8 XCDs; give each XCD one contiguous run of block indices so
+    // that neighbours in the map share an L2.
+    const int per_xcd = (total + 7) >> 3;
+    const int slot = blockIdx.x >> 3;
+    if (slot >= per_xcd) return false;
+    const int B = (blockIdx.x & 7) * per_xcd + slot;
+    if (B >= total) return false;
+    L = map_layout(a.E);
+    tc = decode_block(map, L, BM_BIG, B, BM_SMALL, a.small_max_rows);
+    return true;
+}
+
+// One tiling strategy for every expert.
+template <class C>
+__global__ __launch_bounds__(C::NT) void moe_gemm_pipe_kernel(GemmArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    MapLayout L;
+    TileCoord tc;
+    if (!locate_tile<C::BM, C::BN, 0>(a, a.map, L, tc)) return;
+    pipe_tile<C>(a, a.map, L, tc, smem);
+}
+
+// Two tiling strategies in one launch (Alg. 3 with K = 2 task types): the expert's row count picks the task
+// function; both share the thread count, the n-tile width and the LDS allocation.
+template <class CBIG, class CSMALL>
+__global__ __launch_bounds__(CBIG::NT) void moe_gemm_pipe2_kernel(GemmArgs a) {
+    static_assert(CBIG::NT == CSMALL::NT && CBIG::BN == CSMALL::BN && CBIG::FP8 == CSMALL::FP8, "task functions must be launch-compatible");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    MapLayout L;
+    TileCoord tc;
+    if (!locate_tile<CBIG::BM, CBIG::BN, CSMALL::BM>(a, a.map, L, tc)) return;
+    if (tc.small) pipe_tile<CSMALL>(a, a.map, L, tc, smem);
+    else pipe_tile<CBIG>(a, a.map, L, tc, smem);
 }
 
 }  // namespace moe

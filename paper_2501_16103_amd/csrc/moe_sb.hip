@@ -40,22 +40,24 @@ int launch_pipe(const GemmArgs& a, int64_t grid, hipStream_t s) {
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
-template <class C>
-int launch_gemm(const GemmArgs& a, int64_t grid, hipStream_t s) {
+template <class CBIG, class CSMALL>
+int launch_pipe2(const GemmArgs& a, int64_t grid, hipStream_t s) {
+    constexpr int lds = CBIG::LDS_BYTES > CSMALL::LDS_BYTES ? CBIG::LDS_BYTES : CSMALL::LDS_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&moe_gemm_kernel<C>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES) != hipSuccess)
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&moe_gemm_pipe2_kernel<CBIG, CSMALL>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
             return MOE_ERR_HIP;
         attr_set = true;
     }
-    moe_gemm_kernel<C><<<dim3((unsigned)grid), dim3(C::NT), C::LDS_BYTES, s>>>(a);
+    moe_gemm_pipe2_kernel<CBIG, CSMALL><<<dim3((unsigned)grid), dim3(CBIG::NT), lds, s>>>(a);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
 struct GemmVariant {
     int dtype, tile_m, tile_n, bk;
     gemm_launch_fn fn;
+    int tile_m_small = 0;  // second tiling strategy handled by the same launch (0 = none)
 };
 
 // Pipelined bf16 kernels:  BM   BN   BK  WM WN  ring stages
@@ -90,10 +92,32 @@ const GemmVariant kVariants[] = {
     {MOE_DTYPE_FP8_E4M3, 32, 128, 128, &launch_pipe<P8_32x128>},
 };
 
-const GemmVariant* find_variant(int dtype, int tile_m, int tile_n) {
-    for (const GemmVariant& v : kVariants)
-        if (v.dtype == dtype && v.tile_m == tile_m && v.tile_n == tile_n) return &v;
+// Small-expert task functions that share the launch shape (512 threads, 256-wide n-tiles) of Pb_256x256
+using Ps_64x256 = PipeCfg<64, 256, 64, 1, 8, 3>;
+using Ps_128x256 = PipeCfg<128, 256, 64, 1, 8, 2>;
+
+const GemmVariant kPairVariants[] = {
+    {MOE_DTYPE_BF16, 256, 256, 64, &launch_pipe2<Pb_256x256, Ps_64x256>, 64},
+    {MOE_DTYPE_BF16, 256, 256, 64, &launch_pipe2<Pb_256x256, Ps_128x256>, 128},
+};
+
+const GemmVariant* find_variant(int dtype, int tile_m, int tile_n, int tile_m_small = 0) {
+    if (tile_m_small == 0) {
+        for (const GemmVariant& v : kVariants)
+            if (v.dtype == dtype && v.tile_m == tile_m && v.tile_n == tile_n) return &v;
+    } else {
+        for (const GemmVariant& v : kPairVariants)
+            if (v.dtype == dtype && v.tile_m == tile_m && v.tile_n == tile_n && v.tile_m_small == tile_m_small) return &v;
+    }
     return nullptr;
+}
+
+int check_small_args(int tile_m, int tile_m_small, int small_max_rows) {
+    if (tile_m_small == 0 && small_max_rows == 0) return MOE_OK;
+    if (tile_m_small != 16 && tile_m_small != 32 && tile_m_small != 64 && tile_m_small != 128) return MOE_ERR_UNSUPPORTED;
+    if (tile_m_small >= tile_m) return MOE_ERR_INVALID_ARG;
+    if (small_max_rows < 1 || small_max_rows > 4 * tile_m_small) return MOE_ERR_INVALID_ARG;
+    return MOE_OK;
 }
 
 }  // namespace
@@ -128,7 +152,30 @@ int moe_build_task_map(const int32_t* topk_ids, int T, int k, int E, int tile_m,
 
 int moe_build_task_map_ordered(const int32_t* topk_ids, int T, int k, int E, int tile_m, int tile_n, int N, int order,
                                void* task_map, void* stream) {
+    return moe_build_task_map_tiled(topk_ids, T, k, E, tile_m, tile_n, N, order, 0, 0, task_map, stream);
+}
+
+int64_t moe_grid_upper_bound_tiled(int T, int k, int E, int tile_m, int tile_n, int N, int tile_m_small,
+                                   int small_max_rows) {
+    if (check_map_args(T, k, E, tile_m, tile_n, N) != MOE_OK) return 0;
+    if (check_small_args(tile_m, tile_m_small, small_max_rows) != MOE_OK) return 0;
+    const int64_t R = (int64_t)T * k;
+    const int64_t nt = (N + tile_n - 1) / tile_n;
+    const int64_t per_expert = tile_m_small ? (small_max_rows + tile_m_small - 1) / tile_m_small : 1;
+    return (R / tile_m + (E < R ? E : R) * (per_expert > 1 ? per_expert : 1)) * nt;
+}
+
+int moe_tile_pair_supported(int dtype, int tile_m, int tile_n, int tile_m_small) {
+    return tile_m_small > 0 && find_variant(dtype, tile_m, tile_n, tile_m_small) != nullptr;
+}
+
+int moe_build_task_map_tiled(const int32_t* topk_ids, int T, int k, int E, int tile_m, int tile_n, int N, int order,
+                             int tile_m_small, int small_max_rows, void* task_map, void* stream) {
     if (!task_map || (T > 0 && !topk_ids)) return MOE_ERR_INVALID_ARG;
+    {
+        const int rcs = check_small_args(tile_m, tile_m_small, small_max_rows);
+        if (rcs != MOE_OK) return rcs;
+    }
     if (order != MOE_ORDER_ASCENDING && order != MOE_ORDER_SPREAD) return MOE_ERR_INVALID_ARG;
     if (((uintptr_t)task_map & 15) || ((uintptr_t)topk_ids & 3)) return MOE_ERR_INVALID_ARG;
     const int rc = check_map_args(T, k, E, tile_m, tile_n, N);
@@ -147,13 +194,15 @@ int moe_build_task_map_ordered(const int32_t* topk_ids, int T, int k, int E, int
                 return MOE_ERR_HIP;
             attr_set = true;
         }
-        map_build_small<<<1, kMapThreads, lds, s>>>(topk_ids, map, T, k, E, tile_m, tile_n, N, order);
+        map_build_small<<<1, kMapThreads, lds, s>>>(topk_ids, map, T, k, E, tile_m, tile_n, N, order, tile_m_small,
+                                                    small_max_rows);
     } else {
         const int nchunks = nchunks_for(R);
         int32_t* chunk_hist = map + L.off_rows + round_up64((size_t)R);
         const int hs = hist_stride(L.E64);
         map_hist<<<nchunks, 256, hs * sizeof(int), s>>>(topk_ids, (int)R, E, L.E64, chunk_hist);
-        map_scan<<<1, kMapThreads, 0, s>>>(map, chunk_hist, nchunks, T, k, E, tile_m, tile_n, N, order);
+        map_scan<<<1, kMapThreads, 0, s>>>(map, chunk_hist, nchunks, T, k, E, tile_m, tile_n, N, order, tile_m_small,
+                                           small_max_rows);
         static bool attr_set2 = false;
         if (!attr_set2) {
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(&map_scatter),
@@ -199,7 +248,11 @@ int moe_grouped_gemm(const void* X, const void* W, const int32_t* topk_ids, cons
     if (rc != MOE_OK) return rc;
     if (d->K < 1) return MOE_ERR_INVALID_ARG;
     if (d->dtype != MOE_DTYPE_BF16 && d->dtype != MOE_DTYPE_FP8_E4M3) return MOE_ERR_UNSUPPORTED;
-    const GemmVariant* v = find_variant(d->dtype, d->tile_m, d->tile_n);
+    {
+        const int rcs = check_small_args(d->tile_m, d->tile_m_small, d->small_max_rows);
+        if (rcs != MOE_OK) return rcs;
+    }
+    const GemmVariant* v = find_variant(d->dtype, d->tile_m, d->tile_n, d->tile_m_small);
     if (!v) return MOE_ERR_UNSUPPORTED;
     if (d->K % v->bk != 0 || d->N % d->tile_n != 0) return MOE_ERR_UNSUPPORTED;
     const int es = d->dtype == MOE_DTYPE_FP8_E4M3 ? 1 : 2;
@@ -213,7 +266,9 @@ int moe_grouped_gemm(const void* X, const void* W, const int32_t* topk_ids, cons
     a.X = X; a.W = W; a.map = static_cast<const int32_t*>(task_map); a.Y = Y;
     a.x_scale = d->x_scale; a.w_scale = d->w_scale;
     a.T = d->T; a.k = d->k; a.E = d->E; a.K = d->K; a.N = d->N;
-    int64_t grid = moe_grid_upper_bound(d->T, d->k, d->E, d->tile_m, d->tile_n, d->N);
+    a.tile_m_small = d->tile_m_small; a.small_max_rows = d->small_max_rows;
+    int64_t grid = moe_grid_upper_bound_tiled(d->T, d->k, d->E, d->tile_m, d->tile_n, d->N, d->tile_m_small,
+                                              d->small_max_rows);
     grid = (grid + 7) / 8 * 8;
     if (grid == 0) return MOE_OK;
     if (grid > 0x7fffffff) return MOE_ERR_UNSUPPORTED;

@@ -61,15 +61,24 @@ __device__ __forceinline__ void mapping(const int32_t* __restrict__ tile_prefix,
 
 struct TileCoord {
     int e, m_tile, n_tile, rows, row_base;  // row_base: index into sorted_rows of the tile's first row
+    int small;                              // task type (Alg. 3): 1 = the expert uses the small tiling strategy
 };
 
+// Tiling strategy of an expert with cnt rows: tile_m_small when cnt <= small_max_rows (0 = one strategy).
+__host__ __device__ __forceinline__ int expert_tile_m(int cnt, int tile_m, int tile_m_small, int small_max_rows) {
+    return (small_max_rows > 0 && cnt <= small_max_rows) ? tile_m_small : tile_m;
+}
+
 // Alg. 4: block -> non-empty task -> real expert, then the tile index split m-fastest.
-__device__ __forceinline__ TileCoord decode_block(const int32_t* __restrict__ map, const MapLayout& L, int tile_m, int B) {
+__device__ __forceinline__ TileCoord decode_block(const int32_t* __restrict__ map, const MapLayout& L, int tile_m_big, int B,
+                                                  int tile_m_small = 0, int small_max_rows = 0) {
     int h, l;
     mapping(map + L.off_prefix, L.E64, B, h, l);
     TileCoord c;
     c.e = map[L.off_sigma + h];
     const int cnt = map[L.off_counts + c.e];
+    c.small = small_max_rows > 0 && cnt <= small_max_rows;
+    const int tile_m = c.small ? tile_m_small : tile_m_big;
     const int mt = (cnt + tile_m - 1) / tile_m;
     c.n_tile = l / mt;
     c.m_tile = l - c.n_tile * mt;
@@ -126,12 +135,14 @@ __device__ __forceinline__ int bit_reverse(int r, int nbits) { return nbits ? (i
 // keyed by bitrev(r) over ceil(log2 M) bits, sigma by increasing key.
 // s_work: >= 2*E64 ints of LDS.  Returns this thread's exclusive row offset (valid for tid < E).
 __device__ __forceinline__ int finish_map(int32_t* __restrict__ map, const MapLayout& L, int cnt, int bad, int T, int k,
-                                          int E, int tile_m, int tile_n, int N, int order, int* s_tmp, int* s_work) {
+                                          int E, int tile_m, int tile_n, int N, int order, int tile_m_small,
+                                          int small_max_rows, int* s_tmp, int* s_work) {
     const int tid = threadIdx.x;
     const int R = T * k;
     const int nt = (N + tile_n - 1) / tile_n;
     const int nonempty = cnt > 0;
-    const int tiles = ((cnt + tile_m - 1) / tile_m) * nt;
+    const int etm = expert_tile_m(cnt, tile_m, tile_m_small, small_max_rows);
+    const int tiles = ((cnt + etm - 1) / etm) * nt;
     const int off_incl = block_incl_scan(cnt, s_tmp);
     const int ne_incl = block_incl_scan(nonempty, s_tmp);
     __syncthreads();
@@ -198,6 +209,8 @@ __device__ __forceinline__ int finish_map(int32_t* __restrict__ map, const MapLa
             case MOE_HDR_R: v = R; break;
             case MOE_HDR_E64: v = L.E64; break;
             case MOE_HDR_SIGMA_ORDER: v = order; break;
+            case MOE_HDR_TILE_M_SMALL: v = tile_m_small; break;
+            case MOE_HDR_SMALL_MAX_ROWS: v = small_max_rows; break;
             default: v = 0;
         }
         map[tid] = v;
@@ -214,7 +227,8 @@ __device__ __forceinline__ int key_bits(int E) {
 // One-workgroup build for R <= kChunkRows: histogram, scans and stable scatter fused.
 // Dynamic LDS: kWaves * E64 ints (per-wavefront counts) + E64 ints (offsets) + 32 + 2 * E64 (ordering).
 __global__ __launch_bounds__(kMapThreads) void map_build_small(const int32_t* __restrict__ ids, int32_t* __restrict__ map,
-                                                                int T, int k, int E, int tile_m, int tile_n, int N, int order) {
+                                                                int T, int k, int E, int tile_m, int tile_n, int N, int order,
+                                                                int tile_m_small, int small_max_rows) {
     extern __shared__ int s_mem[];
     const MapLayout L = map_layout(E);
     int* s_wave = s_mem;                   // [kWaves][E64]
@@ -244,7 +258,7 @@ __global__ __launch_bounds__(kMapThreads) void map_build_small(const int32_t* __
             cnt += c;
         }
     }
-    const int off = finish_map(map, L, cnt, bad, T, k, E, tile_m, tile_n, N, order, s_tmp, s_work);
+    const int off = finish_map(map, L, cnt, bad, T, k, E, tile_m, tile_n, N, order, tile_m_small, small_max_rows, s_tmp, s_work);
     if (tid < L.E64) s_off[tid] = off;
     __syncthreads();
     if (valid) map[L.off_rows + s_off[e] + s_wave[w * L.E64 + e] + rank] = tid;
@@ -273,7 +287,7 @@ __global__ __launch_bounds__(256) void map_hist(const int32_t* __restrict__ ids,
 // then counts / offsets / sigma / TilePrefix / header.
 __global__ __launch_bounds__(kMapThreads) void map_scan(int32_t* __restrict__ map, int32_t* __restrict__ chunk_hist,
                                                         int nchunks, int T, int k, int E, int tile_m, int tile_n, int N,
-                                                        int order) {
+                                                        int order, int tile_m_small, int small_max_rows) {
     __shared__ int s_tmp[32];
     __shared__ int s_work[2 * kMaxE];
     const MapLayout L = map_layout(E);
@@ -294,7 +308,7 @@ __global__ __launch_bounds__(kMapThreads) void map_scan(int32_t* __restrict__ ma
     }
     __syncthreads();
     const int bad = s_tmp[31];
-    finish_map(map, L, cnt, bad, T, k, E, tile_m, tile_n, N, order, s_tmp, s_work);
+    finish_map(map, L, cnt, bad, T, k, E, tile_m, tile_n, N, order, tile_m_small, small_max_rows, s_tmp, s_work);
 }
 
 // Step 3: stable scatter of one chunk of rows into the token index arrays.
@@ -336,12 +350,13 @@ __global__ __launch_bounds__(256) void map_expand(const int32_t* __restrict__ ma
     const MapLayout L = map_layout(E);
     const int total = map[MOE_HDR_TOTAL_TILES];
     const int tile_m = map[MOE_HDR_TILE_M];
+    const int tile_m_small = map[MOE_HDR_TILE_M_SMALL], small_max_rows = map[MOE_HDR_SMALL_MAX_ROWS];
     const long long wave = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
     const long long nwaves = (long long)gridDim.x * 4;
     for (long long B = wave; B < grid; B += nwaves) {
         int4 out = make_int4(-1, -1, -1, -1);
         if (B < total) {
-            const TileCoord c = decode_block(map, L, tile_m, (int)B);
+            const TileCoord c = decode_block(map, L, tile_m, (int)B, tile_m_small, small_max_rows);
             out = make_int4(c.e, c.m_tile, c.n_tile, c.rows);
         }
         if (__lane_id() == 0) reinterpret_cast<int4*>(table)[B] = out;

@@ -44,6 +44,14 @@ def test_host_only_entry_points():
     assert mb.moe_grid_upper_bound(4096, 2, 8, 256, 256, 28672) == (32 + 8) * 112
     assert mb.moe_grid_upper_bound(1, 6, 64, 16, 64, 2816) == (0 + 6) * 44
     assert mb.moe_grid_upper_bound(0, 2, 8, 16, 128, 512) == 0
+    # two strategies: (floor(R/tile_m) + min(E,R)*ceil(small_max/tile_m_small)) * ceil(N/tile_n)
+    assert mb.moe_grid_upper_bound_tiled(4096, 8, 64, 256, 256, 2560, 64, 64) == (128 + 64) * 10
+    assert mb.moe_grid_upper_bound_tiled(4096, 8, 64, 256, 256, 2560, 64, 200) == (128 + 64 * 4) * 10
+    assert mb.moe_grid_upper_bound_tiled(4096, 8, 64, 256, 256, 2560, 0, 0) == mb.moe_grid_upper_bound(4096, 8, 64, 256, 256, 2560)
+    assert mb.moe_grid_upper_bound_tiled(4096, 8, 64, 256, 256, 2560, 64, 0) == 0       # invalid pair
+    assert mb.moe_tile_pair_supported(mb.MOE_DTYPE_BF16, 256, 256, 64)
+    assert not mb.moe_tile_pair_supported(mb.MOE_DTYPE_BF16, 256, 256, 0)
+    assert not mb.moe_tile_pair_supported(mb.MOE_DTYPE_FP8_E4M3, 256, 256, 64)
     assert mb.moe_tile_supported(mb.MOE_DTYPE_BF16, 256, 256)
     assert mb.moe_tile_supported(mb.MOE_DTYPE_FP8_E4M3, 16, 128)
     assert not mb.moe_tile_supported(mb.MOE_DTYPE_FP8_E4M3, 256, 256)

@@ -25,10 +25,12 @@ def dev():
     return torch.device("cuda:0")
 
 
-def _build_map(ids_dev, T, k, E, tile_m, tile_n, N, order=0):
+def _build_map(ids_dev, T, k, E, tile_m, tile_n, N, order=0, small=0, thr=0):
     tmap = mb.alloc_task_map(max(T, 1), k, E, tile_m, tile_n, N)
     tmap.fill_(0x5A5A5A5A)
-    if order == 0:
+    if small:
+        mb.moe_build_task_map_tiled(ids_dev, T, k, E, tile_m, tile_n, N, order, small, thr, tmap)
+    elif order == 0:
         mb.moe_build_task_map(ids_dev, T, k, E, tile_m, tile_n, N, tmap)
     else:
         mb.moe_build_task_map_ordered(ids_dev, T, k, E, tile_m, tile_n, N, order, tmap)
@@ -129,17 +131,17 @@ def test_argument_errors(dev):
     assert bool(torch.isnan(Y).all())
 
 
-def _run_gemm(dev, wl, ids, X, W, xs=None, ws=None, order=0):
+def _run_gemm(dev, wl, ids, X, W, xs=None, ws=None, order=0, small=0, thr=0):
     """Run map build + GEMM with Y embedded between poisoned canary rows; returns Y bits [R,N]."""
     R, N = wl.R, wl.N
     pad = 4
     buf = torch.empty((R + 2 * pad, N), dtype=torch.int16, device=dev)
     buf.fill_(POISON)
     Y = buf[pad: pad + R]
-    tmap = _build_map(ids.to(dev), wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, N, order)
+    tmap = _build_map(ids.to(dev), wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, N, order, small, thr)
     dt = mb.MOE_DTYPE_FP8_E4M3 if wl.dtype == "fp8" else mb.MOE_DTYPE_BF16
     desc = mb.GemmDesc(dt, wl.T, wl.k, wl.E, wl.K, N, wl.tile_m, wl.tile_n,
-                       None if xs is None else xs.to(dev), None if ws is None else ws.to(dev))
+                       None if xs is None else xs.to(dev), None if ws is None else ws.to(dev), small, thr)
     mb.moe_grouped_gemm(X.to(dev), W.to(dev), ids.to(dev), tmap, Y, desc)
     torch.cuda.synchronize()
     assert mb.moe_task_map_status(tmap) == mb.MOE_OK
@@ -198,6 +200,58 @@ def test_gemm_bf16_parity(dev, oracle_mod, tile_m, tile_n, T, E, k, K, N, routin
     got = _run_gemm(dev, wl, ids, X, W, order=order)
     res = oracle_mod.grouped_gemm_bf16(wk.bits(X), wk.bits(W), ids.numpy())
     _check_y(got, res, X.double().numpy(), W.double().numpy(), ids.numpy(), k, K, H.tol_bf16(K))
+
+
+TILED_CASES = [
+    # T, E, k, K, N, routing, tile_m_small, small_max_rows   (large strategy: 256 x 256)
+    (1200, 16, 2, 256, 512, "zipf", 64, 64),
+    (700, 16, 2, 128, 256, "zipf", 128, 128),
+    (600, 64, 8, 128, 256, "worst", 64, 64),          # 56 one-row experts next to 8 busy ones
+    (1200, 8, 2, 256, 512, "gauss_topk", 64, 64),     # nobody is small
+    (300, 16, 2, 128, 256, "gauss_topk", 64, 200),    # everybody is small, several small tiles each
+]
+
+
+@pytest.mark.parametrize("order", [0, 1], ids=["ascending", "spread"])
+@pytest.mark.parametrize("T,E,k,K,N,routing,small,thr", TILED_CASES)
+def test_two_tiling_strategies_parity(dev, oracle_mod, T, E, k, K, N, routing, small, thr, order):
+    """Alg. 3 with two task types in one launch: map bit-exact, expanded table == nested-loop table, Y == oracle."""
+    wl = wk.Workload("parity_tiled", T, E, k, K, N, "bf16", routing, 256, 256)
+    assert mb.moe_tile_pair_supported(mb.MOE_DTYPE_BF16, 256, 256, small)
+    ids, X, W = wk.make_routing(wl), wk.make_x(wl), wk.make_w(wl)
+    tm = oracle_mod.build_task_map(ids.numpy(), T, k, E, 256, 256, N, order=order, tile_m_small=small, small_max_rows=thr)
+    tmap = _build_map(ids.to(dev), T, k, E, 256, 256, N, order, small, thr)
+    want = H.expected_blob(tm)
+    np.testing.assert_array_equal(tmap.cpu().numpy()[: len(want)], want)
+    grid = mb.moe_grid_upper_bound_tiled(T, k, E, 256, 256, N, small, thr)
+    assert grid >= tm.total_tiles
+    table = torch.full((grid, 4), 7, dtype=torch.int32, device=dev)
+    mb.moe_task_map_expand(tmap, E, table, grid)
+    tab = table.cpu().numpy()
+    np.testing.assert_array_equal(tab[: tm.total_tiles], oracle_mod.full_table(tm.counts, 256, 256, N, sigma=tm.sigma,
+                                                                                tile_m_small=small, small_max_rows=thr))
+    assert np.all(tab[tm.total_tiles:] == -1)
+    got = _run_gemm(dev, wl, ids, X, W, order=order, small=small, thr=thr)
+    res = oracle_mod.grouped_gemm_bf16(wk.bits(X), wk.bits(W), ids.numpy())
+    _check_y(got, res, X.double().numpy(), W.double().numpy(), ids.numpy(), k, K, H.tol_bf16(K))
+
+
+def test_tiling_pair_mismatch_is_a_noop(dev):
+    """A two-strategy map run through the one-strategy kernel (or the other way round) must do nothing."""
+    T, E, k, K, N = 300, 16, 2, 128, 256
+    wl = wk.Workload("pair_mismatch", T, E, k, K, N, "bf16", "zipf", 256, 256)
+    ids = wk.make_routing(wl).to(dev)
+    X, W = wk.make_x(wl, dev), wk.make_w(wl, dev)
+    Y = torch.full((T * k, N), float("nan"), device=dev, dtype=torch.bfloat16)
+    tiled = _build_map(ids, T, k, E, 256, 256, N, 0, 64, 64)
+    plain = _build_map(ids, T, k, E, 256, 256, N, 0)
+    mb.moe_grouped_gemm(X, W, ids, tiled, Y, mb.GemmDesc(mb.MOE_DTYPE_BF16, T, k, E, K, N, 256, 256))
+    mb.moe_grouped_gemm(X, W, ids, plain, Y, mb.GemmDesc(mb.MOE_DTYPE_BF16, T, k, E, K, N, 256, 256, None, None, 64, 64))
+    mb.moe_grouped_gemm(X, W, ids, tiled, Y, mb.GemmDesc(mb.MOE_DTYPE_BF16, T, k, E, K, N, 256, 256, None, None, 64, 32))
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(Y).all())
+    d = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, k, E, K, N, 256, 256, None, None, 32, 32)
+    assert mb.moe_grouped_gemm(X, W, ids, tiled, Y, d, check=False) == mb.MOE_ERR_UNSUPPORTED
 
 
 FP8_CASES = [
