@@ -53,6 +53,7 @@ class Point:
         self.wl = wl
         self.order = order
         self.small = small  # (tile_m_small, small_max_rows) of the second tiling strategy, or (0, 0)
+        self.slack = 0 if small[0] else wl.tile_m_slack  # no kernel combines the two
         self.dev = dev
         self.ids_cpu = wk.make_routing(wl)
         self.ids = self.ids_cpu.to(dev)
@@ -68,12 +69,12 @@ class Point:
         self.Y = torch.empty((wl.R, wl.N), dtype=torch.bfloat16, device=dev)
         self.tmap = mb.alloc_task_map(wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N, dev)
         dt = mb.MOE_DTYPE_FP8_E4M3 if wl.dtype == "fp8" else mb.MOE_DTYPE_BF16
-        self.desc = mb.GemmDesc(dt, wl.T, wl.k, wl.E, wl.K, wl.N, wl.tile_m, wl.tile_n, self.xs, self.ws, *small)
+        self.desc = mb.GemmDesc(dt, wl.T, wl.k, wl.E, wl.K, wl.N, wl.tile_m, wl.tile_n, self.xs, self.ws, *small, self.slack)
+        self.tiling = mb.Tiling(wl.tile_m, wl.tile_n, order, small[0], small[1], self.slack)
 
     def build_map(self):
         wl = self.wl
-        mb.moe_build_task_map_tiled(self.ids, wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N, self.order,
-                                    self.small[0], self.small[1], self.tmap)
+        mb.moe_build_task_map_ex(self.ids, wl.T, wl.k, wl.E, wl.N, self.tiling, self.tmap)
 
     def gemm(self, i: int = 0):
         mb.moe_grouped_gemm(self.X, self.W[i % len(self.W)], self.ids, self.tmap, self.Y, self.desc)
@@ -120,7 +121,7 @@ class Point:
         ideal_hbm = abytes / (PEAK_HBM_GBS * 1e9)
         bound = "mfma" if ideal_mfma >= ideal_hbm else "hbm"
         return dict(workload=f"{wl.name}_T{wl.T}", dtype=wl.dtype, T=wl.T, E=wl.E, k=wl.k, K=wl.K, N=wl.N,
-                    tile=[wl.tile_m, wl.tile_n], sigma_order=("spread" if self.order else "ascending"), small_strategy=list(self.small), ms_per_step=round(wall_ms, 4), gemm_ms=round(gemm_ms, 4),
+                    tile=[wl.tile_m, wl.tile_n], sigma_order=("spread" if self.order else "ascending"), small_strategy=list(self.small), tile_m_slack=self.slack, ms_per_step=round(wall_ms, 4), gemm_ms=round(gemm_ms, 4),
                     map_ms=round(map_ms, 4), tflops_step=round(tf_step, 2), tflops_gemm=round(tf_gemm, 2),
                     frac_mfma=round(tf_gemm / peak_t, 4), gbs_gemm=round(gbs, 1),
                     frac_hbm=round(gbs / PEAK_HBM_GBS, 4), bound=bound, alg_bytes=abytes, flops=wl.flops)
@@ -192,6 +193,7 @@ def main():
                     help="expert order in sigma for the extra points (the headline always uses ascending)")
     ap.add_argument("--small", default="0,0",
                     help="tile_m_small,small_max_rows: second tiling strategy for the extra points with 256x256 tiles")
+    ap.add_argument("--slack", type=int, default=-1, help="override tile_m_slack of every workload (0 = plain ceil tiling)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (a kernel of known traffic to scale profiler byte counters by)")
@@ -208,7 +210,9 @@ def main():
     wl = wk.mixtral_up(4096)
     if args.tile:
         tm, tn = (int(v) for v in args.tile.split(","))
-        wl = wl.with_T(wl.T, tile_m=tm, tile_n=tn)
+        wl = wl.with_T(wl.T, tile_m=tm, tile_n=tn, tile_m_slack=0)
+    if args.slack >= 0:
+        wl = wl.with_T(wl.T, tile_m_slack=args.slack)
     pt = Point(wl)
     head = pt.report(args.steps, args.warmup)
     out = {
@@ -217,7 +221,7 @@ def main():
         "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": HEADLINE, "T": wl.T, "E": wl.E, "top_k": wl.k, "K": wl.K, "N": wl.N,
-                   "tile_m": wl.tile_m, "tile_n": wl.tile_n, "routing": wl.routing},
+                   "tile_m": wl.tile_m, "tile_n": wl.tile_n, "tile_m_slack": wl.tile_m_slack, "routing": wl.routing},
         "roofline": {"bound": "mfma", "achieved": head["tflops_gemm"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(head["tflops_gemm"] / PEAK_BF16_TFLOPS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get(HEADLINE), "kernel": "moe_gemm_kernel",
@@ -242,6 +246,8 @@ def main():
             name = f"{w.name}_T{w.T}"
             if want is not None and name not in want and w.name not in want:
                 continue
+            if args.slack >= 0:
+                w = w.with_T(w.T, tile_m_slack=args.slack)
             if name == HEADLINE and not args.tile:
                 points.append(head)
                 continue

@@ -81,7 +81,8 @@ enum {
     MOE_HDR_E64 = 13,
     MOE_HDR_SIGMA_ORDER = 14,    /* MOE_ORDER_* the map was built with */
     MOE_HDR_TILE_M_SMALL = 15,   /* second tiling strategy (0 = none), see moe_build_task_map_tiled */
-    MOE_HDR_SMALL_MAX_ROWS = 16
+    MOE_HDR_SMALL_MAX_ROWS = 16,
+    MOE_HDR_TILE_M_SLACK = 17    /* extra rows the last m-tile of an expert may hold, see moe_build_task_map_ex */
 };
 
 /* Word offsets of the blob's fields for a given E (HOST, pure). */
@@ -153,6 +154,33 @@ int64_t moe_grid_upper_bound_tiled(int T, int k, int E, int tile_m, int tile_n, 
                                    int small_max_rows);
 
 /*
+ * All tiling choices of a batch in one place.  The paper leaves the tiling strategy of each task
+ * to the task function (Sec. 3.2, Alg. 3); these are the strategies this library implements.
+ */
+typedef struct moe_tiling {
+    int32_t tile_m, tile_n;   /* rows and columns of an output tile */
+    int32_t order;            /* MOE_ORDER_* */
+    int32_t tile_m_small, small_max_rows; /* second strategy for small experts, or 0, 0 */
+    int32_t tile_m_slack;     /* 0, or: the last m-tile of a tile_m-strategy expert may hold up to
+                                 tile_m + tile_m_slack rows, so that a remainder of at most
+                                 tile_m_slack rows does not open a nearly empty tile of its own:
+                                     m_tiles(c) = max(1, ceil((c - tile_m_slack) / tile_m))  for c > 0.
+                                 Tile m of the expert starts at row m * tile_m of its segment; all
+                                 tiles but the last hold tile_m rows.  0 <= tile_m_slack < tile_m. */
+} moe_tiling;
+
+/*
+ * The general builder: moe_build_task_map_tiled plus tile_m_slack.  Same arguments, blob and errors;
+ * header word MOE_HDR_TILE_M_SLACK records the slack.  `tiling` is a HOST pointer, read before return.
+ * The same moe_tiling values must reach moe_grouped_gemm through its descriptor.
+ */
+int moe_build_task_map_ex(const int32_t* topk_ids, int T, int k, int E, int N, const moe_tiling* tiling,
+                          void* task_map, void* stream);
+
+/* 1 if moe_grouped_gemm has a kernel for this dtype and tiling (order is ignored), else 0. HOST, pure. */
+int moe_tiling_supported(int dtype, const moe_tiling* tiling);
+
+/*
  * Synchronises the stream and returns MOE_ERR_ROUTING if the map recorded a
  * bad routing id, MOE_ERR_INVALID_ARG if the blob is not a map, else MOE_OK.
  */
@@ -162,7 +190,7 @@ int moe_task_map_status(const void* task_map, void* stream);
  * Expand the compressed map into the full per-block table (the prior-art
  * representation of Sec. 2.1 / 3.1), using the same device decode routine the
  * GEMM kernel uses.  table: DEVICE int32 [grid][4] = {expert, m_tile, n_tile,
- * rows_in_tile}; entries B >= total_tiles are set to -1.  `grid` is normally
+ * rows_in_tile}; rows_in_tile <= tile_m + tile_m_slack; entries B >= total_tiles are set to -1.  `grid` is normally
  * moe_grid_upper_bound(...).
  */
 int moe_task_map_expand(const void* task_map, int E, int32_t* table, int64_t grid, void* stream);
@@ -175,6 +203,7 @@ typedef struct moe_gemm_desc {
     const float* x_scale; /* DEVICE fp32 [T], per-token scale  (fp8 only, else NULL) */
     const float* w_scale; /* DEVICE fp32 [E], per-expert scale (fp8 only, else NULL) */
     int32_t tile_m_small, small_max_rows; /* second tiling strategy of the map, or 0, 0 */
+    int32_t tile_m_slack; /* slack rows of the map's last m-tiles, or 0 */
 } moe_gemm_desc;
 
 /*

@@ -107,6 +107,7 @@ class TaskMap:
     order: int = 0            # 0: sigma ascending, 1: spread (Sec. 4.2)
     tile_m_small: int = 0     # second tiling strategy: experts with <= small_max_rows rows use this tile_m
     small_max_rows: int = 0
+    tile_m_slack: int = 0     # rows the last tile of a tile_m-strategy expert may hold beyond tile_m
 
     def expert_tile_m(self, e: int) -> int:
         c = int(self.counts[e])
@@ -135,7 +136,7 @@ def mapping(prefix, B: int):
 
 
 def build_task_map(topk_ids, T: int, k: int, E: int, tile_m: int, tile_n: int, N: int, order: int = 0,
-                   tile_m_small: int = 0, small_max_rows: int = 0) -> TaskMap:
+                   tile_m_small: int = 0, small_max_rows: int = 0, tile_m_slack: int = 0) -> TaskMap:
     ids = _i32(topk_ids).reshape(-1)
     assert ids.size == T * k
     counts = np.zeros(E, dtype=np.int32)
@@ -147,20 +148,20 @@ def build_task_map(topk_ids, T: int, k: int, E: int, tile_m: int, tile_n: int, N
     total = ctypes.c_int32(0)
     rc = _load().orc_build_task_map(_p(ids), ctypes.c_int(T), ctypes.c_int(k), ctypes.c_int(E),
                                     ctypes.c_int(tile_m), ctypes.c_int(tile_n), ctypes.c_int(N), ctypes.c_int(order),
-                                    ctypes.c_int(tile_m_small), ctypes.c_int(small_max_rows), _p(counts), _p(offsets), _p(sorted_rows), _p(sigma), _p(prefix),
+                                    ctypes.c_int(tile_m_small), ctypes.c_int(small_max_rows), ctypes.c_int(tile_m_slack), _p(counts), _p(offsets), _p(sorted_rows), _p(sigma), _p(prefix),
                                     ctypes.byref(M), ctypes.byref(total))
     if rc != 0:
         raise ValueError("routing id outside [0, E)")
     return TaskMap(T, k, E, N, tile_m, tile_n, counts, offsets, sorted_rows[: T * k].copy(),
                    sigma[: M.value].copy(), prefix[: M.value].copy(), M.value, total.value, order,
-                   tile_m_small, small_max_rows)
+                   tile_m_small, small_max_rows, tile_m_slack)
 
 
 def decode_block(tm: TaskMap, B: int):
     """Alg. 4 for block B -> (expert, m_tile, n_tile, rows_in_tile)."""
     out = np.zeros(4, dtype=np.int32)
     _load().orc_decode_block(_p(tm.tile_prefix), _p(tm.sigma), ctypes.c_int(tm.M), _p(tm.counts),
-                             ctypes.c_int(tm.tile_m), ctypes.c_int(tm.tile_m_small), ctypes.c_int(tm.small_max_rows),
+                             ctypes.c_int(tm.tile_m), ctypes.c_int(tm.tile_m_small), ctypes.c_int(tm.small_max_rows), ctypes.c_int(tm.tile_m_slack),
                              ctypes.c_int(B), _p(out))
     return tuple(int(v) for v in out)
 
@@ -172,14 +173,14 @@ def decode_all(tm: TaskMap) -> np.ndarray:
     row = np.zeros(4, dtype=np.int32)
     for B in range(tm.total_tiles):
         lib.orc_decode_block(_p(tm.tile_prefix), _p(tm.sigma), ctypes.c_int(tm.M), _p(tm.counts),
-                             ctypes.c_int(tm.tile_m), ctypes.c_int(tm.tile_m_small), ctypes.c_int(tm.small_max_rows),
+                             ctypes.c_int(tm.tile_m), ctypes.c_int(tm.tile_m_small), ctypes.c_int(tm.small_max_rows), ctypes.c_int(tm.tile_m_slack),
                              ctypes.c_int(B), _p(row))
         out[B] = row
     return out
 
 
 def full_table(counts, tile_m: int, tile_n: int, N: int, sigma=None, tile_m_small: int = 0,
-               small_max_rows: int = 0) -> np.ndarray:
+               small_max_rows: int = 0, tile_m_slack: int = 0) -> np.ndarray:
     """Prior-art full per-block table by nested loops -> [total, 4].  `sigma` (non-empty experts in
     visiting order) defaults to ascending expert index."""
     counts = _i32(counts)
@@ -190,12 +191,13 @@ def full_table(counts, tile_m: int, tile_n: int, N: int, sigma=None, tile_m_smal
     nt = -(-N // tile_n)
     def _tm(c):
         return tile_m_small if (small_max_rows > 0 and c <= small_max_rows) else tile_m
-    cap = int(sum(-(-int(c) // _tm(int(c))) for c in counts) * nt)
+    cap = int(sum(-(-int(c) // _tm(int(c))) for c in counts) * nt)   # room for the no-slack tiling, the largest
     table = np.zeros((max(cap, 1), 4), dtype=np.int32)
     n = _load().orc_full_table(_p(counts), ctypes.c_int(len(counts)), _p(order), ctypes.c_int(tile_m),
-                               ctypes.c_int(tile_m_small), ctypes.c_int(small_max_rows), ctypes.c_int(tile_n), ctypes.c_int(N), _p(table), ctypes.c_int(cap))
-    assert n == cap
-    return table[:cap]
+                               ctypes.c_int(tile_m_small), ctypes.c_int(small_max_rows), ctypes.c_int(tile_m_slack),
+                               ctypes.c_int(tile_n), ctypes.c_int(N), _p(table), ctypes.c_int(cap))
+    assert 0 <= n <= cap and (tile_m_slack > 0 or n == cap)
+    return table[:n]
 
 
 # ------------------------------------------------------------------ result

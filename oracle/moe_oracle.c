@@ -16,6 +16,11 @@
  *     several pre-defined tiling strategies"; thresholds are not given in the paper).  Two
  *     strategies here: experts with at most small_max_rows rows use tile_m_small, all
  *     others tile_m; small_max_rows = 0 means one strategy for every expert.
+ *     A third knob of the tile_m strategy, also this library's own: with tile_m_slack > 0
+ *     an expert's rows are cut into tiles of tile_m rows from the front, but as soon as
+ *     what is left fits into tile_m + tile_m_slack rows it becomes the last tile, so a
+ *     remainder of a few rows never gets a tile to itself.  Tile m still starts at row
+ *     m * tile_m of the expert's segment.  tile_m_slack = 0 is the plain ceil(c / tile_m).
  *   - sigma lists the non-empty experts in ascending expert index (Sec. 4.1), or, with
  *     order = 1, "spread" in the half-interval manner of Sec. 4.2: the non-empty experts
  *     are ranked by tile count (largest first, ties by lower index), rank r gets the key
@@ -133,6 +138,26 @@ static int expert_tile_m(int c, int tile_m, int tile_m_small, int small_max_rows
     return (small_max_rows > 0 && c <= small_max_rows) ? tile_m_small : tile_m;
 }
 
+/* m-tiles of an expert with c rows, and the rows of its tile m_tile (conventions at the top):
+ * tiles are cut from the front; what fits into tm + slack rows is the last tile. */
+static int expert_m_tiles(int c, int tile_m, int tile_m_small, int small_max_rows, int slack) {
+    int tm = expert_tile_m(c, tile_m, tile_m_small, small_max_rows);
+    if (tm != tile_m) slack = 0; /* the slack belongs to the tile_m strategy only */
+    int tiles = 0, left = c;
+    while (left > 0) {
+        tiles += 1;
+        if (left <= tm + slack) left = 0;
+        else left -= tm;
+    }
+    return tiles;
+}
+static int expert_tile_rows(int c, int tile_m, int tile_m_small, int small_max_rows, int slack, int m_tile) {
+    int tm = expert_tile_m(c, tile_m, tile_m_small, small_max_rows);
+    if (tm != tile_m) slack = 0;
+    int left = c - m_tile * tm;
+    return left <= tm + slack ? left : tm;
+}
+
 /* Bit reversal of r over nbits bits. */
 static int bit_reverse(int r, int nbits) {
     int v = 0;
@@ -168,9 +193,10 @@ static void spread_order(const int32_t* experts, const int32_t* nu, int M, int32
  *   token is r / k), sigma[M] (non-empty -> real expert), tile_prefix[M].
  *   order: 0 = sigma ascending, 1 = spread (Sec. 4.2).
  *   tile_m_small, small_max_rows: the second tiling strategy (0, 0 = none).
+ *   tile_m_slack: rows the last tile of a tile_m-strategy expert may hold beyond tile_m.
  * Returns 0, or -1 if an id is outside [0,E).                               */
 int orc_build_task_map(const int32_t* topk_ids, int T, int k, int E, int tile_m, int tile_n, int N, int order,
-                       int tile_m_small, int small_max_rows, int32_t* counts, int32_t* offsets, int32_t* sorted_rows, int32_t* sigma,
+                       int tile_m_small, int small_max_rows, int tile_m_slack, int32_t* counts, int32_t* offsets, int32_t* sorted_rows, int32_t* sigma,
                        int32_t* tile_prefix, int32_t* M_out, int32_t* total_tiles_out) {
     int R = T * k;
     for (int e = 0; e < E; ++e) counts[e] = 0;
@@ -195,7 +221,7 @@ int orc_build_task_map(const int32_t* topk_ids, int T, int k, int E, int tile_m,
     for (int e = 0; e < E; ++e) {
         if (counts[e] > 0) {
             ne[M] = e;
-            nu[M] = ceil_div(counts[e], expert_tile_m(counts[e], tile_m, tile_m_small, small_max_rows)) * nt;
+            nu[M] = expert_m_tiles(counts[e], tile_m, tile_m_small, small_max_rows, tile_m_slack) * nt;
             M += 1;
         }
     }
@@ -203,7 +229,7 @@ int orc_build_task_map(const int32_t* topk_ids, int T, int k, int E, int tile_m,
     else for (int i = 0; i < M; ++i) sigma[i] = ne[i];
     /* tile counts in sigma order, then Alg. 1 */
     for (int i = 0; i < M; ++i)
-        nu[i] = ceil_div(counts[sigma[i]], expert_tile_m(counts[sigma[i]], tile_m, tile_m_small, small_max_rows)) * nt;
+        nu[i] = expert_m_tiles(counts[sigma[i]], tile_m, tile_m_small, small_max_rows, tile_m_slack) * nt;
     orc_tile_prefix(nu, M, tile_prefix);
     free(nu);
     free(ne);
@@ -216,15 +242,14 @@ int orc_build_task_map(const int32_t* topk_ids, int T, int k, int E, int tile_m,
  * index l split into (m_tile, n_tile), m fastest.  out = {e, m_tile, n_tile,
  * rows_in_tile}.                                                           */
 void orc_decode_block(const int32_t* tile_prefix, const int32_t* sigma, int M, const int32_t* counts,
-                      int tile_m, int tile_m_small, int small_max_rows, int B, int32_t* out4) {
+                      int tile_m, int tile_m_small, int small_max_rows, int tile_m_slack, int B, int32_t* out4) {
     int32_t h, l;
     orc_mapping(tile_prefix, M, B, &h, &l);
     int e = sigma[h];
-    int tm = expert_tile_m(counts[e], tile_m, tile_m_small, small_max_rows); /* Alg. 3: the task's type */
-    int mt = ceil_div(counts[e], tm);
+    /* Alg. 3: the task's type decides its tiling */
+    int mt = expert_m_tiles(counts[e], tile_m, tile_m_small, small_max_rows, tile_m_slack);
     int m_tile = l % mt, n_tile = l / mt;
-    int rows = counts[e] - m_tile * tm;
-    if (rows > tm) rows = tm;
+    int rows = expert_tile_rows(counts[e], tile_m, tile_m_small, small_max_rows, tile_m_slack, m_tile);
     out4[0] = e; out4[1] = m_tile; out4[2] = n_tile; out4[3] = rows;
 }
 
@@ -234,22 +259,27 @@ void orc_decode_block(const int32_t* tile_prefix, const int32_t* sigma, int M, c
  * lists all E experts in visiting order (empty ones contribute no entry).
  * Returns the number of entries written (room for cap entries of 4 ints).  */
 int orc_full_table(const int32_t* counts, int E, const int32_t* expert_order, int tile_m, int tile_m_small,
-                   int small_max_rows, int tile_n, int N, int32_t* table, int cap) {
+                   int small_max_rows, int tile_m_slack, int tile_n, int N, int32_t* table, int cap) {
     int b = 0;
     int nt = ceil_div(N, tile_n);
     for (int i = 0; i < E; ++i) {
         int e = expert_order ? expert_order[i] : i; /* experts are visited in this order; NULL = 0,1,2,... */
         int tm = expert_tile_m(counts[e], tile_m, tile_m_small, small_max_rows);
-        int mt = ceil_div(counts[e], tm);
-        for (int n_tile = 0; n_tile < nt; ++n_tile)
-            for (int m_tile = 0; m_tile < mt; ++m_tile) {
+        int slack = tm == tile_m ? tile_m_slack : 0;
+        for (int n_tile = 0; n_tile < nt; ++n_tile) {
+            /* walk the expert's rows: a tile of tm rows at a time, the rest as one tile once it fits tm + slack */
+            int first_row = 0, m_tile = 0;
+            while (first_row < counts[e]) {
                 if (b >= cap) return -1;
-                int rows = counts[e] - m_tile * tm;
-                if (rows > tm) rows = tm;
+                int rest = counts[e] - first_row;
+                int rows = rest <= tm + slack ? rest : tm;
                 table[4 * b + 0] = e; table[4 * b + 1] = m_tile;
                 table[4 * b + 2] = n_tile; table[4 * b + 3] = rows;
                 b += 1;
+                first_row += rows;
+                m_tile += 1;
             }
+        }
     }
     return b;
 }

@@ -31,12 +31,13 @@ MOE_MAP_MAGIC = 0x3142534D
 MOE_MAP_HDR_WORDS = 32
 HDR = dict(MAGIC=0, T=1, K_TOP=2, E=3, N=4, TILE_M=5, TILE_N=6, NT=7, M=8, TOTAL_TILES=9, ORDER=10,
            STATUS=11, R=12, E64=13, SIGMA_ORDER=14, TILE_M_SMALL=15,
-           SMALL_MAX_ROWS=16)
+           SMALL_MAX_ROWS=16, TILE_M_SLACK=17)
 
 EXPORTS = [
     "moe_map_off_counts", "moe_map_off_offsets", "moe_map_off_sigma", "moe_map_off_tile_prefix",
     "moe_map_off_sorted_rows", "moe_task_map_bytes", "moe_grid_upper_bound", "moe_build_task_map",
     "moe_build_task_map_ordered", "moe_build_task_map_tiled", "moe_grid_upper_bound_tiled", "moe_tile_pair_supported",
+    "moe_build_task_map_ex", "moe_tiling_supported",
     "moe_task_map_status", "moe_task_map_expand", "moe_grouped_gemm", "moe_tile_supported", "moe_strerror",
 ]
 
@@ -51,7 +52,14 @@ class moe_gemm_desc(ctypes.Structure):
     _fields_ = [("dtype", ctypes.c_int32), ("T", ctypes.c_int32), ("k", ctypes.c_int32), ("E", ctypes.c_int32),
                 ("K", ctypes.c_int32), ("N", ctypes.c_int32), ("tile_m", ctypes.c_int32),
                 ("tile_n", ctypes.c_int32), ("x_scale", ctypes.c_void_p), ("w_scale", ctypes.c_void_p),
-                ("tile_m_small", ctypes.c_int32), ("small_max_rows", ctypes.c_int32)]
+                ("tile_m_small", ctypes.c_int32), ("small_max_rows", ctypes.c_int32),
+                ("tile_m_slack", ctypes.c_int32)]
+
+
+class moe_tiling(ctypes.Structure):
+    _fields_ = [("tile_m", ctypes.c_int32), ("tile_n", ctypes.c_int32), ("order", ctypes.c_int32),
+                ("tile_m_small", ctypes.c_int32), ("small_max_rows", ctypes.c_int32),
+                ("tile_m_slack", ctypes.c_int32)]
 
 
 _lib = None
@@ -82,6 +90,11 @@ def lib() -> ctypes.CDLL:
         L.moe_grid_upper_bound_tiled.argtypes = [ctypes.c_int] * 8
         L.moe_tile_pair_supported.restype = ctypes.c_int
         L.moe_tile_pair_supported.argtypes = [ctypes.c_int] * 4
+        L.moe_build_task_map_ex.restype = ctypes.c_int
+        L.moe_build_task_map_ex.argtypes = [ctypes.c_void_p] + [ctypes.c_int] * 4 + [ctypes.POINTER(moe_tiling),
+                                                                                      ctypes.c_void_p, ctypes.c_void_p]
+        L.moe_tiling_supported.restype = ctypes.c_int
+        L.moe_tiling_supported.argtypes = [ctypes.c_int, ctypes.POINTER(moe_tiling)]
         L.moe_task_map_status.restype = ctypes.c_int
         L.moe_task_map_status.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
         L.moe_task_map_expand.restype = ctypes.c_int
@@ -169,6 +182,33 @@ def moe_tile_pair_supported(dtype: int, tile_m: int, tile_n: int, tile_m_small: 
     return bool(lib().moe_tile_pair_supported(dtype, tile_m, tile_n, tile_m_small))
 
 
+@dataclass
+class Tiling:
+    tile_m: int
+    tile_n: int
+    order: int = 0
+    tile_m_small: int = 0
+    small_max_rows: int = 0
+    tile_m_slack: int = 0
+
+    def c_struct(self) -> moe_tiling:
+        return moe_tiling(self.tile_m, self.tile_n, self.order, self.tile_m_small, self.small_max_rows, self.tile_m_slack)
+
+
+def moe_build_task_map_ex(topk_ids: torch.Tensor, T: int, k: int, E: int, N: int, tiling: Tiling,
+                          task_map: torch.Tensor, check: bool = True) -> int:
+    g = tiling.c_struct()
+    rc = lib().moe_build_task_map_ex(_ptr(topk_ids), T, k, E, N, ctypes.byref(g), _ptr(task_map), _stream())
+    if check and rc != MOE_OK:
+        raise MoeError(rc, "moe_build_task_map_ex")
+    return rc
+
+
+def moe_tiling_supported(dtype: int, tiling: Tiling) -> bool:
+    g = tiling.c_struct()
+    return bool(lib().moe_tiling_supported(dtype, ctypes.byref(g)))
+
+
 def moe_task_map_status(task_map: torch.Tensor) -> int:
     return int(lib().moe_task_map_status(_ptr(task_map), _stream()))
 
@@ -194,12 +234,13 @@ class GemmDesc:
     w_scale: Optional[torch.Tensor] = None
     tile_m_small: int = 0
     small_max_rows: int = 0
+    tile_m_slack: int = 0
 
     def c_struct(self) -> moe_gemm_desc:
         return moe_gemm_desc(self.dtype, self.T, self.k, self.E, self.K, self.N, self.tile_m, self.tile_n,
                              None if self.x_scale is None else self.x_scale.data_ptr(),
                              None if self.w_scale is None else self.w_scale.data_ptr(),
-                             self.tile_m_small, self.small_max_rows)
+                             self.tile_m_small, self.small_max_rows, self.tile_m_slack)
 
 
 def moe_grouped_gemm(X: torch.Tensor, W: torch.Tensor, topk_ids: Optional[torch.Tensor], task_map: torch.Tensor,

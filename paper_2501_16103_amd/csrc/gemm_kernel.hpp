@@ -45,6 +45,7 @@ struct GemmArgs {
     const float* w_scale;
     int T, k, E, K, N;
     int tile_m_small, small_max_rows;  // second tiling strategy of the map (0, 0 = none)
+    int tile_m_slack;                  // slack rows of the map's last m-tiles
 };
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
@@ -73,31 +74,37 @@ __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14));
 }
 
-template <int BM_, int BN_, int BK_, int WM_, int WN_, int NS_, bool FP8_ = false>
+// NS_ ring stages of token tiles, NSW_ ring stages of weight tiles (each k-tile deep).  SLACK_: rows a tile may
+// hold beyond BM_ (the map's tile_m), for maps built with tile_m_slack.
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int NS_, bool FP8_ = false, int NSW_ = NS_, int SLACK_ = 0>
 struct PipeCfg {
-    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, NS = NS_;
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, NS = NS_, NSW = NSW_, SLACK = SLACK_;
+    static constexpr int BMC = BM + SLACK;                     // row capacity of the tile in LDS and registers
     static constexpr bool FP8 = FP8_;
     static constexpr int ES = FP8 ? 1 : 2;
     static constexpr int NT = 64 * WM * WN;
-    static constexpr int WTM = BM / WM, WTN = BN / WN;
+    static constexpr int WTM = BMC / WM, WTN = BN / WN;
     static constexpr int MF = (!FP8 && WTM >= 32) ? 32 : 16;   // MFMA block edge
     static constexpr int KS = MF == 32 ? 16 : 32;              // k elements per MFMA
     static constexpr int KSTEPS = BK / KS;
     static constexpr int NBW = WTN / MF, MBW = WTM / MF;
+    static constexpr int MBW_BODY = BM / WM / MF;              // row blocks per wavefront without the slack rows
     static constexpr int ACC = MF == 32 ? 16 : 4;              // accumulator registers per block
     static constexpr int XROW = BK * ES, CPR = XROW / 16;
     static constexpr int WROW = BN * ES, CPRW = WROW / 16;
-    static constexpr int XS_BYTES = BM * XROW, WS_BYTES = BK * WROW;
-    static constexpr int STAGE_BYTES = XS_BYTES + WS_BYTES;
-    static constexpr int LDS_BYTES = NS * STAGE_BYTES + BM * 4;
-    // LDS reads per k-step: weight fragments (two 4-k halves for bf16, one 8-k piece for fp8), token fragments
-    static constexpr int WREADS = NBW * (FP8 ? 1 : 2), NREADS = WREADS + MBW, NM = NBW * MBW;
+    static constexpr int XS_BYTES = BMC * XROW, WS_BYTES = BK * WROW;
+    static constexpr int W_RING = NS * XS_BYTES;               // byte offset of the weight ring
+    static constexpr int LDS_BYTES = NS * XS_BYTES + NSW * WS_BYTES;
+    // weight-fragment LDS reads per k-step (two 4-k halves for bf16, one 8-k piece for fp8)
+    static constexpr int WREADS = NBW * (FP8 ? 1 : 2);
     // memory-bound tiles start the weight stream before the token rows are known
     static constexpr bool EARLY_W = MF == 16;
     static_assert(XROW == 64 || XROW == 128, "token tile rows are 64 or 128 bytes");
     static_assert(WTM % MF == 0 && WTN % MF == 0 && KSTEPS >= 2 && BK % KS == 0, "wave tile");
+    static_assert(BM % (WM * MF) == 0 && SLACK % (WM * MF) == 0, "body and slack rows split evenly over the wavefront rows");
     static_assert(WROW <= 1024, "weight tile row");
     static_assert(XS_BYTES % 1024 == 0 && WS_BYTES % 1024 == 0, "DMA granularity");
+    static_assert(NSW >= NS && NS >= 2, "the weight ring is at least as deep as the token ring");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS");
 };
 
@@ -114,38 +121,47 @@ __device__ __forceinline__ int pswz_w(int krow) {
     return s & (C::CPRW - 1);
 }
 
-// Main loop, per k-tile kt held in ring stage `cur` (NS stages of [token tile | weight tile]):
-//   k-steps 0 .. KSTEPS-2 : MFMA of the step, interleaved with the LDS reads of the next step
-//   wait for tile kt+1's DMA, workgroup barrier  (every wavefront has now read all of stage `cur`)
-//   last k-step           : its MFMAs, interleaved with the first LDS reads of tile kt+1 and with the DMA
-//                           instructions that refill stage `cur` with tile kt+NS
-// so neither the barrier nor the DMA issue leaves the MFMA pipe without queued work, and NS-1 tiles of
-// weights per workgroup are in flight from HBM at any time.
 // One tile of the batch: everything after the task-map decode.  A task function in the sense of Alg. 3.
+//
+// LDS holds two rings: NS stages of token tiles and NSW >= NS stages of weight tiles.
+// Main loop, per k-tile kt (token stage kt % NS, weight stage kt % NSW):
+//   k-steps 0 .. KSTEPS-2 : MFMA of the step, interleaved with the LDS reads of the next step
+//   wait for tile kt+1's DMA, workgroup barrier  (every wavefront has now read all of tile kt)
+//   last k-step           : its MFMAs, interleaved with the first LDS reads of tile kt+1 and with the DMA
+//                           instructions that refill the two stages with token tile kt+NS and weight tile kt+NSW
+// so neither the barrier nor the DMA issue leaves the MFMA pipe without queued work, and NSW-1 tiles of
+// weights per workgroup are in flight from HBM at any time.
+//
+// Rows: MF-row block b of the tile belongs to wavefront row b % WM (its block b / WM), so a partly filled tile
+// spreads its live blocks evenly over the wavefront rows.  The loop exists in copies for a compile-time number of
+// blocks per wavefront (all of them, or all but the slack block) and in one copy that tests each block at run time.
 template <class C>
 __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __restrict__ map, const MapLayout& L,
                                           const TileCoord& tc, char* smem) {
-    constexpr int BM = C::BM, BN = C::BN, BK = C::BK, ES = C::ES, NT = C::NT, NW = NT / 64, NS = C::NS, MF = C::MF;
-    constexpr int KSTEPS = C::KSTEPS, NREADS = C::NREADS, NM = C::NM, WREADS = C::WREADS;
+    constexpr int BN = C::BN, BK = C::BK, ES = C::ES, NT = C::NT, NW = NT / 64, NS = C::NS, NSW = C::NSW, MF = C::MF;
+    constexpr int KSTEPS = C::KSTEPS, WREADS = C::WREADS, NBW = C::NBW, MBW = C::MBW;
     const int n0 = tc.n_tile * BN;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / C::WN, wn = wave % C::WN;
     const int g = lane >> 4, li = lane & 15;
+    const int lrow = MF == 32 ? (lane & 31) : li;  // row of this lane inside an MF-row block
 
     // ---- DMA geometry: one wave instruction moves 64 x 16 B = 1 KiB, linear in LDS
     constexpr int XI_TOT = C::XS_BYTES / 1024, WI_TOT = C::WS_BYTES / 1024;
     static_assert(XI_TOT % NW == 0 && WI_TOT % NW == 0, "every wave issues the same number of DMA instructions");
-    constexpr int XI = XI_TOT / NW, WI = WI_TOT / NW, ND = XI + WI;
+    constexpr int XI = XI_TOT / NW, WI = WI_TOT / NW;
+    constexpr int XI_BODY = C::BM * C::XROW / 1024 / NW;   // instructions that cover rows < BM
+    static_assert(C::SLACK == 0 || (C::BM * C::XROW) % (1024 * NW) == 0, "slack rows start at a DMA instruction boundary");
     constexpr int XROWS_PER_INST = 1024 / C::XROW, WROWS_PER_INST = 1024 / C::WROW;
-    static_assert((NS - 1) * ND < 64, "vmcnt range");
-    uint32_t d_off[ND];
+    static_assert((NS - 1) * XI + (NSW - 1) * WI < 64, "vmcnt range");
+    uint32_t dx_off[XI], dw_off[WI];
     const uint32_t w_row_bytes = (uint32_t)a.N * ES;
 #pragma unroll
     for (int j = 0; j < WI; ++j) {
         const int inst = j * NW + wave;
         const int krow = inst * WROWS_PER_INST + lane / C::CPRW, pos = lane % C::CPRW;
-        d_off[XI + j] = (uint32_t)krow * w_row_bytes + ((pos ^ pswz_w<C>(krow)) << 4);
+        dw_off[j] = (uint32_t)krow * w_row_bytes + ((pos ^ pswz_w<C>(krow)) << 4);
     }
     const char* Xb = static_cast<const char*>(a.X);
     const char* Wt = static_cast<const char*>(a.W) + ((size_t)tc.e * a.K * a.N + n0) * ES;
@@ -153,53 +169,53 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
     const uint32_t lds0 = (uint32_t)(uintptr_t)(MOE_LDS(char)*)smem;
     const int KT = a.K / BK;
 
-    // d-th DMA instruction of this wave for k-tile kt: token rows first (d < XI), then weight rows
-    auto dma_one = [&](int d, int kt, int stage) {
-        const uint32_t sb = lds0 + stage * C::STAGE_BYTES;
-        if (d < XI) dma16(d_off[d], Xb + (size_t)kt * (BK * ES), sb + (d * NW + wave) * 1024);
-        else dma16(d_off[d], Wt + (size_t)kt * w_kt_stride, sb + C::XS_BYTES + ((d - XI) * NW + wave) * 1024);
+    // j-th token-row / weight-row DMA instruction of this wave for k-tile kt, into ring stage `stage`
+    auto dma_x = [&](int j, int kt, int stage) {
+        dma16(dx_off[j], Xb + (size_t)kt * (BK * ES), lds0 + stage * C::XS_BYTES + (j * NW + wave) * 1024);
+    };
+    auto dma_w = [&](int j, int kt, int stage) {
+        dma16(dw_off[j], Wt + (size_t)kt * w_kt_stride, lds0 + C::W_RING + stage * C::WS_BYTES + (j * NW + wave) * 1024);
     };
 
     if (C::EARLY_W) {
 #pragma unroll
-        for (int s = 0; s < NS; ++s)
+        for (int s = 0; s < NSW; ++s)
             if (s < KT) {
 #pragma unroll
-                for (int d = XI; d < ND; ++d) dma_one(d, s, s);
+                for (int j = 0; j < WI; ++j) dma_w(j, s, s);
             }
     }
 
-    int* s_row = reinterpret_cast<int*>(smem + NS * C::STAGE_BYTES);
-    for (int i = tid; i < BM; i += NT) s_row[i] = i < tc.rows ? map[L.off_rows + tc.row_base + i] : -1;
-    __syncthreads();
+    const int32_t* rows_of_tile = map + L.off_rows + tc.row_base;
 #pragma unroll
     for (int j = 0; j < XI; ++j) {
         const int inst = j * NW + wave;
         const int row = inst * XROWS_PER_INST + lane / C::CPR, pos = lane % C::CPR;
-        int r = s_row[row];
-        if (r < 0) r = s_row[0];  // rows past the expert's count: fetch a valid row, never store it
-        d_off[j] = (uint32_t)(r / a.k) * (uint32_t)(a.K * ES) + ((pos ^ pswz_x<C>(row)) << 4);
+        // rows past the tile's count: fetch a valid row, never store it
+        const int r = rows_of_tile[row < tc.rows ? row : 0];
+        dx_off[j] = (uint32_t)(r / a.k) * (uint32_t)(a.K * ES) + ((pos ^ pswz_x<C>(row)) << 4);
     }
 
     using acc_t = typename std::conditional<MF == 32, f32x16_t, f32x4_t>::type;
-    acc_t acc[C::NBW][C::MBW];
+    acc_t acc[NBW][MBW];
 #pragma unroll
-    for (int nb = 0; nb < C::NBW; ++nb)
+    for (int nb = 0; nb < NBW; ++nb)
 #pragma unroll
-        for (int mb = 0; mb < C::MBW; ++mb)
+        for (int mb = 0; mb < MBW; ++mb)
 #pragma unroll
             for (int j = 0; j < C::ACC; ++j) acc[nb][mb][j] = 0.f;
 
-    // whole MF-row blocks of this wave's token sub-tile that hold at least one real row
-    int mb_live = (tc.rows - wm * C::WTM + MF - 1) / MF;
-    mb_live = mb_live < 0 ? 0 : (mb_live > C::MBW ? C::MBW : mb_live);
+    // blocks of this wavefront that hold at least one real row: blocks wm, wm + WM, ... below ceil(rows / MF)
+    const int live_blocks = (tc.rows + MF - 1) / MF;
+    int mb_live = (live_blocks - wm + C::WM - 1) / C::WM;
+    mb_live = mb_live < 0 ? 0 : (mb_live > MBW ? MBW : mb_live);
 
     // ---- fragment registers, double-buffered across k-steps; per-lane LDS offsets of k-step 0
-    u32x2_t wq[2][C::NBW][2];
-    u32x4_t xq[2][C::MBW];
-    int w_rd[C::NBW], x_rd[C::MBW];
+    u32x2_t wq[2][NBW][2];
+    u32x4_t xq[2][MBW];
+    int w_rd[NBW];
 #pragma unroll
-    for (int nb = 0; nb < C::NBW; ++nb) {
+    for (int nb = 0; nb < NBW; ++nb) {
         int kr0, ncol, c, within;
         if constexpr (C::FP8) {
             kr0 = 8 * g + (li >> 1);
@@ -217,13 +233,17 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
         // the swizzle of row kr0 also holds for kr0 + 4 and kr0 + KS*kk (see pswz_w), so later k-steps add a constant
         w_rd[nb] = kr0 * C::WROW + ((c ^ pswz_w<C>(kr0)) << 4) + within;
     }
-#pragma unroll
-    for (int mb = 0; mb < C::MBW; ++mb) x_rd[mb] = (wm * C::WTM + mb * MF + (MF == 32 ? (lane & 31) : li)) * C::XROW;
+    // tile row of this lane in its block mb; the swizzle only looks at row bits below MF, so it is the same for every block
+    const int row0 = wm * MF + lrow;
+    const int x_rd = row0 * C::XROW;
+    constexpr int X_BLOCK_STRIDE = C::WM * MF * C::XROW;
+    static_assert(MF % 16 == 0, "pswz_x must not depend on the block");
+    const int xswz = pswz_x<C>(row0);
 
     // r-th LDS read of k-step kk, ordered by first use in the MFMA sequence (token block 0, weights, token blocks 1..)
-    auto read_one = [&](int r, int stage, int kk, int buf, bool tail) {
-        const char* xs = smem + stage * C::STAGE_BYTES;
-        const char* ws = xs + C::XS_BYTES;
+    auto read_one = [&](int r, int sx, int sw, int kk, int buf, bool tail) {
+        const char* xs = smem + sx * C::XS_BYTES;
+        const char* ws = smem + C::W_RING + sw * C::WS_BYTES;
         if (r >= 1 && r <= WREADS) {
             if constexpr (C::FP8) {
                 const int nb = r - 1;
@@ -237,19 +257,19 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
         } else {
             const int mb = r == 0 ? 0 : r - WREADS;
             if (tail && mb >= mb_live) return;
-            const int row = wm * C::WTM + mb * MF + (MF == 32 ? (lane & 31) : li);
+            const char* xrow = xs + x_rd + mb * X_BLOCK_STRIDE;
             if constexpr (C::FP8) {
                 const int c = kk * 2 + (g >> 1);
-                const u32x2_t v = *reinterpret_cast<const u32x2_t*>(xs + x_rd[mb] + ((c ^ pswz_x<C>(row)) << 4) + (g & 1) * 8);
+                const u32x2_t v = *reinterpret_cast<const u32x2_t*>(xrow + ((c ^ xswz) << 4) + (g & 1) * 8);
                 xq[buf][mb].x = v.x; xq[buf][mb].y = v.y;
             } else {
                 const int c = MF == 32 ? kk * 2 + (lane >> 5) : kk * 4 + g;
-                xq[buf][mb] = *reinterpret_cast<const u32x4_t*>(xs + x_rd[mb] + ((c ^ pswz_x<C>(row)) << 4));
+                xq[buf][mb] = *reinterpret_cast<const u32x4_t*>(xrow + ((c ^ xswz) << 4));
             }
         }
     };
     auto mfma_one = [&](int i, int buf, bool tail) {
-        const int mb = i / C::NBW, nb = i % C::NBW;
+        const int mb = i / NBW, nb = i % NBW;
         if (tail && mb >= mb_live) return;
         if constexpr (C::FP8) {
             const u32x2_t xv = {xq[buf][mb].x, xq[buf][mb].y};
@@ -263,38 +283,49 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
         }
     };
 
-    // ---- prologue: fill the ring, first fragments into registers
-#pragma unroll
-    for (int s = 0; s < NS; ++s) {
-        if (s < KT) {
-#pragma unroll
-            for (int d = 0; d < (C::EARLY_W ? XI : ND); ++d) dma_one(d, s, s);
-        }
-    }
-    // EARLY_W issued weights and token rows in two batches: wait for all of it; else only tile 0 is needed
-    if (!C::EARLY_W && NS <= KT) wait_vmcnt<(NS - 1) * ND>(); else wait_vmcnt<0>();
-    __syncthreads();
-#pragma unroll
-    for (int r = 0; r < NREADS; ++r) read_one(r, 0, 0, 0, false);
-
-    auto main_loop = [&](auto tail_tag) {
+    // The tile's whole k loop for NMB row blocks per wavefront and XIL token-row DMA instructions per stage.
+    auto run = [&](auto nmb_tag, auto xil_tag, auto tail_tag) {
+        constexpr int NMB = decltype(nmb_tag)::value, XIL = decltype(xil_tag)::value;
         constexpr bool TAIL = decltype(tail_tag)::value;
-        int cur = 0;
+        constexpr int NM = NBW * NMB, NREADS = WREADS + NMB, ND = XIL + WI;
+        // d-th DMA instruction of a stage: token rows first
+        auto dma_one = [&](int d, int ktx, int ktw, int sx, int sw, bool do_x, bool do_w) {
+            if (d < XIL) { if (do_x) dma_x(d, ktx, sx); }
+            else if (do_w) dma_w(d - XIL, ktw, sw);
+        };
+        // ---- prologue: fill the rings, first fragments into registers
+#pragma unroll
+        for (int s = 0; s < NSW; ++s) {
+            if (s < KT) {
+#pragma unroll
+                for (int d = (s < NS ? 0 : XIL); d < (C::EARLY_W ? XIL : ND); ++d) dma_one(d, s, s, s, s, true, true);
+            }
+        }
+        // EARLY_W issued weights and token rows in two batches: wait for all of it; else only tile 0 is needed
+        if (!C::EARLY_W && NSW <= KT) wait_vmcnt<(NS - 1) * XIL + (NSW - 1) * WI>(); else wait_vmcnt<0>();
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < NREADS; ++r) read_one(r, 0, 0, 0, 0, TAIL);
+
+        int cur = 0, curw = 0;
         auto iteration = [&](int kt, auto steady_tag) {
-            constexpr bool STEADY = decltype(steady_tag)::value;  // kt + NS < KT: every fetch below is in range
+            constexpr bool STEADY = decltype(steady_tag)::value;  // kt + NSW < KT: every fetch below is in range
             const int nxt = cur + 1 == NS ? 0 : cur + 1;
+            const int nxtw = curw + 1 == NSW ? 0 : curw + 1;
 #pragma unroll
             for (int kk = 0; kk < KSTEPS - 1; ++kk) {
 #pragma unroll
                 for (int i = 0; i < NM; ++i) {
                     mfma_one(i, kk & 1, TAIL);
 #pragma unroll
-                    for (int r = i * NREADS / NM; r < (i + 1) * NREADS / NM; ++r) read_one(r, cur, kk + 1, (kk + 1) & 1, TAIL);
+                    for (int r = i * NREADS / NM; r < (i + 1) * NREADS / NM; ++r) read_one(r, cur, curw, kk + 1, (kk + 1) & 1, TAIL);
                     MOE_SCHED_FENCE();
                 }
             }
-            // the next tile must have landed; the NS-2 tiles behind it may still be in flight
-            if (STEADY || kt + NS - 1 < KT) wait_vmcnt<(NS - 2) * ND>(); else wait_vmcnt<0>();
+            // Tile kt+1 must have landed.  Issue order is [X(j+NS) W(j+NSW)] per iteration j, so what may still
+            // be in flight is the NS-2 iterations' worth issued after X(kt+1), plus, with a deeper weight ring,
+            // the weight rows issued right behind X(kt+1).
+            if (STEADY || kt + NSW - 1 < KT) wait_vmcnt<(NS - 2) * ND + (NSW > NS ? WI : 0)>(); else wait_vmcnt<0>();
             __syncthreads();
             MOE_SCHED_FENCE();
 #pragma unroll
@@ -302,36 +333,44 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
                 mfma_one(i, (KSTEPS - 1) & 1, TAIL);
                 if (STEADY || kt + 1 < KT) {
 #pragma unroll
-                    for (int r = i * NREADS / NM; r < (i + 1) * NREADS / NM; ++r) read_one(r, nxt, 0, KSTEPS & 1, TAIL);
+                    for (int r = i * NREADS / NM; r < (i + 1) * NREADS / NM; ++r) read_one(r, nxt, nxtw, 0, KSTEPS & 1, TAIL);
                 }
-                if (STEADY || kt + NS < KT) {
 #pragma unroll
-                    for (int d = i * ND / NM; d < (i + 1) * ND / NM; ++d) dma_one(d, kt + NS, cur);
-                }
+                for (int d = i * ND / NM; d < (i + 1) * ND / NM; ++d)
+                    dma_one(d, kt + NS, kt + NSW, cur, curw, STEADY || kt + NS < KT, STEADY || kt + NSW < KT);
                 MOE_SCHED_FENCE();
             }
             cur = nxt;
+            curw = nxtw;
         };
         int kt = 0;
-        for (; kt + NS < KT; ++kt) iteration(kt, std::true_type{});
+        for (; kt + NSW < KT; ++kt) iteration(kt, std::true_type{});
         for (; kt < KT; ++kt) iteration(kt, std::false_type{});
     };
-    if (mb_live == C::MBW) main_loop(std::false_type{}); else main_loop(std::true_type{});
+    using std::integral_constant;
+    if (C::SLACK > 0 && tc.rows > C::BM) {
+        // the slack block of a wavefront row without real rows there is computed on padding and never stored
+        run(integral_constant<int, MBW>{}, integral_constant<int, XI>{}, std::false_type{});
+    } else if (mb_live == C::MBW_BODY) {
+        run(integral_constant<int, C::MBW_BODY>{}, integral_constant<int, XI_BODY>{}, std::false_type{});
+    } else {
+        run(integral_constant<int, C::MBW_BODY>{}, integral_constant<int, XI_BODY>{}, std::true_type{});
+    }
     wait_vmcnt<0>();
 
     // ---- epilogue: fp32 -> bf16 (RNE), scatter to Y[r, n]; fp8 applies the two scales first
     char* Yb = static_cast<char*>(a.Y);
     const size_t y_row_bytes = (size_t)a.N * 2;
 #pragma unroll
-    for (int mb = 0; mb < C::MBW; ++mb) {
-        const int m_local = wm * C::WTM + mb * MF + (MF == 32 ? (lane & 31) : li);
-        const int r = s_row[m_local];
-        if (r < 0) continue;
+    for (int mb = 0; mb < MBW; ++mb) {
+        const int m_local = (mb * C::WM + wm) * MF + lrow;
+        if (m_local >= tc.rows) continue;
+        const int r = rows_of_tile[m_local];
         float xsc = 1.f, wsc = 1.f;
         if constexpr (C::FP8) { xsc = a.x_scale[r / a.k]; wsc = a.w_scale[tc.e]; }
         char* yrow = Yb + (size_t)r * y_row_bytes + (size_t)n0 * 2;
 #pragma unroll
-        for (int nb = 0; nb < C::NBW; ++nb) {
+        for (int nb = 0; nb < NBW; ++nb) {
 #pragma unroll
             for (int jq = 0; jq < C::ACC / 4; ++jq) {
                 const int n_local = MF == 32 ? wn * C::WTN + nb * 32 + 8 * jq + 4 * (lane >> 5) : wn * C::WTN + nb * 16 + 4 * g;
@@ -351,14 +390,14 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
 
 // Block index -> tile (Alg. 2 + 4), shared by the kernels below.  Returns false for surplus workgroups and for
 // a map that does not belong to this launch (wrong shape, tiling or status): those do nothing.
-template <int BM_BIG, int BN, int BM_SMALL>
+template <int BM_BIG, int BN, int BM_SMALL, int SLACK>
 __device__ __forceinline__ bool locate_tile(const GemmArgs& a, const int32_t* __restrict__ map, MapLayout& L, TileCoord& tc) {
     const int total = map[MOE_HDR_TOTAL_TILES];
     const bool hdr_ok = map[MOE_HDR_MAGIC] == MOE_MAP_MAGIC && map[MOE_HDR_T] == a.T && map[MOE_HDR_K_TOP] == a.k &&
                         map[MOE_HDR_E] == a.E && map[MOE_HDR_N] == a.N && map[MOE_HDR_TILE_M] == BM_BIG &&
                         map[MOE_HDR_TILE_N] == BN && map[MOE_HDR_STATUS] == 0 &&
                         map[MOE_HDR_TILE_M_SMALL] == BM_SMALL && map[MOE_HDR_SMALL_MAX_ROWS] == a.small_max_rows &&
-                        a.tile_m_small == BM_SMALL;
+                        a.tile_m_small == BM_SMALL && map[MOE_HDR_TILE_M_SLACK] == SLACK && a.tile_m_slack == SLACK;
     if (!hdr_ok) return false;
     // Workgroup ids are dealt round-robin to the 8 XCDs; give each XCD one contiguous run of block indices so
     // that neighbours in the map share an L2.
@@ -368,31 +407,49 @@ __device__ __forceinline__ bool locate_tile(const GemmArgs& a, const int32_t* __
     const int B = (blockIdx.x & 7) * per_xcd + slot;
     if (B >= total) return false;
     L = map_layout(a.E);
-    tc = decode_block(map, L, BM_BIG, B, BM_SMALL, a.small_max_rows);
+    const moe_tiling g = {BM_BIG, BN, 0, BM_SMALL, a.small_max_rows, SLACK};
+    tc = decode_block(map, L, g, B);
     return true;
 }
 
-// One tiling strategy for every expert.
+// Run one tile with the narrowest task function that holds its rows.  An expert's last m-tile is often almost
+// empty (c_e just above a multiple of tile_m); a narrower function of the same launch shape moves fewer token
+// rows and issues no MFMA for the padding.  The map is unchanged: the choice only depends on the tile's row count.
 template <class C>
+__device__ __forceinline__ void run_tile(const GemmArgs& a, const int32_t* __restrict__ map, const MapLayout& L,
+                                         const TileCoord& tc, char* smem) {
+    pipe_tile<C>(a, map, L, tc, smem);
+}
+template <class C, class T0, class... Ts>
+__device__ __forceinline__ void run_tile(const GemmArgs& a, const int32_t* __restrict__ map, const MapLayout& L,
+                                         const TileCoord& tc, char* smem) {
+    static_assert(T0::BM < C::BM && T0::NT == C::NT && T0::BN == C::BN && T0::FP8 == C::FP8 && T0::LDS_BYTES <= C::LDS_BYTES,
+                  "a tail function shares the launch shape of the full one");
+    if (tc.rows <= T0::BM) pipe_tile<T0>(a, map, L, tc, smem);
+    else run_tile<C, Ts...>(a, map, L, tc, smem);
+}
+
+// One tiling strategy for every expert.  Tails: narrower task functions for partly filled tiles, narrowest first.
+template <class C, class... Tails>
 __global__ __launch_bounds__(C::NT) void moe_gemm_pipe_kernel(GemmArgs a) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     MapLayout L;
     TileCoord tc;
-    if (!locate_tile<C::BM, C::BN, 0>(a, a.map, L, tc)) return;
-    pipe_tile<C>(a, a.map, L, tc, smem);
+    if (!locate_tile<C::BM, C::BN, 0, C::SLACK>(a, a.map, L, tc)) return;
+    run_tile<C, Tails...>(a, a.map, L, tc, smem);
 }
 
 // Two tiling strategies in one launch (Alg. 3 with K = 2 task types): the expert's row count picks the task
 // function; both share the thread count, the n-tile width and the LDS allocation.
-template <class CBIG, class CSMALL>
+template <class CBIG, class CSMALL, class... Tails>
 __global__ __launch_bounds__(CBIG::NT) void moe_gemm_pipe2_kernel(GemmArgs a) {
     static_assert(CBIG::NT == CSMALL::NT && CBIG::BN == CSMALL::BN && CBIG::FP8 == CSMALL::FP8, "task functions must be launch-compatible");
     extern __shared__ __attribute__((aligned(16))) char smem[];
     MapLayout L;
     TileCoord tc;
-    if (!locate_tile<CBIG::BM, CBIG::BN, CSMALL::BM>(a, a.map, L, tc)) return;
+    if (!locate_tile<CBIG::BM, CBIG::BN, CSMALL::BM, CBIG::SLACK>(a, a.map, L, tc)) return;
     if (tc.small) pipe_tile<CSMALL>(a, a.map, L, tc, smem);
-    else pipe_tile<CBIG>(a, a.map, L, tc, smem);
+    else run_tile<CBIG, Tails...>(a, a.map, L, tc, smem);
 }
 
 }  // namespace moe

@@ -27,30 +27,30 @@ int nchunks_for(int64_t R) { return (int)((R + kChunkRows - 1) / kChunkRows); }
 
 typedef int (*gemm_launch_fn)(const GemmArgs&, int64_t grid, hipStream_t);
 
-template <class C>
+template <class C, class... Tails>
 int launch_pipe(const GemmArgs& a, int64_t grid, hipStream_t s) {
     static bool attr_set = false;
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&moe_gemm_pipe_kernel<C>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&moe_gemm_pipe_kernel<C, Tails...>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES) != hipSuccess)
             return MOE_ERR_HIP;
         attr_set = true;
     }
-    moe_gemm_pipe_kernel<C><<<dim3((unsigned)grid), dim3(C::NT), C::LDS_BYTES, s>>>(a);
+    moe_gemm_pipe_kernel<C, Tails...><<<dim3((unsigned)grid), dim3(C::NT), C::LDS_BYTES, s>>>(a);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
-template <class CBIG, class CSMALL>
+template <class CBIG, class CSMALL, class... Tails>
 int launch_pipe2(const GemmArgs& a, int64_t grid, hipStream_t s) {
     constexpr int lds = CBIG::LDS_BYTES > CSMALL::LDS_BYTES ? CBIG::LDS_BYTES : CSMALL::LDS_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&moe_gemm_pipe2_kernel<CBIG, CSMALL>),
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&moe_gemm_pipe2_kernel<CBIG, CSMALL, Tails...>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
             return MOE_ERR_HIP;
         attr_set = true;
     }
-    moe_gemm_pipe2_kernel<CBIG, CSMALL><<<dim3((unsigned)grid), dim3(CBIG::NT), lds, s>>>(a);
+    moe_gemm_pipe2_kernel<CBIG, CSMALL, Tails...><<<dim3((unsigned)grid), dim3(CBIG::NT), lds, s>>>(a);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
@@ -58,16 +58,23 @@ struct GemmVariant {
     int dtype, tile_m, tile_n, bk;
     gemm_launch_fn fn;
     int tile_m_small = 0;  // second tiling strategy handled by the same launch (0 = none)
+    int tile_m_slack = 0;  // rows the last m-tile may hold beyond tile_m
 };
 
 // Pipelined bf16 kernels:  BM   BN   BK  WM WN  ring stages
-using Pb_256x256 = PipeCfg<256, 256, 64, 2, 4, 2>;
+using Pb_256x256 = PipeCfg<256, 256, 64, 2, 4, 2, false, 3>;
+// same, for maps whose last m-tiles hold up to 64 slack rows
+using Pb_256x256s = PipeCfg<256, 256, 64, 2, 4, 2, false, 2, 64>;
 using Pb_128x256 = PipeCfg<128, 256, 64, 1, 4, 3>;
 using Pb_128x128 = PipeCfg<128, 128, 64, 2, 2, 4>;
 using Pb_64x256 = PipeCfg<64, 256, 64, 1, 4, 3>;
 using Pb_64x128 = PipeCfg<64, 128, 64, 1, 4, 4>;
 using Pb_32x256 = PipeCfg<32, 256, 64, 1, 4, 4>;
 using Pb_32x128 = PipeCfg<32, 128, 64, 1, 4, 6>;
+// Narrow task functions that share the launch shape (512 threads, 256-wide n-tiles) of Pb_256x256: used for its
+// partly filled tiles and as the small-expert strategy of a two-strategy launch
+using Ps_64x256 = PipeCfg<64, 256, 64, 1, 8, 3>;
+using Ps_128x256 = PipeCfg<128, 256, 64, 1, 8, 2>;
 // 16-row tiles (two wavefronts) and fp8: the weight stream starts before the token rows are known
 using Pb_16x256 = PipeCfg<16, 256, 64, 1, 2, 2>;
 using Pb_16x128 = PipeCfg<16, 128, 64, 1, 2, 4>;
@@ -77,7 +84,8 @@ using P8_16x64 = PipeCfg<16, 64, 128, 1, 2, 4, true>;
 using P8_32x128 = PipeCfg<32, 128, 128, 1, 2, 4, true>;
 
 const GemmVariant kVariants[] = {
-    {MOE_DTYPE_BF16, 256, 256, 64, &launch_pipe<Pb_256x256>},
+    {MOE_DTYPE_BF16, 256, 256, 64, &launch_pipe<Pb_256x256, Ps_64x256, Ps_128x256>},
+    {MOE_DTYPE_BF16, 256, 256, 64, &launch_pipe<Pb_256x256s, Ps_64x256, Ps_128x256>, 0, 64},
     {MOE_DTYPE_BF16, 128, 256, 64, &launch_pipe<Pb_128x256>},
     {MOE_DTYPE_BF16, 128, 128, 64, &launch_pipe<Pb_128x128>},
     {MOE_DTYPE_BF16, 64, 256, 64, &launch_pipe<Pb_64x256>},
@@ -92,27 +100,26 @@ const GemmVariant kVariants[] = {
     {MOE_DTYPE_FP8_E4M3, 32, 128, 128, &launch_pipe<P8_32x128>},
 };
 
-// Small-expert task functions that share the launch shape (512 threads, 256-wide n-tiles) of Pb_256x256
-using Ps_64x256 = PipeCfg<64, 256, 64, 1, 8, 3>;
-using Ps_128x256 = PipeCfg<128, 256, 64, 1, 8, 2>;
-
 const GemmVariant kPairVariants[] = {
-    {MOE_DTYPE_BF16, 256, 256, 64, &launch_pipe2<Pb_256x256, Ps_64x256>, 64},
-    {MOE_DTYPE_BF16, 256, 256, 64, &launch_pipe2<Pb_256x256, Ps_128x256>, 128},
+    {MOE_DTYPE_BF16, 256, 256, 64, &launch_pipe2<Pb_256x256, Ps_64x256, Ps_64x256, Ps_128x256>, 64},
+    {MOE_DTYPE_BF16, 256, 256, 64, &launch_pipe2<Pb_256x256, Ps_128x256, Ps_64x256, Ps_128x256>, 128},
 };
 
-const GemmVariant* find_variant(int dtype, int tile_m, int tile_n, int tile_m_small = 0) {
+const GemmVariant* find_variant(int dtype, int tile_m, int tile_n, int tile_m_small = 0, int tile_m_slack = 0) {
     if (tile_m_small == 0) {
         for (const GemmVariant& v : kVariants)
-            if (v.dtype == dtype && v.tile_m == tile_m && v.tile_n == tile_n) return &v;
+            if (v.dtype == dtype && v.tile_m == tile_m && v.tile_n == tile_n && v.tile_m_slack == tile_m_slack) return &v;
     } else {
         for (const GemmVariant& v : kPairVariants)
-            if (v.dtype == dtype && v.tile_m == tile_m && v.tile_n == tile_n && v.tile_m_small == tile_m_small) return &v;
+            if (v.dtype == dtype && v.tile_m == tile_m && v.tile_n == tile_n && v.tile_m_small == tile_m_small &&
+                v.tile_m_slack == tile_m_slack)
+                return &v;
     }
     return nullptr;
 }
 
-int check_small_args(int tile_m, int tile_m_small, int small_max_rows) {
+int check_small_args(int tile_m, int tile_m_small, int small_max_rows, int tile_m_slack = 0) {
+    if (tile_m_slack < 0 || tile_m_slack >= tile_m) return MOE_ERR_INVALID_ARG;
     if (tile_m_small == 0 && small_max_rows == 0) return MOE_OK;
     if (tile_m_small != 16 && tile_m_small != 32 && tile_m_small != 64 && tile_m_small != 128) return MOE_ERR_UNSUPPORTED;
     if (tile_m_small >= tile_m) return MOE_ERR_INVALID_ARG;
@@ -171,9 +178,24 @@ int moe_tile_pair_supported(int dtype, int tile_m, int tile_n, int tile_m_small)
 
 int moe_build_task_map_tiled(const int32_t* topk_ids, int T, int k, int E, int tile_m, int tile_n, int N, int order,
                              int tile_m_small, int small_max_rows, void* task_map, void* stream) {
+    const moe_tiling g = {tile_m, tile_n, order, tile_m_small, small_max_rows, 0};
+    return moe_build_task_map_ex(topk_ids, T, k, E, N, &g, task_map, stream);
+}
+
+int moe_tiling_supported(int dtype, const moe_tiling* g) {
+    if (!g || check_small_args(g->tile_m, g->tile_m_small, g->small_max_rows, g->tile_m_slack) != MOE_OK) return 0;
+    return find_variant(dtype, g->tile_m, g->tile_n, g->tile_m_small, g->tile_m_slack) != nullptr;
+}
+
+int moe_build_task_map_ex(const int32_t* topk_ids, int T, int k, int E, int N, const moe_tiling* tiling,
+                          void* task_map, void* stream) {
+    if (!tiling) return MOE_ERR_INVALID_ARG;
+    const moe_tiling g = *tiling;
+    const int tile_m = g.tile_m, tile_n = g.tile_n, order = g.order;
     if (!task_map || (T > 0 && !topk_ids)) return MOE_ERR_INVALID_ARG;
+    if (tile_m < 1) return MOE_ERR_UNSUPPORTED;
     {
-        const int rcs = check_small_args(tile_m, tile_m_small, small_max_rows);
+        const int rcs = check_small_args(tile_m, g.tile_m_small, g.small_max_rows, g.tile_m_slack);
         if (rcs != MOE_OK) return rcs;
     }
     if (order != MOE_ORDER_ASCENDING && order != MOE_ORDER_SPREAD) return MOE_ERR_INVALID_ARG;
@@ -194,15 +216,13 @@ int moe_build_task_map_tiled(const int32_t* topk_ids, int T, int k, int E, int t
                 return MOE_ERR_HIP;
             attr_set = true;
         }
-        map_build_small<<<1, kMapThreads, lds, s>>>(topk_ids, map, T, k, E, tile_m, tile_n, N, order, tile_m_small,
-                                                    small_max_rows);
+        map_build_small<<<1, kMapThreads, lds, s>>>(topk_ids, map, T, k, E, N, g);
     } else {
         const int nchunks = nchunks_for(R);
         int32_t* chunk_hist = map + L.off_rows + round_up64((size_t)R);
         const int hs = hist_stride(L.E64);
         map_hist<<<nchunks, 256, hs * sizeof(int), s>>>(topk_ids, (int)R, E, L.E64, chunk_hist);
-        map_scan<<<1, kMapThreads, 0, s>>>(map, chunk_hist, nchunks, T, k, E, tile_m, tile_n, N, order, tile_m_small,
-                                           small_max_rows);
+        map_scan<<<1, kMapThreads, 0, s>>>(map, chunk_hist, nchunks, T, k, E, N, g);
         static bool attr_set2 = false;
         if (!attr_set2) {
             if (hipFuncSetAttribute(reinterpret_cast<const void*>(&map_scatter),
@@ -249,10 +269,10 @@ int moe_grouped_gemm(const void* X, const void* W, const int32_t* topk_ids, cons
     if (d->K < 1) return MOE_ERR_INVALID_ARG;
     if (d->dtype != MOE_DTYPE_BF16 && d->dtype != MOE_DTYPE_FP8_E4M3) return MOE_ERR_UNSUPPORTED;
     {
-        const int rcs = check_small_args(d->tile_m, d->tile_m_small, d->small_max_rows);
+        const int rcs = check_small_args(d->tile_m, d->tile_m_small, d->small_max_rows, d->tile_m_slack);
         if (rcs != MOE_OK) return rcs;
     }
-    const GemmVariant* v = find_variant(d->dtype, d->tile_m, d->tile_n, d->tile_m_small);
+    const GemmVariant* v = find_variant(d->dtype, d->tile_m, d->tile_n, d->tile_m_small, d->tile_m_slack);
     if (!v) return MOE_ERR_UNSUPPORTED;
     if (d->K % v->bk != 0 || d->N % d->tile_n != 0) return MOE_ERR_UNSUPPORTED;
     const int es = d->dtype == MOE_DTYPE_FP8_E4M3 ? 1 : 2;
@@ -266,7 +286,7 @@ int moe_grouped_gemm(const void* X, const void* W, const int32_t* topk_ids, cons
     a.X = X; a.W = W; a.map = static_cast<const int32_t*>(task_map); a.Y = Y;
     a.x_scale = d->x_scale; a.w_scale = d->w_scale;
     a.T = d->T; a.k = d->k; a.E = d->E; a.K = d->K; a.N = d->N;
-    a.tile_m_small = d->tile_m_small; a.small_max_rows = d->small_max_rows;
+    a.tile_m_small = d->tile_m_small; a.small_max_rows = d->small_max_rows; a.tile_m_slack = d->tile_m_slack;
     int64_t grid = moe_grid_upper_bound_tiled(d->T, d->k, d->E, d->tile_m, d->tile_n, d->N, d->tile_m_small,
                                               d->small_max_rows);
     grid = (grid + 7) / 8 * 8;

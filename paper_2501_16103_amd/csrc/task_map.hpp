@@ -68,22 +68,29 @@ struct TileCoord {
 __host__ __device__ __forceinline__ int expert_tile_m(int cnt, int tile_m, int tile_m_small, int small_max_rows) {
     return (small_max_rows > 0 && cnt <= small_max_rows) ? tile_m_small : tile_m;
 }
+// m-tiles of an expert with cnt rows.  With slack > 0 the last tile of a big-strategy expert may hold up to
+// tile_m + slack rows, so a remainder of at most `slack` rows does not open a tile of its own.
+__host__ __device__ __forceinline__ int expert_m_tiles(int cnt, const moe_tiling& g) {
+    if (cnt <= 0) return 0;
+    if (g.small_max_rows > 0 && cnt <= g.small_max_rows) return (cnt + g.tile_m_small - 1) / g.tile_m_small;
+    const int mt = (cnt - g.tile_m_slack + g.tile_m - 1) / g.tile_m;
+    return mt < 1 ? 1 : mt;
+}
 
-// Alg. 4: block -> non-empty task -> real expert, then the tile index split m-fastest.
-__device__ __forceinline__ TileCoord decode_block(const int32_t* __restrict__ map, const MapLayout& L, int tile_m_big, int B,
-                                                  int tile_m_small = 0, int small_max_rows = 0) {
+// Alg. 2 + Alg. 4 for workgroup B, then the tile index split m-fastest (the task function's own convention).
+__device__ __forceinline__ TileCoord decode_block(const int32_t* __restrict__ map, const MapLayout& L, const moe_tiling& g, int B) {
     int h, l;
     mapping(map + L.off_prefix, L.E64, B, h, l);
     TileCoord c;
     c.e = map[L.off_sigma + h];
     const int cnt = map[L.off_counts + c.e];
-    c.small = small_max_rows > 0 && cnt <= small_max_rows;
-    const int tile_m = c.small ? tile_m_small : tile_m_big;
-    const int mt = (cnt + tile_m - 1) / tile_m;
+    c.small = g.small_max_rows > 0 && cnt <= g.small_max_rows;
+    const int tile_m = c.small ? g.tile_m_small : g.tile_m;
+    const int mt = expert_m_tiles(cnt, g);
     c.n_tile = l / mt;
     c.m_tile = l - c.n_tile * mt;
     const int left = cnt - c.m_tile * tile_m;
-    c.rows = left < tile_m ? left : tile_m;
+    c.rows = c.m_tile + 1 < mt ? tile_m : left;
     c.row_base = map[L.off_offsets + c.e] + c.m_tile * tile_m;
     return c;
 }
@@ -135,14 +142,13 @@ __device__ __forceinline__ int bit_reverse(int r, int nbits) { return nbits ? (i
 // keyed by bitrev(r) over ceil(log2 M) bits, sigma by increasing key.
 // s_work: >= 2*E64 ints of LDS.  Returns this thread's exclusive row offset (valid for tid < E).
 __device__ __forceinline__ int finish_map(int32_t* __restrict__ map, const MapLayout& L, int cnt, int bad, int T, int k,
-                                          int E, int tile_m, int tile_n, int N, int order, int tile_m_small,
-                                          int small_max_rows, int* s_tmp, int* s_work) {
+                                          int E, int N, const moe_tiling& g, int* s_tmp, int* s_work) {
     const int tid = threadIdx.x;
     const int R = T * k;
-    const int nt = (N + tile_n - 1) / tile_n;
+    const int nt = (N + g.tile_n - 1) / g.tile_n;
     const int nonempty = cnt > 0;
-    const int etm = expert_tile_m(cnt, tile_m, tile_m_small, small_max_rows);
-    const int tiles = ((cnt + etm - 1) / etm) * nt;
+    const int tiles = expert_m_tiles(cnt, g) * nt;
+    const int order = g.order;
     const int off_incl = block_incl_scan(cnt, s_tmp);
     const int ne_incl = block_incl_scan(nonempty, s_tmp);
     __syncthreads();
@@ -199,8 +205,8 @@ __device__ __forceinline__ int finish_map(int32_t* __restrict__ map, const MapLa
             case MOE_HDR_K_TOP: v = k; break;
             case MOE_HDR_E: v = E; break;
             case MOE_HDR_N: v = N; break;
-            case MOE_HDR_TILE_M: v = tile_m; break;
-            case MOE_HDR_TILE_N: v = tile_n; break;
+            case MOE_HDR_TILE_M: v = g.tile_m; break;
+            case MOE_HDR_TILE_N: v = g.tile_n; break;
             case MOE_HDR_NT: v = nt; break;
             case MOE_HDR_M: v = M; break;
             case MOE_HDR_TOTAL_TILES: v = bad ? 0 : total; break;
@@ -209,8 +215,9 @@ __device__ __forceinline__ int finish_map(int32_t* __restrict__ map, const MapLa
             case MOE_HDR_R: v = R; break;
             case MOE_HDR_E64: v = L.E64; break;
             case MOE_HDR_SIGMA_ORDER: v = order; break;
-            case MOE_HDR_TILE_M_SMALL: v = tile_m_small; break;
-            case MOE_HDR_SMALL_MAX_ROWS: v = small_max_rows; break;
+            case MOE_HDR_TILE_M_SMALL: v = g.tile_m_small; break;
+            case MOE_HDR_SMALL_MAX_ROWS: v = g.small_max_rows; break;
+            case MOE_HDR_TILE_M_SLACK: v = g.tile_m_slack; break;
             default: v = 0;
         }
         map[tid] = v;
@@ -227,8 +234,7 @@ __device__ __forceinline__ int key_bits(int E) {
 // One-workgroup build for R <= kChunkRows: histogram, scans and stable scatter fused.
 // Dynamic LDS: kWaves * E64 ints (per-wavefront counts) + E64 ints (offsets) + 32 + 2 * E64 (ordering).
 __global__ __launch_bounds__(kMapThreads) void map_build_small(const int32_t* __restrict__ ids, int32_t* __restrict__ map,
-                                                                int T, int k, int E, int tile_m, int tile_n, int N, int order,
-                                                                int tile_m_small, int small_max_rows) {
+                                                                int T, int k, int E, int N, moe_tiling g) {
     extern __shared__ int s_mem[];
     const MapLayout L = map_layout(E);
     int* s_wave = s_mem;                   // [kWaves][E64]
@@ -258,7 +264,7 @@ __global__ __launch_bounds__(kMapThreads) void map_build_small(const int32_t* __
             cnt += c;
         }
     }
-    const int off = finish_map(map, L, cnt, bad, T, k, E, tile_m, tile_n, N, order, tile_m_small, small_max_rows, s_tmp, s_work);
+    const int off = finish_map(map, L, cnt, bad, T, k, E, N, g, s_tmp, s_work);
     if (tid < L.E64) s_off[tid] = off;
     __syncthreads();
     if (valid) map[L.off_rows + s_off[e] + s_wave[w * L.E64 + e] + rank] = tid;
@@ -286,8 +292,7 @@ __global__ __launch_bounds__(256) void map_hist(const int32_t* __restrict__ ids,
 // Step 2 (one workgroup): turn the chunk histograms into per-chunk exclusive bases,
 // then counts / offsets / sigma / TilePrefix / header.
 __global__ __launch_bounds__(kMapThreads) void map_scan(int32_t* __restrict__ map, int32_t* __restrict__ chunk_hist,
-                                                        int nchunks, int T, int k, int E, int tile_m, int tile_n, int N,
-                                                        int order, int tile_m_small, int small_max_rows) {
+                                                        int nchunks, int T, int k, int E, int N, moe_tiling g) {
     __shared__ int s_tmp[32];
     __shared__ int s_work[2 * kMaxE];
     const MapLayout L = map_layout(E);
@@ -308,7 +313,7 @@ __global__ __launch_bounds__(kMapThreads) void map_scan(int32_t* __restrict__ ma
     }
     __syncthreads();
     const int bad = s_tmp[31];
-    finish_map(map, L, cnt, bad, T, k, E, tile_m, tile_n, N, order, tile_m_small, small_max_rows, s_tmp, s_work);
+    finish_map(map, L, cnt, bad, T, k, E, N, g, s_tmp, s_work);
 }
 
 // Step 3: stable scatter of one chunk of rows into the token index arrays.
@@ -349,14 +354,16 @@ __global__ __launch_bounds__(256) void map_expand(const int32_t* __restrict__ ma
                                                    long long grid) {
     const MapLayout L = map_layout(E);
     const int total = map[MOE_HDR_TOTAL_TILES];
-    const int tile_m = map[MOE_HDR_TILE_M];
-    const int tile_m_small = map[MOE_HDR_TILE_M_SMALL], small_max_rows = map[MOE_HDR_SMALL_MAX_ROWS];
+    moe_tiling g;
+    g.tile_m = map[MOE_HDR_TILE_M]; g.tile_n = map[MOE_HDR_TILE_N]; g.order = map[MOE_HDR_SIGMA_ORDER];
+    g.tile_m_small = map[MOE_HDR_TILE_M_SMALL]; g.small_max_rows = map[MOE_HDR_SMALL_MAX_ROWS];
+    g.tile_m_slack = map[MOE_HDR_TILE_M_SLACK];
     const long long wave = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
     const long long nwaves = (long long)gridDim.x * 4;
     for (long long B = wave; B < grid; B += nwaves) {
         int4 out = make_int4(-1, -1, -1, -1);
         if (B < total) {
-            const TileCoord c = decode_block(map, L, tile_m, (int)B, tile_m_small, small_max_rows);
+            const TileCoord c = decode_block(map, L, g, (int)B);
             out = make_int4(c.e, c.m_tile, c.n_tile, c.rows);
         }
         if (__lane_id() == 0) reinterpret_cast<int4*>(table)[B] = out;

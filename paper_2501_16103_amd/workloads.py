@@ -40,6 +40,7 @@ class Workload:
     routing: str = "gauss_topk"
     tile_m: int = 128            # default tiling the benchmark uses for this point
     tile_n: int = 128
+    tile_m_slack: int = 0        # rows the last m-tile of an expert may hold beyond tile_m
 
     @property
     def R(self) -> int:
@@ -71,17 +72,17 @@ def tiny(T: int = 64) -> Workload:
 
 def mixtral_up(T: int) -> Workload:
     tm = 256 if T >= 2048 else (128 if T >= 256 else 16)
-    return Workload("mixtral_up", T, 8, 2, 4096, 28672, "bf16", "gauss_topk", tm, 256)
+    return Workload("mixtral_up", T, 8, 2, 4096, 28672, "bf16", "gauss_topk", tm, 256, 64 if tm == 256 else 0)
 
 
 def mixtral_down_zipf(T: int) -> Workload:
     tm = 256 if T >= 2048 else 64
-    return Workload("mixtral_down_zipf", T, 8, 2, 14336, 4096, "bf16", "zipf", tm, 256)
+    return Workload("mixtral_down_zipf", T, 8, 2, 14336, 4096, "bf16", "zipf", tm, 256, 64 if tm == 256 else 0)
 
 
 def fine_grained(T: int) -> Workload:
     tm = 256 if T >= 8192 else (128 if T >= 2048 else 16)
-    return Workload("fine_grained", T, 256, 8, 7168, 4096, "bf16", "gauss_topk", tm, 256)
+    return Workload("fine_grained", T, 256, 8, 7168, 4096, "bf16", "gauss_topk", tm, 256, 64 if tm == 256 else 0)
 
 
 def decode_fp8(T: int) -> Workload:
@@ -90,7 +91,7 @@ def decode_fp8(T: int) -> Workload:
 
 def paper_eval(scenario: str = "balanced", T: int = 4096) -> Workload:
     """Sec. 5: T=4096, 64 experts, top-8, expert weight [3584, 2560]."""
-    return Workload("paper_eval_" + scenario, T, 64, 8, 3584, 2560, "bf16", scenario, 256, 256)
+    return Workload("paper_eval_" + scenario, T, 64, 8, 3584, 2560, "bf16", scenario, 256, 256, 64)
 
 
 def make_routing(wl: Workload, device="cpu") -> torch.Tensor:

@@ -41,9 +41,10 @@ def _run_full(wl, dev, order=0):
     buf.fill_(POISON)
     Y = buf[pad: pad + wl.R]
     tmap = mb.alloc_task_map(wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N, dev)
-    mb.moe_build_task_map_ordered(ids.to(dev), wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N, order, tmap)
+    mb.moe_build_task_map_ex(ids.to(dev), wl.T, wl.k, wl.E, wl.N, mb.Tiling(wl.tile_m, wl.tile_n, order, 0, 0, wl.tile_m_slack), tmap)
     dt = mb.MOE_DTYPE_FP8_E4M3 if wl.dtype == "fp8" else mb.MOE_DTYPE_BF16
-    mb.moe_grouped_gemm(X, W, ids.to(dev), tmap, Y, mb.GemmDesc(dt, wl.T, wl.k, wl.E, wl.K, wl.N, wl.tile_m, wl.tile_n, xs, ws))
+    mb.moe_grouped_gemm(X, W, ids.to(dev), tmap, Y,
+                        mb.GemmDesc(dt, wl.T, wl.k, wl.E, wl.K, wl.N, wl.tile_m, wl.tile_n, xs, ws, tile_m_slack=wl.tile_m_slack))
     torch.cuda.synchronize()
     assert mb.moe_task_map_status(tmap) == mb.MOE_OK
     # properties that hold at any size
@@ -105,6 +106,7 @@ def _check_elements(oracle_mod, wl, ids, X, W, xs, ws, Y, rr, nn):
 FULL = [
     # workload, samples per tile, complete rows, sigma order
     (wk.mixtral_up(4096), 8, 64, 0),
+    (wk.mixtral_up(4096).with_T(4096, tile_m_slack=0), 8, 64, 0),   # the same point with the plain ceil tiling
     (wk.mixtral_up(256), 8, 32, 0),
     (wk.mixtral_up(16), 8, 32, 0),
     (wk.mixtral_down_zipf(4096), 8, 64, 0),
@@ -124,10 +126,10 @@ def test_full_size_sampled(oracle_mod, wl, per_tile, nrows, order):
     rng = np.random.default_rng(wl.T * 7 + wl.E)
     ids, X, W, xs, ws, Y, tmap = _run_full(wl, dev, order)
     # task map: whole and bit-exact
-    tm = oracle_mod.build_task_map(ids.numpy(), wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N, order=order)
+    tm = oracle_mod.build_task_map(ids.numpy(), wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N, order=order, tile_m_slack=wl.tile_m_slack)
     want = H.expected_blob(tm)
     np.testing.assert_array_equal(tmap.cpu().numpy()[: len(want)], want)
-    table = oracle_mod.full_table(tm.counts, wl.tile_m, wl.tile_n, wl.N, sigma=tm.sigma)
+    table = oracle_mod.full_table(tm.counts, wl.tile_m, wl.tile_n, wl.N, sigma=tm.sigma, tile_m_slack=wl.tile_m_slack)
     assert len(table) == tm.total_tiles
     # (a) samples in every tile
     rr, nn = _sample_points(tm, table, rng, per_tile)

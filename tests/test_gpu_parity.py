@@ -25,10 +25,12 @@ def dev():
     return torch.device("cuda:0")
 
 
-def _build_map(ids_dev, T, k, E, tile_m, tile_n, N, order=0, small=0, thr=0):
+def _build_map(ids_dev, T, k, E, tile_m, tile_n, N, order=0, small=0, thr=0, slack=0):
     tmap = mb.alloc_task_map(max(T, 1), k, E, tile_m, tile_n, N)
     tmap.fill_(0x5A5A5A5A)
-    if small:
+    if slack:
+        mb.moe_build_task_map_ex(ids_dev, T, k, E, N, mb.Tiling(tile_m, tile_n, order, small, thr, slack), tmap)
+    elif small:
         mb.moe_build_task_map_tiled(ids_dev, T, k, E, tile_m, tile_n, N, order, small, thr, tmap)
     elif order == 0:
         mb.moe_build_task_map(ids_dev, T, k, E, tile_m, tile_n, N, tmap)
@@ -131,17 +133,17 @@ def test_argument_errors(dev):
     assert bool(torch.isnan(Y).all())
 
 
-def _run_gemm(dev, wl, ids, X, W, xs=None, ws=None, order=0, small=0, thr=0):
+def _run_gemm(dev, wl, ids, X, W, xs=None, ws=None, order=0, small=0, thr=0, slack=0):
     """Run map build + GEMM with Y embedded between poisoned canary rows; returns Y bits [R,N]."""
     R, N = wl.R, wl.N
     pad = 4
     buf = torch.empty((R + 2 * pad, N), dtype=torch.int16, device=dev)
     buf.fill_(POISON)
     Y = buf[pad: pad + R]
-    tmap = _build_map(ids.to(dev), wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, N, order, small, thr)
+    tmap = _build_map(ids.to(dev), wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, N, order, small, thr, slack)
     dt = mb.MOE_DTYPE_FP8_E4M3 if wl.dtype == "fp8" else mb.MOE_DTYPE_BF16
     desc = mb.GemmDesc(dt, wl.T, wl.k, wl.E, wl.K, N, wl.tile_m, wl.tile_n,
-                       None if xs is None else xs.to(dev), None if ws is None else ws.to(dev), small, thr)
+                       None if xs is None else xs.to(dev), None if ws is None else ws.to(dev), small, thr, slack)
     mb.moe_grouped_gemm(X.to(dev), W.to(dev), ids.to(dev), tmap, Y, desc)
     torch.cuda.synchronize()
     assert mb.moe_task_map_status(tmap) == mb.MOE_OK
@@ -252,6 +254,68 @@ def test_tiling_pair_mismatch_is_a_noop(dev):
     assert bool(torch.isnan(Y).all())
     d = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, k, E, K, N, 256, 256, None, None, 32, 32)
     assert mb.moe_grouped_gemm(X, W, ids, tiled, Y, d, check=False) == mb.MOE_ERR_UNSUPPORTED
+
+
+def _ids_from_counts(counts, seed):
+    """k = 1 routing with exactly these per-expert row counts, rows shuffled."""
+    flat = np.concatenate([np.full(c, e, np.int32) for e, c in enumerate(counts)])
+    np.random.default_rng(seed).shuffle(flat)
+    return torch.from_numpy(flat.reshape(-1, 1).copy())
+
+
+SLACK_CASES = [
+    # per-expert row counts (k = 1), K, N    (tile 256 x 256, slack 64)
+    ([257, 320, 321, 256, 1, 64, 65, 0, 576, 639, 640, 641], 128, 256),
+    ([300, 0, 0, 513, 129, 255, 319], 192, 512),
+    ([1025, 1040, 991, 1055], 64, 256),     # the remainders of the Mixtral benchmark point
+]
+
+
+@pytest.mark.parametrize("order", [0, 1], ids=["ascending", "spread"])
+@pytest.mark.parametrize("counts,K,N", SLACK_CASES)
+def test_slack_rows_parity(dev, oracle_mod, counts, K, N, order):
+    """Last m-tiles with up to tile_m + 64 rows: map bit-exact, expanded table == nested-loop table, Y == oracle."""
+    E, T, slack = len(counts), int(sum(counts)), 64
+    tiling = mb.Tiling(256, 256, order, 0, 0, slack)
+    assert mb.moe_tiling_supported(mb.MOE_DTYPE_BF16, tiling)
+    wl = wk.Workload("parity_slack", T, E, 1, K, N, "bf16", "gauss_topk", 256, 256)
+    ids = _ids_from_counts(counts, 5 + E + K)
+    X, W = wk.make_x(wl), wk.make_w(wl)
+    tm = oracle_mod.build_task_map(ids.numpy(), T, 1, E, 256, 256, N, order=order, tile_m_slack=slack)
+    tmap = _build_map(ids.to(dev), T, 1, E, 256, 256, N, order, slack=slack)
+    want = H.expected_blob(tm)
+    np.testing.assert_array_equal(tmap.cpu().numpy()[: len(want)], want)
+    grid = mb.moe_grid_upper_bound(T, 1, E, 256, 256, N)
+    assert grid >= tm.total_tiles
+    table = torch.full((grid, 4), 7, dtype=torch.int32, device=dev)
+    mb.moe_task_map_expand(tmap, E, table, grid)
+    tab = table.cpu().numpy()
+    np.testing.assert_array_equal(tab[: tm.total_tiles], oracle_mod.full_table(tm.counts, 256, 256, N, sigma=tm.sigma, tile_m_slack=slack))
+    assert np.all(tab[tm.total_tiles:] == -1)
+    assert tab[: tm.total_tiles, 3].max() > 256, "the case must contain a tile that uses its slack rows"
+    got = _run_gemm(dev, wl, ids, X, W, order=order, slack=slack)
+    res = oracle_mod.grouped_gemm_bf16(wk.bits(X), wk.bits(W), ids.numpy())
+    _check_y(got, res, X.double().numpy(), W.double().numpy(), ids.numpy(), 1, K, H.tol_bf16(K))
+
+
+def test_slack_mismatch_is_a_noop(dev):
+    """A map built with slack rows run through the kernel without them (or the other way round) must do nothing."""
+    counts, K, N = [300, 20, 600], 64, 256
+    T, E = sum(counts), len(counts)
+    wl = wk.Workload("slack_mismatch", T, E, 1, K, N, "bf16", "gauss_topk", 256, 256)
+    ids = _ids_from_counts(counts, 3).to(dev)
+    X, W = wk.make_x(wl, dev), wk.make_w(wl, dev)
+    Y = torch.full((T, N), float("nan"), device=dev, dtype=torch.bfloat16)
+    with_slack = _build_map(ids, T, 1, E, 256, 256, N, 0, slack=64)
+    plain = _build_map(ids, T, 1, E, 256, 256, N, 0)
+    mb.moe_grouped_gemm(X, W, ids, with_slack, Y, mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 256, 256))
+    mb.moe_grouped_gemm(X, W, ids, plain, Y, mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 256, 256, tile_m_slack=64))
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(Y).all())
+    d = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 256, 256, tile_m_slack=32)
+    assert mb.moe_grouped_gemm(X, W, ids, with_slack, Y, d, check=False) == mb.MOE_ERR_UNSUPPORTED
+    g = mb.Tiling(256, 256, 0, 0, 0, 256)
+    assert mb.moe_build_task_map_ex(ids, T, 1, E, N, g, with_slack, check=False) == mb.MOE_ERR_INVALID_ARG
 
 
 FP8_CASES = [

@@ -267,3 +267,63 @@ def test_two_tilings_properties(oracle_mod, T, k, E, tile_m, tile_n, N, skew, or
         assert sub[:, 3].sum() == T * k
     for e, m_tile, n_tile, rows in table.tolist():
         assert rows == min(etm[e], tm.counts[e] - m_tile * etm[e]) and rows >= 1
+
+
+# ------------------------------------------------------------------ slack rows in the last m-tile
+def test_slack_tiling_hand_example(oracle_mod):
+    g = _gold("slack_tiling_example.json")
+    ids = np.concatenate([np.full(c, e, np.int32) for e, c in enumerate(g["counts"])]).reshape(-1, 1)
+    tm = oracle_mod.build_task_map(ids, len(ids), 1, g["E"], g["tile_m"], g["tile_n"], g["N"], tile_m_slack=g["tile_m_slack"])
+    assert tm.sigma.tolist() == g["sigma"]
+    assert tm.tile_prefix.tolist() == g["tile_prefix"]
+    assert oracle_mod.decode_all(tm).tolist() == g["table"]
+    assert oracle_mod.full_table(tm.counts, g["tile_m"], g["tile_n"], g["N"], tile_m_slack=g["tile_m_slack"]).tolist() == g["table"]
+
+
+@pytest.mark.parametrize("tile_m,slack", [(4, 1), (4, 3), (16, 4), (32, 8), (256, 64)])
+def test_slack_tiling_closed_form_and_shape(oracle_mod, tile_m, slack):
+    """For every row count: the number of tiles is max(1, ceil((c - slack) / tile_m)); all tiles but the last are
+    full; the last holds more than `slack` rows unless it is the only one; slack 0 is the plain ceil."""
+    for c in list(range(1, 6 * tile_m + 3)):
+        counts = np.array([c], np.int32)
+        t = oracle_mod.full_table(counts, tile_m, 8, 8, tile_m_slack=slack)
+        mt = len(t)
+        assert mt == max(1, -(-(c - slack) // tile_m))
+        assert t[:, 1].tolist() == list(range(mt))
+        assert (t[:-1, 3] == tile_m).all() and t[:, 3].sum() == c
+        assert 1 <= t[-1, 3] <= tile_m + slack
+        assert mt == 1 or t[-1, 3] > slack
+        t0 = oracle_mod.full_table(counts, tile_m, 8, 8, tile_m_slack=0)
+        assert len(t0) == -(-c // tile_m) and len(t0) - mt in (0, 1)
+
+
+@pytest.mark.parametrize("order", [0, 1])
+@pytest.mark.parametrize("T,k,E,tile_m,tile_n,N,skew", CASES)
+def test_slack_tiling_properties(oracle_mod, T, k, E, tile_m, tile_n, N, skew, order):
+    rng = np.random.default_rng(4242 + T + E)
+    ids = _random_ids(rng, T, k, E, skew)
+    slack = max(1, tile_m // 4)
+    tm = oracle_mod.build_task_map(ids, T, k, E, tile_m, tile_n, N, order=order, tile_m_slack=slack)
+    nt = -(-N // tile_n)
+    mt = np.where(tm.counts > 0, np.maximum(1, -(-(tm.counts - slack) // tile_m)), 0)
+    np.testing.assert_array_equal(tm.tile_prefix, np.cumsum(mt[tm.sigma] * nt))
+    table = oracle_mod.decode_all(tm)
+    np.testing.assert_array_equal(table, oracle_mod.full_table(tm.counts, tile_m, tile_n, N, sigma=tm.sigma, tile_m_slack=slack))
+    # every routed row is covered exactly once per n-tile: tile m of an expert starts at row m * tile_m of its segment
+    for n in range(nt):
+        sub = table[table[:, 2] == n]
+        covered = np.zeros(T * k, dtype=np.int32)
+        for e, m_tile, _, rows in sub.tolist():
+            lo = tm.offsets[e] + m_tile * tile_m
+            covered[tm.sorted_rows[lo: lo + rows]] += 1
+            assert lo + rows <= tm.offsets[e + 1]
+        assert (covered == 1).all()
+    # a small second strategy keeps its own plain tiling
+    tm2 = oracle_mod.build_task_map(ids, T, k, E, max(tile_m, 32), tile_n, N, order=order, tile_m_small=16, small_max_rows=24,
+                                    tile_m_slack=8)
+    t2 = oracle_mod.decode_all(tm2)
+    np.testing.assert_array_equal(t2, oracle_mod.full_table(tm2.counts, max(tile_m, 32), tile_n, N, sigma=tm2.sigma, tile_m_small=16,
+                                                             small_max_rows=24, tile_m_slack=8))
+    for e, m_tile, _, rows in t2.tolist():
+        if tm2.counts[e] <= 24:
+            assert rows == min(16, tm2.counts[e] - 16 * m_tile)
