@@ -33,7 +33,7 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per GEMM launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a
 # copy kernel of known size; see profiles/.  None where it has not been measured.
-MEASURED_TRAFFIC_BYTES = {"mixtral_up_T4096": 6.226e9}
+MEASURED_TRAFFIC_BYTES = {"mixtral_up_T4096": 3.842e9}
 
 
 def algorithmic_bytes(wl: wk.Workload, ids: torch.Tensor) -> int:
@@ -224,7 +224,8 @@ def main():
                    "tile_m": wl.tile_m, "tile_n": wl.tile_n, "tile_m_slack": wl.tile_m_slack, "routing": wl.routing},
         "roofline": {"bound": "mfma", "achieved": head["tflops_gemm"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(head["tflops_gemm"] / PEAK_BF16_TFLOPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(HEADLINE), "kernel": "moe_gemm_kernel",
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(HEADLINE) if wl == wk.mixtral_up(4096) else None,
+                     "kernel": "moe_gemm_pipe_kernel",
                      "kernel_ms": head["gemm_ms"], "map_ms": head["map_ms"], "alg_bytes": head["alg_bytes"]},
     }
     if args.copy_calibration:

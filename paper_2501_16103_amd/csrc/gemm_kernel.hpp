@@ -349,8 +349,9 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
     };
     using std::integral_constant;
     if (C::SLACK > 0 && tc.rows > C::BM) {
-        // the slack block of a wavefront row without real rows there is computed on padding and never stored
-        run(integral_constant<int, MBW>{}, integral_constant<int, XI>{}, std::false_type{});
+        // every wavefront moves its share of the slack rows; only those whose slack block holds a real row compute it
+        if (mb_live == MBW) run(integral_constant<int, MBW>{}, integral_constant<int, XI>{}, std::false_type{});
+        else run(integral_constant<int, C::MBW_BODY>{}, integral_constant<int, XI>{}, std::false_type{});
     } else if (mb_live == C::MBW_BODY) {
         run(integral_constant<int, C::MBW_BODY>{}, integral_constant<int, XI_BODY>{}, std::false_type{});
     } else {
