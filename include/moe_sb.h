@@ -51,6 +51,9 @@ enum { MOE_ORDER_ASCENDING = 0, MOE_ORDER_SPREAD = 1 };
  *   tile_prefix  [E64]       inclusive prefix sum of tiles per non-empty expert
  *                            (Alg. 1, built over non-empty experts only, Sec. 4.1);
  *                            pad INT32_MAX (Sec. 3.1 allows "the maximum value")
+ *   task_records [E64][4]    the same map packed per non-empty task i, for a decode with one memory
+ *                            round trip: {tile_prefix[i], sigma[i], counts[sigma[i]], offsets[sigma[i]]};
+ *                            pads {INT32_MAX, -1, 0, 0}
  *   sorted_rows  [R]         the per-expert token index arrays (Sec. 4.3) back to
  *                            back: rows of expert e are sorted_rows[offsets[e] ..
  *                            offsets[e+1]), ascending in r; token = r / k
@@ -90,6 +93,7 @@ size_t moe_map_off_counts(int E);
 size_t moe_map_off_offsets(int E);
 size_t moe_map_off_sigma(int E);
 size_t moe_map_off_tile_prefix(int E);
+size_t moe_map_off_task_records(int E);
 size_t moe_map_off_sorted_rows(int E);
 
 /*

@@ -35,7 +35,7 @@ HDR = dict(MAGIC=0, T=1, K_TOP=2, E=3, N=4, TILE_M=5, TILE_N=6, NT=7, M=8, TOTAL
 
 EXPORTS = [
     "moe_map_off_counts", "moe_map_off_offsets", "moe_map_off_sigma", "moe_map_off_tile_prefix",
-    "moe_map_off_sorted_rows", "moe_task_map_bytes", "moe_grid_upper_bound", "moe_build_task_map",
+    "moe_map_off_task_records", "moe_map_off_sorted_rows", "moe_task_map_bytes", "moe_grid_upper_bound", "moe_build_task_map",
     "moe_build_task_map_ordered", "moe_build_task_map_tiled", "moe_grid_upper_bound_tiled", "moe_tile_pair_supported",
     "moe_build_task_map_ex", "moe_tiling_supported",
     "moe_task_map_status", "moe_task_map_expand", "moe_grouped_gemm", "moe_tile_supported", "moe_strerror",
@@ -73,7 +73,7 @@ def lib() -> ctypes.CDLL:
                               "(or __graft_entry__.build()). There is no fallback implementation.")
         L = ctypes.CDLL(LIB_PATH)
         for n in ("moe_map_off_counts", "moe_map_off_offsets", "moe_map_off_sigma", "moe_map_off_tile_prefix",
-                  "moe_map_off_sorted_rows"):
+                  "moe_map_off_task_records", "moe_map_off_sorted_rows"):
             getattr(L, n).restype = ctypes.c_size_t
             getattr(L, n).argtypes = [ctypes.c_int]
         L.moe_task_map_bytes.restype = ctypes.c_size_t
@@ -137,6 +137,7 @@ def moe_map_offsets(E: int) -> dict:
     L = lib()
     return dict(counts=int(L.moe_map_off_counts(E)), offsets=int(L.moe_map_off_offsets(E)),
                 sigma=int(L.moe_map_off_sigma(E)), tile_prefix=int(L.moe_map_off_tile_prefix(E)),
+                task_records=int(L.moe_map_off_task_records(E)),
                 sorted_rows=int(L.moe_map_off_sorted_rows(E)))
 
 

@@ -393,6 +393,9 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
 // a map that does not belong to this launch (wrong shape, tiling or status): those do nothing.
 template <int BM_BIG, int BN, int BM_SMALL, int SLACK>
 __device__ __forceinline__ bool locate_tile(const GemmArgs& a, const int32_t* __restrict__ map, MapLayout& L, TileCoord& tc) {
+    // the first 64 task records travel together with the header: one memory round trip before the tile is known
+    L = map_layout(a.E);
+    const int4 first_record = reinterpret_cast<const int4*>(map + L.off_records)[__lane_id()];
     const int total = map[MOE_HDR_TOTAL_TILES];
     const bool hdr_ok = map[MOE_HDR_MAGIC] == MOE_MAP_MAGIC && map[MOE_HDR_T] == a.T && map[MOE_HDR_K_TOP] == a.k &&
                         map[MOE_HDR_E] == a.E && map[MOE_HDR_N] == a.N && map[MOE_HDR_TILE_M] == BM_BIG &&
@@ -407,9 +410,8 @@ __device__ __forceinline__ bool locate_tile(const GemmArgs& a, const int32_t* __
     if (slot >= per_xcd) return false;
     const int B = (blockIdx.x & 7) * per_xcd + slot;
     if (B >= total) return false;
-    L = map_layout(a.E);
     const moe_tiling g = {BM_BIG, BN, 0, BM_SMALL, a.small_max_rows, SLACK};
-    tc = decode_block(map, L, g, B);
+    tc = decode_block(map, L, g, B, first_record);
     return true;
 }
 

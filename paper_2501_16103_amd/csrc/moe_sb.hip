@@ -135,6 +135,7 @@ size_t moe_map_off_counts(int E) { return map_layout(E).off_counts; }
 size_t moe_map_off_offsets(int E) { return map_layout(E).off_offsets; }
 size_t moe_map_off_sigma(int E) { return map_layout(E).off_sigma; }
 size_t moe_map_off_tile_prefix(int E) { return map_layout(E).off_prefix; }
+size_t moe_map_off_task_records(int E) { return map_layout(E).off_records; }
 size_t moe_map_off_sorted_rows(int E) { return map_layout(E).off_rows; }
 
 size_t moe_task_map_bytes(int T_max, int k, int E, int tile_m, int tile_n, int N) {

@@ -21,7 +21,7 @@ constexpr int kWaves = kMapThreads / 64;
 
 struct MapLayout {
     int E64;
-    size_t off_counts, off_offsets, off_sigma, off_prefix, off_rows;
+    size_t off_counts, off_offsets, off_sigma, off_prefix, off_records, off_rows;
 };
 
 __host__ __device__ inline MapLayout map_layout(int E) {
@@ -31,7 +31,8 @@ __host__ __device__ inline MapLayout map_layout(int E) {
     L.off_offsets = L.off_counts + L.E64;
     L.off_sigma = L.off_offsets + L.E64 + 64;
     L.off_prefix = L.off_sigma + L.E64;
-    L.off_rows = L.off_prefix + L.E64;
+    L.off_records = L.off_prefix + L.E64;
+    L.off_rows = L.off_records + 4 * (size_t)L.E64;
     return L;
 }
 
@@ -44,18 +45,29 @@ __host__ __device__ inline int hist_stride(int E64) { return E64 + 64; }
 // Alg. 2 on one wavefront: lane t tests p = (B >= TilePrefix[t]); the ballot is the
 // warp vote, its population count is the task index h.  For more than 64 tasks the
 // vote is repeated over the array (Sec. 3.1); pads are INT32_MAX and never vote.
-__device__ __forceinline__ void mapping(const int32_t* __restrict__ tile_prefix, int E64, int B, int& h, int& l) {
+// The prefix comes from the packed task records {TilePrefix, expert, count, row offset}, so the record of
+// task h is already in a register of lane h when the vote is over: rec = that record, l = tile index in the task.
+// `first` is records[lane] (the caller loads it early, next to the header); B must be below the total tile count.
+__device__ __forceinline__ void mapping(const int4* __restrict__ records, int E64, int B, int4 first, int& h, int& l, int4& rec) {
     const int lane = __lane_id();
-    int cnt = 0;
-    for (int base = 0; base < E64; base += 64) {
-        const int p = B >= tile_prefix[base + lane];
-        const int votes = __popcll(__ballot(p));
-        cnt += votes;
-        if (votes < 64) break;  // the array is non-decreasing: nothing further can vote
-    }
-    h = cnt;
+    int4 r = first;
     int kprev = 0;
-    if (h > 0) kprev = tile_prefix[h - 1];
+    h = 0;
+    rec = make_int4(0, 0, 0, 0);
+    for (int base = 0; base < E64; base += 64) {
+        const int votes = __popcll(__ballot(B >= r.x));
+        if (votes < 64) {  // the array is non-decreasing: task h sits in this round, at lane `votes`
+            h = base + votes;
+            rec.x = __builtin_amdgcn_readlane(r.x, votes);
+            rec.y = __builtin_amdgcn_readlane(r.y, votes);
+            rec.z = __builtin_amdgcn_readlane(r.z, votes);
+            rec.w = __builtin_amdgcn_readlane(r.w, votes);
+            if (votes > 0) kprev = __builtin_amdgcn_readlane(r.x, votes - 1);
+            break;
+        }
+        kprev = __builtin_amdgcn_readlane(r.x, 63);
+        if (base + 64 < E64) r = records[base + 64 + lane];
+    }
     l = B - kprev;
 }
 
@@ -78,12 +90,14 @@ __host__ __device__ __forceinline__ int expert_m_tiles(int cnt, const moe_tiling
 }
 
 // Alg. 2 + Alg. 4 for workgroup B, then the tile index split m-fastest (the task function's own convention).
-__device__ __forceinline__ TileCoord decode_block(const int32_t* __restrict__ map, const MapLayout& L, const moe_tiling& g, int B) {
+__device__ __forceinline__ TileCoord decode_block(const int32_t* __restrict__ map, const MapLayout& L, const moe_tiling& g, int B,
+                                                  int4 first_record) {
     int h, l;
-    mapping(map + L.off_prefix, L.E64, B, h, l);
+    int4 rec;
+    mapping(reinterpret_cast<const int4*>(map + L.off_records), L.E64, B, first_record, h, l, rec);
     TileCoord c;
-    c.e = map[L.off_sigma + h];
-    const int cnt = map[L.off_counts + c.e];
+    c.e = rec.y;
+    const int cnt = rec.z;
     c.small = g.small_max_rows > 0 && cnt <= g.small_max_rows;
     const int tile_m = c.small ? g.tile_m_small : g.tile_m;
     const int mt = expert_m_tiles(cnt, g);
@@ -91,7 +105,7 @@ __device__ __forceinline__ TileCoord decode_block(const int32_t* __restrict__ ma
     c.m_tile = l - c.n_tile * mt;
     const int left = cnt - c.m_tile * tile_m;
     c.rows = c.m_tile + 1 < mt ? tile_m : left;
-    c.row_base = map[L.off_offsets + c.e] + c.m_tile * tile_m;
+    c.row_base = rec.w + c.m_tile * tile_m;
     return c;
 }
 
@@ -179,6 +193,9 @@ __device__ __forceinline__ int finish_map(int32_t* __restrict__ map, const MapLa
     if (tid < L.E64) {
         map[L.off_counts + tid] = cnt;
         map[L.off_sigma + tid] = -1;
+        map[L.off_records + 4 * tid + 1] = -1;
+        map[L.off_records + 4 * tid + 2] = 0;
+        map[L.off_records + 4 * tid + 3] = 0;
         s_work[tid] = 0;
     }
     for (int i = tid; i < L.E64 + 64; i += kMapThreads) map[L.off_offsets + i] = i <= E ? 0 : R;
@@ -187,12 +204,18 @@ __device__ __forceinline__ int finish_map(int32_t* __restrict__ map, const MapLa
     if (tid == 0) map[L.off_offsets + E] = R - bad;
     if (nonempty) {
         map[L.off_sigma + pos] = tid;
+        map[L.off_records + 4 * pos + 1] = tid;
+        map[L.off_records + 4 * pos + 2] = cnt;
+        map[L.off_records + 4 * pos + 3] = off_incl - cnt;
         s_work[pos] = tiles;
     }
     __syncthreads();
     // Alg. 1 over the non-empty experts in sigma order
     const int tile_incl = block_incl_scan(tid < M ? s_work[tid] : 0, s_tmp);
-    if (tid < L.E64) map[L.off_prefix + tid] = tid < M ? tile_incl : 0x7fffffff;
+    if (tid < L.E64) {
+        map[L.off_prefix + tid] = tid < M ? tile_incl : 0x7fffffff;
+        map[L.off_records + 4 * tid] = tid < M ? tile_incl : 0x7fffffff;
+    }
     __syncthreads();
     if (tid == kMapThreads - 1) s_tmp[17] = tile_incl;
     __syncthreads();
@@ -363,7 +386,7 @@ __global__ __launch_bounds__(256) void map_expand(const int32_t* __restrict__ ma
     for (long long B = wave; B < grid; B += nwaves) {
         int4 out = make_int4(-1, -1, -1, -1);
         if (B < total) {
-            const TileCoord c = decode_block(map, L, g, (int)B);
+            const TileCoord c = decode_block(map, L, g, (int)B, reinterpret_cast<const int4*>(map + L.off_records)[__lane_id()]);
             out = make_int4(c.e, c.m_tile, c.n_tile, c.rows);
         }
         if (__lane_id() == 0) reinterpret_cast<int4*>(table)[B] = out;

@@ -18,8 +18,9 @@ def blob_offsets(E: int) -> dict:
     offsets = counts + E64
     sigma = offsets + E64 + 64
     prefix = sigma + E64
-    rows = prefix + E64
-    return dict(E64=E64, counts=counts, offsets=offsets, sigma=sigma, tile_prefix=prefix, sorted_rows=rows)
+    records = prefix + E64
+    rows = records + 4 * E64
+    return dict(E64=E64, counts=counts, offsets=offsets, sigma=sigma, tile_prefix=prefix, task_records=records, sorted_rows=rows)
 
 
 def expected_blob(tm) -> np.ndarray:
@@ -38,6 +39,12 @@ def expected_blob(tm) -> np.ndarray:
     b[o["sigma"]: o["sigma"] + tm.M] = tm.sigma
     b[o["tile_prefix"]: o["tile_prefix"] + o["E64"]] = INT32_MAX
     b[o["tile_prefix"]: o["tile_prefix"] + tm.M] = tm.tile_prefix
+    rec = np.zeros((o["E64"], 4), dtype=np.int32)
+    rec[:, 0], rec[:, 1] = INT32_MAX, -1
+    for i in range(tm.M):
+        e = int(tm.sigma[i])
+        rec[i] = (tm.tile_prefix[i], e, tm.counts[e], tm.offsets[e])
+    b[o["task_records"]: o["task_records"] + 4 * o["E64"]] = rec.reshape(-1)
     b[o["sorted_rows"]: o["sorted_rows"] + R] = tm.sorted_rows
     return b
 
