@@ -305,3 +305,28 @@ def norm_scale_elements(X, W, topk_ids, k: int, rr, nn, x_scale=None, w_scale=No
                                     ctypes.c_int(N), ctypes.c_int(int(is_fp8)), _p(rr), _p(nn),
                                     ctypes.c_int(len(rr)), _p(out))
     return out
+
+
+def swiglu(Y64):
+    """Gated activation of the fp64 sums Y64 [rows, N] (gate columns [0, N/2), up columns [N/2, N)):
+    returns (H64 [rows, N/2], Hbf uint16 bf16 bits)."""
+    Y64 = np.ascontiguousarray(np.asarray(Y64, dtype=np.float64))
+    n, N = Y64.shape
+    assert N % 2 == 0
+    H64 = np.zeros((n, N // 2), dtype=np.float64)
+    Hbf = np.zeros((n, N // 2), dtype=np.uint16)
+    _load().orc_swiglu(_p(Y64), ctypes.c_int(n), ctypes.c_int(N), _p(H64), _p(Hbf))
+    return H64, Hbf
+
+
+def combine(Y_bits, weights, T: int, k: int):
+    """Sum over a token's k experts of Y_bits [T*k, N] (bf16 bits), weighted by weights [T, k] fp32 or None:
+    returns (out64 [T, N], outbf uint16)."""
+    Y = _as_u16(Y_bits).reshape(T * k, -1)
+    N = Y.shape[1]
+    w = None if weights is None else np.ascontiguousarray(np.asarray(weights, dtype=np.float32).reshape(T, k))
+    out64 = np.zeros((T, N), dtype=np.float64)
+    outbf = np.zeros((T, N), dtype=np.uint16)
+    _load().orc_combine(_p(Y), _p(w) if w is not None else None, ctypes.c_int(T), ctypes.c_int(k), ctypes.c_int(N),
+                        _p(out64), _p(outbf))
+    return out64, outbf

@@ -430,3 +430,39 @@ void orc_norm_scale_elements(const void* X, const void* W, const float* x_scale,
         out[i] = s;
     }
 }
+
+/* ---------------------------------------------------------------- neighbours of the product */
+
+/* Gated activation of an expert whose weight holds the gate projection in columns [0, N/2) and the up
+ * projection in [N/2, N) (the "fused gate+up projection" of the benchmark shapes; the paper's MoE layer,
+ * Sec. 2.2, leaves the expert's internals open):
+ *     H[r, i] = silu(G) * U,  G = Y[r, i], U = Y[r, N/2 + i],  silu(g) = g / (1 + exp(-g)),
+ * from the fp64 sums Y64 [nrows, N] of orc_grouped_gemm_*.  Outputs [nrows, N/2]: H64, and Hbf = one
+ * rounding of H64 to bf16.                                                                              */
+void orc_swiglu(const double* Y64, int nrows, int N, double* H64, uint16_t* Hbf) {
+    int I = N / 2;
+    for (int r = 0; r < nrows; ++r)
+        for (int i = 0; i < I; ++i) {
+            double g = Y64[(size_t)r * N + i];
+            double u = Y64[(size_t)r * N + I + i];
+            double h = g / (1.0 + exp(-g)) * u;
+            if (H64) H64[(size_t)r * I + i] = h;
+            if (Hbf) Hbf[(size_t)r * I + i] = orc_f64_to_bf16_rne(h);
+        }
+}
+
+/* The sum over a token's selected experts (Sec. 2.2: the products are finally summed up), weighted by the
+ * router when w != NULL:   out[t, n] = sum_j w[t, j] * Y[t, j, n],  j ascending.
+ * Y: [T, k, N] bf16 bits (what the product stored).  Outputs [T, N]: out64, outbf = one rounding to bf16. */
+void orc_combine(const uint16_t* Y, const float* w, int T, int k, int N, double* out64, uint16_t* outbf) {
+    for (int t = 0; t < T; ++t)
+        for (int n = 0; n < N; ++n) {
+            double acc = 0.0;
+            for (int j = 0; j < k; ++j) {
+                double wj = w ? (double)w[(size_t)t * k + j] : 1.0;
+                acc += wj * (double)orc_bf16_to_f32(Y[((size_t)t * k + j) * N + n]);
+            }
+            if (out64) out64[(size_t)t * N + n] = acc;
+            if (outbf) outbf[(size_t)t * N + n] = orc_f64_to_bf16_rne(acc);
+        }
+}
