@@ -36,11 +36,11 @@ PEAK_HBM_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES = {"mixtral_up_T4096": 3.842e9}
 
 
-def algorithmic_bytes(wl: wk.Workload, ids: torch.Tensor) -> int:
+def algorithmic_bytes(wl: wk.Workload, ids: torch.Tensor, swiglu: bool = False) -> int:
     """Weights of every touched expert once + X once + Y once + the map."""
     es = 1 if wl.dtype == "fp8" else 2
     touched = int(torch.unique(ids).numel())
-    b = touched * wl.K * wl.N * es + wl.T * wl.K * es + wl.R * wl.N * 2 + 4 * (wl.R + 3 * wl.E)
+    b = touched * wl.K * wl.N * es + wl.T * wl.K * es + wl.R * (wl.N // 2 if swiglu else wl.N) * 2 + 4 * (wl.R + 3 * wl.E)
     if wl.dtype == "fp8":
         b += 4 * (wl.T + wl.E)
     return b
@@ -49,8 +49,9 @@ def algorithmic_bytes(wl: wk.Workload, ids: torch.Tensor) -> int:
 class Point:
     """Device buffers of one workload (optionally several weight copies to defeat the caches)."""
 
-    def __init__(self, wl: wk.Workload, copies: int = 1, dev="cuda:0", order: int = 0, small=(0, 0)):
+    def __init__(self, wl: wk.Workload, copies: int = 1, dev="cuda:0", order: int = 0, small=(0, 0), swiglu: bool = False):
         self.wl = wl
+        self.swiglu = swiglu  # fused gated activation: Y is [R, N/2]
         self.order = order
         self.small = small  # (tile_m_small, small_max_rows) of the second tiling strategy, or (0, 0)
         self.slack = 0 if small[0] else wl.tile_m_slack  # no kernel combines the two
@@ -66,10 +67,11 @@ class Point:
             self.X = wk.make_x(wl, dev)
             W = wk.make_w(wl, dev)
         self.W = [W] + [W.clone() for _ in range(copies - 1)]
-        self.Y = torch.empty((wl.R, wl.N), dtype=torch.bfloat16, device=dev)
+        self.Y = torch.empty((wl.R, wl.N // 2 if swiglu else wl.N), dtype=torch.bfloat16, device=dev)
         self.tmap = mb.alloc_task_map(wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N, dev)
         dt = mb.MOE_DTYPE_FP8_E4M3 if wl.dtype == "fp8" else mb.MOE_DTYPE_BF16
-        self.desc = mb.GemmDesc(dt, wl.T, wl.k, wl.E, wl.K, wl.N, wl.tile_m, wl.tile_n, self.xs, self.ws, *small, self.slack)
+        self.desc = mb.GemmDesc(dt, wl.T, wl.k, wl.E, wl.K, wl.N, wl.tile_m, wl.tile_n, self.xs, self.ws, *small, self.slack,
+                                mb.MOE_EPILOGUE_SWIGLU if swiglu else mb.MOE_EPILOGUE_NONE)
         self.tiling = mb.Tiling(wl.tile_m, wl.tile_n, order, small[0], small[1], self.slack)
 
     def build_map(self):
@@ -113,14 +115,14 @@ class Point:
         wl = self.wl
         wall_ms, gemm_ms, map_ms = self.time(steps, warmup)
         peak_t = PEAK_FP8_TFLOPS if wl.dtype == "fp8" else PEAK_BF16_TFLOPS
-        abytes = algorithmic_bytes(wl, self.ids_cpu)
+        abytes = algorithmic_bytes(wl, self.ids_cpu, self.swiglu)
         tf_step = wl.flops / (wall_ms * 1e-3) / 1e12
         tf_gemm = wl.flops / (gemm_ms * 1e-3) / 1e12
         gbs = abytes / (gemm_ms * 1e-3) / 1e9
         ideal_mfma = wl.flops / (peak_t * 1e12)
         ideal_hbm = abytes / (PEAK_HBM_GBS * 1e9)
         bound = "mfma" if ideal_mfma >= ideal_hbm else "hbm"
-        return dict(workload=f"{wl.name}_T{wl.T}", dtype=wl.dtype, T=wl.T, E=wl.E, k=wl.k, K=wl.K, N=wl.N,
+        return dict(workload=f"{wl.name}_T{wl.T}" + ("_swiglu" if self.swiglu else ""), dtype=wl.dtype, T=wl.T, E=wl.E, k=wl.k, K=wl.K, N=wl.N,
                     tile=[wl.tile_m, wl.tile_n], sigma_order=("spread" if self.order else "ascending"), small_strategy=list(self.small), tile_m_slack=self.slack, ms_per_step=round(wall_ms, 4), gemm_ms=round(gemm_ms, 4),
                     map_ms=round(map_ms, 4), tflops_step=round(tf_step, 2), tflops_gemm=round(tf_gemm, 2),
                     frac_mfma=round(tf_gemm / peak_t, 4), gbs_gemm=round(gbs, 1),
@@ -170,6 +172,28 @@ def cpu_baseline(pt: Point, target_s: float = 15.0) -> dict:
 
 
 HEADLINE = "mixtral_up_T4096"
+
+
+def combine_point(T: int, k: int, N: int, steps: int, warmup: int, dev="cuda:0") -> dict:
+    """The sum over a token's experts on a [T, k, N] bf16 product: pure streaming, priced against HBM."""
+    g = torch.Generator(device=dev).manual_seed(wk.BASE_SEED + T + k)
+    Y = torch.randn((T * k, N), generator=g, device=dev).to(torch.bfloat16)
+    w = torch.rand((T, k), generator=g, device=dev, dtype=torch.float32)
+    out = torch.empty((T, N), dtype=torch.bfloat16, device=dev)
+    for _ in range(warmup):
+        mb.moe_combine(Y, w, T, k, N, out)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
+    torch.cuda._sleep(int(4e6))
+    for i in range(steps):
+        ev[i][0].record()
+        mb.moe_combine(Y, w, T, k, N, out)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    nbytes = T * k * N * 2 + T * N * 2 + T * k * 4
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    return dict(workload=f"combine_T{T}_k{k}_N{N}", dtype="bf16", T=T, k=k, N=N, kernel_ms=round(ms, 4),
+                gbs=round(gbs, 1), frac_hbm=round(gbs / PEAK_HBM_GBS, 4), bound="hbm", alg_bytes=nbytes)
 
 
 def all_points():
@@ -265,6 +289,15 @@ def main():
                 p = Point(w, copies, order=order, small=small)
                 points.append(p.report(max(10, args.steps // 2), max(3, args.warmup // 2)))
                 del p
+                torch.cuda.empty_cache()
+        if want is None or "neighbours" in want:
+            # the fused gated activation on the headline shape, and the sum over a token's experts
+            p = Point(wl, swiglu=True)
+            points.append(p.report(max(10, args.steps // 2), max(3, args.warmup // 2)))
+            del p
+            torch.cuda.empty_cache()
+            for (T, k, N) in ((4096, 2, 4096), (8192, 8, 4096), (32, 6, 2816)):
+                points.append(combine_point(T, k, N, max(10, args.steps // 2), max(3, args.warmup // 2)))
                 torch.cuda.empty_cache()
         out["points"] = points
     print(json.dumps(out))

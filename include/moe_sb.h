@@ -37,6 +37,9 @@ enum {
 
 enum { MOE_DTYPE_BF16 = 0, MOE_DTYPE_FP8_E4M3 = 1 };
 
+/* What the GEMM's epilogue stores (moe_gemm_desc.epilogue). */
+enum { MOE_EPILOGUE_NONE = 0, MOE_EPILOGUE_SWIGLU = 1 };
+
 /* Order of the non-empty experts in sigma (Sec. 4.1, Sec. 4.2). */
 enum { MOE_ORDER_ASCENDING = 0, MOE_ORDER_SPREAD = 1 };
 
@@ -208,6 +211,7 @@ typedef struct moe_gemm_desc {
     const float* w_scale; /* DEVICE fp32 [E], per-expert scale (fp8 only, else NULL) */
     int32_t tile_m_small, small_max_rows; /* second tiling strategy of the map, or 0, 0 */
     int32_t tile_m_slack; /* slack rows of the map's last m-tiles, or 0 */
+    int32_t epilogue;     /* MOE_EPILOGUE_* */
 } moe_gemm_desc;
 
 /*
@@ -226,6 +230,12 @@ typedef struct moe_gemm_desc {
  * `desc`, or whose status is non-zero, makes the kernel a no-op.
  * topk_ids is accepted for symmetry with the problem statement and may be
  * NULL: the kernel reads the routing from the map.
+ *
+ * desc->epilogue = MOE_EPILOGUE_SWIGLU fuses the activation of a gated expert into the same task function
+ * (Sec. 3.2: the work of a tile is whatever its task function does): W holds the gate projection in columns
+ * [0, N/2) and the up projection in [N/2, N), and with G = X.W_gate, U = X.W_up (fp32 sums, fp8 scaled first)
+ *     Y[t, j, i] = bf16( G_i / (1 + exp(-G_i)) * U_i ),   i in [0, N/2);   Y is DEVICE [T, k, N/2].
+ * The map is the one built for N (an n-tile of tile_n weight columns yields tile_n/2 outputs).  N % 64 == 0.
  */
 int moe_grouped_gemm(const void* X, const void* W, const int32_t* topk_ids, const void* task_map, void* Y,
                      const moe_gemm_desc* desc, void* stream);
@@ -234,6 +244,16 @@ int moe_grouped_gemm(const void* X, const void* W, const int32_t* topk_ids, cons
 int moe_tile_supported(int dtype, int tile_m, int tile_n);
 /* 1 if a two-strategy GEMM kernel exists for (dtype, tile_m, tile_n) + tile_m_small.  HOST, pure. */
 int moe_tile_pair_supported(int dtype, int tile_m, int tile_n, int tile_m_small);
+
+/*
+ * The last step of the MoE layer (Sec. 2.2: the products of a token with its selected experts are summed up):
+ *     out[t, n] = bf16( sum_{j=0..k-1} w[t, j] * Y[t, j, n] )     (fp32, j ascending)
+ *   Y            DEVICE [T, k, N] bf16 (what moe_grouped_gemm wrote), 16-byte aligned
+ *   topk_weights DEVICE [T, k] fp32 router weights, or NULL for the plain sum
+ *   out          DEVICE [T, N] bf16, 16-byte aligned, must not overlap Y
+ * N % 8 == 0, else MOE_ERR_UNSUPPORTED.  Enqueued on `stream`; allocates nothing.
+ */
+int moe_combine(const void* Y, const float* topk_weights, int T, int k, int N, void* out, void* stream);
 
 /* Static string for a return code. */
 const char* moe_strerror(int code);

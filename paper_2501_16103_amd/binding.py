@@ -25,6 +25,8 @@ MOE_ERR_ROUTING = -3
 MOE_ERR_HIP = -4
 MOE_DTYPE_BF16 = 0
 MOE_DTYPE_FP8_E4M3 = 1
+MOE_EPILOGUE_NONE = 0
+MOE_EPILOGUE_SWIGLU = 1
 MOE_ORDER_ASCENDING = 0
 MOE_ORDER_SPREAD = 1
 MOE_MAP_MAGIC = 0x3142534D
@@ -38,7 +40,8 @@ EXPORTS = [
     "moe_map_off_task_records", "moe_map_off_sorted_rows", "moe_task_map_bytes", "moe_grid_upper_bound", "moe_build_task_map",
     "moe_build_task_map_ordered", "moe_build_task_map_tiled", "moe_grid_upper_bound_tiled", "moe_tile_pair_supported",
     "moe_build_task_map_ex", "moe_tiling_supported",
-    "moe_task_map_status", "moe_task_map_expand", "moe_grouped_gemm", "moe_tile_supported", "moe_strerror",
+    "moe_task_map_status", "moe_task_map_expand", "moe_grouped_gemm", "moe_tile_supported", "moe_combine",
+    "moe_strerror",
 ]
 
 
@@ -53,7 +56,7 @@ class moe_gemm_desc(ctypes.Structure):
                 ("K", ctypes.c_int32), ("N", ctypes.c_int32), ("tile_m", ctypes.c_int32),
                 ("tile_n", ctypes.c_int32), ("x_scale", ctypes.c_void_p), ("w_scale", ctypes.c_void_p),
                 ("tile_m_small", ctypes.c_int32), ("small_max_rows", ctypes.c_int32),
-                ("tile_m_slack", ctypes.c_int32)]
+                ("tile_m_slack", ctypes.c_int32), ("epilogue", ctypes.c_int32)]
 
 
 class moe_tiling(ctypes.Structure):
@@ -103,6 +106,9 @@ def lib() -> ctypes.CDLL:
         L.moe_grouped_gemm.argtypes = [ctypes.c_void_p] * 5 + [ctypes.POINTER(moe_gemm_desc), ctypes.c_void_p]
         L.moe_tile_supported.restype = ctypes.c_int
         L.moe_tile_supported.argtypes = [ctypes.c_int] * 3
+        L.moe_combine.restype = ctypes.c_int
+        L.moe_combine.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
+                                  ctypes.c_void_p, ctypes.c_void_p]
         L.moe_strerror.restype = ctypes.c_char_p
         L.moe_strerror.argtypes = [ctypes.c_int]
         _lib = L
@@ -236,12 +242,13 @@ class GemmDesc:
     tile_m_small: int = 0
     small_max_rows: int = 0
     tile_m_slack: int = 0
+    epilogue: int = 0
 
     def c_struct(self) -> moe_gemm_desc:
         return moe_gemm_desc(self.dtype, self.T, self.k, self.E, self.K, self.N, self.tile_m, self.tile_n,
                              None if self.x_scale is None else self.x_scale.data_ptr(),
                              None if self.w_scale is None else self.w_scale.data_ptr(),
-                             self.tile_m_small, self.small_max_rows, self.tile_m_slack)
+                             self.tile_m_small, self.small_max_rows, self.tile_m_slack, self.epilogue)
 
 
 def moe_grouped_gemm(X: torch.Tensor, W: torch.Tensor, topk_ids: Optional[torch.Tensor], task_map: torch.Tensor,
@@ -250,4 +257,12 @@ def moe_grouped_gemm(X: torch.Tensor, W: torch.Tensor, topk_ids: Optional[torch.
     rc = lib().moe_grouped_gemm(_ptr(X), _ptr(W), _ptr(topk_ids), _ptr(task_map), _ptr(Y), ctypes.byref(d), _stream())
     if check and rc != MOE_OK:
         raise MoeError(rc, "moe_grouped_gemm")
+    return rc
+
+
+def moe_combine(Y: torch.Tensor, topk_weights: Optional[torch.Tensor], T: int, k: int, N: int, out: torch.Tensor,
+                check: bool = True) -> int:
+    rc = lib().moe_combine(_ptr(Y), _ptr(topk_weights), T, k, N, _ptr(out), _stream())
+    if check and rc != MOE_OK:
+        raise MoeError(rc, "moe_combine")
     return rc

@@ -46,6 +46,7 @@ struct GemmArgs {
     int T, k, E, K, N;
     int tile_m_small, small_max_rows;  // second tiling strategy of the map (0, 0 = none)
     int tile_m_slack;                  // slack rows of the map's last m-tiles
+    int swiglu;                        // 1: W = [gate | up] halves of N, Y[r, i] = silu(gate_i) * up_i, Y is [R, N/2]
 };
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
@@ -161,10 +162,20 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
     for (int j = 0; j < WI; ++j) {
         const int inst = j * NW + wave;
         const int krow = inst * WROWS_PER_INST + lane / C::CPRW, pos = lane % C::CPRW;
-        dw_off[j] = (uint32_t)krow * w_row_bytes + ((pos ^ pswz_w<C>(krow)) << 4);
+        // 16-byte chunk of the tile's k-row this lane fetches (the swizzle is applied on the source side)
+        const int chunk = pos ^ pswz_w<C>(krow);
+        uint32_t col_bytes = (uint32_t)(n0 * ES) + (chunk << 4);
+        if (a.swiglu) {
+            // Tile columns come in units of 16: even units are gate columns, odd units the up columns of the same
+            // 16 outputs, so that a lane ends up with a gate value and its up value in its own accumulators.
+            const int c0 = chunk * (16 / ES);                  // first tile column of the chunk
+            const int unit = c0 >> 4, src = (n0 >> 1) + (unit >> 1) * 16 + (c0 & 15) + (unit & 1) * (a.N >> 1);
+            col_bytes = (uint32_t)src * ES;
+        }
+        dw_off[j] = (uint32_t)krow * w_row_bytes + col_bytes;
     }
     const char* Xb = static_cast<const char*>(a.X);
-    const char* Wt = static_cast<const char*>(a.W) + ((size_t)tc.e * a.K * a.N + n0) * ES;
+    const char* Wt = static_cast<const char*>(a.W) + (size_t)tc.e * a.K * a.N * ES;
     const size_t w_kt_stride = (size_t)BK * w_row_bytes;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(MOE_LDS(char)*)smem;
     const int KT = a.K / BK;
@@ -361,7 +372,14 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
 
     // ---- epilogue: fp32 -> bf16 (RNE), scatter to Y[r, n]; fp8 applies the two scales first
     char* Yb = static_cast<char*>(a.Y);
-    const size_t y_row_bytes = (size_t)a.N * 2;
+    const size_t y_row_bytes = (size_t)(a.swiglu ? a.N >> 1 : a.N) * 2;
+    auto store4 = [](char* p, float v0, float v1, float v2, float v3) {
+        u32x2_t v;
+        v.x = pack_bf16(v0, v1);
+        v.y = pack_bf16(v2, v3);
+        *reinterpret_cast<u32x2_t*>(p) = v;
+    };
+    auto silu_mul = [](float gate, float up) { return gate / (1.f + __expf(-gate)) * up; };
 #pragma unroll
     for (int mb = 0; mb < MBW; ++mb) {
         const int m_local = (mb * C::WM + wm) * MF + lrow;
@@ -369,21 +387,47 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
         const int r = rows_of_tile[m_local];
         float xsc = 1.f, wsc = 1.f;
         if constexpr (C::FP8) { xsc = a.x_scale[r / a.k]; wsc = a.w_scale[tc.e]; }
-        char* yrow = Yb + (size_t)r * y_row_bytes + (size_t)n0 * 2;
+        if (!a.swiglu) {
+            char* yrow = Yb + (size_t)r * y_row_bytes + (size_t)n0 * 2;
 #pragma unroll
-        for (int nb = 0; nb < NBW; ++nb) {
+            for (int nb = 0; nb < NBW; ++nb) {
 #pragma unroll
-            for (int jq = 0; jq < C::ACC / 4; ++jq) {
-                const int n_local = MF == 32 ? wn * C::WTN + nb * 32 + 8 * jq + 4 * (lane >> 5) : wn * C::WTN + nb * 16 + 4 * g;
-                float v0 = acc[nb][mb][4 * jq + 0], v1 = acc[nb][mb][4 * jq + 1];
-                float v2 = acc[nb][mb][4 * jq + 2], v3 = acc[nb][mb][4 * jq + 3];
-                if constexpr (C::FP8) {
-                    v0 = (v0 * xsc) * wsc; v1 = (v1 * xsc) * wsc; v2 = (v2 * xsc) * wsc; v3 = (v3 * xsc) * wsc;
+                for (int jq = 0; jq < C::ACC / 4; ++jq) {
+                    const int n_local = MF == 32 ? wn * C::WTN + nb * 32 + 8 * jq + 4 * (lane >> 5) : wn * C::WTN + nb * 16 + 4 * g;
+                    float v0 = acc[nb][mb][4 * jq + 0], v1 = acc[nb][mb][4 * jq + 1];
+                    float v2 = acc[nb][mb][4 * jq + 2], v3 = acc[nb][mb][4 * jq + 3];
+                    if constexpr (C::FP8) {
+                        v0 = (v0 * xsc) * wsc; v1 = (v1 * xsc) * wsc; v2 = (v2 * xsc) * wsc; v3 = (v3 * xsc) * wsc;
+                    }
+                    store4(yrow + n_local * 2, v0, v1, v2, v3);
                 }
-                u32x2_t v;
-                v.x = pack_bf16(v0, v1);
-                v.y = pack_bf16(v2, v3);
-                *reinterpret_cast<u32x2_t*>(yrow + n_local * 2) = v;
+            }
+        } else {
+            // gate and up of one output sit in the same lane: accumulators j and j + 8 of a 32-row block
+            // (its rows 0-15 are a gate unit, 16-31 the up unit), or blocks nb and nb + 1 of 16 rows
+            char* yrow = Yb + (size_t)r * y_row_bytes + (size_t)(n0 >> 1) * 2;
+            if constexpr (MF == 32) {
+#pragma unroll
+                for (int nb = 0; nb < NBW; ++nb) {
+#pragma unroll
+                    for (int jq = 0; jq < 2; ++jq) {
+                        const int n_local = ((wn * C::WTN + nb * 32) >> 1) + 8 * jq + 4 * (lane >> 5);
+                        float h[4];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) h[i] = silu_mul((acc[nb][mb][4 * jq + i] * xsc) * wsc, (acc[nb][mb][8 + 4 * jq + i] * xsc) * wsc);
+                        store4(yrow + n_local * 2, h[0], h[1], h[2], h[3]);
+                    }
+                }
+            } else {
+                static_assert(MF == 32 || NBW % 2 == 0, "gate and up blocks pair up inside a wavefront");
+#pragma unroll
+                for (int nb = 0; nb + 1 < NBW; nb += 2) {
+                    const int n_local = ((wn * C::WTN + nb * 16) >> 1) + 4 * g;
+                    float h[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) h[i] = silu_mul((acc[nb][mb][i] * xsc) * wsc, (acc[nb + 1][mb][i] * xsc) * wsc);
+                    store4(yrow + n_local * 2, h[0], h[1], h[2], h[3]);
+                }
             }
         }
     }

@@ -6,6 +6,7 @@
 
 #include "../../include/moe_sb.h"
 #include "gemm_kernel.hpp"
+#include "combine.hpp"
 #include "task_map.hpp"
 
 using namespace moe;
@@ -276,6 +277,7 @@ int moe_grouped_gemm(const void* X, const void* W, const int32_t* topk_ids, cons
     const GemmVariant* v = find_variant(d->dtype, d->tile_m, d->tile_n, d->tile_m_small, d->tile_m_slack);
     if (!v) return MOE_ERR_UNSUPPORTED;
     if (d->K % v->bk != 0 || d->N % d->tile_n != 0) return MOE_ERR_UNSUPPORTED;
+    if (d->epilogue != MOE_EPILOGUE_NONE && d->epilogue != MOE_EPILOGUE_SWIGLU) return MOE_ERR_INVALID_ARG;
     const int es = d->dtype == MOE_DTYPE_FP8_E4M3 ? 1 : 2;
     if ((int64_t)d->T * d->K * es >= (int64_t)1 << 32) return MOE_ERR_UNSUPPORTED;
     if (d->T == 0) return MOE_OK;
@@ -288,12 +290,35 @@ int moe_grouped_gemm(const void* X, const void* W, const int32_t* topk_ids, cons
     a.x_scale = d->x_scale; a.w_scale = d->w_scale;
     a.T = d->T; a.k = d->k; a.E = d->E; a.K = d->K; a.N = d->N;
     a.tile_m_small = d->tile_m_small; a.small_max_rows = d->small_max_rows; a.tile_m_slack = d->tile_m_slack;
+    a.swiglu = d->epilogue == MOE_EPILOGUE_SWIGLU;
     int64_t grid = moe_grid_upper_bound_tiled(d->T, d->k, d->E, d->tile_m, d->tile_n, d->N, d->tile_m_small,
                                               d->small_max_rows);
     grid = (grid + 7) / 8 * 8;
     if (grid == 0) return MOE_OK;
     if (grid > 0x7fffffff) return MOE_ERR_UNSUPPORTED;
     return v->fn(a, grid, static_cast<hipStream_t>(stream));
+}
+
+int moe_combine(const void* Y, const float* topk_weights, int T, int k, int N, void* out, void* stream) {
+    if (T < 0 || k < 1 || N < 1) return MOE_ERR_INVALID_ARG;
+    if (N % 8 != 0) return MOE_ERR_UNSUPPORTED;
+    if (T == 0) return MOE_OK;
+    if (!Y || !out || ((uintptr_t)Y & 15) || ((uintptr_t)out & 15) || ((uintptr_t)topk_weights & 3)) return MOE_ERR_INVALID_ARG;
+    const long long chunks = (long long)T * (N / 8);
+    long long blocks = (chunks + 255) / 256;
+    if (blocks > 256 * 64) blocks = 256 * 64;  // grid-stride beyond 64 workgroups per CU
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const u32x4_t* y = static_cast<const u32x4_t*>(Y);
+    u32x4_t* o = static_cast<u32x4_t*>(out);
+    switch (k) {  // the usual top-k values get their loads unrolled
+        case 1: moe_combine_kernel<1><<<(unsigned)blocks, 256, 0, s>>>(y, topk_weights, o, T, k, N); break;
+        case 2: moe_combine_kernel<2><<<(unsigned)blocks, 256, 0, s>>>(y, topk_weights, o, T, k, N); break;
+        case 4: moe_combine_kernel<4><<<(unsigned)blocks, 256, 0, s>>>(y, topk_weights, o, T, k, N); break;
+        case 6: moe_combine_kernel<6><<<(unsigned)blocks, 256, 0, s>>>(y, topk_weights, o, T, k, N); break;
+        case 8: moe_combine_kernel<8><<<(unsigned)blocks, 256, 0, s>>>(y, topk_weights, o, T, k, N); break;
+        default: moe_combine_kernel<0><<<(unsigned)blocks, 256, 0, s>>>(y, topk_weights, o, T, k, N); break;
+    }
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
 const char* moe_strerror(int code) {

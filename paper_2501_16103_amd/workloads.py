@@ -77,7 +77,7 @@ def mixtral_up(T: int) -> Workload:
 
 def mixtral_down_zipf(T: int) -> Workload:
     tm = 256 if T >= 2048 else 64
-    return Workload("mixtral_down_zipf", T, 8, 2, 14336, 4096, "bf16", "zipf", tm, 256, 64 if tm == 256 else 0)
+    return Workload("mixtral_down_zipf", T, 8, 2, 14336, 4096, "bf16", "zipf", tm, 256)
 
 
 def fine_grained(T: int) -> Workload:
@@ -91,7 +91,7 @@ def decode_fp8(T: int) -> Workload:
 
 def paper_eval(scenario: str = "balanced", T: int = 4096) -> Workload:
     """Sec. 5: T=4096, 64 experts, top-8, expert weight [3584, 2560]."""
-    return Workload("paper_eval_" + scenario, T, 64, 8, 3584, 2560, "bf16", scenario, 256, 256, 64)
+    return Workload("paper_eval_" + scenario, T, 64, 8, 3584, 2560, "bf16", scenario, 256, 256)
 
 
 def make_routing(wl: Workload, device="cpu") -> torch.Tensor:

@@ -1,0 +1,167 @@
+"""GPU parity of the fused gated activation (epilogue of the grouped GEMM) and of the sum over a token's experts.
+
+Every tile shape is covered, because the gate/up pairing differs between the 32-row and the 16-row MFMA blocks
+and the fp8 path applies its scales before the activation.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2501_16103_amd import binding as mb
+from paper_2501_16103_amd import workloads as wk
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+
+POISON = 0x7FC1
+
+
+@pytest.fixture(scope="module")
+def dev():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    mb.lib()
+    return torch.device("cuda:0")
+
+
+def _run_swiglu(dev, wl, ids, X, W, xs=None, ws=None, slack=0):
+    R, I = wl.R, wl.N // 2
+    pad = 4
+    buf = torch.empty((R + 2 * pad, I), dtype=torch.int16, device=dev)
+    buf.fill_(POISON)
+    Y = buf[pad: pad + R]
+    tmap = mb.alloc_task_map(max(wl.T, 1), wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N)
+    mb.moe_build_task_map_ex(ids.to(dev), wl.T, wl.k, wl.E, wl.N, mb.Tiling(wl.tile_m, wl.tile_n, 0, 0, 0, slack), tmap)
+    dt = mb.MOE_DTYPE_FP8_E4M3 if wl.dtype == "fp8" else mb.MOE_DTYPE_BF16
+    desc = mb.GemmDesc(dt, wl.T, wl.k, wl.E, wl.K, wl.N, wl.tile_m, wl.tile_n,
+                       None if xs is None else xs.to(dev), None if ws is None else ws.to(dev),
+                       tile_m_slack=slack, epilogue=mb.MOE_EPILOGUE_SWIGLU)
+    mb.moe_grouped_gemm(X.to(dev), W.to(dev), ids.to(dev), tmap, Y, desc)
+    torch.cuda.synchronize()
+    allbits = buf.cpu().numpy().view(np.uint16)
+    assert np.all(allbits[:pad] == POISON) and np.all(allbits[pad + R:] == POISON), "wrote outside Y"
+    return allbits[pad: pad + R]
+
+
+def _check_swiglu(oracle_mod, got_bits, res, Xf, Wf, ids, k, K, xs=None, ws=None):
+    """got_bits [R, N/2]; res: oracle GemmResult of the un-gated product [R, N]."""
+    assert not np.any(got_bits == POISON), "an output was never written"
+    N = res.Y64.shape[1]
+    I = N // 2
+    H64, Hbf = oracle_mod.swiglu(res.Y64)
+    got = H.bf16_bits_to_f64(got_bits)
+    flat = ids.reshape(-1)
+    xi = np.arange(len(flat)) // k
+    A = np.stack([np.abs(Xf[xi[r]]) @ np.abs(Wf[flat[r]]) for r in range(len(flat))])     # sum |x||w| per (row, n)
+    if xs is not None:
+        A = A * (xs[xi][:, None] * ws[flat][:, None])
+    eps = 1.01 * K * 2.0 ** -24 * A + 4 * 2.0 ** -24 * np.abs(res.Y64)     # fp32 sums in any order (+ the two scale products)
+    g, u = res.Y64[:, :I], res.Y64[:, I:]
+    silu = g / (1.0 + np.exp(-g))
+    # |d silu / dg| <= 1.1; exp, division and the product in fp32 add a few 2^-24 relative; one bf16 rounding
+    tight = 2.0 ** -8 * np.abs(H64) * 1.001 + 1.1 * eps[:, :I] * np.abs(u) + np.abs(silu) * eps[:, I:] + 4e-6 * np.abs(H64) + 1e-30
+    err = np.abs(got - H64)
+    assert np.all(err <= tight), f"max err/tight = {(err / tight).max():.3f}"
+    assert (H.ulp_distance(got_bits, Hbf) == 0).mean() > 0.95
+
+
+SWIGLU_BF16 = [
+    # tile_m, tile_n, slack, T, E, k, K, N, routing
+    (256, 256, 0, 700, 8, 2, 128, 512, "zipf"),        # full tiles, 128- and 64-row tail functions
+    (256, 256, 64, 1100, 8, 2, 128, 256, "gauss_topk"),  # counts just above 256: slack block in use
+    (128, 256, 0, 300, 8, 2, 128, 512, "zipf"),
+    (128, 128, 0, 300, 8, 2, 128, 256, "gauss_topk"),
+    (64, 256, 0, 150, 8, 2, 192, 512, "zipf"),
+    (64, 128, 0, 150, 8, 2, 128, 256, "gauss_topk"),
+    (32, 256, 0, 100, 8, 2, 128, 512, "zipf"),
+    (32, 128, 0, 64, 8, 2, 256, 512, "gauss_topk"),
+    (16, 256, 0, 40, 8, 2, 128, 512, "zipf"),
+    (16, 128, 0, 40, 16, 2, 128, 256, "gauss_topk"),
+]
+
+
+@pytest.mark.parametrize("tile_m,tile_n,slack,T,E,k,K,N,routing", SWIGLU_BF16)
+def test_swiglu_bf16_parity(dev, oracle_mod, tile_m, tile_n, slack, T, E, k, K, N, routing):
+    wl = wk.Workload("parity_swiglu", T, E, k, K, N, "bf16", routing, tile_m, tile_n)
+    ids, X = wk.make_routing(wl), wk.make_x(wl)
+    W = wk.make_w(wl) * 4.0     # gates of a few units, so that the activation is exercised away from its linear part
+    got = _run_swiglu(dev, wl, ids, X, W, slack=slack)
+    res = oracle_mod.grouped_gemm_bf16(wk.bits(X), wk.bits(W), ids.numpy())
+    _check_swiglu(oracle_mod, got, res, X.double().numpy(), W.double().numpy(), ids.numpy(), k, K)
+
+
+SWIGLU_FP8 = [
+    (16, 64, 8, 64, 6, 256, 128, "uniform_topk"),
+    (16, 128, 32, 64, 6, 256, 256, "uniform_topk"),
+    (16, 256, 32, 16, 2, 384, 512, "zipf"),
+    (32, 128, 100, 8, 2, 256, 256, "zipf"),
+]
+
+
+@pytest.mark.parametrize("tile_m,tile_n,T,E,k,K,N,routing", SWIGLU_FP8)
+def test_swiglu_fp8_parity(dev, oracle_mod, tile_m, tile_n, T, E, k, K, N, routing):
+    wl = wk.Workload("parity_swiglu_fp8", T, E, k, K, N, "fp8", routing, tile_m, tile_n)
+    ids = wk.make_routing(wl)
+    X, xs = wk.make_x(wl)
+    W, ws = wk.make_w(wl)
+    ws = ws * 4.0
+    got = _run_swiglu(dev, wl, ids, X, W, xs, ws)
+    res = oracle_mod.grouped_gemm_fp8(wk.bits(X), wk.bits(W), xs.numpy(), ws.numpy(), ids.numpy())
+    Xf = X.view(torch.float8_e4m3fn).double().numpy()
+    Wf = W.view(torch.float8_e4m3fn).double().numpy()
+    _check_swiglu(oracle_mod, got, res, Xf, Wf, ids.numpy(), k, K, xs.double().numpy(), ws.double().numpy())
+
+
+def test_swiglu_argument_errors(dev):
+    wl = wk.Workload("swiglu_args", 8, 4, 2, 64, 128, "bf16", "gauss_topk", 16, 128)
+    ids = wk.make_routing(wl).to(dev)
+    X, W = wk.make_x(wl, dev), wk.make_w(wl, dev)
+    Y = torch.empty((wl.R, wl.N // 2), dtype=torch.bfloat16, device=dev)
+    tmap = mb.alloc_task_map(wl.T, wl.k, wl.E, 16, 128, wl.N)
+    mb.moe_build_task_map(ids, wl.T, wl.k, wl.E, 16, 128, wl.N, tmap)
+    d = mb.GemmDesc(mb.MOE_DTYPE_BF16, wl.T, wl.k, wl.E, wl.K, wl.N, 16, 128, epilogue=7)
+    assert mb.moe_grouped_gemm(X, W, ids, tmap, Y, d, check=False) == mb.MOE_ERR_INVALID_ARG
+
+
+COMBINE_CASES = [
+    # T, k, N, weighted
+    (1, 6, 2816, True),
+    (37, 2, 512, True),
+    (300, 8, 4096, True),
+    (300, 8, 4096, False),
+    (4096, 2, 4096, True),
+    (5, 1, 8, True),
+]
+
+
+@pytest.mark.parametrize("T,k,N,weighted", COMBINE_CASES)
+def test_combine_parity(dev, oracle_mod, T, k, N, weighted):
+    g = torch.Generator().manual_seed(1000 + T + k + N)
+    Y = torch.randn((T * k, N), generator=g).to(torch.bfloat16)
+    w = torch.rand((T, k), generator=g, dtype=torch.float32) if weighted else None
+    pad = 2
+    buf = torch.empty((T + 2 * pad, N), dtype=torch.int16, device=dev)
+    buf.fill_(POISON)
+    out = buf[pad: pad + T]
+    mb.moe_combine(Y.to(dev), None if w is None else w.to(dev), T, k, N, out)
+    torch.cuda.synchronize()
+    allbits = buf.cpu().numpy().view(np.uint16)
+    assert np.all(allbits[:pad] == POISON) and np.all(allbits[pad + T:] == POISON), "wrote outside out"
+    got_bits = allbits[pad: pad + T]
+    bits = Y.view(torch.int16).numpy().view(np.uint16)
+    out64, outbf = oracle_mod.combine(bits, None if w is None else w.numpy(), T, k)
+    yabs = np.abs(Y.double().numpy()).reshape(T, k, N)
+    wabs = np.ones((T, k)) if w is None else np.abs(w.double().numpy())
+    A = np.einsum("tj,tjn->tn", wabs, yabs)
+    tight = 2.0 ** -8 * np.abs(out64) * 1.001 + (k + 1) * 2.0 ** -24 * A + 1e-30
+    err = np.abs(H.bf16_bits_to_f64(got_bits) - out64)
+    assert np.all(err <= tight), f"max err/tight = {(err / tight).max():.3f}"
+    assert (H.ulp_distance(got_bits, outbf) == 0).mean() > 0.97
+
+
+def test_combine_argument_errors(dev):
+    Y = torch.zeros((4, 8), dtype=torch.bfloat16, device=dev)
+    out = torch.zeros((2, 8), dtype=torch.bfloat16, device=dev)
+    assert mb.moe_combine(Y, None, 2, 2, 12, out, check=False) == mb.MOE_ERR_UNSUPPORTED
+    assert mb.moe_combine(Y, None, 2, 0, 8, out, check=False) == mb.MOE_ERR_INVALID_ARG
+    assert mb.moe_combine(None, None, 2, 2, 8, out, check=False) == mb.MOE_ERR_INVALID_ARG
+    assert mb.moe_combine(None, None, 0, 2, 8, None, check=False) == mb.MOE_OK
