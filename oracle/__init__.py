@@ -135,6 +135,16 @@ def mapping(prefix, B: int):
     return h.value, l.value
 
 
+def mapping_two_level(prefix, group: int, B: int):
+    """Two-level TilePrefix decode (Sec. 3.1) with groups of `group` tasks: (h, l) for block index B."""
+    prefix = _i32(prefix)
+    h = ctypes.c_int32(0)
+    l = ctypes.c_int32(0)
+    _load().orc_mapping_two_level(_p(prefix), ctypes.c_int(len(prefix)), ctypes.c_int(group), ctypes.c_int(B),
+                                  ctypes.byref(h), ctypes.byref(l))
+    return h.value, l.value
+
+
 def build_task_map(topk_ids, T: int, k: int, E: int, tile_m: int, tile_n: int, N: int, order: int = 0,
                    tile_m_small: int = 0, small_max_rows: int = 0, tile_m_slack: int = 0) -> TaskMap:
     ids = _i32(topk_ids).reshape(-1)

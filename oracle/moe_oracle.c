@@ -133,6 +133,29 @@ void orc_mapping(const int32_t* tile_prefix, int n, int B, int32_t* h_out, int32
     *l_out = B - kk;
 }
 
+/* Two-level TilePrefix (Sec. 3.1 mentions it for task counts beyond a few warps and omits the details; our
+ * reading): the tasks are cut into groups of `group` consecutive tasks, the first level holds the last
+ * TilePrefix entry of every group (a group cut short by the end of the array counts as ending at +infinity).
+ * A vote over the first level gives the group of block B, Alg. 2 inside that group gives the task.
+ * Must return exactly what orc_mapping returns.                                                        */
+void orc_mapping_two_level(const int32_t* tile_prefix, int n, int group, int B, int32_t* h_out, int32_t* l_out) {
+    int groups = (n + group - 1) / group;
+    int g = 0; /* groups that lie entirely at or before B */
+    for (int i = 0; i < groups; ++i) {
+        int last = i * group + group - 1;
+        if (last < n && B >= tile_prefix[last]) g += 1;
+    }
+    int begin = g * group;
+    int len = n - begin < group ? n - begin : group;
+    if (len < 0) len = 0;
+    int32_t h = 0, l = 0;
+    orc_mapping(tile_prefix + begin, len, B, &h, &l);
+    /* l from the in-group vote is relative to the group's first entry only when h > 0 there */
+    if (h == 0) l = B - (begin > 0 ? tile_prefix[begin - 1] : 0);
+    *h_out = begin + h;
+    *l_out = l;
+}
+
 /* Tiling strategy of an expert with c rows (see the conventions at the top). */
 static int expert_tile_m(int c, int tile_m, int tile_m_small, int small_max_rows) {
     return (small_max_rows > 0 && c <= small_max_rows) ? tile_m_small : tile_m;

@@ -43,31 +43,33 @@ __host__ __device__ inline int hist_stride(int E64) { return E64 + 64; }
 // ---------------------------------------------------------------- decode
 
 // Alg. 2 on one wavefront: lane t tests p = (B >= TilePrefix[t]); the ballot is the
-// warp vote, its population count is the task index h.  For more than 64 tasks the
-// vote is repeated over the array (Sec. 3.1); pads are INT32_MAX and never vote.
+// warp vote, its population count is the task index h.  Pads are INT32_MAX and never vote.
 // The prefix comes from the packed task records {TilePrefix, expert, count, row offset}, so the record of
 // task h is already in a register of lane h when the vote is over: rec = that record, l = tile index in the task.
+// More than 64 tasks (Sec. 3.1, two-level TilePrefix): the last entry of every group of 64 tasks is the
+// first level; one vote over it (read in place, up to 64 groups) finds the group, a second vote the task in it.
 // `first` is records[lane] (the caller loads it early, next to the header); B must be below the total tile count.
 __device__ __forceinline__ void mapping(const int4* __restrict__ records, int E64, int B, int4 first, int& h, int& l, int4& rec) {
     const int lane = __lane_id();
     int4 r = first;
-    int kprev = 0;
-    h = 0;
-    rec = make_int4(0, 0, 0, 0);
-    for (int base = 0; base < E64; base += 64) {
-        const int votes = __popcll(__ballot(B >= r.x));
-        if (votes < 64) {  // the array is non-decreasing: task h sits in this round, at lane `votes`
-            h = base + votes;
-            rec.x = __builtin_amdgcn_readlane(r.x, votes);
-            rec.y = __builtin_amdgcn_readlane(r.y, votes);
-            rec.z = __builtin_amdgcn_readlane(r.z, votes);
-            rec.w = __builtin_amdgcn_readlane(r.w, votes);
-            if (votes > 0) kprev = __builtin_amdgcn_readlane(r.x, votes - 1);
-            break;
+    int base = 0, kprev = 0;
+    if (E64 > 64) {
+        const int groups = E64 >> 6;  // <= 16 for E <= 1024
+        const int top = lane < groups ? records[64 * lane + 63].x : 0x7fffffff;
+        const int grp = __popcll(__ballot(B >= top));  // groups that end at or before B
+        if (grp > 0) {
+            base = grp << 6;
+            kprev = __builtin_amdgcn_readlane(top, grp - 1);
+            r = records[base + lane];
         }
-        kprev = __builtin_amdgcn_readlane(r.x, 63);
-        if (base + 64 < E64) r = records[base + 64 + lane];
     }
+    const int votes = __popcll(__ballot(B >= r.x));  // < 64: the group's last entry is above B
+    h = base + votes;
+    rec.x = __builtin_amdgcn_readlane(r.x, votes);
+    rec.y = __builtin_amdgcn_readlane(r.y, votes);
+    rec.z = __builtin_amdgcn_readlane(r.z, votes);
+    rec.w = __builtin_amdgcn_readlane(r.w, votes);
+    if (votes > 0) kprev = __builtin_amdgcn_readlane(r.x, votes - 1);
     l = B - kprev;
 }
 

@@ -55,6 +55,8 @@ MAP_CASES = [
     (4096, 8, 64, 256, 256, 2560, "worst"),
     (4096, 8, 64, 256, 256, 2560, "best"),
     (1000, 1, 1, 128, 128, 128, "best"),
+    (3000, 4, 1000, 16, 64, 128, "gauss_topk"),    # 16 groups of 64 tasks: two-level decode
+    (700, 2, 640, 16, 64, 128, "zipf"),            # E64 = 640, most experts empty
 ]
 
 

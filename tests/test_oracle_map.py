@@ -327,3 +327,19 @@ def test_slack_tiling_properties(oracle_mod, T, k, E, tile_m, tile_n, N, skew, o
     for e, m_tile, _, rows in t2.tolist():
         if tm2.counts[e] <= 24:
             assert rows == min(16, tm2.counts[e] - 16 * m_tile)
+
+
+# ------------------------------------------------------------------ two-level TilePrefix (Sec. 3.1)
+@pytest.mark.parametrize("n,group", [(1, 64), (5, 2), (64, 64), (65, 64), (130, 64), (200, 8), (1000, 64)])
+def test_two_level_mapping_equals_brute_force(oracle_mod, n, group):
+    """Against the definition itself: block B belongs to the task whose half-open tile range contains it."""
+    rng = np.random.default_rng(n * 131 + group)
+    nu = rng.integers(0, 5, size=n)          # zero-tile tasks included: equal neighbours in the prefix
+    nu[rng.integers(0, n)] += 1              # at least one tile
+    prefix = np.cumsum(nu).astype(np.int32)
+    owner = np.repeat(np.arange(n), nu)      # brute force: the task of every block, written out
+    first = np.concatenate([[0], prefix[:-1]])
+    for B in range(int(prefix[-1])):
+        h, l = oracle_mod.mapping_two_level(prefix, group, B)
+        assert h == owner[B] and l == B - first[h]
+        assert (h, l) == oracle_mod.mapping(prefix, B)
