@@ -49,8 +49,10 @@ def algorithmic_bytes(wl: wk.Workload, ids: torch.Tensor, swiglu: bool = False) 
 class Point:
     """Device buffers of one workload (optionally several weight copies to defeat the caches)."""
 
-    def __init__(self, wl: wk.Workload, copies: int = 1, dev="cuda:0", order: int = 0, small=(0, 0), swiglu: bool = False):
+    def __init__(self, wl: wk.Workload, copies: int = 1, dev="cuda:0", order: int = 0, small=(0, 0), swiglu: bool = False,
+                 w_nk: bool = False):
         self.wl = wl
+        self.w_nk = w_nk      # weights pre-packed as [E][N][K] (a labelled extra, never the headline)
         self.swiglu = swiglu  # fused gated activation: Y is [R, N/2]
         self.order = order
         self.small = small  # (tile_m_small, small_max_rows) of the second tiling strategy, or (0, 0)
@@ -66,12 +68,18 @@ class Point:
         else:
             self.X = wk.make_x(wl, dev)
             W = wk.make_w(wl, dev)
+        if w_nk:
+            Wt = torch.empty((wl.E, wl.N, wl.K), dtype=W.dtype, device=dev)
+            for e in range(wl.E):   # expert by expert: no second full-size temporary
+                Wt[e].copy_(W[e].t())
+            W = Wt
         self.W = [W] + [W.clone() for _ in range(copies - 1)]
         self.Y = torch.empty((wl.R, wl.N // 2 if swiglu else wl.N), dtype=torch.bfloat16, device=dev)
         self.tmap = mb.alloc_task_map(wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N, dev)
         dt = mb.MOE_DTYPE_FP8_E4M3 if wl.dtype == "fp8" else mb.MOE_DTYPE_BF16
         self.desc = mb.GemmDesc(dt, wl.T, wl.k, wl.E, wl.K, wl.N, wl.tile_m, wl.tile_n, self.xs, self.ws, *small, self.slack,
-                                mb.MOE_EPILOGUE_SWIGLU if swiglu else mb.MOE_EPILOGUE_NONE)
+                                mb.MOE_EPILOGUE_SWIGLU if swiglu else mb.MOE_EPILOGUE_NONE,
+                                mb.MOE_W_LAYOUT_NK if w_nk else mb.MOE_W_LAYOUT_KN)
         self.tiling = mb.Tiling(wl.tile_m, wl.tile_n, order, small[0], small[1], self.slack)
 
     def build_map(self):
@@ -122,7 +130,7 @@ class Point:
         ideal_mfma = wl.flops / (peak_t * 1e12)
         ideal_hbm = abytes / (PEAK_HBM_GBS * 1e9)
         bound = "mfma" if ideal_mfma >= ideal_hbm else "hbm"
-        return dict(workload=f"{wl.name}_T{wl.T}" + ("_swiglu" if self.swiglu else ""), dtype=wl.dtype, T=wl.T, E=wl.E, k=wl.k, K=wl.K, N=wl.N,
+        return dict(workload=f"{wl.name}_T{wl.T}" + ("_swiglu" if self.swiglu else "") + ("_wNK" if self.w_nk else ""), dtype=wl.dtype, T=wl.T, E=wl.E, k=wl.k, K=wl.K, N=wl.N,
                     tile=[wl.tile_m, wl.tile_n], sigma_order=("spread" if self.order else "ascending"), small_strategy=list(self.small), tile_m_slack=self.slack, ms_per_step=round(wall_ms, 4), gemm_ms=round(gemm_ms, 4),
                     map_ms=round(map_ms, 4), tflops_step=round(tf_step, 2), tflops_gemm=round(tf_gemm, 2),
                     frac_mfma=round(tf_gemm / peak_t, 4), gbs_gemm=round(gbs, 1),
@@ -296,6 +304,16 @@ def main():
             points.append(p.report(max(10, args.steps // 2), max(3, args.warmup // 2)))
             del p
             torch.cuda.empty_cache()
+            # labelled extra: the same products with the weights pre-packed as [E][N][K]
+            for w in (wl, wk.mixtral_up(256), wk.mixtral_up(16), wk.decode_fp8(32), wk.decode_fp8(8)):
+                copies = 1
+                if w.dtype == "fp8":
+                    touched = int(torch.unique(wk.make_routing(w)).numel()) * w.K * w.N
+                    copies = min(16, max(4, -(-int(1.2e9) // touched)))
+                p = Point(w, copies, w_nk=True)
+                points.append(p.report(max(10, args.steps // 2), max(3, args.warmup // 2)))
+                del p
+                torch.cuda.empty_cache()
             for (T, k, N) in ((4096, 2, 4096), (8192, 8, 4096), (32, 6, 2816)):
                 points.append(combine_point(T, k, N, max(10, args.steps // 2), max(3, args.warmup // 2)))
                 torch.cuda.empty_cache()

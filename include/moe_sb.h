@@ -37,6 +37,11 @@ enum {
 
 enum { MOE_DTYPE_BF16 = 0, MOE_DTYPE_FP8_E4M3 = 1 };
 
+/* Storage order of the expert weights (moe_gemm_desc.w_layout).  KN is the layout of the problem statement:
+ * W[e][k][n], n contiguous.  NK is a pre-packed alternative, W[e][n][k], k contiguous (the order in which
+ * linear layers are usually stored); only some tilings have a kernel for it, see moe_w_layout_supported. */
+enum { MOE_W_LAYOUT_KN = 0, MOE_W_LAYOUT_NK = 1 };
+
 /* What the GEMM's epilogue stores (moe_gemm_desc.epilogue). */
 enum { MOE_EPILOGUE_NONE = 0, MOE_EPILOGUE_SWIGLU = 1 };
 
@@ -212,6 +217,7 @@ typedef struct moe_gemm_desc {
     int32_t tile_m_small, small_max_rows; /* second tiling strategy of the map, or 0, 0 */
     int32_t tile_m_slack; /* slack rows of the map's last m-tiles, or 0 */
     int32_t epilogue;     /* MOE_EPILOGUE_* */
+    int32_t w_layout;     /* MOE_W_LAYOUT_* */
 } moe_gemm_desc;
 
 /*
@@ -219,7 +225,7 @@ typedef struct moe_gemm_desc {
  * function; Sec. 4.3 gathered token rows; Sec. 4.4 pipeline):
  *     Y[t, j, :] = X[t, :] . W[e(t,j), :, :]        e(t,j) = topk_ids[t, j]
  *   X  DEVICE [T, K]    bf16 or e4m3 bytes, K contiguous, 16-byte aligned rows
- *   W  DEVICE [E, K, N] same element type, N contiguous
+ *   W  DEVICE [E, K, N] same element type, N contiguous  (or [E, N, K] with desc->w_layout = MOE_W_LAYOUT_NK)
  *   Y  DEVICE [T, k, N] bf16, written once per element; rows of a partial
  *      m-tile beyond the expert's count write nothing.
  *   fp8: Y = (sum over e4m3 products in fp32) * x_scale[t] * w_scale[e].
@@ -242,6 +248,8 @@ int moe_grouped_gemm(const void* X, const void* W, const int32_t* topk_ids, cons
 
 /* 1 if a GEMM kernel exists for this (dtype, tile_m, tile_n), else 0.  HOST, pure. */
 int moe_tile_supported(int dtype, int tile_m, int tile_n);
+/* 1 if a GEMM kernel exists for this dtype, tiling and weight layout, else 0.  HOST, pure. */
+int moe_w_layout_supported(int dtype, const moe_tiling* tiling, int w_layout);
 /* 1 if a two-strategy GEMM kernel exists for (dtype, tile_m, tile_n) + tile_m_small.  HOST, pure. */
 int moe_tile_pair_supported(int dtype, int tile_m, int tile_n, int tile_m_small);
 

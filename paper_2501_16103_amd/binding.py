@@ -25,6 +25,8 @@ MOE_ERR_ROUTING = -3
 MOE_ERR_HIP = -4
 MOE_DTYPE_BF16 = 0
 MOE_DTYPE_FP8_E4M3 = 1
+MOE_W_LAYOUT_KN = 0
+MOE_W_LAYOUT_NK = 1
 MOE_EPILOGUE_NONE = 0
 MOE_EPILOGUE_SWIGLU = 1
 MOE_ORDER_ASCENDING = 0
@@ -39,7 +41,7 @@ EXPORTS = [
     "moe_map_off_counts", "moe_map_off_offsets", "moe_map_off_sigma", "moe_map_off_tile_prefix",
     "moe_map_off_task_records", "moe_map_off_sorted_rows", "moe_task_map_bytes", "moe_grid_upper_bound", "moe_build_task_map",
     "moe_build_task_map_ordered", "moe_build_task_map_tiled", "moe_grid_upper_bound_tiled", "moe_tile_pair_supported",
-    "moe_build_task_map_ex", "moe_tiling_supported",
+    "moe_build_task_map_ex", "moe_tiling_supported", "moe_w_layout_supported",
     "moe_task_map_status", "moe_task_map_expand", "moe_grouped_gemm", "moe_tile_supported", "moe_combine",
     "moe_strerror",
 ]
@@ -56,7 +58,7 @@ class moe_gemm_desc(ctypes.Structure):
                 ("K", ctypes.c_int32), ("N", ctypes.c_int32), ("tile_m", ctypes.c_int32),
                 ("tile_n", ctypes.c_int32), ("x_scale", ctypes.c_void_p), ("w_scale", ctypes.c_void_p),
                 ("tile_m_small", ctypes.c_int32), ("small_max_rows", ctypes.c_int32),
-                ("tile_m_slack", ctypes.c_int32), ("epilogue", ctypes.c_int32)]
+                ("tile_m_slack", ctypes.c_int32), ("epilogue", ctypes.c_int32), ("w_layout", ctypes.c_int32)]
 
 
 class moe_tiling(ctypes.Structure):
@@ -98,6 +100,8 @@ def lib() -> ctypes.CDLL:
                                                                                       ctypes.c_void_p, ctypes.c_void_p]
         L.moe_tiling_supported.restype = ctypes.c_int
         L.moe_tiling_supported.argtypes = [ctypes.c_int, ctypes.POINTER(moe_tiling)]
+        L.moe_w_layout_supported.restype = ctypes.c_int
+        L.moe_w_layout_supported.argtypes = [ctypes.c_int, ctypes.POINTER(moe_tiling), ctypes.c_int]
         L.moe_task_map_status.restype = ctypes.c_int
         L.moe_task_map_status.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
         L.moe_task_map_expand.restype = ctypes.c_int
@@ -216,6 +220,11 @@ def moe_tiling_supported(dtype: int, tiling: Tiling) -> bool:
     return bool(lib().moe_tiling_supported(dtype, ctypes.byref(g)))
 
 
+def moe_w_layout_supported(dtype: int, tiling: Tiling, w_layout: int) -> bool:
+    g = tiling.c_struct()
+    return bool(lib().moe_w_layout_supported(dtype, ctypes.byref(g), w_layout))
+
+
 def moe_task_map_status(task_map: torch.Tensor) -> int:
     return int(lib().moe_task_map_status(_ptr(task_map), _stream()))
 
@@ -243,12 +252,13 @@ class GemmDesc:
     small_max_rows: int = 0
     tile_m_slack: int = 0
     epilogue: int = 0
+    w_layout: int = 0
 
     def c_struct(self) -> moe_gemm_desc:
         return moe_gemm_desc(self.dtype, self.T, self.k, self.E, self.K, self.N, self.tile_m, self.tile_n,
                              None if self.x_scale is None else self.x_scale.data_ptr(),
                              None if self.w_scale is None else self.w_scale.data_ptr(),
-                             self.tile_m_small, self.small_max_rows, self.tile_m_slack, self.epilogue)
+                             self.tile_m_small, self.small_max_rows, self.tile_m_slack, self.epilogue, self.w_layout)
 
 
 def moe_grouped_gemm(X: torch.Tensor, W: torch.Tensor, topk_ids: Optional[torch.Tensor], task_map: torch.Tensor,

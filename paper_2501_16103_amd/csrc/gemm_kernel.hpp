@@ -76,9 +76,13 @@ __device__ __forceinline__ void wait_vmcnt() {
 }
 
 // NS_ ring stages of token tiles, NSW_ ring stages of weight tiles (each k-tile deep).  SLACK_: rows a tile may
-// hold beyond BM_ (the map's tile_m), for maps built with tile_m_slack.
-template <int BM_, int BN_, int BK_, int WM_, int WN_, int NS_, bool FP8_ = false, int NSW_ = NS_, int SLACK_ = 0>
+// hold beyond BM_ (the map's tile_m), for maps built with tile_m_slack.  WKC_: the weights are stored [E][N][K]
+// (K contiguous, a pre-packed layout) instead of [E][K][N]: the weight tile then has the token tile's geometry
+// and needs no transposing LDS reads.
+template <int BM_, int BN_, int BK_, int WM_, int WN_, int NS_, bool FP8_ = false, int NSW_ = NS_, int SLACK_ = 0,
+          bool WKC_ = false>
 struct PipeCfg {
+    static constexpr bool WKC = WKC_;
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, NS = NS_, NSW = NSW_, SLACK = SLACK_;
     static constexpr int BMC = BM + SLACK;                     // row capacity of the tile in LDS and registers
     static constexpr bool FP8 = FP8_;
@@ -93,11 +97,11 @@ struct PipeCfg {
     static constexpr int ACC = MF == 32 ? 16 : 4;              // accumulator registers per block
     static constexpr int XROW = BK * ES, CPR = XROW / 16;
     static constexpr int WROW = BN * ES, CPRW = WROW / 16;
-    static constexpr int XS_BYTES = BMC * XROW, WS_BYTES = BK * WROW;
+    static constexpr int XS_BYTES = BMC * XROW, WS_BYTES = BK * WROW;  // (BN rows of XROW bytes when WKC: same size)
     static constexpr int W_RING = NS * XS_BYTES;               // byte offset of the weight ring
     static constexpr int LDS_BYTES = NS * XS_BYTES + NSW * WS_BYTES;
     // weight-fragment LDS reads per k-step (two 4-k halves for bf16, one 8-k piece for fp8)
-    static constexpr int WREADS = NBW * (FP8 ? 1 : 2);
+    static constexpr int WREADS = NBW * ((FP8 || WKC) ? 1 : 2);
     // memory-bound tiles start the weight stream before the token rows are known
     static constexpr bool EARLY_W = MF == 16;
     static_assert(XROW == 64 || XROW == 128, "token tile rows are 64 or 128 bytes");
@@ -161,6 +165,14 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
 #pragma unroll
     for (int j = 0; j < WI; ++j) {
         const int inst = j * NW + wave;
+        if constexpr (C::WKC) {
+            // tile row = weight column; a lane's 16 bytes are 8 (16) consecutive k of that column
+            const int row = inst * XROWS_PER_INST + lane / C::CPR, pos = lane % C::CPR;
+            int src = n0 + row;
+            if (a.swiglu) src = (n0 >> 1) + (row >> 5) * 16 + (row & 15) + ((row >> 4) & 1) * (a.N >> 1);
+            dw_off[j] = (uint32_t)src * (uint32_t)(a.K * ES) + ((pos ^ pswz_x<C>(row)) << 4);
+            continue;
+        }
         const int krow = inst * WROWS_PER_INST + lane / C::CPRW, pos = lane % C::CPRW;
         // 16-byte chunk of the tile's k-row this lane fetches (the swizzle is applied on the source side)
         const int chunk = pos ^ pswz_w<C>(krow);
@@ -176,7 +188,7 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
     }
     const char* Xb = static_cast<const char*>(a.X);
     const char* Wt = static_cast<const char*>(a.W) + (size_t)tc.e * a.K * a.N * ES;
-    const size_t w_kt_stride = (size_t)BK * w_row_bytes;
+    const size_t w_kt_stride = C::WKC ? (size_t)BK * ES : (size_t)BK * w_row_bytes;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(MOE_LDS(char)*)smem;
     const int KT = a.K / BK;
 
@@ -256,7 +268,19 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
         const char* xs = smem + sx * C::XS_BYTES;
         const char* ws = smem + C::W_RING + sw * C::WS_BYTES;
         if (r >= 1 && r <= WREADS) {
-            if constexpr (C::FP8) {
+            if constexpr (C::WKC) {
+                const int nb = r - 1;
+                const int row = wn * C::WTN + nb * MF + lrow;
+                const char* wrow = ws + row * C::XROW;
+                if constexpr (C::FP8) {
+                    const int c = kk * 2 + (g >> 1);
+                    wq[buf][nb][0] = *reinterpret_cast<const u32x2_t*>(wrow + ((c ^ pswz_x<C>(row)) << 4) + (g & 1) * 8);
+                } else {
+                    const int c = MF == 32 ? kk * 2 + (lane >> 5) : kk * 4 + g;
+                    const u32x4_t v = *reinterpret_cast<const u32x4_t*>(wrow + ((c ^ pswz_x<C>(row)) << 4));
+                    wq[buf][nb][0].x = v.x; wq[buf][nb][0].y = v.y; wq[buf][nb][1].x = v.z; wq[buf][nb][1].y = v.w;
+                }
+            } else if constexpr (C::FP8) {
                 const int nb = r - 1;
                 const char* p = ws + w_rd[nb] + (kk * 32) * C::WROW;
                 wq[buf][nb][0] = __builtin_bit_cast(u32x2_t, __builtin_amdgcn_ds_read_tr8_b64_v2i32((MOE_LDS(i32x2_t)*)(p)));

@@ -60,6 +60,7 @@ struct GemmVariant {
     gemm_launch_fn fn;
     int tile_m_small = 0;  // second tiling strategy handled by the same launch (0 = none)
     int tile_m_slack = 0;  // rows the last m-tile may hold beyond tile_m
+    int w_layout = MOE_W_LAYOUT_KN;
 };
 
 // Pipelined bf16 kernels:  BM   BN   BK  WM WN  ring stages
@@ -84,7 +85,23 @@ using P8_16x128 = PipeCfg<16, 128, 128, 1, 2, 4, true>;
 using P8_16x64 = PipeCfg<16, 64, 128, 1, 2, 4, true>;
 using P8_32x128 = PipeCfg<32, 128, 128, 1, 2, 4, true>;
 
+// The pre-packed weight layout [E][N][K] (K contiguous): the shapes the benchmark uses
+using Pk_256x256 = PipeCfg<256, 256, 64, 2, 4, 2, false, 3, 0, true>;
+using Pk_256x256s = PipeCfg<256, 256, 64, 2, 4, 2, false, 2, 64, true>;
+using Pks_64x256 = PipeCfg<64, 256, 64, 1, 8, 3, false, 3, 0, true>;
+using Pks_128x256 = PipeCfg<128, 256, 64, 1, 8, 2, false, 2, 0, true>;
+using Pk_128x256 = PipeCfg<128, 256, 64, 1, 4, 3, false, 3, 0, true>;
+using Pk_16x256 = PipeCfg<16, 256, 64, 1, 2, 2, false, 2, 0, true>;
+using P8k_16x256 = PipeCfg<16, 256, 128, 1, 2, 2, true, 2, 0, true>;
+using P8k_16x128 = PipeCfg<16, 128, 128, 1, 2, 4, true, 4, 0, true>;
+
 const GemmVariant kVariants[] = {
+    {MOE_DTYPE_BF16, 256, 256, 64, &launch_pipe<Pk_256x256, Pks_64x256, Pks_128x256>, 0, 0, MOE_W_LAYOUT_NK},
+    {MOE_DTYPE_BF16, 256, 256, 64, &launch_pipe<Pk_256x256s, Pks_64x256, Pks_128x256>, 0, 64, MOE_W_LAYOUT_NK},
+    {MOE_DTYPE_BF16, 128, 256, 64, &launch_pipe<Pk_128x256>, 0, 0, MOE_W_LAYOUT_NK},
+    {MOE_DTYPE_BF16, 16, 256, 64, &launch_pipe<Pk_16x256>, 0, 0, MOE_W_LAYOUT_NK},
+    {MOE_DTYPE_FP8_E4M3, 16, 256, 128, &launch_pipe<P8k_16x256>, 0, 0, MOE_W_LAYOUT_NK},
+    {MOE_DTYPE_FP8_E4M3, 16, 128, 128, &launch_pipe<P8k_16x128>, 0, 0, MOE_W_LAYOUT_NK},
     {MOE_DTYPE_BF16, 256, 256, 64, &launch_pipe<Pb_256x256, Ps_64x256, Ps_128x256>},
     {MOE_DTYPE_BF16, 256, 256, 64, &launch_pipe<Pb_256x256s, Ps_64x256, Ps_128x256>, 0, 64},
     {MOE_DTYPE_BF16, 128, 256, 64, &launch_pipe<Pb_128x256>},
@@ -106,14 +123,17 @@ const GemmVariant kPairVariants[] = {
     {MOE_DTYPE_BF16, 256, 256, 64, &launch_pipe2<Pb_256x256, Ps_128x256, Ps_64x256, Ps_128x256>, 128},
 };
 
-const GemmVariant* find_variant(int dtype, int tile_m, int tile_n, int tile_m_small = 0, int tile_m_slack = 0) {
+const GemmVariant* find_variant(int dtype, int tile_m, int tile_n, int tile_m_small = 0, int tile_m_slack = 0,
+                                int w_layout = MOE_W_LAYOUT_KN) {
     if (tile_m_small == 0) {
         for (const GemmVariant& v : kVariants)
-            if (v.dtype == dtype && v.tile_m == tile_m && v.tile_n == tile_n && v.tile_m_slack == tile_m_slack) return &v;
+            if (v.dtype == dtype && v.tile_m == tile_m && v.tile_n == tile_n && v.tile_m_slack == tile_m_slack &&
+                v.w_layout == w_layout)
+                return &v;
     } else {
         for (const GemmVariant& v : kPairVariants)
             if (v.dtype == dtype && v.tile_m == tile_m && v.tile_n == tile_n && v.tile_m_small == tile_m_small &&
-                v.tile_m_slack == tile_m_slack)
+                v.tile_m_slack == tile_m_slack && v.w_layout == w_layout)
                 return &v;
     }
     return nullptr;
@@ -262,6 +282,11 @@ int moe_task_map_expand(const void* task_map, int E, int32_t* table, int64_t gri
 
 int moe_tile_supported(int dtype, int tile_m, int tile_n) { return find_variant(dtype, tile_m, tile_n) != nullptr; }
 
+int moe_w_layout_supported(int dtype, const moe_tiling* g, int w_layout) {
+    if (!g || check_small_args(g->tile_m, g->tile_m_small, g->small_max_rows, g->tile_m_slack) != MOE_OK) return 0;
+    return find_variant(dtype, g->tile_m, g->tile_n, g->tile_m_small, g->tile_m_slack, w_layout) != nullptr;
+}
+
 int moe_grouped_gemm(const void* X, const void* W, const int32_t* topk_ids, const void* task_map, void* Y,
                      const moe_gemm_desc* d, void* stream) {
     (void)topk_ids;
@@ -274,7 +299,8 @@ int moe_grouped_gemm(const void* X, const void* W, const int32_t* topk_ids, cons
         const int rcs = check_small_args(d->tile_m, d->tile_m_small, d->small_max_rows, d->tile_m_slack);
         if (rcs != MOE_OK) return rcs;
     }
-    const GemmVariant* v = find_variant(d->dtype, d->tile_m, d->tile_n, d->tile_m_small, d->tile_m_slack);
+    if (d->w_layout != MOE_W_LAYOUT_KN && d->w_layout != MOE_W_LAYOUT_NK) return MOE_ERR_INVALID_ARG;
+    const GemmVariant* v = find_variant(d->dtype, d->tile_m, d->tile_n, d->tile_m_small, d->tile_m_slack, d->w_layout);
     if (!v) return MOE_ERR_UNSUPPORTED;
     if (d->K % v->bk != 0 || d->N % d->tile_n != 0) return MOE_ERR_UNSUPPORTED;
     if (d->epilogue != MOE_EPILOGUE_NONE && d->epilogue != MOE_EPILOGUE_SWIGLU) return MOE_ERR_INVALID_ARG;

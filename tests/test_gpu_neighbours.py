@@ -165,3 +165,76 @@ def test_combine_argument_errors(dev):
     assert mb.moe_combine(Y, None, 2, 0, 8, out, check=False) == mb.MOE_ERR_INVALID_ARG
     assert mb.moe_combine(None, None, 2, 2, 8, out, check=False) == mb.MOE_ERR_INVALID_ARG
     assert mb.moe_combine(None, None, 0, 2, 8, None, check=False) == mb.MOE_OK
+
+
+# ------------------------------------------------------------------ pre-packed weight layout [E][N][K]
+NK_CASES = [
+    # dtype, tile_m, tile_n, slack, T, E, k, K, N, routing, swiglu
+    ("bf16", 256, 256, 0, 700, 8, 2, 128, 512, "zipf", False),
+    ("bf16", 256, 256, 64, 1100, 8, 2, 192, 256, "gauss_topk", False),
+    ("bf16", 256, 256, 0, 700, 8, 2, 128, 512, "zipf", True),
+    ("bf16", 128, 256, 0, 300, 8, 2, 128, 512, "zipf", False),
+    ("bf16", 16, 256, 0, 40, 8, 2, 128, 512, "zipf", True),
+    ("fp8", 16, 128, 0, 32, 64, 6, 256, 256, "uniform_topk", False),
+    ("fp8", 16, 256, 0, 32, 16, 2, 384, 512, "zipf", True),
+]
+
+
+@pytest.mark.parametrize("dtype,tile_m,tile_n,slack,T,E,k,K,N,routing,swiglu", NK_CASES)
+def test_nk_weight_layout_parity(dev, oracle_mod, dtype, tile_m, tile_n, slack, T, E, k, K, N, routing, swiglu):
+    """The same product with the weights handed over as [E][N][K]; the oracle keeps the [E][K][N] statement."""
+    wl = wk.Workload("parity_nk", T, E, k, K, N, dtype, routing, tile_m, tile_n)
+    tiling = mb.Tiling(tile_m, tile_n, 0, 0, 0, slack)
+    dt = mb.MOE_DTYPE_FP8_E4M3 if dtype == "fp8" else mb.MOE_DTYPE_BF16
+    assert mb.moe_w_layout_supported(dt, tiling, mb.MOE_W_LAYOUT_NK)
+    ids = wk.make_routing(wl)
+    xs = ws = None
+    if dtype == "fp8":
+        X, xs = wk.make_x(wl)
+        W, ws = wk.make_w(wl)
+        if swiglu:
+            ws = ws * 4.0
+    else:
+        X, W = wk.make_x(wl), wk.make_w(wl) * (4.0 if swiglu else 1.0)
+    W_nk = W.transpose(1, 2).contiguous()
+    R, NO = wl.R, (N // 2 if swiglu else N)
+    pad = 4
+    buf = torch.empty((R + 2 * pad, NO), dtype=torch.int16, device=dev)
+    buf.fill_(POISON)
+    Y = buf[pad: pad + R]
+    tmap = mb.alloc_task_map(T, k, E, tile_m, tile_n, N)
+    mb.moe_build_task_map_ex(ids.to(dev), T, k, E, N, tiling, tmap)
+    desc = mb.GemmDesc(dt, T, k, E, K, N, tile_m, tile_n, None if xs is None else xs.to(dev), None if ws is None else ws.to(dev),
+                       tile_m_slack=slack, epilogue=mb.MOE_EPILOGUE_SWIGLU if swiglu else mb.MOE_EPILOGUE_NONE,
+                       w_layout=mb.MOE_W_LAYOUT_NK)
+    mb.moe_grouped_gemm(X.to(dev), W_nk.to(dev), ids.to(dev), tmap, Y, desc)
+    torch.cuda.synchronize()
+    allbits = buf.cpu().numpy().view(np.uint16)
+    assert np.all(allbits[:pad] == POISON) and np.all(allbits[pad + R:] == POISON), "wrote outside Y"
+    got = allbits[pad: pad + R]
+    if dtype == "fp8":
+        res = oracle_mod.grouped_gemm_fp8(wk.bits(X), wk.bits(W), xs.numpy(), ws.numpy(), ids.numpy())
+        Xf = X.view(torch.float8_e4m3fn).double().numpy()
+        Wf = W.view(torch.float8_e4m3fn).double().numpy()
+        sx, sw = xs.double().numpy(), ws.double().numpy()
+    else:
+        res = oracle_mod.grouped_gemm_bf16(wk.bits(X), wk.bits(W), ids.numpy())
+        Xf, Wf, sx, sw = X.double().numpy(), W.double().numpy(), None, None
+    if swiglu:
+        _check_swiglu(oracle_mod, got, res, Xf, Wf, ids.numpy(), k, K, sx, sw)
+    else:
+        from tests.test_gpu_parity import _check_y
+        _check_y(got, res, Xf, Wf, ids.numpy(), k, K, H.tol_fp8(K) if dtype == "fp8" else H.tol_bf16(K), sx, sw)
+
+
+def test_nk_layout_unsupported_tiling_is_refused(dev):
+    wl = wk.Workload("nk_args", 8, 4, 2, 64, 128, "bf16", "gauss_topk", 32, 128)
+    ids = wk.make_routing(wl).to(dev)
+    X, W = wk.make_x(wl, dev), wk.make_w(wl, dev)
+    Y = torch.empty((wl.R, wl.N), dtype=torch.bfloat16, device=dev)
+    tmap = mb.alloc_task_map(wl.T, wl.k, wl.E, 32, 128, wl.N)
+    mb.moe_build_task_map(ids, wl.T, wl.k, wl.E, 32, 128, wl.N, tmap)
+    d = mb.GemmDesc(mb.MOE_DTYPE_BF16, wl.T, wl.k, wl.E, wl.K, wl.N, 32, 128, w_layout=mb.MOE_W_LAYOUT_NK)
+    assert mb.moe_grouped_gemm(X, W, ids, tmap, Y, d, check=False) == mb.MOE_ERR_UNSUPPORTED
+    d = mb.GemmDesc(mb.MOE_DTYPE_BF16, wl.T, wl.k, wl.E, wl.K, wl.N, 32, 128, w_layout=5)
+    assert mb.moe_grouped_gemm(X, W, ids, tmap, Y, d, check=False) == mb.MOE_ERR_INVALID_ARG
