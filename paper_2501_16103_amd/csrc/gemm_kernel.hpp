@@ -140,12 +140,68 @@ __device__ __forceinline__ int pswz_w(int krow) {
 // Rows: MF-row block b of the tile belongs to wavefront row b % WM (its block b / WM), so a partly filled tile
 // spreads its live blocks evenly over the wavefront rows.  The loop exists in copies for a compile-time number of
 // blocks per wavefront (all of them, or all but the slack block) and in one copy that tests each block at run time.
-template <class C>
+// A workgroup's run of consecutive tiles for the streaming kernel: the task records stay in registers, so the
+// tile after the current one is known without touching memory and its loads can be issued while the current
+// tile still multiplies.
+struct TileStream {
+    static constexpr int MAX_GROUPS = 4;  // E <= 256
+    int4 rec[MAX_GROUPS];                 // lane-held task records, group by group
+    int next_B, end_B;                    // tiles still to run: [next_B, end_B)
+    moe_tiling tiling;
+    const float* xs_lds;                  // LDS copies of x_scale[T] and w_scale[E] (fp8)
+    const float* ws_lds;
+};
+
+// Alg. 2 + 4 on registers (see decode_block): B must be below the total tile count.
+__device__ __forceinline__ TileCoord decode_from_registers(const TileStream& ts, int B) {
+    int h = 0;
+#pragma unroll
+    for (int gi = 0; gi < TileStream::MAX_GROUPS; ++gi) h += __popcll(__ballot(B >= ts.rec[gi].x));  // pads never vote
+    int4 rec = make_int4(0, 0, 0, 0);
+    int kprev = 0;
+#pragma unroll
+    for (int gi = 0; gi < TileStream::MAX_GROUPS; ++gi) {
+        if ((h >> 6) == gi) {
+            rec.x = __builtin_amdgcn_readlane(ts.rec[gi].x, h & 63);
+            rec.y = __builtin_amdgcn_readlane(ts.rec[gi].y, h & 63);
+            rec.z = __builtin_amdgcn_readlane(ts.rec[gi].z, h & 63);
+            rec.w = __builtin_amdgcn_readlane(ts.rec[gi].w, h & 63);
+        }
+        if (h > 0 && ((h - 1) >> 6) == gi) kprev = __builtin_amdgcn_readlane(ts.rec[gi].x, (h - 1) & 63);
+    }
+    const int l = B - kprev;
+    TileCoord c;
+    c.e = rec.y;
+    const int cnt = rec.z;
+    c.small = 0;
+    const int mt = expert_m_tiles(cnt, ts.tiling);
+    c.n_tile = l / mt;
+    c.m_tile = l - c.n_tile * mt;
+    const int left = cnt - c.m_tile * ts.tiling.tile_m;
+    c.rows = c.m_tile + 1 < mt ? ts.tiling.tile_m : left;
+    c.row_base = rec.w + c.m_tile * ts.tiling.tile_m;
+    return c;
+}
+
+typedef __attribute__((ext_vector_type(8))) int i32x8_t;
+// Eight consecutive words through the scalar data path (read only): these loads count in lgkmcnt, so they do
+// not disturb the vmcnt bookkeeping of the DMA ring.  p must be wavefront-uniform and 4-byte aligned.
+__device__ __forceinline__ i32x8_t scalar_load8(const int32_t* p) {
+    i32x8_t v;
+    asm volatile("s_load_dwordx8 %0, %1, 0x0" : "=s"(v) : "s"(p) : "memory");
+    return v;
+}
+__device__ __forceinline__ void scalar_wait(i32x8_t& a, i32x8_t& b) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(a), "+s"(b)::"memory");
+}
+
+// One tile of the batch (STREAM = false), or a run of tiles taken from `ts` (STREAM = true; 16-row tiles only):
+// everything after the task-map decode.  A task function in the sense of Alg. 3.
+template <class C, bool STREAM = false>
 __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __restrict__ map, const MapLayout& L,
-                                          const TileCoord& tc, char* smem) {
+                                          TileCoord tc, char* smem, TileStream* ts = nullptr) {
     constexpr int BN = C::BN, BK = C::BK, ES = C::ES, NT = C::NT, NW = NT / 64, NS = C::NS, NSW = C::NSW, MF = C::MF;
     constexpr int KSTEPS = C::KSTEPS, WREADS = C::WREADS, NBW = C::NBW, MBW = C::MBW;
-    const int n0 = tc.n_tile * BN;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / C::WN, wn = wave % C::WN;
@@ -160,7 +216,10 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
     static_assert(C::SLACK == 0 || (C::BM * C::XROW) % (1024 * NW) == 0, "slack rows start at a DMA instruction boundary");
     constexpr int XROWS_PER_INST = 1024 / C::XROW, WROWS_PER_INST = 1024 / C::WROW;
     static_assert((NS - 1) * XI + (NSW - 1) * WI < 64, "vmcnt range");
-    uint32_t dx_off[XI], dw_off[WI];
+    static_assert(!STREAM || (C::BM == 16 && MF == 16 && MBW == 1 && XI == 1 && NS == NSW && C::SLACK == 0 && KSTEPS % 2 == 0),
+                  "the streaming loop is written for 16-row tiles");
+    // per-lane source offsets inside a tile; everything that depends on the tile (expert, n-tile) is in the base pointer
+    uint32_t dx_off[XI], dx_next = 0, dw_off[WI];
     const uint32_t w_row_bytes = (uint32_t)a.N * ES;
 #pragma unroll
     for (int j = 0; j < WI; ++j) {
@@ -168,36 +227,43 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
         if constexpr (C::WKC) {
             // tile row = weight column; a lane's 16 bytes are 8 (16) consecutive k of that column
             const int row = inst * XROWS_PER_INST + lane / C::CPR, pos = lane % C::CPR;
-            int src = n0 + row;
-            if (a.swiglu) src = (n0 >> 1) + (row >> 5) * 16 + (row & 15) + ((row >> 4) & 1) * (a.N >> 1);
+            int src = row;
+            if (a.swiglu) src = (row >> 5) * 16 + (row & 15) + ((row >> 4) & 1) * (a.N >> 1);
             dw_off[j] = (uint32_t)src * (uint32_t)(a.K * ES) + ((pos ^ pswz_x<C>(row)) << 4);
             continue;
         }
         const int krow = inst * WROWS_PER_INST + lane / C::CPRW, pos = lane % C::CPRW;
         // 16-byte chunk of the tile's k-row this lane fetches (the swizzle is applied on the source side)
         const int chunk = pos ^ pswz_w<C>(krow);
-        uint32_t col_bytes = (uint32_t)(n0 * ES) + (chunk << 4);
+        uint32_t col_bytes = chunk << 4;
         if (a.swiglu) {
             // Tile columns come in units of 16: even units are gate columns, odd units the up columns of the same
             // 16 outputs, so that a lane ends up with a gate value and its up value in its own accumulators.
             const int c0 = chunk * (16 / ES);                  // first tile column of the chunk
-            const int unit = c0 >> 4, src = (n0 >> 1) + (unit >> 1) * 16 + (c0 & 15) + (unit & 1) * (a.N >> 1);
+            const int unit = c0 >> 4, src = (unit >> 1) * 16 + (c0 & 15) + (unit & 1) * (a.N >> 1);
             col_bytes = (uint32_t)src * ES;
         }
         dw_off[j] = (uint32_t)krow * w_row_bytes + col_bytes;
     }
     const char* Xb = static_cast<const char*>(a.X);
-    const char* Wt = static_cast<const char*>(a.W) + (size_t)tc.e * a.K * a.N * ES;
+    // weight base of a tile: expert, and the first column the tile reads (half as far with the fused activation)
+    auto w_base = [&](const TileCoord& t) {
+        const size_t col = (size_t)(a.swiglu ? (t.n_tile * BN) >> 1 : t.n_tile * BN);
+        return static_cast<const char*>(a.W) + ((size_t)t.e * a.K * a.N + (C::WKC ? col * a.K : col)) * ES;
+    };
+    const char* Wt = w_base(tc);
+    const char* Wt_next = Wt;
     const size_t w_kt_stride = C::WKC ? (size_t)BK * ES : (size_t)BK * w_row_bytes;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(MOE_LDS(char)*)smem;
     const int KT = a.K / BK;
 
     // j-th token-row / weight-row DMA instruction of this wave for k-tile kt, into ring stage `stage`
-    auto dma_x = [&](int j, int kt, int stage) {
-        dma16(dx_off[j], Xb + (size_t)kt * (BK * ES), lds0 + stage * C::XS_BYTES + (j * NW + wave) * 1024);
+    auto dma_x = [&](int j, int kt, int stage, bool next) {
+        dma16(next ? dx_next : dx_off[j], Xb + (size_t)kt * (BK * ES), lds0 + stage * C::XS_BYTES + (j * NW + wave) * 1024);
     };
-    auto dma_w = [&](int j, int kt, int stage) {
-        dma16(dw_off[j], Wt + (size_t)kt * w_kt_stride, lds0 + C::W_RING + stage * C::WS_BYTES + (j * NW + wave) * 1024);
+    auto dma_w = [&](int j, int kt, int stage, bool next) {
+        dma16(dw_off[j], (next ? Wt_next : Wt) + (size_t)kt * w_kt_stride,
+              lds0 + C::W_RING + stage * C::WS_BYTES + (j * NW + wave) * 1024);
     };
 
     if (C::EARLY_W) {
@@ -205,28 +271,43 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
         for (int s = 0; s < NSW; ++s)
             if (s < KT) {
 #pragma unroll
-                for (int j = 0; j < WI; ++j) dma_w(j, s, s);
+                for (int j = 0; j < WI; ++j) dma_w(j, s, s, false);
             }
     }
 
+    // ---- per-tile row information
     const int32_t* rows_of_tile = map + L.off_rows + tc.row_base;
+    // streaming: lane j < 16 holds the flat row id of tile row j (row 0's for j past the tile's rows) and the
+    // token's scale; fetched through the scalar path and LDS so that no vector-memory wait is ever generated
+    int rows_v = 0, rows_v_next = 0;
+    auto stream_rows = [&](const TileCoord& t, int& rv, uint32_t& dxo) {
+        const int32_t* p = map + L.off_rows + t.row_base;
+        i32x8_t lo = scalar_load8(p), hi = scalar_load8(p + 8);
+        scalar_wait(lo, hi);
+        int v = lo[0];
 #pragma unroll
-    for (int j = 0; j < XI; ++j) {
-        const int inst = j * NW + wave;
-        const int row = inst * XROWS_PER_INST + lane / C::CPR, pos = lane % C::CPR;
-        // rows past the tile's count: fetch a valid row, never store it
-        const int r = rows_of_tile[row < tc.rows ? row : 0];
-        dx_off[j] = (uint32_t)(r / a.k) * (uint32_t)(a.K * ES) + ((pos ^ pswz_x<C>(row)) << 4);
+        for (int j = 1; j < 16; ++j) v = (lane == j && j < t.rows) ? (j < 8 ? lo[j] : hi[j - 8]) : v;
+        rv = v;
+        const int tok = v / a.k;                                       // lanes 0..15
+        const int row = wave * XROWS_PER_INST + lane / C::CPR, pos = lane % C::CPR;
+        const int tok_of_row = __shfl(tok, row);
+        dxo = (uint32_t)tok_of_row * (uint32_t)(a.K * ES) + ((pos ^ pswz_x<C>(row)) << 4);
+    };
+    if constexpr (STREAM) {
+        stream_rows(tc, rows_v, dx_off[0]);
+    } else {
+#pragma unroll
+        for (int j = 0; j < XI; ++j) {
+            const int inst = j * NW + wave;
+            const int row = inst * XROWS_PER_INST + lane / C::CPR, pos = lane % C::CPR;
+            // rows past the tile's count: fetch a valid row, never store it
+            const int r = rows_of_tile[row < tc.rows ? row : 0];
+            dx_off[j] = (uint32_t)(r / a.k) * (uint32_t)(a.K * ES) + ((pos ^ pswz_x<C>(row)) << 4);
+        }
     }
 
     using acc_t = typename std::conditional<MF == 32, f32x16_t, f32x4_t>::type;
     acc_t acc[NBW][MBW];
-#pragma unroll
-    for (int nb = 0; nb < NBW; ++nb)
-#pragma unroll
-        for (int mb = 0; mb < MBW; ++mb)
-#pragma unroll
-            for (int j = 0; j < C::ACC; ++j) acc[nb][mb][j] = 0.f;
 
     // blocks of this wavefront that hold at least one real row: blocks wm, wm + WM, ... below ceil(rows / MF)
     const int live_blocks = (tc.rows + MF - 1) / MF;
@@ -318,33 +399,44 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
         }
     };
 
+    int cur = 0, curw = 0;        // ring positions; they run on from tile to tile when streaming
+    bool first = true;            // the rings are empty: fill them before the loop
+    bool has_next = false;        // streaming: another tile follows, its first k-tiles are fetched by this tile's last iterations
+
     // The tile's whole k loop for NMB row blocks per wavefront and XIL token-row DMA instructions per stage.
     auto run = [&](auto nmb_tag, auto xil_tag, auto tail_tag) {
         constexpr int NMB = decltype(nmb_tag)::value, XIL = decltype(xil_tag)::value;
         constexpr bool TAIL = decltype(tail_tag)::value;
         constexpr int NM = NBW * NMB, NREADS = WREADS + NMB, ND = XIL + WI;
-        // d-th DMA instruction of a stage: token rows first
-        auto dma_one = [&](int d, int ktx, int ktw, int sx, int sw, bool do_x, bool do_w) {
-            if (d < XIL) { if (do_x) dma_x(d, ktx, sx); }
-            else if (do_w) dma_w(d - XIL, ktw, sw);
-        };
-        // ---- prologue: fill the rings, first fragments into registers
-#pragma unroll
-        for (int s = 0; s < NSW; ++s) {
-            if (s < KT) {
-#pragma unroll
-                for (int d = (s < NS ? 0 : XIL); d < (C::EARLY_W ? XIL : ND); ++d) dma_one(d, s, s, s, s, true, true);
+        // d-th DMA instruction of a stage (token rows first) for k-tile kt of this tile, or, past its end, of the next
+        auto dma_one = [&](int d, int ktx, int ktw, int sx, int sw, bool all_in_range) {
+            if (d < XIL) {
+                if (all_in_range || ktx < KT) dma_x(d, ktx, sx, false);
+                else if (STREAM && has_next) dma_x(d, ktx - KT, sx, true);
+            } else {
+                if (all_in_range || ktw < KT) dma_w(d - XIL, ktw, sw, false);
+                else if (STREAM && has_next) dma_w(d - XIL, ktw - KT, sw, true);
             }
-        }
-        // EARLY_W issued weights and token rows in two batches: wait for all of it; else only tile 0 is needed
-        if (!C::EARLY_W && NSW <= KT) wait_vmcnt<(NS - 1) * XIL + (NSW - 1) * WI>(); else wait_vmcnt<0>();
-        __syncthreads();
+        };
+        if (first) {
+            // ---- prologue: fill the rings, first fragments into registers
 #pragma unroll
-        for (int r = 0; r < NREADS; ++r) read_one(r, 0, 0, 0, 0, TAIL);
+            for (int s = 0; s < NSW; ++s) {
+                if (s < KT) {
+#pragma unroll
+                    for (int d = (s < NS ? 0 : XIL); d < (C::EARLY_W ? XIL : ND); ++d) dma_one(d, s, s, s, s, true);
+                }
+            }
+            // EARLY_W issued weights and token rows in two batches: wait for all of it; else only tile 0 is needed
+            if (!C::EARLY_W && NSW <= KT) wait_vmcnt<(NS - 1) * XIL + (NSW - 1) * WI>(); else wait_vmcnt<0>();
+            __syncthreads();
+#pragma unroll
+            for (int r = 0; r < NREADS; ++r) read_one(r, 0, 0, 0, 0, TAIL);
+        }
 
-        int cur = 0, curw = 0;
         auto iteration = [&](int kt, auto steady_tag) {
             constexpr bool STEADY = decltype(steady_tag)::value;  // kt + NSW < KT: every fetch below is in range
+            const bool more = STEADY || (STREAM && has_next);     // every fetch below has a target
             const int nxt = cur + 1 == NS ? 0 : cur + 1;
             const int nxtw = curw + 1 == NSW ? 0 : curw + 1;
 #pragma unroll
@@ -360,19 +452,18 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
             // Tile kt+1 must have landed.  Issue order is [X(j+NS) W(j+NSW)] per iteration j, so what may still
             // be in flight is the NS-2 iterations' worth issued after X(kt+1), plus, with a deeper weight ring,
             // the weight rows issued right behind X(kt+1).
-            if (STEADY || kt + NSW - 1 < KT) wait_vmcnt<(NS - 2) * ND + (NSW > NS ? WI : 0)>(); else wait_vmcnt<0>();
+            if (more || kt + NSW - 1 < KT) wait_vmcnt<(NS - 2) * ND + (NSW > NS ? WI : 0)>(); else wait_vmcnt<0>();
             __syncthreads();
             MOE_SCHED_FENCE();
 #pragma unroll
             for (int i = 0; i < NM; ++i) {
                 mfma_one(i, (KSTEPS - 1) & 1, TAIL);
-                if (STEADY || kt + 1 < KT) {
+                if (more || kt + 1 < KT) {
 #pragma unroll
                     for (int r = i * NREADS / NM; r < (i + 1) * NREADS / NM; ++r) read_one(r, nxt, nxtw, 0, KSTEPS & 1, TAIL);
                 }
 #pragma unroll
-                for (int d = i * ND / NM; d < (i + 1) * ND / NM; ++d)
-                    dma_one(d, kt + NS, kt + NSW, cur, curw, STEADY || kt + NS < KT, STEADY || kt + NSW < KT);
+                for (int d = i * ND / NM; d < (i + 1) * ND / NM; ++d) dma_one(d, kt + NS, kt + NSW, cur, curw, STEADY);
                 MOE_SCHED_FENCE();
             }
             cur = nxt;
@@ -382,19 +473,7 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
         for (; kt + NSW < KT; ++kt) iteration(kt, std::true_type{});
         for (; kt < KT; ++kt) iteration(kt, std::false_type{});
     };
-    using std::integral_constant;
-    if (C::SLACK > 0 && tc.rows > C::BM) {
-        // every wavefront moves its share of the slack rows; only those whose slack block holds a real row compute it
-        if (mb_live == MBW) run(integral_constant<int, MBW>{}, integral_constant<int, XI>{}, std::false_type{});
-        else run(integral_constant<int, C::MBW_BODY>{}, integral_constant<int, XI>{}, std::false_type{});
-    } else if (mb_live == C::MBW_BODY) {
-        run(integral_constant<int, C::MBW_BODY>{}, integral_constant<int, XI_BODY>{}, std::false_type{});
-    } else {
-        run(integral_constant<int, C::MBW_BODY>{}, integral_constant<int, XI_BODY>{}, std::true_type{});
-    }
-    wait_vmcnt<0>();
 
-    // ---- epilogue: fp32 -> bf16 (RNE), scatter to Y[r, n]; fp8 applies the two scales first
     char* Yb = static_cast<char*>(a.Y);
     const size_t y_row_bytes = (size_t)(a.swiglu ? a.N >> 1 : a.N) * 2;
     auto store4 = [](char* p, float v0, float v1, float v2, float v3) {
@@ -404,56 +483,104 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
         *reinterpret_cast<u32x2_t*>(p) = v;
     };
     auto silu_mul = [](float gate, float up) { return gate / (1.f + __expf(-gate)) * up; };
-#pragma unroll
-    for (int mb = 0; mb < MBW; ++mb) {
-        const int m_local = (mb * C::WM + wm) * MF + lrow;
-        if (m_local >= tc.rows) continue;
-        const int r = rows_of_tile[m_local];
-        float xsc = 1.f, wsc = 1.f;
-        if constexpr (C::FP8) { xsc = a.x_scale[r / a.k]; wsc = a.w_scale[tc.e]; }
-        if (!a.swiglu) {
-            char* yrow = Yb + (size_t)r * y_row_bytes + (size_t)n0 * 2;
-#pragma unroll
-            for (int nb = 0; nb < NBW; ++nb) {
-#pragma unroll
-                for (int jq = 0; jq < C::ACC / 4; ++jq) {
-                    const int n_local = MF == 32 ? wn * C::WTN + nb * 32 + 8 * jq + 4 * (lane >> 5) : wn * C::WTN + nb * 16 + 4 * g;
-                    float v0 = acc[nb][mb][4 * jq + 0], v1 = acc[nb][mb][4 * jq + 1];
-                    float v2 = acc[nb][mb][4 * jq + 2], v3 = acc[nb][mb][4 * jq + 3];
-                    if constexpr (C::FP8) {
-                        v0 = (v0 * xsc) * wsc; v1 = (v1 * xsc) * wsc; v2 = (v2 * xsc) * wsc; v3 = (v3 * xsc) * wsc;
-                    }
-                    store4(yrow + n_local * 2, v0, v1, v2, v3);
-                }
+
+    while (true) {
+        const int n0 = tc.n_tile * BN;
+        TileCoord tc_next = tc;
+        if constexpr (STREAM) {
+            has_next = ts->next_B < ts->end_B;
+            if (has_next) {
+                tc_next = decode_from_registers(*ts, ts->next_B);
+                ts->next_B += 1;
+                Wt_next = w_base(tc_next);
+                stream_rows(tc_next, rows_v_next, dx_next);
             }
+        }
+#pragma unroll
+        for (int nb = 0; nb < NBW; ++nb)
+#pragma unroll
+            for (int mb = 0; mb < MBW; ++mb)
+#pragma unroll
+                for (int j = 0; j < C::ACC; ++j) acc[nb][mb][j] = 0.f;
+
+        using std::integral_constant;
+        if (C::SLACK > 0 && tc.rows > C::BM) {
+            // every wavefront moves its share of the slack rows; only those whose slack block holds a real row compute it
+            if (mb_live == MBW) run(integral_constant<int, MBW>{}, integral_constant<int, XI>{}, std::false_type{});
+            else run(integral_constant<int, C::MBW_BODY>{}, integral_constant<int, XI>{}, std::false_type{});
+        } else if (STREAM || mb_live == C::MBW_BODY) {
+            run(integral_constant<int, C::MBW_BODY>{}, integral_constant<int, XI_BODY>{}, std::false_type{});
         } else {
-            // gate and up of one output sit in the same lane: accumulators j and j + 8 of a 32-row block
-            // (its rows 0-15 are a gate unit, 16-31 the up unit), or blocks nb and nb + 1 of 16 rows
-            char* yrow = Yb + (size_t)r * y_row_bytes + (size_t)(n0 >> 1) * 2;
-            if constexpr (MF == 32) {
+            run(integral_constant<int, C::MBW_BODY>{}, integral_constant<int, XI_BODY>{}, std::true_type{});
+        }
+        if (!(STREAM && has_next)) wait_vmcnt<0>();  // a following tile's loads stay in flight across the epilogue
+
+        // ---- epilogue: fp32 -> bf16 (RNE), scatter to Y[r, n]; fp8 applies the two scales first
+#pragma unroll
+        for (int mb = 0; mb < MBW; ++mb) {
+            const int m_local = (mb * C::WM + wm) * MF + lrow;
+            int r;
+            float xsc = 1.f, wsc = 1.f;
+            if constexpr (STREAM) {
+                r = __shfl(rows_v, m_local);
+                if constexpr (C::FP8) { xsc = ts->xs_lds[r / a.k]; wsc = ts->ws_lds[tc.e]; }
+                if (m_local >= tc.rows) continue;
+            } else {
+                if (m_local >= tc.rows) continue;
+                r = rows_of_tile[m_local];
+                if constexpr (C::FP8) { xsc = a.x_scale[r / a.k]; wsc = a.w_scale[tc.e]; }
+            }
+            if (!a.swiglu) {
+                char* yrow = Yb + (size_t)r * y_row_bytes + (size_t)n0 * 2;
 #pragma unroll
                 for (int nb = 0; nb < NBW; ++nb) {
 #pragma unroll
-                    for (int jq = 0; jq < 2; ++jq) {
-                        const int n_local = ((wn * C::WTN + nb * 32) >> 1) + 8 * jq + 4 * (lane >> 5);
-                        float h[4];
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) h[i] = silu_mul((acc[nb][mb][4 * jq + i] * xsc) * wsc, (acc[nb][mb][8 + 4 * jq + i] * xsc) * wsc);
-                        store4(yrow + n_local * 2, h[0], h[1], h[2], h[3]);
+                    for (int jq = 0; jq < C::ACC / 4; ++jq) {
+                        const int n_local = MF == 32 ? wn * C::WTN + nb * 32 + 8 * jq + 4 * (lane >> 5) : wn * C::WTN + nb * 16 + 4 * g;
+                        float v0 = acc[nb][mb][4 * jq + 0], v1 = acc[nb][mb][4 * jq + 1];
+                        float v2 = acc[nb][mb][4 * jq + 2], v3 = acc[nb][mb][4 * jq + 3];
+                        if constexpr (C::FP8) {
+                            v0 = (v0 * xsc) * wsc; v1 = (v1 * xsc) * wsc; v2 = (v2 * xsc) * wsc; v3 = (v3 * xsc) * wsc;
+                        }
+                        store4(yrow + n_local * 2, v0, v1, v2, v3);
                     }
                 }
             } else {
-                static_assert(MF == 32 || NBW % 2 == 0, "gate and up blocks pair up inside a wavefront");
+                // gate and up of one output sit in the same lane: accumulators j and j + 8 of a 32-row block
+                // (its rows 0-15 are a gate unit, 16-31 the up unit), or blocks nb and nb + 1 of 16 rows
+                char* yrow = Yb + (size_t)r * y_row_bytes + (size_t)(n0 >> 1) * 2;
+                if constexpr (MF == 32) {
 #pragma unroll
-                for (int nb = 0; nb + 1 < NBW; nb += 2) {
-                    const int n_local = ((wn * C::WTN + nb * 16) >> 1) + 4 * g;
-                    float h[4];
+                    for (int nb = 0; nb < NBW; ++nb) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) h[i] = silu_mul((acc[nb][mb][i] * xsc) * wsc, (acc[nb + 1][mb][i] * xsc) * wsc);
-                    store4(yrow + n_local * 2, h[0], h[1], h[2], h[3]);
+                        for (int jq = 0; jq < 2; ++jq) {
+                            const int n_local = ((wn * C::WTN + nb * 32) >> 1) + 8 * jq + 4 * (lane >> 5);
+                            float h[4];
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) h[i] = silu_mul((acc[nb][mb][4 * jq + i] * xsc) * wsc, (acc[nb][mb][8 + 4 * jq + i] * xsc) * wsc);
+                            store4(yrow + n_local * 2, h[0], h[1], h[2], h[3]);
+                        }
+                    }
+                } else {
+                    static_assert(MF == 32 || NBW % 2 == 0, "gate and up blocks pair up inside a wavefront");
+#pragma unroll
+                    for (int nb = 0; nb + 1 < NBW; nb += 2) {
+                        const int n_local = ((wn * C::WTN + nb * 16) >> 1) + 4 * g;
+                        float h[4];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) h[i] = silu_mul((acc[nb][mb][i] * xsc) * wsc, (acc[nb + 1][mb][i] * xsc) * wsc);
+                        store4(yrow + n_local * 2, h[0], h[1], h[2], h[3]);
+                    }
                 }
             }
         }
+        if (!(STREAM && has_next)) break;
+        // the following tile becomes the current one; its first k-tiles are already in the rings
+        tc = tc_next;
+        Wt = Wt_next;
+        dx_off[0] = dx_next;
+        rows_v = rows_v_next;
+        first = false;
     }
 }
 
