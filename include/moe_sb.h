@@ -263,6 +263,13 @@ int moe_tile_pair_supported(int dtype, int tile_m, int tile_n, int tile_m_small)
  */
 int moe_combine(const void* Y, const float* topk_weights, int T, int k, int N, void* out, void* stream);
 
+/* Measurement and test aid.  Where the shape allows it (16-row tiles, E <= 256, fp8: T + E <= 2048)
+ * moe_grouped_gemm keeps workgroups resident and streams several tiles through each instead of launching one
+ * workgroup per tile; by default it does so when the grid bound is at least two tiles per resident workgroup.
+ * mode 0: that default; 1: never; 2: always; >= 8: always, with at most `mode` workgroups (rounded down to a
+ * multiple of 8).  Results are identical in every mode.  Process-wide, not thread-safe. */
+void moe_debug_streaming(int mode);
+
 /* Static string for a return code. */
 const char* moe_strerror(int code);
 

@@ -43,7 +43,7 @@ EXPORTS = [
     "moe_build_task_map_ordered", "moe_build_task_map_tiled", "moe_grid_upper_bound_tiled", "moe_tile_pair_supported",
     "moe_build_task_map_ex", "moe_tiling_supported", "moe_w_layout_supported",
     "moe_task_map_status", "moe_task_map_expand", "moe_grouped_gemm", "moe_tile_supported", "moe_combine",
-    "moe_strerror",
+    "moe_debug_streaming", "moe_strerror",
 ]
 
 
@@ -113,6 +113,8 @@ def lib() -> ctypes.CDLL:
         L.moe_combine.restype = ctypes.c_int
         L.moe_combine.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                   ctypes.c_void_p, ctypes.c_void_p]
+        L.moe_debug_streaming.restype = None
+        L.moe_debug_streaming.argtypes = [ctypes.c_int]
         L.moe_strerror.restype = ctypes.c_char_p
         L.moe_strerror.argtypes = [ctypes.c_int]
         _lib = L
@@ -276,3 +278,7 @@ def moe_combine(Y: torch.Tensor, topk_weights: Optional[torch.Tensor], T: int, k
     if check and rc != MOE_OK:
         raise MoeError(rc, "moe_combine")
     return rc
+
+
+def moe_debug_streaming(mode: int) -> None:
+    lib().moe_debug_streaming(int(mode))

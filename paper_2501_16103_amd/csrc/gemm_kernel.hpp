@@ -650,4 +650,53 @@ __global__ __launch_bounds__(CBIG::NT) void moe_gemm_pipe2_kernel(GemmArgs a) {
     else run_tile<CBIG, Tails...>(a, a.map, L, tc, smem);
 }
 
+// Streaming launch for 16-row tiles (the weight-streaming regime): a fixed number of resident workgroups, each
+// running a contiguous share of its XCD's tiles through pipe_tile<C, true>, so that the weight stream of a
+// workgroup does not stop at tile boundaries.  Requires E <= 256, K / BK >= ring depth, one tiling strategy;
+// fp8 scales are staged in LDS behind the rings (T + E floats).
+template <class C>
+__global__ __launch_bounds__(C::NT) void moe_gemm_stream_kernel(GemmArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int32_t* __restrict__ map = a.map;
+    const MapLayout L = map_layout(a.E);
+    const int lane = __lane_id();
+    TileStream ts;
+    const int4* recs = reinterpret_cast<const int4*>(map + L.off_records);
+#pragma unroll
+    for (int gi = 0; gi < TileStream::MAX_GROUPS; ++gi)
+        ts.rec[gi] = 64 * gi < L.E64 ? recs[64 * gi + lane] : make_int4(0x7fffffff, -1, 0, 0);
+    const int total = map[MOE_HDR_TOTAL_TILES];
+    const bool hdr_ok = map[MOE_HDR_MAGIC] == MOE_MAP_MAGIC && map[MOE_HDR_T] == a.T && map[MOE_HDR_K_TOP] == a.k &&
+                        map[MOE_HDR_E] == a.E && map[MOE_HDR_N] == a.N && map[MOE_HDR_TILE_M] == C::BM &&
+                        map[MOE_HDR_TILE_N] == C::BN && map[MOE_HDR_STATUS] == 0 && map[MOE_HDR_TILE_M_SMALL] == 0 &&
+                        map[MOE_HDR_SMALL_MAX_ROWS] == 0 && a.tile_m_small == 0 && a.small_max_rows == 0 &&
+                        map[MOE_HDR_TILE_M_SLACK] == 0 && a.tile_m_slack == 0;
+    if (!hdr_ok) return;
+    // each XCD owns one contiguous run of block indices (see locate_tile); its resident workgroups split it evenly
+    const int per_xcd = (total + 7) >> 3;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3, slots = gridDim.x >> 3;
+    const int x0 = xcd * per_xcd;
+    const int n_x = total - x0 < per_xcd ? total - x0 : per_xcd;
+    if (n_x <= 0) return;
+    const int per_wg = (n_x + slots - 1) / slots;
+    const int t0 = x0 + slot * per_wg;
+    int t1 = t0 + per_wg;
+    if (t1 > x0 + n_x) t1 = x0 + n_x;
+    if (t0 >= t1) return;
+    float* xs_lds = reinterpret_cast<float*>(smem + C::LDS_BYTES);
+    float* ws_lds = xs_lds + a.T;
+    if constexpr (C::FP8) {
+        for (int i = threadIdx.x; i < a.T; i += C::NT) xs_lds[i] = a.x_scale[i];
+        for (int i = threadIdx.x; i < a.E; i += C::NT) ws_lds[i] = a.w_scale[i];
+        __syncthreads();
+    }
+    ts.xs_lds = xs_lds;
+    ts.ws_lds = ws_lds;
+    ts.tiling = moe_tiling{C::BM, C::BN, 0, 0, 0, 0};
+    ts.next_B = t0 + 1;
+    ts.end_B = t1;
+    const TileCoord tc = decode_from_registers(ts, t0);
+    pipe_tile<C, true>(a, map, L, tc, smem, &ts);
+}
+
 }  // namespace moe

@@ -24,6 +24,8 @@ int check_map_args(int T, int k, int E, int tile_m, int tile_n, int N) {
     return MOE_OK;
 }
 
+int g_stream_mode = 0;  // set by moe_debug_streaming: 0 automatic, 1 never, 2 always, >= 8 always with that many workgroups
+
 int nchunks_for(int64_t R) { return (int)((R + kChunkRows - 1) / kChunkRows); }
 
 typedef int (*gemm_launch_fn)(const GemmArgs&, int64_t grid, hipStream_t);
@@ -38,6 +40,30 @@ int launch_pipe(const GemmArgs& a, int64_t grid, hipStream_t s) {
         attr_set = true;
     }
     moe_gemm_pipe_kernel<C, Tails...><<<dim3((unsigned)grid), dim3(C::NT), C::LDS_BYTES, s>>>(a);
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
+// Streaming launch: as many workgroups as stay resident at once (grid is only an upper bound here).
+template <class C>
+int launch_stream(const GemmArgs& a, int64_t grid, hipStream_t s) {
+    const int lds = C::LDS_BYTES + (C::FP8 ? 4 * (a.T + a.E) : 0);
+    static int lds_set = -1, resident = 0;
+    if (lds != lds_set) {
+        const void* fn = reinterpret_cast<const void*>(&moe_gemm_stream_kernel<C>);
+        int dev = 0, cus = 0, per_cu = 0;
+        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess ||
+            hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, C::NT, lds) != hipSuccess || per_cu < 1 || cus < 8)
+            return MOE_ERR_HIP;
+        resident = per_cu * cus / 8 * 8;
+        lds_set = lds;
+    }
+    // with fewer than two tiles per resident workgroup there is nothing to stream across: one workgroup per tile
+    if (g_stream_mode == 0 && grid < 2 * (int64_t)resident) return launch_pipe<C>(a, grid, s);
+    int64_t g = grid < resident ? grid : resident;
+    if (g_stream_mode >= 8 && g > g_stream_mode) g = g_stream_mode / 8 * 8;
+    moe_gemm_stream_kernel<C><<<dim3((unsigned)g), dim3(C::NT), lds, s>>>(a);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
@@ -61,6 +87,9 @@ struct GemmVariant {
     int tile_m_small = 0;  // second tiling strategy handled by the same launch (0 = none)
     int tile_m_slack = 0;  // rows the last m-tile may hold beyond tile_m
     int w_layout = MOE_W_LAYOUT_KN;
+    // the same tile as a streaming launch (resident workgroups run several tiles back to back), or nullptr
+    gemm_launch_fn fn_stream = nullptr;
+    int ring = 0;  // ring depth of the streaming kernel: it needs K / bk >= ring
 };
 
 // Pipelined bf16 kernels:  BM   BN   BK  WM WN  ring stages
@@ -110,11 +139,11 @@ const GemmVariant kVariants[] = {
     {MOE_DTYPE_BF16, 64, 128, 64, &launch_pipe<Pb_64x128>},
     {MOE_DTYPE_BF16, 32, 256, 64, &launch_pipe<Pb_32x256>},
     {MOE_DTYPE_BF16, 32, 128, 64, &launch_pipe<Pb_32x128>},
-    {MOE_DTYPE_BF16, 16, 256, 64, &launch_pipe<Pb_16x256>},
-    {MOE_DTYPE_BF16, 16, 128, 64, &launch_pipe<Pb_16x128>},
-    {MOE_DTYPE_FP8_E4M3, 16, 256, 128, &launch_pipe<P8_16x256>},
-    {MOE_DTYPE_FP8_E4M3, 16, 128, 128, &launch_pipe<P8_16x128>},
-    {MOE_DTYPE_FP8_E4M3, 16, 64, 128, &launch_pipe<P8_16x64>},
+    {MOE_DTYPE_BF16, 16, 256, 64, &launch_pipe<Pb_16x256>, 0, 0, MOE_W_LAYOUT_KN, &launch_stream<Pb_16x256>, Pb_16x256::NS},
+    {MOE_DTYPE_BF16, 16, 128, 64, &launch_pipe<Pb_16x128>, 0, 0, MOE_W_LAYOUT_KN, &launch_stream<Pb_16x128>, Pb_16x128::NS},
+    {MOE_DTYPE_FP8_E4M3, 16, 256, 128, &launch_pipe<P8_16x256>, 0, 0, MOE_W_LAYOUT_KN, &launch_stream<P8_16x256>, P8_16x256::NS},
+    {MOE_DTYPE_FP8_E4M3, 16, 128, 128, &launch_pipe<P8_16x128>, 0, 0, MOE_W_LAYOUT_KN, &launch_stream<P8_16x128>, P8_16x128::NS},
+    {MOE_DTYPE_FP8_E4M3, 16, 64, 128, &launch_pipe<P8_16x64>, 0, 0, MOE_W_LAYOUT_KN, &launch_stream<P8_16x64>, P8_16x64::NS},
     {MOE_DTYPE_FP8_E4M3, 32, 128, 128, &launch_pipe<P8_32x128>},
 };
 
@@ -322,7 +351,10 @@ int moe_grouped_gemm(const void* X, const void* W, const int32_t* topk_ids, cons
     grid = (grid + 7) / 8 * 8;
     if (grid == 0) return MOE_OK;
     if (grid > 0x7fffffff) return MOE_ERR_UNSUPPORTED;
-    return v->fn(a, grid, static_cast<hipStream_t>(stream));
+    // weight-streaming tiles: keep the workgroups resident and stream tile after tile where the shape allows it
+    const bool can_stream = v->fn_stream && d->E <= 256 && d->K / v->bk >= v->ring &&
+                            (d->dtype != MOE_DTYPE_FP8_E4M3 || d->T + d->E <= 2048) && g_stream_mode != 1;
+    return (can_stream ? v->fn_stream : v->fn)(a, grid, static_cast<hipStream_t>(stream));
 }
 
 int moe_combine(const void* Y, const float* topk_weights, int T, int k, int N, void* out, void* stream) {
@@ -346,6 +378,8 @@ int moe_combine(const void* Y, const float* topk_weights, int T, int k, int N, v
     }
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
+
+void moe_debug_streaming(int mode) { g_stream_mode = mode < 0 ? 0 : mode; }
 
 const char* moe_strerror(int code) {
     switch (code) {

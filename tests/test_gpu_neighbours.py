@@ -238,3 +238,56 @@ def test_nk_layout_unsupported_tiling_is_refused(dev):
     assert mb.moe_grouped_gemm(X, W, ids, tmap, Y, d, check=False) == mb.MOE_ERR_UNSUPPORTED
     d = mb.GemmDesc(mb.MOE_DTYPE_BF16, wl.T, wl.k, wl.E, wl.K, wl.N, 32, 128, w_layout=5)
     assert mb.moe_grouped_gemm(X, W, ids, tmap, Y, d, check=False) == mb.MOE_ERR_INVALID_ARG
+
+
+# ------------------------------------------------------------------ resident workgroups streaming tile after tile
+STREAM_CASES = [
+    # dtype, tile_n, T, E, k, K, N, routing, swiglu, workgroups
+    ("bf16", 128, 40, 16, 2, 256, 1024, "gauss_topk", False, 8),     # every workgroup runs a dozen tiles
+    ("bf16", 256, 100, 8, 2, 128, 1024, "zipf", False, 16),          # several m-tiles per expert
+    ("bf16", 128, 64, 256, 8, 256, 256, "gauss_topk", True, 24),     # four record groups, fused activation
+    ("fp8", 128, 32, 64, 6, 512, 512, "uniform_topk", False, 8),
+    ("fp8", 64, 8, 64, 6, 512, 256, "uniform_topk", False, 16),
+    ("fp8", 256, 32, 16, 2, 512, 1024, "zipf", True, 8),
+]
+
+
+@pytest.mark.parametrize("dtype,tile_n,T,E,k,K,N,routing,swiglu,wgs", STREAM_CASES)
+def test_streaming_kernel_parity(dev, oracle_mod, dtype, tile_n, T, E, k, K, N, routing, swiglu, wgs):
+    """16-row tiles with a handful of resident workgroups, so that each streams many tiles back to back; the
+    result must equal the oracle's and, bit for bit, the one-workgroup-per-tile launch."""
+    wl = wk.Workload("parity_stream", T, E, k, K, N, dtype, routing, 16, tile_n)
+    ids = wk.make_routing(wl)
+    xs = ws = None
+    if dtype == "fp8":
+        X, xs = wk.make_x(wl)
+        W, ws = wk.make_w(wl)
+        if swiglu:
+            ws = ws * 4.0
+    else:
+        X, W = wk.make_x(wl), wk.make_w(wl) * (4.0 if swiglu else 1.0)
+    outs = []
+    try:
+        for mode in (wgs, 1):
+            mb.moe_debug_streaming(mode)
+            if swiglu:
+                outs.append(_run_swiglu(dev, wl, ids, X, W, xs, ws))
+            else:
+                from tests.test_gpu_parity import _run_gemm
+                outs.append(_run_gemm(dev, wl, ids, X, W, xs, ws))
+    finally:
+        mb.moe_debug_streaming(0)
+    np.testing.assert_array_equal(outs[0], outs[1])
+    if dtype == "fp8":
+        res = oracle_mod.grouped_gemm_fp8(wk.bits(X), wk.bits(W), xs.numpy(), ws.numpy(), ids.numpy())
+        Xf = X.view(torch.float8_e4m3fn).double().numpy()
+        Wf = W.view(torch.float8_e4m3fn).double().numpy()
+        sx, sw = xs.double().numpy(), ws.double().numpy()
+    else:
+        res = oracle_mod.grouped_gemm_bf16(wk.bits(X), wk.bits(W), ids.numpy())
+        Xf, Wf, sx, sw = X.double().numpy(), W.double().numpy(), None, None
+    if swiglu:
+        _check_swiglu(oracle_mod, outs[0], res, Xf, Wf, ids.numpy(), k, K, sx, sw)
+    else:
+        from tests.test_gpu_parity import _check_y
+        _check_y(outs[0], res, Xf, Wf, ids.numpy(), k, K, H.tol_fp8(K) if dtype == "fp8" else H.tol_bf16(K), sx, sw)
