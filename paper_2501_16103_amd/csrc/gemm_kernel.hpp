@@ -280,10 +280,15 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
     // streaming: lane j < 16 holds the flat row id of tile row j (row 0's for j past the tile's rows) and the
     // token's scale; fetched through the scalar path and LDS so that no vector-memory wait is ever generated
     int rows_v = 0, rows_v_next = 0;
-    auto stream_rows = [&](const TileCoord& t, int& rv, uint32_t& dxo) {
+    i32x8_t srow_lo, srow_hi;   // a tile's 16 row ids on their way through the scalar path
+    auto stream_rows_issue = [&](const TileCoord& t) {
         const int32_t* p = map + L.off_rows + t.row_base;
-        i32x8_t lo = scalar_load8(p), hi = scalar_load8(p + 8);
-        scalar_wait(lo, hi);
+        srow_lo = scalar_load8(p);
+        srow_hi = scalar_load8(p + 8);
+    };
+    auto stream_rows_finish = [&](const TileCoord& t, int& rv, uint32_t& dxo) {
+        scalar_wait(srow_lo, srow_hi);
+        const i32x8_t lo = srow_lo, hi = srow_hi;
         int v = lo[0];
 #pragma unroll
         for (int j = 1; j < 16; ++j) v = (lane == j && j < t.rows) ? (j < 8 ? lo[j] : hi[j - 8]) : v;
@@ -294,7 +299,8 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
         dxo = (uint32_t)tok_of_row * (uint32_t)(a.K * ES) + ((pos ^ pswz_x<C>(row)) << 4);
     };
     if constexpr (STREAM) {
-        stream_rows(tc, rows_v, dx_off[0]);
+        stream_rows_issue(tc);
+        stream_rows_finish(tc, rows_v, dx_off[0]);
     } else {
 #pragma unroll
         for (int j = 0; j < XI; ++j) {
@@ -399,6 +405,7 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
         }
     };
 
+    TileCoord tc_next = tc;       // streaming: the tile after the current one
     int cur = 0, curw = 0;        // ring positions; they run on from tile to tile when streaming
     bool first = true;            // the rings are empty: fill them before the loop
     bool has_next = false;        // streaming: another tile follows, its first k-tiles are fetched by this tile's last iterations
@@ -471,6 +478,11 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
         };
         int kt = 0;
         for (; kt + NSW < KT; ++kt) iteration(kt, std::true_type{});
+        if constexpr (STREAM) {
+            // the following tile's row ids were requested before the loop: turn them into its token-row offsets
+            // now, just before the iterations that start fetching it
+            if (has_next) stream_rows_finish(tc_next, rows_v_next, dx_next);
+        }
         for (; kt < KT; ++kt) iteration(kt, std::false_type{});
     };
 
@@ -486,14 +498,13 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
 
     while (true) {
         const int n0 = tc.n_tile * BN;
-        TileCoord tc_next = tc;
         if constexpr (STREAM) {
             has_next = ts->next_B < ts->end_B;
             if (has_next) {
                 tc_next = decode_from_registers(*ts, ts->next_B);
                 ts->next_B += 1;
                 Wt_next = w_base(tc_next);
-                stream_rows(tc_next, rows_v_next, dx_next);
+                stream_rows_issue(tc_next);
             }
         }
 #pragma unroll
