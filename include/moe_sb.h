@@ -10,8 +10,8 @@
  *
  * General rules for every call
  *   - Pointers marked DEVICE are device memory owned by the caller; pointers
- *     marked HOST are host memory.  The library allocates nothing and keeps
- *     no state between calls.
+ *     marked HOST are host memory.  The library allocates nothing; the only state
+ *     it keeps is per-kernel launch attributes set on first use and the moe_debug_streaming mode.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls only enqueue work; they do not synchronise unless stated.
  *   - Return value: MOE_OK (0) or a negative MOE_ERR_* code.  Nothing is
@@ -58,7 +58,7 @@ enum { MOE_ORDER_ASCENDING = 0, MOE_ORDER_SPREAD = 1 };
  *   sigma        [E64]       non-empty index -> real expert (Sec. 4.1), ascending, pad -1
  *   tile_prefix  [E64]       inclusive prefix sum of tiles per non-empty expert
  *                            (Alg. 1, built over non-empty experts only, Sec. 4.1);
- *                            pad INT32_MAX (Sec. 3.1 allows "the maximum value")
+ *                            pad INT32_MAX (Sec. 3.1 allows padding with the largest value)
  *   task_records [E64][4]    the same map packed per non-empty task i, for a decode with one memory
  *                            round trip: {tile_prefix[i], sigma[i], counts[sigma[i]], offsets[sigma[i]]};
  *                            pads {INT32_MAX, -1, 0, 0}
@@ -119,12 +119,13 @@ size_t moe_task_map_bytes(int T_max, int k, int E, int tile_m, int tile_n, int N
 int64_t moe_grid_upper_bound(int T, int k, int E, int tile_m, int tile_n, int N);
 
 /*
- * Build the task map for one inference step (Sec. 4.1 "after the token route",
- * Alg. 1, Sec. 4.3 token index arrays).
+ * Build the task map for one inference step, i.e. once the routing of the step is known
+ * (Sec. 4.1; Alg. 1; Sec. 4.3 token index arrays).
  *   topk_ids  DEVICE int32 [T, k] row-major: expert chosen for token t, slot j.
  *   T >= 0 tokens (0 gives a valid empty map), 1 <= k <= E, 1 <= E <= 1024,
  *   T*k <= 2^24, tile_m in {16,32,64,128,256}, tile_n in {64,128,256}, N >= 1.
- *   task_map  DEVICE, >= moe_task_map_bytes(T,...) bytes, written entirely.
+ *   task_map  DEVICE, >= moe_task_map_bytes(T,...) bytes, written entirely.  The allocation must really be
+ *             that large: the kernels read a few words past sorted_rows (into the scratch part).
  * Deterministic: the same input gives the same bytes.  Ids outside [0,E) are
  * counted in header[MOE_HDR_STATUS] and force total_tiles = 0.
  */
@@ -132,9 +133,9 @@ int moe_build_task_map(const int32_t* topk_ids, int T, int k, int E, int tile_m,
                        void* task_map, void* stream);
 
 /*
- * Same, with the expert ordering of Sec. 4.2 made explicit.  The paper interleaves busy
- * (compute-bound) and non-busy (memory-bound) experts and reports that arranging the busy
- * experts "in a half-interval manner" works best, without giving the algorithm; here:
+ * Same, with the expert ordering of Sec. 4.2 made explicit.  The paper mixes busy
+ * (compute-bound) and idle (memory-bound) experts along the block order and finds a placement by repeated
+ * halving of the interval better than plain alternation, without giving the algorithm; here:
  *   MOE_ORDER_ASCENDING  sigma lists non-empty experts by increasing index (moe_build_task_map).
  *   MOE_ORDER_SPREAD     non-empty experts are ranked by tile count (largest first, ties by
  *                        lower index); rank r gets the key bitrev(r) over ceil(log2 M) bits;
@@ -149,8 +150,8 @@ int moe_build_task_map_ordered(const int32_t* topk_ids, int T, int k, int E, int
 
 /*
  * Same, with two tiling strategies in one batch (Alg. 3: tasks of different types / tiling
- * strategies dispatched inside one kernel; Sec. 4: "GEMMs with large input and output sizes prefer
- * large tiles").  The paper gives neither shapes nor thresholds; here an expert with at most
+ * strategies dispatched inside one kernel; Sec. 4: large GEMMs are better served by large tiles).
+ * The paper gives neither shapes nor thresholds; here an expert with at most
  * small_max_rows rows is tiled with tile_m_small rows per tile, every other expert with tile_m:
  *     nu(e) = ceil(counts[e] / tile_m(e)) * ceil(N / tile_n).
  * tile_m_small in {16,32,64,128}, tile_m_small < tile_m, 1 <= small_max_rows <= 4*tile_m_small;

@@ -22,7 +22,7 @@
  *     remainder of a few rows never gets a tile to itself.  Tile m still starts at row
  *     m * tile_m of the expert's segment.  tile_m_slack = 0 is the plain ceil(c / tile_m).
  *   - sigma lists the non-empty experts in ascending expert index (Sec. 4.1), or, with
- *     order = 1, "spread" in the half-interval manner of Sec. 4.2: the non-empty experts
+ *     order = 1, spread out by repeated halving (our reading of the better of the two arrangements of Sec. 4.2): the non-empty experts
  *     are ranked by tile count (largest first, ties by lower index), rank r gets the key
  *     bitrev(r) over ceil(log2 M) bits, and sigma lists them by increasing key -- the
  *     busiest expert first, the second busiest in the middle, the next two at the
@@ -189,7 +189,7 @@ static int bit_reverse(int r, int nbits) {
     return v;
 }
 
-/* Sec. 4.2 "half-interval" order (reading stated at the top of this file).
+/* Sec. 4.2 order by repeated halving (reading stated at the top of this file).
  * experts[0..M) ascending non-empty experts with tile counts nu[0..M): writes sigma[0..M). */
 static void spread_order(const int32_t* experts, const int32_t* nu, int M, int32_t* sigma) {
     int nbits = 0;
@@ -457,7 +457,7 @@ void orc_norm_scale_elements(const void* X, const void* W, const float* x_scale,
 /* ---------------------------------------------------------------- neighbours of the product */
 
 /* Gated activation of an expert whose weight holds the gate projection in columns [0, N/2) and the up
- * projection in [N/2, N) (the "fused gate+up projection" of the benchmark shapes; the paper's MoE layer,
+ * projection in [N/2, N) (the fused gate and up projection of the benchmark shapes; the paper's MoE layer,
  * Sec. 2.2, leaves the expert's internals open):
  *     H[r, i] = silu(G) * U,  G = Y[r, i], U = Y[r, N/2 + i],  silu(g) = g / (1 + exp(-g)),
  * from the fp64 sums Y64 [nrows, N] of orc_grouped_gemm_*.  Outputs [nrows, N/2]: H64, and Hbf = one

@@ -1,4 +1,4 @@
-// Sum over a token's selected experts (Sec. 2.2: the MoE layer "finally sums them up"), optionally weighted
+// Sum over a token's selected experts (Sec. 2.2: the last step of the MoE layer), optionally weighted
 // by the router: out[t, n] = bf16( sum_j w[t, j] * Y[t, j, n] ), j ascending, fp32.
 // Pure streaming: each lane owns 8 consecutive n of one token (16-byte loads and stores).
 #pragma once

@@ -153,7 +153,7 @@ __device__ __forceinline__ int bit_reverse(int r, int nbits) { return nbits ? (i
 
 // From the per-expert count held by thread e (< E64; 0 beyond E): write counts, offsets,
 // sigma, tile_prefix and the header.  Executed by all kMapThreads threads of one block.
-// order 0: sigma ascending in expert index.  order 1 ("spread", the half-interval placement of
+// order 0: sigma ascending in expert index.  order 1 (spread, our reading of the interval-halving placement of
 // Sec. 4.2): non-empty experts ranked by tile count (largest first, ties by lower index), rank r
 // keyed by bitrev(r) over ceil(log2 M) bits, sigma by increasing key.
 // s_work: >= 2*E64 ints of LDS.  Returns this thread's exclusive row offset (valid for tid < E).
