@@ -97,7 +97,7 @@ def _check_elements(oracle_mod, wl, ids, X, W, xs, ws, Y, rr, nn):
     scale = np.linalg.norm(Xf, axis=1) * np.linalg.norm(Wf, axis=1) * sc
     assert np.all(err <= tol * scale), f"max err/scale {(err / scale).max():.3e} > {tol:.3e}"
     A = (np.abs(Xf) * np.abs(Wf)).sum(axis=1) * sc
-    tight = 2.0 ** -8 * np.abs(want) * 1.001 + 1.01 * wl.K * 2.0 ** -24 * A + 1e-30
+    tight = 2.0 ** -8 * np.abs(want) * 1.001 + H.sum_err_coeff(wl.K, wl.dtype == "fp8") * A + 1e-30
     assert np.all(err <= tight), f"max err/tight {(err / tight).max():.3f}"
     want_bits = np.array([oracle_mod.f64_to_bf16_rne(float(v)) for v in want], dtype=np.uint16)
     assert (H.ulp_distance(got_bits, want_bits) == 0).mean() > 0.97

@@ -54,7 +54,7 @@ def _check_swiglu(oracle_mod, got_bits, res, Xf, Wf, ids, k, K, xs=None, ws=None
     A = np.stack([np.abs(Xf[xi[r]]) @ np.abs(Wf[flat[r]]) for r in range(len(flat))])     # sum |x||w| per (row, n)
     if xs is not None:
         A = A * (xs[xi][:, None] * ws[flat][:, None])
-    eps = 1.01 * K * 2.0 ** -24 * A + 4 * 2.0 ** -24 * np.abs(res.Y64)     # fp32 sums in any order (+ the two scale products)
+    eps = H.sum_err_coeff(K, xs is not None) * A + 4 * 2.0 ** -24 * np.abs(res.Y64)     # fp32 sums in any order (+ the two scale products)
     g, u = res.Y64[:, :I], res.Y64[:, I:]
     silu = g / (1.0 + np.exp(-g))
     # |d silu / dg| <= 1.1; exp, division and the product in fp32 add a few 2^-24 relative; one bf16 rounding

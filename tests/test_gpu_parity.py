@@ -172,7 +172,7 @@ def _check_y(got_bits, res, Xf, Wf, ids, k, K, tol, xs=None, ws=None):
     A = np.stack([np.abs(Xf[xi[r]]) @ np.abs(Wf[flat[r]]) for r in range(len(flat))])
     if xs is not None:
         A = A * (xs[xi][:, None] * ws[flat][:, None])
-    tight = 2.0 ** -8 * np.abs(res.Y64) * 1.001 + 1.01 * K * 2.0 ** -24 * A + 1e-30
+    tight = 2.0 ** -8 * np.abs(res.Y64) * 1.001 + H.sum_err_coeff(K, xs is not None) * A + 1e-30
     assert np.all(err <= tight), f"max err/tight = {(err / tight).max():.3f}"
     # and nearly every stored value is bit-identical to the oracle's single-rounded bf16
     ulp = H.ulp_distance(got_bits, res.Ybf)
