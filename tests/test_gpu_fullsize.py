@@ -166,3 +166,69 @@ def test_fine_grained_full_size_sampled(oracle_mod):
     table = oracle_mod.full_table(tm.counts, wl.tile_m, wl.tile_n, wl.N)
     rr, nn = _sample_points(tm, table, rng, 2)
     _check_elements(oracle_mod, wl, ids, X, W, xs, ws, Y, rr, nn)
+
+
+def test_fine_grained_T8192_full_size_sampled(oracle_mod):
+    """E=256, top-8, T=8192: 256-row tiles with slack rows (about one tile per expert), 2 samples per tile."""
+    wl = wk.fine_grained(8192)
+    assert wl.tile_m_slack > 0
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(12)
+    ids, X, W, xs, ws, Y, tmap = _run_full(wl, dev)
+    tm = oracle_mod.build_task_map(ids.numpy(), wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N, tile_m_slack=wl.tile_m_slack)
+    want = H.expected_blob(tm)
+    np.testing.assert_array_equal(tmap.cpu().numpy()[: len(want)], want)
+    table = oracle_mod.full_table(tm.counts, wl.tile_m, wl.tile_n, wl.N, tile_m_slack=wl.tile_m_slack)
+    assert table[:, 3].max() > wl.tile_m, "the point must exercise the slack rows"
+    rr, nn = _sample_points(tm, table, rng, 2)
+    _check_elements(oracle_mod, wl, ids, X, W, xs, ws, Y, rr, nn)
+
+
+def test_headline_with_fused_activation_sampled(oracle_mod):
+    """The headline shape with the gated activation fused into the epilogue: 4 samples in every tile."""
+    wl = wk.mixtral_up(4096)
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(13)
+    ids = wk.make_routing(wl)
+    X = wk.make_x(wl, dev)
+    W = wk.make_w(wl, dev)
+    W.mul_(4.0)   # gates of a few units
+    I = wl.N // 2
+    pad = 2
+    buf = torch.empty((wl.R + 2 * pad, I), dtype=torch.int16, device=dev)
+    buf.fill_(POISON)
+    Y = buf[pad: pad + wl.R]
+    tmap = mb.alloc_task_map(wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N, dev)
+    mb.moe_build_task_map_ex(ids.to(dev), wl.T, wl.k, wl.E, wl.N, mb.Tiling(wl.tile_m, wl.tile_n, 0, 0, 0, wl.tile_m_slack), tmap)
+    mb.moe_grouped_gemm(X, W, ids.to(dev), tmap, Y,
+                        mb.GemmDesc(mb.MOE_DTYPE_BF16, wl.T, wl.k, wl.E, wl.K, wl.N, wl.tile_m, wl.tile_n,
+                                    tile_m_slack=wl.tile_m_slack, epilogue=mb.MOE_EPILOGUE_SWIGLU))
+    torch.cuda.synchronize()
+    assert bool((buf[:pad] == POISON).all()) and bool((buf[pad + wl.R:] == POISON).all()), "wrote outside Y"
+    assert not bool((Y == POISON).any()), "some output was never written"
+    tm = oracle_mod.build_task_map(ids.numpy(), wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N, tile_m_slack=wl.tile_m_slack)
+    table = oracle_mod.full_table(tm.counts, wl.tile_m, wl.tile_n, wl.N, tile_m_slack=wl.tile_m_slack)
+    rr, nn = _sample_points(tm, table, rng, 4)      # nn: weight columns of the tile; the tile's outputs are half as many
+    out_col = (nn // wl.tile_n) * (wl.tile_n // 2) + (nn % wl.tile_n) // 2
+    flat = ids.numpy().reshape(-1)
+    toks, exps = rr // wl.k, flat[rr]
+    Xs = X[torch.as_tensor(toks, dtype=torch.long, device=dev)].cpu()
+    S = len(rr)
+    ids_c = np.arange(S, dtype=np.int32).reshape(S, 1)
+    sel, zero = np.arange(S, dtype=np.int32), np.zeros(S, dtype=np.int32)
+    vals, absum = [], []
+    for cols in (out_col, out_col + I):             # gate column, up column
+        Wc = _gather_columns(W, exps, cols)
+        vals.append(oracle_mod.gemm_elements(wk.bits(Xs), wk.bits(Wc).reshape(S, wl.K, 1), ids_c, 1, sel, zero))
+        absum.append((np.abs(Xs.double().numpy()) * np.abs(Wc.double().numpy())).sum(axis=1))
+    H64, Hbf = oracle_mod.swiglu(np.stack(vals, axis=1))
+    H64, Hbf = H64[:, 0], Hbf[:, 0]
+    got_bits = H.y_bits(Y[torch.as_tensor(rr, dtype=torch.long, device=dev), torch.as_tensor(out_col, dtype=torch.long, device=dev)])
+    got = H.bf16_bits_to_f64(got_bits)
+    g, u = vals
+    eps_g, eps_u = (H.sum_err_coeff(wl.K, False) * a for a in absum)
+    silu = g / (1.0 + np.exp(-g))
+    tight = 2.0 ** -8 * np.abs(H64) * 1.001 + 1.1 * eps_g * np.abs(u) + np.abs(silu) * eps_u + 4e-6 * np.abs(H64) + 1e-30
+    err = np.abs(got - H64)
+    assert np.all(err <= tight), f"max err/tight {(err / tight).max():.3f}"
+    assert (H.ulp_distance(got_bits, Hbf) == 0).mean() > 0.95
