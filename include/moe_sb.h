@@ -190,6 +190,18 @@ typedef struct moe_tiling {
 int moe_build_task_map_ex(const int32_t* topk_ids, int T, int k, int E, int N, const moe_tiling* tiling,
                           void* task_map, void* stream);
 
+/*
+ * A reasonable tiling for a problem shape, from the measurements behind this library (HOST, pure; the routing
+ * itself is not known to the host, so the choice goes by the mean rows per expert T*k/E):
+ *   fp8 (the decode regime): 16-row tiles, 256 wide when that gives between one and two workgroups per CU, else 128;
+ *   bf16: up to 24 rows per expert 16 x 256; up to 160 rows 128 x 256 when there are enough n-tiles to fill the
+ *   chip three times over, else 64 x 256; above that 256 x 256 with 64 slack rows.
+ * Always ascending order, one strategy.  The result satisfies moe_tiling_supported when N % tile_n == 0 allows
+ * it (tile_n falls back to 128 or 64).  Returns MOE_ERR_INVALID_ARG on bad arguments, MOE_ERR_UNSUPPORTED when
+ * no kernel fits (N not a multiple of 64).
+ */
+int moe_default_tiling(int dtype, int T, int k, int E, int K, int N, moe_tiling* out);
+
 /* 1 if moe_grouped_gemm has a kernel for this dtype and tiling (order is ignored), else 0. HOST, pure. */
 int moe_tiling_supported(int dtype, const moe_tiling* tiling);
 

@@ -41,7 +41,7 @@ EXPORTS = [
     "moe_map_off_counts", "moe_map_off_offsets", "moe_map_off_sigma", "moe_map_off_tile_prefix",
     "moe_map_off_task_records", "moe_map_off_sorted_rows", "moe_task_map_bytes", "moe_grid_upper_bound", "moe_build_task_map",
     "moe_build_task_map_ordered", "moe_build_task_map_tiled", "moe_grid_upper_bound_tiled", "moe_tile_pair_supported",
-    "moe_build_task_map_ex", "moe_tiling_supported", "moe_w_layout_supported",
+    "moe_build_task_map_ex", "moe_tiling_supported", "moe_w_layout_supported", "moe_default_tiling",
     "moe_task_map_status", "moe_task_map_expand", "moe_grouped_gemm", "moe_tile_supported", "moe_combine",
     "moe_debug_streaming", "moe_strerror",
 ]
@@ -100,6 +100,8 @@ def lib() -> ctypes.CDLL:
                                                                                       ctypes.c_void_p, ctypes.c_void_p]
         L.moe_tiling_supported.restype = ctypes.c_int
         L.moe_tiling_supported.argtypes = [ctypes.c_int, ctypes.POINTER(moe_tiling)]
+        L.moe_default_tiling.restype = ctypes.c_int
+        L.moe_default_tiling.argtypes = [ctypes.c_int] * 6 + [ctypes.POINTER(moe_tiling)]
         L.moe_w_layout_supported.restype = ctypes.c_int
         L.moe_w_layout_supported.argtypes = [ctypes.c_int, ctypes.POINTER(moe_tiling), ctypes.c_int]
         L.moe_task_map_status.restype = ctypes.c_int
@@ -220,6 +222,14 @@ def moe_build_task_map_ex(topk_ids: torch.Tensor, T: int, k: int, E: int, N: int
 def moe_tiling_supported(dtype: int, tiling: Tiling) -> bool:
     g = tiling.c_struct()
     return bool(lib().moe_tiling_supported(dtype, ctypes.byref(g)))
+
+
+def moe_default_tiling(dtype: int, T: int, k: int, E: int, K: int, N: int) -> Tiling:
+    g = moe_tiling()
+    rc = lib().moe_default_tiling(dtype, T, k, E, K, N, ctypes.byref(g))
+    if rc != MOE_OK:
+        raise MoeError(rc, "moe_default_tiling")
+    return Tiling(g.tile_m, g.tile_n, g.order, g.tile_m_small, g.small_max_rows, g.tile_m_slack)
 
 
 def moe_w_layout_supported(dtype: int, tiling: Tiling, w_layout: int) -> bool:

@@ -1,6 +1,7 @@
 // C-ABI entry points of libmoe_sb: argument checks, launch geometry, kernel selection.
 // Everything that computes lives in task_map.hpp / gemm_kernel.hpp.
 #include <hip/hip_runtime.h>
+#include <math.h>
 #include <stdint.h>
 #include <type_traits>
 
@@ -231,6 +232,44 @@ int moe_build_task_map_tiled(const int32_t* topk_ids, int T, int k, int E, int t
                              int tile_m_small, int small_max_rows, void* task_map, void* stream) {
     const moe_tiling g = {tile_m, tile_n, order, tile_m_small, small_max_rows, 0};
     return moe_build_task_map_ex(topk_ids, T, k, E, N, &g, task_map, stream);
+}
+
+int moe_default_tiling(int dtype, int T, int k, int E, int K, int N, moe_tiling* out) {
+    if (!out || T < 0 || k < 1 || E < 1 || k > E || K < 1 || N < 1) return MOE_ERR_INVALID_ARG;
+    if (dtype != MOE_DTYPE_BF16 && dtype != MOE_DTYPE_FP8_E4M3) return MOE_ERR_INVALID_ARG;
+    const int64_t R = (int64_t)T * k;
+    const double mean_rows = (double)R / E;
+    const int64_t active = R < E ? R : E;   // experts that can have rows at all
+    const int cus = 256;
+    moe_tiling g = {16, 128, MOE_ORDER_ASCENDING, 0, 0, 0};
+    if (dtype == MOE_DTYPE_FP8_E4M3) {
+        // expected tiles under a uniform routing: E * (1 - (1 - 1/E)^R) experts are hit, plus full extra m-tiles
+        const double hit = E * (1.0 - pow(1.0 - 1.0 / E, (double)R));
+        const double t256 = (hit + (double)(R / 16)) * ((N + 255) / 256);
+        g.tile_m = 16;
+        g.tile_n = (N % 256 == 0 && t256 >= cus && t256 <= 2 * cus) ? 256 : 128;
+    } else if (mean_rows <= 24) {
+        g.tile_m = 16; g.tile_n = 256;
+    } else if (mean_rows <= 160) {
+        g.tile_m = active * ((N + 255) / 256) >= 3 * cus ? 128 : 64;
+        g.tile_n = 256;
+    } else {
+        g.tile_m = 256; g.tile_n = 256; g.tile_m_slack = 64;
+    }
+    // the n-tile must divide N; narrower tiles keep the same row tiling where a kernel exists
+    for (int tn = g.tile_n; tn >= 64; tn >>= 1) {
+        if (N % tn != 0) continue;
+        moe_tiling c = g;
+        c.tile_n = tn;
+        if (find_variant(dtype, c.tile_m, c.tile_n, 0, c.tile_m_slack)) { *out = c; return MOE_OK; }
+        c.tile_m_slack = 0;
+        if (find_variant(dtype, c.tile_m, c.tile_n, 0, 0)) { *out = c; return MOE_OK; }
+        for (int tm : {128, 64, 32, 16}) {
+            c.tile_m = tm;
+            if (tm <= g.tile_m && find_variant(dtype, tm, tn, 0, 0)) { *out = c; return MOE_OK; }
+        }
+    }
+    return MOE_ERR_UNSUPPORTED;
 }
 
 int moe_tiling_supported(int dtype, const moe_tiling* g) {

@@ -78,3 +78,23 @@ def test_null_arguments_rejected_on_host():
     assert lib.moe_task_map_status(None, None) == mb.MOE_ERR_INVALID_ARG
     assert lib.moe_grouped_gemm(None, None, None, None, None, None, None) == mb.MOE_ERR_INVALID_ARG
     assert lib.moe_task_map_expand(None, 8, None, 0, None) == mb.MOE_ERR_INVALID_ARG
+
+
+def test_default_tiling_is_supported_and_matches_the_benchmark_choices():
+    """Host-only: the heuristic returns a tiling a kernel exists for, and reproduces the tilings the benchmark
+    points were tuned to (slack rows aside, where the heuristic always enables them for 256-row tiles)."""
+    from paper_2501_16103_amd import workloads as wk
+    pts = [wk.mixtral_up(T) for T in (16, 256, 4096)] + [wk.mixtral_down_zipf(T) for T in (256, 4096)]
+    pts += [wk.fine_grained(T) for T in (128, 2048, 8192)] + [wk.decode_fp8(T) for T in (1, 8, 32)] + [wk.paper_eval("worst")]
+    for w in pts:
+        dt = mb.MOE_DTYPE_FP8_E4M3 if w.dtype == "fp8" else mb.MOE_DTYPE_BF16
+        g = mb.moe_default_tiling(dt, w.T, w.k, w.E, w.K, w.N)
+        assert mb.moe_tiling_supported(dt, g)
+        assert (g.tile_m, g.tile_n) == (w.tile_m, w.tile_n), (w.name, w.T)
+    # N that only 64-wide tiles divide, and one nothing divides
+    g = mb.moe_default_tiling(mb.MOE_DTYPE_FP8_E4M3, 8, 2, 16, 256, 192)
+    assert (g.tile_m, g.tile_n) == (16, 64) and mb.moe_tiling_supported(mb.MOE_DTYPE_FP8_E4M3, g)
+    with pytest.raises(mb.MoeError):
+        mb.moe_default_tiling(mb.MOE_DTYPE_BF16, 8, 2, 16, 256, 100)
+    with pytest.raises(mb.MoeError):
+        mb.moe_default_tiling(mb.MOE_DTYPE_BF16, 8, 20, 16, 256, 128)
