@@ -227,6 +227,13 @@ def main():
                     help="tile_m_small,small_max_rows: second tiling strategy for the extra points with 256x256 tiles")
     ap.add_argument("--slack", type=int, default=-1, help="override tile_m_slack of every workload (0 = plain ceil tiling)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--operand-fill", default="", choices=["", "zeros", "ones"],
+                    help="measurement aid: ALSO time the headline launch with X and W overwritten by a constant (the "
+                         "kernel's duration depends on the operand values through the chip's power management); "
+                         "reported under 'operand_fill', never as the headline")
+    ap.add_argument("--dense-reference", action="store_true",
+                    help="also time the tensor library's dense bf16 matmul of the same size and weight layout "
+                         "([T*k, K] x [K, N]) on random data; reported under 'dense_reference'")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (a kernel of known traffic to scale profiler byte counters by)")
     args = ap.parse_args()
@@ -269,6 +276,35 @@ def main():
         del src, dst
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(pt)
+    if args.operand_fill:
+        # same map, same launch, constant operands: separates what the instruction stream costs from what the data costs
+        v = 0.0 if args.operand_fill == "zeros" else 1.0
+        keep = (pt.X.clone(), pt.W[0].clone())
+        pt.X.fill_(v)
+        pt.W[0].fill_(v)
+        _, g_ms, _ = pt.time(args.steps, args.warmup)
+        pt.X.copy_(keep[0])
+        pt.W[0].copy_(keep[1])
+        del keep
+        out["operand_fill"] = {"fill": args.operand_fill, "kernel_ms": round(g_ms, 4),
+                               "tflops": round(wl.flops / (g_ms * 1e-3) / 1e12, 2),
+                               "random_kernel_ms": head["gemm_ms"]}
+    if args.dense_reference:
+        A = torch.randn((wl.R, wl.K), device="cuda:0").to(torch.bfloat16)
+        B = torch.randn((wl.K, wl.N), device="cuda:0").to(torch.bfloat16)
+        for _ in range(3):
+            C = A @ B
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        torch.cuda.synchronize()
+        ev[0].record()
+        for _ in range(10):
+            C = A @ B
+        ev[1].record()
+        torch.cuda.synchronize()
+        d_ms = ev[0].elapsed_time(ev[1]) / 10
+        del A, B, C
+        out["dense_reference"] = {"what": f"torch.matmul bf16 [{wl.R},{wl.K}] x [{wl.K},{wl.N}] row-major, random data",
+                                  "ms": round(d_ms, 4), "tflops": round(wl.flops / (d_ms * 1e-3) / 1e12, 2)}
     del pt
     torch.cuda.empty_cache()
 
