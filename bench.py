@@ -137,7 +137,7 @@ class Point:
                     frac_hbm=round(gbs / PEAK_HBM_GBS, 4), bound=bound, alg_bytes=abytes, flops=wl.flops)
 
 
-def cpu_baseline(pt: Point, target_s: float = 15.0) -> dict:
+def cpu_baseline(pt: Point, target_s: float = 30.0) -> dict:
     """Time the CPU oracle (as it stands) on a bounded sample of complete routed rows of the same
     workload, and check the GPU output on those rows against it."""
     import oracle
@@ -148,7 +148,7 @@ def cpu_baseline(pt: Point, target_s: float = 15.0) -> dict:
     ids_h = pt.ids_cpu.numpy()
     # the oracle reads one expert's weights per row: copy to the host only the experts sampled
     n_probe = 8
-    rows = rng.choice(wl.R, size=min(wl.R, 2048), replace=False).astype(np.int32)
+    rows = rng.choice(wl.R, size=min(wl.R, 4096), replace=False).astype(np.int32)
     experts = sorted(set(int(ids_h.reshape(-1)[r]) for r in rows))
     remap = {e: i for i, e in enumerate(experts)}
     Wh = np.stack([wk.bits(pt.W[0][e]) for e in experts])
