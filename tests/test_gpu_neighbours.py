@@ -291,3 +291,48 @@ def test_streaming_kernel_parity(dev, oracle_mod, dtype, tile_n, T, E, k, K, N, 
     else:
         from tests.test_gpu_parity import _check_y
         _check_y(outs[0], res, Xf, Wf, ids.numpy(), k, K, H.tol_fp8(K) if dtype == "fp8" else H.tol_bf16(K), sx, sw)
+
+
+# ------------------------------------------------------------------ the whole step inside a HIP graph
+def test_step_captured_in_a_graph_replays_exactly(dev):
+    """Map build + grouped GEMM + combine captured once and replayed with new inputs: every replay must equal the
+    eager result bit for bit (the library enqueues kernels only: no memset nodes, no host synchronisation)."""
+    wl = wk.decode_fp8(32)
+    T, k, E, K, N = wl.T, wl.k, wl.E, wl.K, wl.N
+    X, xs = wk.make_x(wl, dev)
+    W, ws = wk.make_w(wl, dev)
+    ids = wk.make_routing(wl).to(dev)
+    wts = torch.rand((T, k), device=dev, dtype=torch.float32)
+    tmap = mb.alloc_task_map(T, k, E, wl.tile_m, wl.tile_n, N)
+    Y = torch.empty((T * k, N), dtype=torch.bfloat16, device=dev)
+    out = torch.empty((T, N), dtype=torch.bfloat16, device=dev)
+    desc = mb.GemmDesc(mb.MOE_DTYPE_FP8_E4M3, T, k, E, K, N, wl.tile_m, wl.tile_n, xs, ws)
+
+    def step():
+        mb.moe_build_task_map(ids, T, k, E, wl.tile_m, wl.tile_n, N, tmap)
+        mb.moe_grouped_gemm(X, W, ids, tmap, Y, desc)
+        mb.moe_combine(Y, wts, T, k, N, out)
+
+    step()                      # first call sets the kernels' launch attributes: not a thing to capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    g = torch.Generator(device=dev).manual_seed(5)
+    for it in range(4):
+        # new tokens and a new routing in the same buffers, eager work and synchronisations between the replays
+        X.copy_(torch.randint(0, 120, X.shape, generator=g, device=dev, dtype=torch.uint8).view(X.dtype))
+        ids.copy_(torch.stack([torch.randperm(E, generator=g, device=dev)[:k] for _ in range(T)]).to(torch.int32))
+        step()
+        torch.cuda.synchronize()
+        want_Y, want_out = Y.clone(), out.clone()
+        Y.fill_(float("nan"))
+        out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Y.view(torch.int16), want_Y.view(torch.int16)), f"replay {it}: Y differs"
+        assert torch.equal(out.view(torch.int16), want_out.view(torch.int16)), f"replay {it}: combine differs"
