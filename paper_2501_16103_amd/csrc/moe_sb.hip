@@ -312,17 +312,16 @@ int moe_build_task_map_ex(const int32_t* topk_ids, int T, int k, int E, int N, c
         int32_t* chunk_hist = map + L.off_rows + round_up64((size_t)R);
         const int hs = hist_stride(L.E64);
         map_hist<<<nchunks, 256, hs * sizeof(int), s>>>(topk_ids, (int)R, E, L.E64, chunk_hist);
-        map_scan<<<1, kMapThreads, 0, s>>>(map, chunk_hist, nchunks, T, k, E, N, g);
         static bool attr_set2 = false;
         if (!attr_set2) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&map_scatter),
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&map_scan_scatter),
                                     hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)((size_t)kWaves * kMaxE * sizeof(int))) != hipSuccess)
+                                    (int)(((size_t)kWaves * kMaxE + kMaxE) * sizeof(int))) != hipSuccess)
                 return MOE_ERR_HIP;
             attr_set2 = true;
         }
-        map_scatter<<<nchunks, kMapThreads, (size_t)kWaves * L.E64 * sizeof(int), s>>>(topk_ids, map, chunk_hist,
-                                                                                      (int)R, E);
+        map_scan_scatter<<<nchunks, kMapThreads, ((size_t)kWaves * L.E64 + L.E64) * sizeof(int), s>>>(
+            topk_ids, map, chunk_hist, nchunks, T, k, E, N, g);
     }
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }

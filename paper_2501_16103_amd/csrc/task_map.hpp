@@ -158,7 +158,7 @@ __device__ __forceinline__ int bit_reverse(int r, int nbits) { return nbits ? (i
 // keyed by bitrev(r) over ceil(log2 M) bits, sigma by increasing key.
 // s_work: >= 2*E64 ints of LDS.  Returns this thread's exclusive row offset (valid for tid < E).
 __device__ __forceinline__ int finish_map(int32_t* __restrict__ map, const MapLayout& L, int cnt, int bad, int T, int k,
-                                          int E, int N, const moe_tiling& g, int* s_tmp, int* s_work) {
+                                          int E, int N, const moe_tiling& g, int* s_tmp, int* s_work, bool write = true) {
     const int tid = threadIdx.x;
     const int R = T * k;
     const int nt = (N + g.tile_n - 1) / g.tile_n;
@@ -192,29 +192,36 @@ __device__ __forceinline__ int finish_map(int32_t* __restrict__ map, const MapLa
             for (int j = 0; j < L.E64; ++j) pos += s_work[L.E64 + j] < key;
         __syncthreads();
     }
+    // `write` is false for the workgroups that only need the returned offsets (every scatter workgroup repeats
+    // this function; the first one stores its results)
     if (tid < L.E64) {
-        map[L.off_counts + tid] = cnt;
-        map[L.off_sigma + tid] = -1;
-        map[L.off_records + 4 * tid + 1] = -1;
-        map[L.off_records + 4 * tid + 2] = 0;
-        map[L.off_records + 4 * tid + 3] = 0;
+        if (write) {
+            map[L.off_counts + tid] = cnt;
+            map[L.off_sigma + tid] = -1;
+            map[L.off_records + 4 * tid + 1] = -1;
+            map[L.off_records + 4 * tid + 2] = 0;
+            map[L.off_records + 4 * tid + 3] = 0;
+        }
         s_work[tid] = 0;
     }
-    for (int i = tid; i < L.E64 + 64; i += kMapThreads) map[L.off_offsets + i] = i <= E ? 0 : R;
+    if (write)
+        for (int i = tid; i < L.E64 + 64; i += kMapThreads) map[L.off_offsets + i] = i <= E ? 0 : R;
     __syncthreads();
-    if (tid < E) map[L.off_offsets + tid] = off_incl - cnt;
-    if (tid == 0) map[L.off_offsets + E] = R - bad;
+    if (write && tid < E) map[L.off_offsets + tid] = off_incl - cnt;
+    if (write && tid == 0) map[L.off_offsets + E] = R - bad;
     if (nonempty) {
-        map[L.off_sigma + pos] = tid;
-        map[L.off_records + 4 * pos + 1] = tid;
-        map[L.off_records + 4 * pos + 2] = cnt;
-        map[L.off_records + 4 * pos + 3] = off_incl - cnt;
+        if (write) {
+            map[L.off_sigma + pos] = tid;
+            map[L.off_records + 4 * pos + 1] = tid;
+            map[L.off_records + 4 * pos + 2] = cnt;
+            map[L.off_records + 4 * pos + 3] = off_incl - cnt;
+        }
         s_work[pos] = tiles;
     }
     __syncthreads();
     // Alg. 1 over the non-empty experts in sigma order
     const int tile_incl = block_incl_scan(tid < M ? s_work[tid] : 0, s_tmp);
-    if (tid < L.E64) {
+    if (write && tid < L.E64) {
         map[L.off_prefix + tid] = tid < M ? tile_incl : 0x7fffffff;
         map[L.off_records + 4 * tid] = tid < M ? tile_incl : 0x7fffffff;
     }
@@ -245,7 +252,7 @@ __device__ __forceinline__ int finish_map(int32_t* __restrict__ map, const MapLa
             case MOE_HDR_TILE_M_SLACK: v = g.tile_m_slack; break;
             default: v = 0;
         }
-        map[tid] = v;
+        if (write) map[tid] = v;
     }
     return off_incl - cnt;
 }
@@ -314,41 +321,23 @@ __global__ __launch_bounds__(256) void map_hist(const int32_t* __restrict__ ids,
     for (int i = threadIdx.x; i < hs; i += 256) chunk_hist[(size_t)blockIdx.x * hs + i] = s_mem[i];
 }
 
-// Step 2 (one workgroup): turn the chunk histograms into per-chunk exclusive bases,
-// then counts / offsets / sigma / TilePrefix / header.
-__global__ __launch_bounds__(kMapThreads) void map_scan(int32_t* __restrict__ map, int32_t* __restrict__ chunk_hist,
-                                                        int nchunks, int T, int k, int E, int N, moe_tiling g) {
+// Multi-chunk path, step 2: every workgroup turns the chunk histograms into counts, offsets and its own chunk's
+// bases (plain loads, no stores in between, so they pipeline), the first one also writes counts / offsets /
+// sigma / TilePrefix / task records / header; then each scatters its chunk of rows, stably, into the token
+// index arrays.  Repeating the scans in every workgroup costs less than a third kernel launch.
+// Dynamic LDS: kWaves * E64 ints (per-wavefront counts) + E64 ints (this chunk's destination per expert).
+__global__ __launch_bounds__(kMapThreads) void map_scan_scatter(const int32_t* __restrict__ ids, int32_t* __restrict__ map,
+                                                                const int32_t* __restrict__ chunk_hist, int nchunks,
+                                                                int T, int k, int E, int N, moe_tiling g) {
+    extern __shared__ int s_mem[];
     __shared__ int s_tmp[32];
     __shared__ int s_work[2 * kMaxE];
     const MapLayout L = map_layout(E);
     const int hs = hist_stride(L.E64);
-    const int tid = threadIdx.x;
-    int cnt = 0;
-    if (tid < L.E64) {
-        for (int c = 0; c < nchunks; ++c) {
-            const int v = chunk_hist[(size_t)c * hs + tid];
-            chunk_hist[(size_t)c * hs + tid] = cnt;
-            cnt += v;
-        }
-    }
-    if (tid == 0) {
-        int b = 0;
-        for (int c = 0; c < nchunks; ++c) b += chunk_hist[(size_t)c * hs + L.E64];
-        s_tmp[31] = b;
-    }
-    __syncthreads();
-    const int bad = s_tmp[31];
-    finish_map(map, L, cnt, bad, T, k, E, N, g, s_tmp, s_work);
-}
-
-// Step 3: stable scatter of one chunk of rows into the token index arrays.
-__global__ __launch_bounds__(kMapThreads) void map_scatter(const int32_t* __restrict__ ids, int32_t* __restrict__ map,
-                                                           const int32_t* __restrict__ chunk_hist, int R, int E) {
-    extern __shared__ int s_mem[];
-    const MapLayout L = map_layout(E);
-    const int hs = hist_stride(L.E64);
-    int* s_wave = s_mem;  // [kWaves][E64]
+    int* s_wave = s_mem;                  // [kWaves][E64]
+    int* s_off = s_mem + kWaves * L.E64;  // [E64]
     const int tid = threadIdx.x, w = tid >> 6;
+    const int R = T * k;
     for (int i = tid; i < kWaves * L.E64; i += kMapThreads) s_wave[i] = 0;
     __syncthreads();
     const int r = blockIdx.x * kChunkRows + tid;
@@ -358,20 +347,33 @@ __global__ __launch_bounds__(kMapThreads) void map_scatter(const int32_t* __rest
     int rank, size;
     wave_match(e, valid, key_bits(E), rank, size);
     if (valid && rank == 0) s_wave[w * L.E64 + e] = size;
-    __syncthreads();
+    int cnt = 0, base = 0;
     if (tid < L.E64) {
+        for (int c = 0; c < nchunks; ++c) {
+            const int v = chunk_hist[(size_t)c * hs + tid];
+            if (c < (int)blockIdx.x) base += v;
+            cnt += v;
+        }
+    }
+    if (tid == kMapThreads - 1) {
+        int b = 0;
+        for (int c = 0; c < nchunks; ++c) b += chunk_hist[(size_t)c * hs + L.E64];
+        s_tmp[31] = b;
+    }
+    __syncthreads();
+    const int bad = s_tmp[31];
+    const int off = finish_map(map, L, cnt, bad, T, k, E, N, g, s_tmp, s_work, blockIdx.x == 0);
+    if (tid < L.E64) {
+        s_off[tid] = off + base;
         int run = 0;
-        for (int i = 0; i < kWaves; ++i) {
+        for (int i = 0; i < kWaves; ++i) {  // exclusive scan over wavefronts, in row order
             const int c = s_wave[i * L.E64 + tid];
             s_wave[i * L.E64 + tid] = run;
             run += c;
         }
     }
     __syncthreads();
-    if (valid) {
-        const int pos = map[L.off_offsets + e] + chunk_hist[(size_t)blockIdx.x * hs + e] + s_wave[w * L.E64 + e] + rank;
-        map[L.off_rows + pos] = r;
-    }
+    if (valid) map[L.off_rows + s_off[e] + s_wave[w * L.E64 + e] + rank] = r;
 }
 
 // Full per-block table from the compressed map, one wavefront per block index.
