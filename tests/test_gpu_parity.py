@@ -193,6 +193,8 @@ BF16_CASES = [
     (256, 256, 700, 16, 2, 128, 256, "zipf"),         # empty experts, one > 2 tiles, ragged tails
     (16, 128, 40, 256, 8, 128, 256, "gauss_topk"),    # E = 256: four voting rounds
     (64, 128, 257, 3, 1, 64, 128, "worst"),
+    (16, 128, 50, 300, 4, 128, 256, "gauss_topk"),    # E = 300: five groups of task records, no streaming launch
+    (64, 128, 200, 1000, 2, 64, 128, "zipf"),         # E = 1000: sixteen groups
 ]
 
 
