@@ -134,7 +134,7 @@ const GemmVariant kVariants[] = {
     {MOE_DTYPE_FP8_E4M3, 16, 128, 128, &launch_pipe<P8k_16x128>, 0, 0, MOE_W_LAYOUT_NK},
     {MOE_DTYPE_BF16, 256, 256, 64, &launch_pipe<Pb_256x256, Ps_64x256, Ps_128x256>},
     {MOE_DTYPE_BF16, 256, 256, 64, &launch_pipe<Pb_256x256s, Ps_64x256, Ps_128x256>, 0, 64},
-    {MOE_DTYPE_BF16, 128, 256, 64, &launch_pipe<Pb_128x256>},
+    {MOE_DTYPE_BF16, 128, 256, 64, &launch_pipe<Pb_128x256, Pb_64x256>},
     {MOE_DTYPE_BF16, 128, 128, 64, &launch_pipe<Pb_128x128>},
     {MOE_DTYPE_BF16, 64, 256, 64, &launch_pipe<Pb_64x256>},
     {MOE_DTYPE_BF16, 64, 128, 64, &launch_pipe<Pb_64x128>},
