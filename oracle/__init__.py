@@ -108,6 +108,7 @@ class TaskMap:
     tile_m_small: int = 0     # second tiling strategy: experts with <= small_max_rows rows use this tile_m
     small_max_rows: int = 0
     tile_m_slack: int = 0     # rows the last tile of a tile_m-strategy expert may hold beyond tile_m
+    heavy_tiles: int = 0      # order 2: tiles of the heavy experts = block index where the light part begins
 
     def expert_tile_m(self, e: int) -> int:
         c = int(self.counts[e])
@@ -156,15 +157,16 @@ def build_task_map(topk_ids, T: int, k: int, E: int, tile_m: int, tile_n: int, N
     prefix = np.zeros(max(E, 1), dtype=np.int32)
     M = ctypes.c_int32(0)
     total = ctypes.c_int32(0)
+    heavy = ctypes.c_int32(0)
     rc = _load().orc_build_task_map(_p(ids), ctypes.c_int(T), ctypes.c_int(k), ctypes.c_int(E),
                                     ctypes.c_int(tile_m), ctypes.c_int(tile_n), ctypes.c_int(N), ctypes.c_int(order),
                                     ctypes.c_int(tile_m_small), ctypes.c_int(small_max_rows), ctypes.c_int(tile_m_slack), _p(counts), _p(offsets), _p(sorted_rows), _p(sigma), _p(prefix),
-                                    ctypes.byref(M), ctypes.byref(total))
+                                    ctypes.byref(M), ctypes.byref(total), ctypes.byref(heavy))
     if rc != 0:
         raise ValueError("routing id outside [0, E)")
     return TaskMap(T, k, E, N, tile_m, tile_n, counts, offsets, sorted_rows[: T * k].copy(),
                    sigma[: M.value].copy(), prefix[: M.value].copy(), M.value, total.value, order,
-                   tile_m_small, small_max_rows, tile_m_slack)
+                   tile_m_small, small_max_rows, tile_m_slack, heavy.value)
 
 
 def decode_block(tm: TaskMap, B: int):

@@ -210,17 +210,47 @@ static void spread_order(const int32_t* experts, const int32_t* nu, int M, int32
     free(key);
 }
 
+/* Sec. 4.2 wants memory-bound (few-token) experts to run at the same time as compute-bound (busy) ones.  Order 2
+ * prepares that: the non-empty experts are split into heavy and light ones (light: all rows fit one m-tile and
+ * fill at most a quarter of it, 4 * c <= tile_m), sigma lists the heavy ones first, by falling tile count (ties by
+ * lower index), then the light ones by rising index; heavy_tiles = the tiles of the heavy part, i.e. the block
+ * index at which the light part begins.  How the kernel then deals heavy and light blocks to its workgroups is
+ * the kernel's business (any bijection of the block indices computes the same Y).
+ * experts[0..M), counts_ne[0..M), nu[0..M): the ascending non-empty experts, their row and tile counts.       */
+static int interleave_order(const int32_t* experts, const int32_t* counts_ne, const int32_t* nu, int M, int tile_m,
+                            int32_t* sigma) {
+    int heavy_tiles = 0, n = 0;
+    char* used = (char*)calloc((size_t)(M > 0 ? M : 1), 1);
+    /* heavy experts by selection: repeatedly take the unused heavy expert with the most tiles (first one on ties) */
+    for (;;) {
+        int best = -1;
+        for (int i = 0; i < M; ++i) {
+            int light = (4 * counts_ne[i] <= tile_m);
+            if (used[i] || light) continue;
+            if (best < 0 || nu[i] > nu[best]) best = i;
+        }
+        if (best < 0) break;
+        used[best] = 1;
+        sigma[n++] = experts[best];
+        heavy_tiles += nu[best];
+    }
+    for (int i = 0; i < M; ++i)
+        if (!used[i]) sigma[n++] = experts[i];
+    free(used);
+    return heavy_tiles;
+}
+
 /* Routing result -> everything the kernel needs (Sec. 4.1, 4.3):
  *   counts[E], offsets[E+1] (exclusive scan), sorted_rows[T*k] (per-expert
  *   token index arrays, stored back to back, as flat row ids r = t*k+j; the
  *   token is r / k), sigma[M] (non-empty -> real expert), tile_prefix[M].
- *   order: 0 = sigma ascending, 1 = spread (Sec. 4.2).
+ *   order: 0 = sigma ascending, 1 = spread (Sec. 4.2), 2 = heavy experts first, then the light ones.
  *   tile_m_small, small_max_rows: the second tiling strategy (0, 0 = none).
  *   tile_m_slack: rows the last tile of a tile_m-strategy expert may hold beyond tile_m.
  * Returns 0, or -1 if an id is outside [0,E).                               */
 int orc_build_task_map(const int32_t* topk_ids, int T, int k, int E, int tile_m, int tile_n, int N, int order,
                        int tile_m_small, int small_max_rows, int tile_m_slack, int32_t* counts, int32_t* offsets, int32_t* sorted_rows, int32_t* sigma,
-                       int32_t* tile_prefix, int32_t* M_out, int32_t* total_tiles_out) {
+                       int32_t* tile_prefix, int32_t* M_out, int32_t* total_tiles_out, int32_t* heavy_tiles_out) {
     int R = T * k;
     for (int e = 0; e < E; ++e) counts[e] = 0;
     for (int r = 0; r < R; ++r) {
@@ -248,8 +278,14 @@ int orc_build_task_map(const int32_t* topk_ids, int T, int k, int E, int tile_m,
             M += 1;
         }
     }
+    int heavy_tiles = 0;
     if (order == 1) spread_order(ne, nu, M, sigma);
-    else for (int i = 0; i < M; ++i) sigma[i] = ne[i];
+    else if (order == 2) {
+        int32_t* cne = (int32_t*)malloc(sizeof(int32_t) * (size_t)(M > 0 ? M : 1));
+        for (int i = 0; i < M; ++i) cne[i] = counts[ne[i]];
+        heavy_tiles = interleave_order(ne, cne, nu, M, tile_m, sigma);
+        free(cne);
+    } else for (int i = 0; i < M; ++i) sigma[i] = ne[i];
     /* tile counts in sigma order, then Alg. 1 */
     for (int i = 0; i < M; ++i)
         nu[i] = expert_m_tiles(counts[sigma[i]], tile_m, tile_m_small, small_max_rows, tile_m_slack) * nt;
@@ -258,6 +294,7 @@ int orc_build_task_map(const int32_t* topk_ids, int T, int k, int E, int tile_m,
     free(ne);
     *M_out = M;
     *total_tiles_out = M > 0 ? tile_prefix[M - 1] : 0;
+    if (heavy_tiles_out) *heavy_tiles_out = heavy_tiles;
     return 0;
 }
 

@@ -343,3 +343,38 @@ def test_two_level_mapping_equals_brute_force(oracle_mod, n, group):
         h, l = oracle_mod.mapping_two_level(prefix, group, B)
         assert h == owner[B] and l == B - first[h]
         assert (h, l) == oracle_mod.mapping(prefix, B)
+
+
+# ------------------------------------------------------------------ heavy-first order (order 2, Sec. 4.2)
+def test_heavy_first_order_hand_example(oracle_mod):
+    g = _gold("heavy_first_order_example.json")
+    ids = np.concatenate([np.full(c, e, np.int32) for e, c in enumerate(g["counts"])]).reshape(-1, 1)
+    tm = oracle_mod.build_task_map(ids, len(ids), 1, g["E"], g["tile_m"], g["tile_n"], g["N"], order=2)
+    assert tm.sigma.tolist() == g["sigma"]
+    assert tm.tile_prefix.tolist() == g["tile_prefix"]
+    assert tm.heavy_tiles == g["heavy_tiles"]
+
+
+@pytest.mark.parametrize("T,k,E,tile_m,tile_n,N,skew", CASES)
+def test_heavy_first_order_properties(oracle_mod, T, k, E, tile_m, tile_n, N, skew):
+    rng = np.random.default_rng(31337 + T + E)
+    ids = _random_ids(rng, T, k, E, skew)
+    tm = oracle_mod.build_task_map(ids, T, k, E, tile_m, tile_n, N, order=2)
+    base = oracle_mod.build_task_map(ids, T, k, E, tile_m, tile_n, N, order=0)
+    # same experts, same per-expert data; only sigma and the prefix move
+    assert sorted(tm.sigma.tolist()) == base.sigma.tolist() and tm.total_tiles == base.total_tiles
+    np.testing.assert_array_equal(tm.counts, base.counts)
+    np.testing.assert_array_equal(tm.sorted_rows, base.sorted_rows)
+    nt = -(-N // tile_n)
+    c = tm.counts[tm.sigma]
+    tiles = -(-c // tile_m) * nt
+    light = 4 * c <= tile_m
+    # heavy block first, light block last, the boundary is heavy_tiles
+    nh = int((~light).sum())
+    assert not light[:nh].any() and light[nh:].all()
+    assert tm.heavy_tiles == int(tiles[:nh].sum())
+    assert all(tiles[i] > tiles[i + 1] or (tiles[i] == tiles[i + 1] and tm.sigma[i] < tm.sigma[i + 1]) for i in range(nh - 1))
+    assert all(tm.sigma[i] < tm.sigma[i + 1] for i in range(nh, tm.M - 1))
+    np.testing.assert_array_equal(tm.tile_prefix, np.cumsum(tiles))
+    # the decode still equals the nested-loop table in that expert order
+    np.testing.assert_array_equal(oracle_mod.decode_all(tm), oracle_mod.full_table(tm.counts, tile_m, tile_n, N, sigma=tm.sigma))
