@@ -155,7 +155,7 @@ class Point:
         ideal_hbm = abytes / (PEAK_HBM_GBS * 1e9)
         bound = "mfma" if ideal_mfma >= ideal_hbm else "hbm"
         return dict(workload=f"{wl.name}_T{wl.T}" + ("_swiglu" if self.swiglu else "") + ("_wNK" if self.w_nk else ""), dtype=wl.dtype, T=wl.T, E=wl.E, k=wl.k, K=wl.K, N=wl.N,
-                    tile=[wl.tile_m, wl.tile_n], sigma_order=("spread" if self.order else "ascending"), small_strategy=list(self.small), tile_m_slack=self.slack, ms_per_step=round(wall_ms, 4),
+                    tile=[wl.tile_m, wl.tile_n], sigma_order=("ascending", "spread", "interleave")[self.order], small_strategy=list(self.small), tile_m_slack=self.slack, ms_per_step=round(wall_ms, 4),
                     ms_per_step_graph=(round(self.time_graph(steps), 4) if wall_ms < 0.5 else None), gemm_ms=round(gemm_ms, 4),
                     map_ms=round(map_ms, 4), tflops_step=round(tf_step, 2), tflops_gemm=round(tf_gemm, 2),
                     frac_mfma=round(tf_gemm / peak_t, 4), gbs_gemm=round(gbs, 1),
@@ -246,7 +246,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--points", default="none", help="'all', 'none', or a comma list of workload names")
     ap.add_argument("--tile", default="", help="override tile_m,tile_n of the headline workload")
-    ap.add_argument("--order", default="ascending", choices=["ascending", "spread", "both"],
+    ap.add_argument("--order", default="ascending", choices=["ascending", "spread", "interleave", "both", "all"],
                     help="expert order in sigma for the extra points (the headline always uses ascending)")
     ap.add_argument("--small", default="0,0",
                     help="tile_m_small,small_max_rows: second tiling strategy for the extra points with 256x256 tiles")
@@ -354,7 +354,7 @@ def main():
             small = tuple(int(v) for v in args.small.split(","))
             if small[0] and not (w.dtype == "bf16" and mb.moe_tile_pair_supported(mb.MOE_DTYPE_BF16, w.tile_m, w.tile_n, small[0])):
                 small = (0, 0)
-            for order in ([0, 1] if args.order == "both" else [1 if args.order == "spread" else 0]):
+            for order in {"both": [0, 1], "all": [0, 1, 2], "spread": [1], "interleave": [2]}.get(args.order, [0]):
                 p = Point(w, copies, order=order, small=small)
                 points.append(p.report(max(10, args.steps // 2), max(3, args.warmup // 2)))
                 del p

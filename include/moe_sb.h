@@ -46,7 +46,7 @@ enum { MOE_W_LAYOUT_KN = 0, MOE_W_LAYOUT_NK = 1 };
 enum { MOE_EPILOGUE_NONE = 0, MOE_EPILOGUE_SWIGLU = 1 };
 
 /* Order of the non-empty experts in sigma (Sec. 4.1, Sec. 4.2). */
-enum { MOE_ORDER_ASCENDING = 0, MOE_ORDER_SPREAD = 1 };
+enum { MOE_ORDER_ASCENDING = 0, MOE_ORDER_SPREAD = 1, MOE_ORDER_INTERLEAVE = 2 };
 
 /*
  * Task-map blob (all int32 words; E64 = E rounded up to a multiple of 64,
@@ -93,7 +93,8 @@ enum {
     MOE_HDR_SIGMA_ORDER = 14,    /* MOE_ORDER_* the map was built with */
     MOE_HDR_TILE_M_SMALL = 15,   /* second tiling strategy (0 = none), see moe_build_task_map_tiled */
     MOE_HDR_SMALL_MAX_ROWS = 16,
-    MOE_HDR_TILE_M_SLACK = 17    /* extra rows the last m-tile of an expert may hold, see moe_build_task_map_ex */
+    MOE_HDR_TILE_M_SLACK = 17,   /* extra rows the last m-tile of an expert may hold, see moe_build_task_map_ex */
+    MOE_HDR_HEAVY_TILES = 18     /* MOE_ORDER_INTERLEAVE: tiles of the heavy experts = block index where the light part begins, else 0 */
 };
 
 /* Word offsets of the blob's fields for a given E (HOST, pure). */
@@ -142,7 +143,14 @@ int moe_build_task_map(const int32_t* topk_ids, int T, int k, int E, int tile_m,
  *                        sigma lists them by increasing key: busiest first, second busiest in
  *                        the middle, the next two at the quarter points, ... so every
  *                        contiguous run of blocks (one per XCD) mixes busy and small experts.
- * Only sigma and tile_prefix depend on the order; counts, offsets and sorted_rows do not.
+ *   MOE_ORDER_INTERLEAVE the way Sec. 4.2's idea is carried out here: experts whose rows fill at most a quarter of
+ *                        one m-tile (4 * count <= tile_m) are light (their tiles only stream weights), the rest
+ *                        heavy; sigma lists the heavy ones by falling tile count (ties by lower index), then
+ *                        the light ones by rising index, and header[MOE_HDR_HEAVY_TILES] holds the block index
+ *                        where the light part begins.  moe_grouped_gemm then deals every XCD a contiguous
+ *                        share of the heavy blocks and one of the light blocks and runs them interleaved in
+ *                        proportion, so that memory-bound tiles stream while compute-bound ones multiply.
+ * Only sigma, tile_prefix and the task records depend on the order; counts, offsets and sorted_rows do not.
  * Any other `order` returns MOE_ERR_INVALID_ARG.
  */
 int moe_build_task_map_ordered(const int32_t* topk_ids, int T, int k, int E, int tile_m, int tile_n, int N,

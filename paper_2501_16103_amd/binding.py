@@ -31,11 +31,12 @@ MOE_EPILOGUE_NONE = 0
 MOE_EPILOGUE_SWIGLU = 1
 MOE_ORDER_ASCENDING = 0
 MOE_ORDER_SPREAD = 1
+MOE_ORDER_INTERLEAVE = 2
 MOE_MAP_MAGIC = 0x3142534D
 MOE_MAP_HDR_WORDS = 32
 HDR = dict(MAGIC=0, T=1, K_TOP=2, E=3, N=4, TILE_M=5, TILE_N=6, NT=7, M=8, TOTAL_TILES=9, ORDER=10,
            STATUS=11, R=12, E64=13, SIGMA_ORDER=14, TILE_M_SMALL=15,
-           SMALL_MAX_ROWS=16, TILE_M_SLACK=17)
+           SMALL_MAX_ROWS=16, TILE_M_SLACK=17, HEAVY_TILES=18)
 
 EXPORTS = [
     "moe_map_off_counts", "moe_map_off_offsets", "moe_map_off_sigma", "moe_map_off_tile_prefix",

@@ -611,11 +611,26 @@ __device__ __forceinline__ bool locate_tile(const GemmArgs& a, const int32_t* __
     if (!hdr_ok) return false;
     // Workgroup ids are dealt round-robin to the 8 XCDs; give each XCD one contiguous run of block indices so
     // that neighbours in the map share an L2.
-    const int per_xcd = (total + 7) >> 3;
-    const int slot = blockIdx.x >> 3;
-    if (slot >= per_xcd) return false;
-    const int B = (blockIdx.x & 7) * per_xcd + slot;
-    if (B >= total) return false;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    int B;
+    if (map[MOE_HDR_SIGMA_ORDER] == MOE_ORDER_INTERLEAVE) {
+        // Sec. 4.2: blocks [0, heavy) are compute-bound, [heavy, total) only stream weights.  Every XCD gets a
+        // contiguous share of each part and walks the two shares interleaved in proportion (slot s takes the
+        // next light block whenever floor((s+1) * nl / n) exceeds floor(s * nl / n)), so that the light tiles'
+        // HBM traffic is spread over the whole run of the heavy ones.
+        const int heavy = map[MOE_HDR_HEAVY_TILES], light = total - heavy;
+        const int h0 = (int)((long long)heavy * xcd >> 3), h1 = (int)((long long)heavy * (xcd + 1) >> 3);
+        const int l0 = (int)((long long)light * xcd >> 3), l1 = (int)((long long)light * (xcd + 1) >> 3);
+        const int nh = h1 - h0, nl = l1 - l0, n = nh + nl;
+        if (slot >= n) return false;
+        const int before = (int)((long long)slot * nl / n), upto = (int)((long long)(slot + 1) * nl / n);
+        B = upto > before ? heavy + l0 + before : h0 + slot - before;
+    } else {
+        const int per_xcd = (total + 7) >> 3;
+        if (slot >= per_xcd) return false;
+        B = xcd * per_xcd + slot;
+        if (B >= total) return false;
+    }
     const moe_tiling g = {BM_BIG, BN, 0, BM_SMALL, a.small_max_rows, SLACK};
     tc = decode_block(map, L, g, B, first_record);
     return true;

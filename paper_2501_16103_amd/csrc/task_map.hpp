@@ -192,6 +192,24 @@ __device__ __forceinline__ int finish_map(int32_t* __restrict__ map, const MapLa
             for (int j = 0; j < L.E64; ++j) pos += s_work[L.E64 + j] < key;
         __syncthreads();
     }
+    // order 2: heavy experts (more than a quarter of an m-tile) by falling tile count, ties by lower index, then the
+    // light ones by rising index; the tiles of the heavy part are summed for the header
+    const bool light = 4 * cnt <= g.tile_m;
+    if (tid == 0) s_tmp[18] = 0;
+    if (order == 2) {
+        const int heavy_key = light ? 0 : tiles;   // every heavy expert has at least one tile
+        if (tid < L.E64) s_work[tid] = nonempty ? heavy_key : -1;
+        __syncthreads();
+        pos = 0;
+        if (nonempty) {
+            for (int j = 0; j < L.E64; ++j) {
+                const int tj = s_work[j];
+                pos += (tj > heavy_key) || (tj == heavy_key && j < tid);
+            }
+            if (!light) atomicAdd(&s_tmp[18], tiles);   // integer sum: the order of the adds does not matter
+        }
+        __syncthreads();
+    }
     // `write` is false for the workgroups that only need the returned offsets (every scatter workgroup repeats
     // this function; the first one stores its results)
     if (tid < L.E64) {
@@ -250,6 +268,7 @@ __device__ __forceinline__ int finish_map(int32_t* __restrict__ map, const MapLa
             case MOE_HDR_TILE_M_SMALL: v = g.tile_m_small; break;
             case MOE_HDR_SMALL_MAX_ROWS: v = g.small_max_rows; break;
             case MOE_HDR_TILE_M_SLACK: v = g.tile_m_slack; break;
+            case MOE_HDR_HEAVY_TILES: v = (order == 2 && !bad) ? s_tmp[18] : 0; break;
             default: v = 0;
         }
         if (write) map[tid] = v;

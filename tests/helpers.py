@@ -30,7 +30,7 @@ def expected_blob(tm) -> np.ndarray:
     b = np.zeros(o["sorted_rows"] + R, dtype=np.int32)
     hdr = [MAGIC, tm.T, tm.k, tm.E, tm.N, tm.tile_m, tm.tile_n, tm.nt, tm.M, tm.total_tiles, 0, 0, R, o["E64"],
            getattr(tm, "order", 0), getattr(tm, "tile_m_small", 0), getattr(tm, "small_max_rows", 0),
-           getattr(tm, "tile_m_slack", 0)]
+           getattr(tm, "tile_m_slack", 0), getattr(tm, "heavy_tiles", 0)]
     b[: len(hdr)] = hdr
     b[o["counts"]: o["counts"] + tm.E] = tm.counts
     b[o["offsets"]: o["offsets"] + o["E64"] + 64] = R

@@ -114,6 +114,8 @@ FULL = [
     (wk.paper_eval("worst"), 8, 64, 0),
     (wk.paper_eval("worst"), 8, 64, 1),
     (wk.mixtral_down_zipf(4096), 8, 64, 1),
+    (wk.paper_eval("worst"), 8, 64, 2),
+    (wk.mixtral_down_zipf(4096), 8, 64, 2),
     (wk.decode_fp8(32), 8, 64, 0),
     (wk.decode_fp8(8), 8, 48, 0),
     (wk.decode_fp8(1), 8, 6, 0),

@@ -60,7 +60,7 @@ MAP_CASES = [
 ]
 
 
-@pytest.mark.parametrize("order", [0, 1], ids=["ascending", "spread"])
+@pytest.mark.parametrize("order", [0, 1, 2], ids=["ascending", "spread", "interleave"])
 @pytest.mark.parametrize("T,k,E,tile_m,tile_n,N,routing", MAP_CASES)
 def test_task_map_bit_exact(dev, oracle_mod, T, k, E, tile_m, tile_n, N, routing, order):
     wl = wk.Workload("mapcase", T, E, k, 64, N, "bf16", routing)
@@ -198,7 +198,7 @@ BF16_CASES = [
 ]
 
 
-@pytest.mark.parametrize("order", [0, 1], ids=["ascending", "spread"])
+@pytest.mark.parametrize("order", [0, 1, 2], ids=["ascending", "spread", "interleave"])
 @pytest.mark.parametrize("tile_m,tile_n,T,E,k,K,N,routing", BF16_CASES)
 def test_gemm_bf16_parity(dev, oracle_mod, tile_m, tile_n, T, E, k, K, N, routing, order):
     wl = wk.Workload("parity_bf16", T, E, k, K, N, "bf16", routing, tile_m, tile_n)
@@ -218,7 +218,7 @@ TILED_CASES = [
 ]
 
 
-@pytest.mark.parametrize("order", [0, 1], ids=["ascending", "spread"])
+@pytest.mark.parametrize("order", [0, 1, 2], ids=["ascending", "spread", "interleave"])
 @pytest.mark.parametrize("T,E,k,K,N,routing,small,thr", TILED_CASES)
 def test_two_tiling_strategies_parity(dev, oracle_mod, T, E, k, K, N, routing, small, thr, order):
     """Alg. 3 with two task types in one launch: map bit-exact, expanded table == nested-loop table, Y == oracle."""
@@ -275,7 +275,7 @@ SLACK_CASES = [
 ]
 
 
-@pytest.mark.parametrize("order", [0, 1], ids=["ascending", "spread"])
+@pytest.mark.parametrize("order", [0, 1, 2], ids=["ascending", "spread", "interleave"])
 @pytest.mark.parametrize("counts,K,N", SLACK_CASES)
 def test_slack_rows_parity(dev, oracle_mod, counts, K, N, order):
     """Last m-tiles with up to tile_m + 64 rows: map bit-exact, expanded table == nested-loop table, Y == oracle."""

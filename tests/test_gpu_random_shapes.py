@@ -33,7 +33,7 @@ def _case(seed):
     K = bk * int(rng.integers(1, 5))
     N = tile_n * int(rng.integers(1, 4))
     routing = str(rng.choice(["gauss_topk", "zipf", "uniform_topk"]))
-    opt = dict(order=int(rng.integers(0, 2)), slack=0, swiglu=bool(rng.random() < 0.4), nk=False, stream=0)
+    opt = dict(order=int(rng.integers(0, 3)), slack=0, swiglu=bool(rng.random() < 0.4), nk=False, stream=0)
     if (tile_m, tile_n) == (256, 256) and not fp8 and rng.random() < 0.5:
         opt["slack"] = 64
     if tile_m == 16:
