@@ -288,7 +288,7 @@ int moe_build_task_map_ex(const int32_t* topk_ids, int T, int k, int E, int N, c
         const int rcs = check_small_args(tile_m, g.tile_m_small, g.small_max_rows, g.tile_m_slack);
         if (rcs != MOE_OK) return rcs;
     }
-    if (order != MOE_ORDER_ASCENDING && order != MOE_ORDER_SPREAD) return MOE_ERR_INVALID_ARG;
+    if (order != MOE_ORDER_ASCENDING && order != MOE_ORDER_SPREAD && order != MOE_ORDER_INTERLEAVE) return MOE_ERR_INVALID_ARG;
     if (((uintptr_t)task_map & 15) || ((uintptr_t)topk_ids & 3)) return MOE_ERR_INVALID_ARG;
     const int rc = check_map_args(T, k, E, tile_m, tile_n, N);
     if (rc != MOE_OK) return rc;
@@ -386,8 +386,8 @@ int moe_grouped_gemm(const void* X, const void* W, const int32_t* topk_ids, cons
     a.swiglu = d->epilogue == MOE_EPILOGUE_SWIGLU;
     int64_t grid = moe_grid_upper_bound_tiled(d->T, d->k, d->E, d->tile_m, d->tile_n, d->N, d->tile_m_small,
                                               d->small_max_rows);
-    grid = (grid + 7) / 8 * 8;
     if (grid == 0) return MOE_OK;
+    grid = (grid + 7) / 8 * 8 + 8;  // one spare slot per XCD: the interleaved dealing rounds two shares up
     if (grid > 0x7fffffff) return MOE_ERR_UNSUPPORTED;
     // weight-streaming tiles: keep the workgroups resident and stream tile after tile where the shape allows it
     const bool can_stream = v->fn_stream && d->E <= 256 && d->K / v->bk >= v->ring &&
