@@ -76,6 +76,7 @@ __device__ __forceinline__ void mapping(const int4* __restrict__ records, int E6
 struct TileCoord {
     int e, m_tile, n_tile, rows, row_base;  // row_base: index into sorted_rows of the tile's first row
     int small;                              // task type (Alg. 3): 1 = the expert uses the small tiling strategy
+    int m_tiles;                            // m-tiles of the expert: 1 = no other tile reads this tile's weight panel
 };
 
 // Tiling strategy of an expert with cnt rows: tile_m_small when cnt <= small_max_rows (0 = one strategy).
@@ -103,6 +104,7 @@ __device__ __forceinline__ TileCoord decode_block(const int32_t* __restrict__ ma
     c.small = g.small_max_rows > 0 && cnt <= g.small_max_rows;
     const int tile_m = c.small ? g.tile_m_small : g.tile_m;
     const int mt = expert_m_tiles(cnt, g);
+    c.m_tiles = mt;
     c.n_tile = l / mt;
     c.m_tile = l - c.n_tile * mt;
     const int left = cnt - c.m_tile * tile_m;
