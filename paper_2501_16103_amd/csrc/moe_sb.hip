@@ -248,13 +248,17 @@ int moe_default_tiling(int dtype, int T, int k, int E, int K, int N, moe_tiling*
         const double t256 = (hit + (double)(R / 16)) * ((N + 255) / 256);
         g.tile_m = 16;
         g.tile_n = (N % 256 == 0 && t256 >= cus && t256 <= 2 * cus) ? 256 : 128;
-    } else if (mean_rows <= 24) {
+    } else if (mean_rows <= 8) {
+        // nearly every expert's rows fit one 16-row tile (count ~ mean +- 3 sqrt(mean))
         g.tile_m = 16; g.tile_n = 256;
-    } else if (mean_rows <= 160) {
+    } else if (mean_rows > 48 && mean_rows <= 96) {
+        // counts straddle 64: the four-wave 64- and 128-row functions of the 128-row launch
         g.tile_m = active * ((N + 255) / 256) >= 3 * cus ? 128 : 64;
         g.tile_n = 256;
     } else {
-        g.tile_m = 256; g.tile_n = 256; g.tile_m_slack = 64;
+        // 256-row tiles; their launch runs tiles of at most 64 / 128 rows with narrower task functions, which
+        // covers the small counts too.  Slack rows pay once experts hold several tiles.
+        g.tile_m = 256; g.tile_n = 256; g.tile_m_slack = mean_rows > 192 ? 64 : 0;
     }
     // the n-tile must divide N; narrower tiles keep the same row tiling where a kernel exists
     for (int tn = g.tile_n; tn >= 64; tn >>= 1) {
