@@ -74,6 +74,14 @@ __device__ __forceinline__ void dma16_nt(uint32_t voff, const void* sbase, uint3
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt" ::"v"(voff), "s"(sbase), "s"(lds_addr)
                  : "memory");
 }
+// f(integral_constant<int, LO>), ..., f(integral_constant<int, HI>)
+template <int LO, int HI, class F>
+__device__ __forceinline__ void for_each_int(F& f) {
+    if constexpr (LO <= HI) {
+        f(std::integral_constant<int, LO>{});
+        for_each_int<LO + 1, HI>(f);
+    }
+}
 // s_waitcnt vmcnt(N) only (expcnt / lgkmcnt fields left at "no wait").
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
@@ -86,7 +94,7 @@ __device__ __forceinline__ void wait_vmcnt() {
 // (K contiguous, a pre-packed layout) instead of [E][K][N]: the weight tile then has the token tile's geometry
 // and needs no transposing LDS reads.
 template <int BM_, int BN_, int BK_, int WM_, int WN_, int NS_, bool FP8_ = false, int NSW_ = NS_, int SLACK_ = 0,
-          bool WKC_ = false>
+          bool WKC_ = false, int MFO_ = 0>
 struct PipeCfg {
     static constexpr bool WKC = WKC_;
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, NS = NS_, NSW = NSW_, SLACK = SLACK_;
@@ -95,15 +103,22 @@ struct PipeCfg {
     static constexpr int ES = FP8 ? 1 : 2;
     static constexpr int NT = 64 * WM * WN;
     static constexpr int WTM = BMC / WM, WTN = BN / WN;
-    static constexpr int MF = (!FP8 && WTM >= 32) ? 32 : 16;   // MFMA block edge
+    static constexpr int MF = MFO_ ? MFO_ : ((!FP8 && WTM >= 32) ? 32 : 16);   // MFMA block edge
     static constexpr int KS = MF == 32 ? 16 : 32;              // k elements per MFMA
     static constexpr int KSTEPS = BK / KS;
     static constexpr int NBW = WTN / MF, MBW = WTM / MF;
     static constexpr int MBW_BODY = BM / WM / MF;              // row blocks per wavefront without the slack rows
     static constexpr int ACC = MF == 32 ? 16 : 4;              // accumulator registers per block
+    // Large tiles on 16-row MFMA blocks hold twice as many fragments per k-step: the token fragments are then
+    // single-buffered, each reloaded for the next k-step as soon as the MFMAs of its row block are issued.
+    static constexpr bool XROLL = MFO_ == 16;
+    // unroll the k loop over the ring so that ring positions are compile-time constants
+    static constexpr bool STATIC_RING = false && NS_ == NSW_ && NS_ == 2 && BM_ >= 256;
     static constexpr int XROW = BK * ES, CPR = XROW / 16;
     static constexpr int WROW = BN * ES, CPRW = WROW / 16;
-    static constexpr int XS_BYTES = BMC * XROW, WS_BYTES = BK * WROW;  // (BN rows of XROW bytes when WKC: same size)
+    // the token tile in LDS is rounded up so that every wavefront issues the same number of DMA instructions
+    static constexpr int XS_BYTES = (BMC * XROW + 16 * NT - 1) / (16 * NT) * (16 * NT);
+    static constexpr int WS_BYTES = BK * WROW;                 // (BN rows of XROW bytes when WKC: same size)
     static constexpr int W_RING = NS * XS_BYTES;               // byte offset of the weight ring
     static constexpr int LDS_BYTES = NS * XS_BYTES + NSW * WS_BYTES;
     // weight-fragment LDS reads per k-step (two 4-k halves for bf16, one 8-k piece for fp8)
@@ -191,15 +206,16 @@ __device__ __forceinline__ TileCoord decode_from_registers(const TileStream& ts,
 }
 
 typedef __attribute__((ext_vector_type(8))) int i32x8_t;
-// Eight consecutive words through the scalar data path (read only): these loads count in lgkmcnt, so they do
+// Sixteen consecutive words through the scalar data path (read only): these loads count in lgkmcnt, so they do
 // not disturb the vmcnt bookkeeping of the DMA ring.  p must be wavefront-uniform and 4-byte aligned.
-__device__ __forceinline__ i32x8_t scalar_load8(const int32_t* p) {
-    i32x8_t v;
-    asm volatile("s_load_dwordx8 %0, %1, 0x0" : "=s"(v) : "s"(p) : "memory");
-    return v;
-}
-__device__ __forceinline__ void scalar_wait(i32x8_t& a, i32x8_t& b) {
-    asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(a), "+s"(b)::"memory");
+// The loads and their wait are ONE statement: the compiler takes an asm's results as available when the
+// statement ends, so a load left in flight across statements can have its destination registers spilled (and
+// reused) before the data arrives.
+__device__ __forceinline__ void scalar_load16(const int32_t* p, i32x8_t& lo, i32x8_t& hi) {
+    asm volatile("s_load_dwordx8 %0, %2, 0x0\n\ts_load_dwordx8 %1, %2, 0x20\n\ts_waitcnt lgkmcnt(0)"
+                 : "=&s"(lo), "=&s"(hi)
+                 : "s"(p)
+                 : "memory");
 }
 
 // One tile of the batch (STREAM = false), or a run of tiles taken from `ts` (STREAM = true; 16-row tiles only):
@@ -226,10 +242,14 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
     static_assert(!STREAM || (C::BM == 16 && MF == 16 && MBW == 1 && XI == 1 && NS == NSW && C::SLACK == 0 && KSTEPS % 2 == 0),
                   "the streaming loop is written for 16-row tiles");
     // per-lane source offsets inside a tile; everything that depends on the tile (expert, n-tile) is in the base pointer
-    uint32_t dx_off[XI], dx_next = 0, dw_off[WI];
+    // When a wavefront's weight instructions lie a multiple of 16 k-rows apart they share swizzle and lane
+    // pattern: one offset register serves them all and the distance goes into the scalar base.
+    constexpr bool W_FOLD = !C::WKC && (NW * WROWS_PER_INST) % 16 == 0;
+    constexpr int WI_OFF = W_FOLD ? 1 : WI;
+    uint32_t dx_off[XI], dx_next = 0, dw_off[WI_OFF];
     const uint32_t w_row_bytes = (uint32_t)a.N * ES;
 #pragma unroll
-    for (int j = 0; j < WI; ++j) {
+    for (int j = 0; j < WI_OFF; ++j) {
         const int inst = j * NW + wave;
         if constexpr (C::WKC) {
             // tile row = weight column; a lane's 16 bytes are 8 (16) consecutive k of that column
@@ -269,14 +289,19 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
     const bool nt_ok = map[MOE_HDR_TOTAL_TILES] >= 256;
     bool w_once = nt_ok && tc.m_tiles == 1, w_once_next = false;
     // j-th token-row / weight-row DMA instruction of this wave for k-tile kt, into ring stage `stage`
-    auto dma_x = [&](int j, int kt, int stage, bool next) {
+    auto dma_x = [&](int j, int kt, int stage, bool next) __attribute__((always_inline)) {
         dma16(next ? dx_next : dx_off[j], Xb + (size_t)kt * (BK * ES), lds0 + stage * C::XS_BYTES + (j * NW + wave) * 1024);
     };
-    auto dma_w = [&](int j, int kt, int stage, bool next) {
-        const char* src = (next ? Wt_next : Wt) + (size_t)kt * w_kt_stride;
+    // ntm: 0 plain, 1 non-temporal, 2 decided at run time.  The 256-row loops are MFMA-bound and always plain:
+    // a branch at each of their DMA instructions measured 2-5 % slower, and a second copy of the loops for the
+    // hinted form made the register allocator spill.
+    auto dma_w = [&](int j, int kt, int stage, bool next, int ntm) __attribute__((always_inline)) {
+        const char* src = (next ? Wt_next : Wt) + (size_t)kt * w_kt_stride +
+                          (W_FOLD ? (size_t)(j * NW * WROWS_PER_INST) * w_row_bytes : (size_t)0);
         const uint32_t dst = lds0 + C::W_RING + stage * C::WS_BYTES + (j * NW + wave) * 1024;
-        if (next ? w_once_next : w_once) dma16_nt(dw_off[j], src, dst);
-        else dma16(dw_off[j], src, dst);
+        const uint32_t voff = dw_off[W_FOLD ? 0 : j];
+        if (ntm == 2 ? (next ? w_once_next : w_once) : ntm == 1) dma16_nt(voff, src, dst);
+        else dma16(voff, src, dst);
     };
 
     if (C::EARLY_W) {
@@ -284,7 +309,7 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
         for (int s = 0; s < NSW; ++s)
             if (s < KT) {
 #pragma unroll
-                for (int j = 0; j < WI; ++j) dma_w(j, s, s, false);
+                for (int j = 0; j < WI; ++j) dma_w(j, s, s, false, 2);
             }
     }
 
@@ -293,15 +318,9 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
     // streaming: lane j < 16 holds the flat row id of tile row j (row 0's for j past the tile's rows) and the
     // token's scale; fetched through the scalar path and LDS so that no vector-memory wait is ever generated
     int rows_v = 0, rows_v_next = 0;
-    i32x8_t srow_lo, srow_hi;   // a tile's 16 row ids on their way through the scalar path
-    auto stream_rows_issue = [&](const TileCoord& t) {
-        const int32_t* p = map + L.off_rows + t.row_base;
-        srow_lo = scalar_load8(p);
-        srow_hi = scalar_load8(p + 8);
-    };
-    auto stream_rows_finish = [&](const TileCoord& t, int& rv, uint32_t& dxo) {
-        scalar_wait(srow_lo, srow_hi);
-        const i32x8_t lo = srow_lo, hi = srow_hi;
+    auto stream_rows = [&](const TileCoord& t, int& rv, uint32_t& dxo) {
+        i32x8_t lo, hi;
+        scalar_load16(map + L.off_rows + t.row_base, lo, hi);
         int v = lo[0];
 #pragma unroll
         for (int j = 1; j < 16; ++j) v = (lane == j && j < t.rows) ? (j < 8 ? lo[j] : hi[j - 8]) : v;
@@ -312,8 +331,7 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
         dxo = (uint32_t)tok_of_row * (uint32_t)(a.K * ES) + ((pos ^ pswz_x<C>(row)) << 4);
     };
     if constexpr (STREAM) {
-        stream_rows_issue(tc);
-        stream_rows_finish(tc, rows_v, dx_off[0]);
+        stream_rows(tc, rows_v, dx_off[0]);
     } else {
 #pragma unroll
         for (int j = 0; j < XI; ++j) {
@@ -334,8 +352,8 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
     mb_live = mb_live < 0 ? 0 : (mb_live > MBW ? MBW : mb_live);
 
     // ---- fragment registers, double-buffered across k-steps; per-lane LDS offsets of k-step 0
-    u32x2_t wq[2][NBW][2];
-    u32x4_t xq[2][MBW];
+    u32x2_t wq[2][NBW][2];       // (XROLL: [1][nb < NBW / 2] is never used)
+    u32x4_t xq[C::XROLL ? 1 : 2][MBW];
     int w_rd[NBW];
 #pragma unroll
     for (int nb = 0; nb < NBW; ++nb) {
@@ -354,7 +372,10 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
             c = ncol >> 3; within = (ncol & 7) * 2;
         }
         // the swizzle of row kr0 also holds for kr0 + 4 and kr0 + KS*kk (see pswz_w), so later k-steps add a constant
-        w_rd[nb] = kr0 * C::WROW + ((c ^ pswz_w<C>(kr0)) << 4) + within;
+        // The ring's offset is part of the register (and hidden from constant folding), so that what a read adds
+        // to it -- k-step, half -- stays within the 16-bit offset field of the LDS instruction.
+        w_rd[nb] = C::W_RING + kr0 * C::WROW + ((c ^ pswz_w<C>(kr0)) << 4) + within;
+        asm volatile("" : "+v"(w_rd[nb]));
     }
     // tile row of this lane in its block mb; the swizzle only looks at row bits below MF, so it is the same for every block
     const int row0 = wm * MF + lrow;
@@ -363,15 +384,17 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
     static_assert(MF % 16 == 0, "pswz_x must not depend on the block");
     const int xswz = pswz_x<C>(row0);
 
+    // weight fragments are double-buffered across k-steps, except (XROLL) the first half of the blocks
+    auto wbuf = [](int buf, int nb) __attribute__((always_inline)) { return (C::XROLL && nb < NBW / 2) ? 0 : buf; };
     // r-th LDS read of k-step kk, ordered by first use in the MFMA sequence (token block 0, weights, token blocks 1..)
-    auto read_one = [&](int r, int sx, int sw, int kk, int buf, bool tail) {
+    auto read_one = [&](int r, int sx, int sw, int kk, int buf, bool tail) __attribute__((always_inline)) {
         const char* xs = smem + sx * C::XS_BYTES;
-        const char* ws = smem + C::W_RING + sw * C::WS_BYTES;
+        const char* ws = smem + sw * C::WS_BYTES;   // w_rd holds the ring's offset
         if (r >= 1 && r <= WREADS) {
             if constexpr (C::WKC) {
                 const int nb = r - 1;
                 const int row = wn * C::WTN + nb * MF + lrow;
-                const char* wrow = ws + row * C::XROW;
+                const char* wrow = ws + C::W_RING + row * C::XROW;
                 if constexpr (C::FP8) {
                     const int c = kk * 2 + (g >> 1);
                     wq[buf][nb][0] = *reinterpret_cast<const u32x2_t*>(wrow + ((c ^ pswz_x<C>(row)) << 4) + (g & 1) * 8);
@@ -387,7 +410,7 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
             } else {
                 const int nb = (r - 1) >> 1, half = (r - 1) & 1;
                 const char* p = ws + w_rd[nb] + (kk * C::KS + half * 4) * C::WROW;
-                wq[buf][nb][half] = __builtin_bit_cast(u32x2_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16((MOE_LDS(s16x4_t)*)(p)));
+                wq[wbuf(buf, nb)][nb][half] = __builtin_bit_cast(u32x2_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16((MOE_LDS(s16x4_t)*)(p)));
             }
         } else {
             const int mb = r == 0 ? 0 : r - WREADS;
@@ -396,46 +419,50 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
             if constexpr (C::FP8) {
                 const int c = kk * 2 + (g >> 1);
                 const u32x2_t v = *reinterpret_cast<const u32x2_t*>(xrow + ((c ^ xswz) << 4) + (g & 1) * 8);
-                xq[buf][mb].x = v.x; xq[buf][mb].y = v.y;
+                xq[C::XROLL ? 0 : buf][mb].x = v.x; xq[C::XROLL ? 0 : buf][mb].y = v.y;
             } else {
                 const int c = MF == 32 ? kk * 2 + (lane >> 5) : kk * 4 + g;
-                xq[buf][mb] = *reinterpret_cast<const u32x4_t*>(xrow + ((c ^ xswz) << 4));
+                xq[C::XROLL ? 0 : buf][mb] = *reinterpret_cast<const u32x4_t*>(xrow + ((c ^ xswz) << 4));
             }
         }
     };
-    auto mfma_one = [&](int i, int buf, bool tail) {
-        const int mb = i / NBW, nb = i % NBW;
+    // i-th MFMA of a k-step over nmb row blocks: row-block-major, or (XROLL) the first half of the weight blocks
+    // for every row block and then the second half, which lets the first half's fragments be reloaded in place
+    auto mfma_one = [&](int i, int nmb, int buf, bool tail) __attribute__((always_inline)) {
+        const int mb = C::XROLL ? (i % (NBW / 2 * nmb)) / (NBW / 2) : i / NBW;
+        const int nb = C::XROLL ? i / (NBW / 2 * nmb) * (NBW / 2) + i % (NBW / 2) : i % NBW;
         if (tail && mb >= mb_live) return;
         if constexpr (C::FP8) {
-            const u32x2_t xv = {xq[buf][mb].x, xq[buf][mb].y};
+            const u32x2_t xv = {xq[C::XROLL ? 0 : buf][mb].x, xq[C::XROLL ? 0 : buf][mb].y};
             acc[nb][mb] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(__builtin_bit_cast(long, wq[buf][nb][0]),
                                                                      __builtin_bit_cast(long, xv), acc[nb][mb], 0, 0, 0);
         } else {
-            const u32x4_t wv = {wq[buf][nb][0].x, wq[buf][nb][0].y, wq[buf][nb][1].x, wq[buf][nb][1].y};
-            const bf16x8_t wf = __builtin_bit_cast(bf16x8_t, wv), xf = __builtin_bit_cast(bf16x8_t, xq[buf][mb]);
+            const int wb = wbuf(buf, nb);
+            const u32x4_t wv = {wq[wb][nb][0].x, wq[wb][nb][0].y, wq[wb][nb][1].x, wq[wb][nb][1].y};
+            const bf16x8_t wf = __builtin_bit_cast(bf16x8_t, wv), xf = __builtin_bit_cast(bf16x8_t, xq[C::XROLL ? 0 : buf][mb]);
             if constexpr (MF == 32) acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[nb][mb], 0, 0, 0);
             else acc[nb][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xf, acc[nb][mb], 0, 0, 0);
         }
     };
 
     TileCoord tc_next = tc;       // streaming: the tile after the current one
-    int cur = 0, curw = 0;        // ring positions; they run on from tile to tile when streaming
+    int cur_rt = 0, curw_rt = 0;  // ring positions; they run on from tile to tile when streaming
     bool first = true;            // the rings are empty: fill them before the loop
     bool has_next = false;        // streaming: another tile follows, its first k-tiles are fetched by this tile's last iterations
 
     // The tile's whole k loop for NMB row blocks per wavefront and XIL token-row DMA instructions per stage.
-    auto run = [&](auto nmb_tag, auto xil_tag, auto tail_tag) {
-        constexpr int NMB = decltype(nmb_tag)::value, XIL = decltype(xil_tag)::value;
+    auto run = [&](auto nmb_tag, auto xil_tag, auto tail_tag, auto nt_tag) __attribute__((always_inline)) {
+        constexpr int NMB = decltype(nmb_tag)::value, XIL = decltype(xil_tag)::value, NTM = decltype(nt_tag)::value;
         constexpr bool TAIL = decltype(tail_tag)::value;
         constexpr int NM = NBW * NMB, NREADS = WREADS + NMB, ND = XIL + WI;
         // d-th DMA instruction of a stage (token rows first) for k-tile kt of this tile, or, past its end, of the next
-        auto dma_one = [&](int d, int ktx, int ktw, int sx, int sw, bool all_in_range) {
+        auto dma_one = [&](int d, int ktx, int ktw, int sx, int sw, bool all_in_range) __attribute__((always_inline)) {
             if (d < XIL) {
                 if (all_in_range || ktx < KT) dma_x(d, ktx, sx, false);
                 else if (STREAM && has_next) dma_x(d, ktx - KT, sx, true);
             } else {
-                if (all_in_range || ktw < KT) dma_w(d - XIL, ktw, sw, false);
-                else if (STREAM && has_next) dma_w(d - XIL, ktw - KT, sw, true);
+                if (all_in_range || ktw < KT) dma_w(d - XIL, ktw, sw, false, NTM);
+                else if (STREAM && has_next) dma_w(d - XIL, ktw - KT, sw, true, NTM);
             }
         };
         if (first) {
@@ -454,18 +481,44 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
             for (int r = 0; r < NREADS; ++r) read_one(r, 0, 0, 0, 0, TAIL);
         }
 
-        auto iteration = [&](int kt, auto steady_tag) {
+        // LDS reads that follow MFMA i of a k-step, for the step after it.  Evenly spread in order of first use;
+        // with single-buffered token fragments a row block's fragment follows the last MFMA that reads it and the
+        // weight fragments fill the other slots.
+        auto reads_after = [&](int i, int sx, int sw, int kk, int buf) __attribute__((always_inline)) {
+            if constexpr (C::XROLL) {
+                // first half of the step: the second-half weight blocks for the next step (into the other buffer);
+                // second half: the first-half weight blocks (in place, their last use is over) and, behind the
+                // last MFMA of each row block, that block's token fragment (in place)
+                constexpr int HB = NBW / 2, H = HB * NMB;
+                static_assert(!C::XROLL || (NBW % 2 == 0 && H >= NBW && NMB * (HB - 1) >= NBW), "reads fit their slots");
+                if (i < H) {
+                    if (i < NBW) read_one(1 + NBW + i, sx, sw, kk, buf, TAIL);
+                } else {
+                    const int mb = (i - H) / HB, p = (i - H) % HB;
+                    if (p == HB - 1) read_one(mb == 0 ? 0 : WREADS + mb, sx, sw, kk, buf, TAIL);
+                    else if (mb * (HB - 1) + p < NBW) read_one(1 + mb * (HB - 1) + p, sx, sw, kk, buf, TAIL);
+                }
+            } else {
+#pragma unroll
+                for (int r = i * NREADS / NM; r < (i + 1) * NREADS / NM; ++r) read_one(r, sx, sw, kk, buf, TAIL);
+            }
+        };
+        // ring_tag >= 0: the ring position is that compile-time value (the loop is unrolled over the ring, so
+        // every LDS address is a register plus a constant); -1: it is the run-time value in cur / curw
+        auto iteration = [&](int kt, auto steady_tag, auto ring_tag) __attribute__((always_inline)) {
             constexpr bool STEADY = decltype(steady_tag)::value;  // kt + NSW < KT: every fetch below is in range
+            constexpr int RING = decltype(ring_tag)::value;
             const bool more = STEADY || (STREAM && has_next);     // every fetch below has a target
+            const int cur = RING >= 0 ? RING : cur_rt;
+            const int curw = RING >= 0 ? RING : curw_rt;
             const int nxt = cur + 1 == NS ? 0 : cur + 1;
             const int nxtw = curw + 1 == NSW ? 0 : curw + 1;
 #pragma unroll
             for (int kk = 0; kk < KSTEPS - 1; ++kk) {
 #pragma unroll
                 for (int i = 0; i < NM; ++i) {
-                    mfma_one(i, kk & 1, TAIL);
-#pragma unroll
-                    for (int r = i * NREADS / NM; r < (i + 1) * NREADS / NM; ++r) read_one(r, cur, curw, kk + 1, (kk + 1) & 1, TAIL);
+                    mfma_one(i, NMB, kk & 1, TAIL);
+                    reads_after(i, cur, curw, kk + 1, (kk + 1) & 1);
                     MOE_SCHED_FENCE();
                 }
             }
@@ -477,26 +530,40 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
             MOE_SCHED_FENCE();
 #pragma unroll
             for (int i = 0; i < NM; ++i) {
-                mfma_one(i, (KSTEPS - 1) & 1, TAIL);
-                if (more || kt + 1 < KT) {
-#pragma unroll
-                    for (int r = i * NREADS / NM; r < (i + 1) * NREADS / NM; ++r) read_one(r, nxt, nxtw, 0, KSTEPS & 1, TAIL);
-                }
+                mfma_one(i, NMB, (KSTEPS - 1) & 1, TAIL);
+                if (more || kt + 1 < KT) reads_after(i, nxt, nxtw, 0, KSTEPS & 1);
 #pragma unroll
                 for (int d = i * ND / NM; d < (i + 1) * ND / NM; ++d) dma_one(d, kt + NS, kt + NSW, cur, curw, STEADY);
                 MOE_SCHED_FENCE();
             }
-            cur = nxt;
-            curw = nxtw;
+            if constexpr (RING < 0) {
+                cur_rt = nxt;
+                curw_rt = nxtw;
+            }
         };
+        using rt_ring = std::integral_constant<int, -1>;
         int kt = 0;
-        for (; kt + NSW < KT; ++kt) iteration(kt, std::true_type{});
-        if constexpr (STREAM) {
-            // the following tile's row ids were requested before the loop: turn them into its token-row offsets
-            // now, just before the iterations that start fetching it
-            if (has_next) stream_rows_finish(tc_next, rows_v_next, dx_next);
+        if constexpr (C::STATIC_RING && !STREAM) {
+            // the rings are at position 0 here and come back to it after every NS iterations
+            for (; kt + NSW + NS - 1 < KT; kt += NS) {
+                auto one = [&](auto u_tag) __attribute__((always_inline)) { iteration(kt + decltype(u_tag)::value, std::true_type{}, u_tag); };
+                for_each_int<0, NS - 1>(one);
+            }
         }
-        for (; kt < KT; ++kt) iteration(kt, std::false_type{});
+        for (; kt + NSW < KT; ++kt) iteration(kt, std::true_type{}, rt_ring{});
+        if constexpr (STREAM) {
+            // the following tile's token-row offsets, just before the iterations that start fetching it; the
+            // n-tiles of one (expert, m-tile) follow each other and share their rows
+            if (has_next) {
+                if (tc_next.row_base == tc.row_base && tc_next.rows == tc.rows) {
+                    rows_v_next = rows_v;
+                    dx_next = dx_off[0];
+                } else {
+                    stream_rows(tc_next, rows_v_next, dx_next);
+                }
+            }
+        }
+        for (; kt < KT; ++kt) iteration(kt, std::false_type{}, rt_ring{});
     };
 
     char* Yb = static_cast<char*>(a.Y);
@@ -518,7 +585,6 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
                 ts->next_B += 1;
                 Wt_next = w_base(tc_next);
                 w_once_next = nt_ok && tc_next.m_tiles == 1;
-                stream_rows_issue(tc_next);
             }
         }
 #pragma unroll
@@ -529,14 +595,32 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
                 for (int j = 0; j < C::ACC; ++j) acc[nb][mb][j] = 0.f;
 
         using std::integral_constant;
-        if (C::SLACK > 0 && tc.rows > C::BM) {
+        auto run_nt = [&](auto nmb_tag, auto xil_tag, auto tail_tag) __attribute__((always_inline)) {
+            run(nmb_tag, xil_tag, tail_tag, integral_constant<int, C::BM <= 128 ? 2 : 0>{});
+        };
+        if constexpr (C::XROLL) {
+            // 16-row blocks: every wavefront runs the copy of the loop compiled for its own number of live blocks
+            // (the copies agree in their barriers and DMA instructions, so wavefronts of one workgroup may differ);
+            // fewer than half the body's blocks only happens when the launch has no narrower task function.
+            const bool over = C::SLACK > 0 && tc.rows > C::BM;
+            bool done = false;
+            auto try_nmb = [&](auto nmb_tag) __attribute__((always_inline)) {
+                if (!done && mb_live == decltype(nmb_tag)::value) {
+                    if (over) { if constexpr (C::SLACK > 0 && decltype(nmb_tag)::value >= C::MBW_BODY) run_nt(nmb_tag, integral_constant<int, XI>{}, std::false_type{}); }
+                    else { if constexpr (decltype(nmb_tag)::value <= C::MBW_BODY) run_nt(nmb_tag, integral_constant<int, XI_BODY>{}, std::false_type{}); }
+                    done = true;
+                }
+            };
+            for_each_int<C::MBW_BODY / 2, MBW>(try_nmb);
+            if (!done) run_nt(integral_constant<int, C::MBW_BODY>{}, integral_constant<int, XI_BODY>{}, std::true_type{});
+        } else if (C::SLACK > 0 && tc.rows > C::BM) {
             // every wavefront moves its share of the slack rows; only those whose slack block holds a real row compute it
-            if (mb_live == MBW) run(integral_constant<int, MBW>{}, integral_constant<int, XI>{}, std::false_type{});
-            else run(integral_constant<int, C::MBW_BODY>{}, integral_constant<int, XI>{}, std::false_type{});
+            if (mb_live == MBW) run_nt(integral_constant<int, MBW>{}, integral_constant<int, XI>{}, std::false_type{});
+            else run_nt(integral_constant<int, C::MBW_BODY>{}, integral_constant<int, XI>{}, std::false_type{});
         } else if (STREAM || mb_live == C::MBW_BODY) {
-            run(integral_constant<int, C::MBW_BODY>{}, integral_constant<int, XI_BODY>{}, std::false_type{});
+            run_nt(integral_constant<int, C::MBW_BODY>{}, integral_constant<int, XI_BODY>{}, std::false_type{});
         } else {
-            run(integral_constant<int, C::MBW_BODY>{}, integral_constant<int, XI_BODY>{}, std::true_type{});
+            run_nt(integral_constant<int, C::MBW_BODY>{}, integral_constant<int, XI_BODY>{}, std::true_type{});
         }
         if (!(STREAM && has_next)) wait_vmcnt<0>();  // a following tile's loads stay in flight across the epilogue
 

@@ -68,6 +68,7 @@ SWIGLU_BF16 = [
     # tile_m, tile_n, slack, T, E, k, K, N, routing
     (256, 256, 0, 700, 8, 2, 128, 512, "zipf"),        # full tiles, 128- and 64-row tail functions
     (256, 256, 64, 1100, 8, 2, 128, 256, "gauss_topk"),  # counts just above 256: slack block in use
+    (256, 256, 32, 1100, 8, 2, 128, 256, "gauss_topk"),
     (128, 256, 0, 300, 8, 2, 128, 512, "zipf"),
     (128, 128, 0, 300, 8, 2, 128, 256, "gauss_topk"),
     (64, 256, 0, 150, 8, 2, 192, 512, "zipf"),

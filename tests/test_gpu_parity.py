@@ -268,18 +268,20 @@ def _ids_from_counts(counts, seed):
 
 
 SLACK_CASES = [
-    # per-expert row counts (k = 1), K, N    (tile 256 x 256, slack 64)
+    # per-expert row counts (k = 1), K, N    (tile 256 x 256, slack 64 and 32)
     ([257, 320, 321, 256, 1, 64, 65, 0, 576, 639, 640, 641], 128, 256),
     ([300, 0, 0, 513, 129, 255, 319], 192, 512),
     ([1025, 1040, 991, 1055], 64, 256),     # the remainders of the Mixtral benchmark point
+    ([288, 289, 272, 273, 257, 130, 200, 231, 17, 544, 545], 256, 256),   # every count of live 16-row blocks
 ]
 
 
+@pytest.mark.parametrize("slack", [64, 32])
 @pytest.mark.parametrize("order", [0, 1, 2], ids=["ascending", "spread", "interleave"])
 @pytest.mark.parametrize("counts,K,N", SLACK_CASES)
-def test_slack_rows_parity(dev, oracle_mod, counts, K, N, order):
-    """Last m-tiles with up to tile_m + 64 rows: map bit-exact, expanded table == nested-loop table, Y == oracle."""
-    E, T, slack = len(counts), int(sum(counts)), 64
+def test_slack_rows_parity(dev, oracle_mod, counts, K, N, order, slack):
+    """Last m-tiles with up to tile_m + slack rows: map bit-exact, expanded table == nested-loop table, Y == oracle."""
+    E, T = len(counts), int(sum(counts))
     tiling = mb.Tiling(256, 256, order, 0, 0, slack)
     assert mb.moe_tiling_supported(mb.MOE_DTYPE_BF16, tiling)
     wl = wk.Workload("parity_slack", T, E, 1, K, N, "bf16", "gauss_topk", 256, 256)
@@ -316,7 +318,10 @@ def test_slack_mismatch_is_a_noop(dev):
     mb.moe_grouped_gemm(X, W, ids, plain, Y, mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 256, 256, tile_m_slack=64))
     torch.cuda.synchronize()
     assert bool(torch.isnan(Y).all())
-    d = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 256, 256, tile_m_slack=32)
+    mb.moe_grouped_gemm(X, W, ids, with_slack, Y, mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 256, 256, tile_m_slack=32))
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(Y).all())
+    d = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 256, 256, tile_m_slack=128)
     assert mb.moe_grouped_gemm(X, W, ids, with_slack, Y, d, check=False) == mb.MOE_ERR_UNSUPPORTED
     g = mb.Tiling(256, 256, 0, 0, 0, 256)
     assert mb.moe_build_task_map_ex(ids, T, 1, E, N, g, with_slack, check=False) == mb.MOE_ERR_INVALID_ARG

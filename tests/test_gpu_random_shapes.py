@@ -35,7 +35,7 @@ def _case(seed):
     routing = str(rng.choice(["gauss_topk", "zipf", "uniform_topk"]))
     opt = dict(order=int(rng.integers(0, 3)), slack=0, swiglu=bool(rng.random() < 0.4), nk=False, stream=0)
     if (tile_m, tile_n) == (256, 256) and not fp8 and rng.random() < 0.5:
-        opt["slack"] = 64
+        opt["slack"] = 64 if T % 2 == 0 else 32
     if tile_m == 16:
         opt["stream"] = int(rng.choice([0, 1, 8, 16]))
     return fp8, tile_m, tile_n, E, k, T, K, N, routing, opt, rng
