@@ -57,6 +57,8 @@ class Point:
         self.order = order
         self.small = small  # (tile_m_small, small_max_rows) of the second tiling strategy, or (0, 0)
         self.slack = 0 if small[0] else wl.tile_m_slack  # no kernel combines the two
+        if w_nk and self.slack == 32:
+            self.slack = 64   # the pre-packed layout has the 64-row slack kernel only
         self.dev = dev
         self.ids_cpu = wk.make_routing(wl)
         self.ids = self.ids_cpu.to(dev)

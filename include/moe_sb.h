@@ -187,7 +187,9 @@ typedef struct moe_tiling {
                                  tile_m_slack rows does not open a nearly empty tile of its own:
                                      m_tiles(c) = max(1, ceil((c - tile_m_slack) / tile_m))  for c > 0.
                                  Tile m of the expert starts at row m * tile_m of its segment; all
-                                 tiles but the last hold tile_m rows.  0 <= tile_m_slack < tile_m. */
+                                 tiles but the last hold tile_m rows.  0 <= tile_m_slack < tile_m.
+                                 GEMM kernels exist for 256 x 256 bf16 tiles with 32 (the faster one, on
+                                 16-row MFMA blocks) or 64 slack rows; moe_tiling_supported tells. */
 } moe_tiling;
 
 /*
@@ -204,7 +206,7 @@ int moe_build_task_map_ex(const int32_t* topk_ids, int T, int k, int E, int N, c
  *   fp8 (the decode regime): 16-row tiles, 256 wide when that gives between one and two workgroups per CU, else 128;
  *   bf16: up to 8 rows per expert 16 x 256; from 48 to 96 rows 128 x 256 when there are enough n-tiles to fill
  *   the chip three times over, else 64 x 256; otherwise 256 x 256 (its launch handles tiles of at most 64 and
- *   128 rows with narrower task functions), with 64 slack rows above 192 rows per expert.
+ *   128 rows with narrower task functions), with 32 slack rows above 192 rows per expert.
  * Always ascending order, one strategy.  The result satisfies moe_tiling_supported when N % tile_n == 0 allows
  * it (tile_n falls back to 128 or 64).  Returns MOE_ERR_INVALID_ARG on bad arguments, MOE_ERR_UNSUPPORTED when
  * no kernel fits (N not a multiple of 64).

@@ -112,8 +112,6 @@ struct PipeCfg {
     // Large tiles on 16-row MFMA blocks hold twice as many fragments per k-step: the token fragments are then
     // single-buffered, each reloaded for the next k-step as soon as the MFMAs of its row block are issued.
     static constexpr bool XROLL = MFO_ == 16;
-    // unroll the k loop over the ring so that ring positions are compile-time constants
-    static constexpr bool STATIC_RING = false && NS_ == NSW_ && NS_ == 2 && BM_ >= 256;
     static constexpr int XROW = BK * ES, CPR = XROW / 16;
     static constexpr int WROW = BN * ES, CPRW = WROW / 16;
     // the token tile in LDS is rounded up so that every wavefront issues the same number of DMA instructions
@@ -446,7 +444,7 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
     };
 
     TileCoord tc_next = tc;       // streaming: the tile after the current one
-    int cur_rt = 0, curw_rt = 0;  // ring positions; they run on from tile to tile when streaming
+    int cur = 0, curw = 0;        // ring positions; they run on from tile to tile when streaming
     bool first = true;            // the rings are empty: fill them before the loop
     bool has_next = false;        // streaming: another tile follows, its first k-tiles are fetched by this tile's last iterations
 
@@ -503,14 +501,9 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
                 for (int r = i * NREADS / NM; r < (i + 1) * NREADS / NM; ++r) read_one(r, sx, sw, kk, buf, TAIL);
             }
         };
-        // ring_tag >= 0: the ring position is that compile-time value (the loop is unrolled over the ring, so
-        // every LDS address is a register plus a constant); -1: it is the run-time value in cur / curw
-        auto iteration = [&](int kt, auto steady_tag, auto ring_tag) __attribute__((always_inline)) {
+        auto iteration = [&](int kt, auto steady_tag) __attribute__((always_inline)) {
             constexpr bool STEADY = decltype(steady_tag)::value;  // kt + NSW < KT: every fetch below is in range
-            constexpr int RING = decltype(ring_tag)::value;
             const bool more = STEADY || (STREAM && has_next);     // every fetch below has a target
-            const int cur = RING >= 0 ? RING : cur_rt;
-            const int curw = RING >= 0 ? RING : curw_rt;
             const int nxt = cur + 1 == NS ? 0 : cur + 1;
             const int nxtw = curw + 1 == NSW ? 0 : curw + 1;
 #pragma unroll
@@ -536,21 +529,11 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
                 for (int d = i * ND / NM; d < (i + 1) * ND / NM; ++d) dma_one(d, kt + NS, kt + NSW, cur, curw, STEADY);
                 MOE_SCHED_FENCE();
             }
-            if constexpr (RING < 0) {
-                cur_rt = nxt;
-                curw_rt = nxtw;
-            }
+            cur = nxt;
+            curw = nxtw;
         };
-        using rt_ring = std::integral_constant<int, -1>;
         int kt = 0;
-        if constexpr (C::STATIC_RING && !STREAM) {
-            // the rings are at position 0 here and come back to it after every NS iterations
-            for (; kt + NSW + NS - 1 < KT; kt += NS) {
-                auto one = [&](auto u_tag) __attribute__((always_inline)) { iteration(kt + decltype(u_tag)::value, std::true_type{}, u_tag); };
-                for_each_int<0, NS - 1>(one);
-            }
-        }
-        for (; kt + NSW < KT; ++kt) iteration(kt, std::true_type{}, rt_ring{});
+        for (; kt + NSW < KT; ++kt) iteration(kt, std::true_type{});
         if constexpr (STREAM) {
             // the following tile's token-row offsets, just before the iterations that start fetching it; the
             // n-tiles of one (expert, m-tile) follow each other and share their rows
@@ -563,7 +546,7 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
                 }
             }
         }
-        for (; kt < KT; ++kt) iteration(kt, std::false_type{}, rt_ring{});
+        for (; kt < KT; ++kt) iteration(kt, std::false_type{});
     };
 
     char* Yb = static_cast<char*>(a.Y);

@@ -262,7 +262,7 @@ int moe_default_tiling(int dtype, int T, int k, int E, int K, int N, moe_tiling*
     } else {
         // 256-row tiles; their launch runs tiles of at most 64 / 128 rows with narrower task functions, which
         // covers the small counts too.  Slack rows pay once experts hold several tiles.
-        g.tile_m = 256; g.tile_n = 256; g.tile_m_slack = mean_rows > 192 ? 64 : 0;
+        g.tile_m = 256; g.tile_n = 256; g.tile_m_slack = mean_rows > 192 ? 32 : 0;
     }
     // the n-tile must divide N; narrower tiles keep the same row tiling where a kernel exists
     for (int tn = g.tile_n; tn >= 64; tn >>= 1) {

@@ -72,7 +72,7 @@ def tiny(T: int = 64) -> Workload:
 
 def mixtral_up(T: int) -> Workload:
     tm = 256 if T >= 2048 else (128 if T >= 256 else 16)
-    return Workload("mixtral_up", T, 8, 2, 4096, 28672, "bf16", "gauss_topk", tm, 256, 64 if tm == 256 else 0)
+    return Workload("mixtral_up", T, 8, 2, 4096, 28672, "bf16", "gauss_topk", tm, 256, 32 if tm == 256 else 0)
 
 
 def mixtral_down_zipf(T: int) -> Workload:
@@ -82,7 +82,7 @@ def mixtral_down_zipf(T: int) -> Workload:
 
 def fine_grained(T: int) -> Workload:
     tm = 256 if T >= 8192 else (128 if T >= 2048 else 16)
-    return Workload("fine_grained", T, 256, 8, 7168, 4096, "bf16", "gauss_topk", tm, 256, 64 if tm == 256 else 0)
+    return Workload("fine_grained", T, 256, 8, 7168, 4096, "bf16", "gauss_topk", tm, 256, 32 if tm == 256 else 0)
 
 
 def decode_fp8(T: int) -> Workload:

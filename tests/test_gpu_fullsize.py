@@ -107,7 +107,7 @@ FULL = [
     # workload, samples per tile, complete rows, sigma order
     (wk.mixtral_up(4096), 8, 64, 0),
     (wk.mixtral_up(4096).with_T(4096, tile_m_slack=0), 8, 64, 0),   # the same point with the plain ceil tiling
-    (wk.mixtral_up(4096).with_T(4096, tile_m_slack=32), 8, 64, 0),  # and with 32 slack rows (16-row MFMA blocks)
+    (wk.mixtral_up(4096).with_T(4096, tile_m_slack=64), 8, 64, 0),  # and with 64 slack rows (32-row MFMA blocks)
     (wk.mixtral_up(256), 8, 32, 0),
     (wk.mixtral_up(16), 8, 32, 0),
     (wk.mixtral_down_zipf(4096), 8, 64, 0),
