@@ -33,7 +33,7 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per GEMM launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a
 # copy kernel of known size; see profiles/.  None where it has not been measured.
-MEASURED_TRAFFIC_BYTES = {"mixtral_up_T4096": 3.842e9}
+MEASURED_TRAFFIC_BYTES = {"mixtral_up_T4096": 3.308e9}
 
 
 def algorithmic_bytes(wl: wk.Workload, ids: torch.Tensor, swiglu: bool = False) -> int:
@@ -261,6 +261,10 @@ def main():
     ap.add_argument("--dense-reference", action="store_true",
                     help="also time the tensor library's dense bf16 matmul of the same size and weight layout "
                          "([T*k, K] x [K, N]) on random data; reported under 'dense_reference'")
+    ap.add_argument("--mfma-probe", action="store_true",
+                    help="also time the library's pure-MFMA probe (no memory traffic) with 16x16x32 and 32x32x16 blocks "
+                         "on random and on constant operands: the sustained ceiling under the chip's power limit; "
+                         "reported under 'mfma_probe'")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (a kernel of known traffic to scale profiler byte counters by)")
     args = ap.parse_args()
@@ -316,6 +320,24 @@ def main():
         out["operand_fill"] = {"fill": args.operand_fill, "kernel_ms": round(g_ms, 4),
                                "tflops": round(wl.flops / (g_ms * 1e-3) / 1e12, 2),
                                "random_kernel_ms": head["gemm_ms"]}
+    if args.mfma_probe:
+        sink = torch.zeros(4, dtype=torch.float32, device="cuda:0")
+        iters = 100000
+        flops = 256 * 8 * iters * 524288
+        res = []
+        for block in (32, 16):
+            for rnd in (False, True):
+                mb.moe_debug_mfma_probe(block, rnd, 1000, sink)
+                ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+                torch.cuda.synchronize()
+                ev[0].record()
+                mb.moe_debug_mfma_probe(block, rnd, iters, sink)
+                ev[1].record()
+                torch.cuda.synchronize()
+                ms = ev[0].elapsed_time(ev[1])
+                res.append({"block": f"{block}x{block}x{512 // block}", "operands": "random" if rnd else "constant",
+                            "ms": round(ms, 3), "tflops": round(flops / (ms * 1e-3) / 1e12, 1)})
+        out["mfma_probe"] = res
     if args.dense_reference:
         A = torch.randn((wl.R, wl.K), device="cuda:0").to(torch.bfloat16)
         B = torch.randn((wl.K, wl.N), device="cuda:0").to(torch.bfloat16)

@@ -294,6 +294,15 @@ int moe_combine(const void* Y, const float* topk_weights, int T, int k, int N, v
  * multiple of 8).  Results are identical in every mode.  Process-wide, not thread-safe. */
 void moe_debug_streaming(int mode);
 
+/* Measurement aid: the chip's sustained MFMA rate without any memory traffic, the ceiling every bf16 GEMM here
+ * is under.  Enqueues one kernel of 256 workgroups x 512 threads in which every wavefront issues
+ * iters x 512 KFLOP of bf16 MFMAs on register operands (32 accumulators of 16x16x32 when block == 16,
+ * 8 accumulators of 32x32x16 when block == 32); operands are pseudo-random bf16 values when
+ * random_operands != 0, else the constant 1.0 (the rate depends on the operand values: switching power).
+ * FLOPs of the launch = 256 * 8 * iters * 524288.  `sink` is DEVICE memory of at least 4 bytes that the kernel
+ * may write.  Returns MOE_ERR_INVALID_ARG for another block size, iters < 1 or a NULL sink. */
+int moe_debug_mfma_probe(int block, int random_operands, int iters, void* sink, void* stream);
+
 /* Static string for a return code. */
 const char* moe_strerror(int code);
 

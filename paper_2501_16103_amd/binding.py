@@ -44,7 +44,7 @@ EXPORTS = [
     "moe_build_task_map_ordered", "moe_build_task_map_tiled", "moe_grid_upper_bound_tiled", "moe_tile_pair_supported",
     "moe_build_task_map_ex", "moe_tiling_supported", "moe_w_layout_supported", "moe_default_tiling",
     "moe_task_map_status", "moe_task_map_expand", "moe_grouped_gemm", "moe_tile_supported", "moe_combine",
-    "moe_debug_streaming", "moe_strerror",
+    "moe_debug_streaming", "moe_debug_mfma_probe", "moe_strerror",
 ]
 
 
@@ -118,6 +118,8 @@ def lib() -> ctypes.CDLL:
                                   ctypes.c_void_p, ctypes.c_void_p]
         L.moe_debug_streaming.restype = None
         L.moe_debug_streaming.argtypes = [ctypes.c_int]
+        L.moe_debug_mfma_probe.restype = ctypes.c_int
+        L.moe_debug_mfma_probe.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
         L.moe_strerror.restype = ctypes.c_char_p
         L.moe_strerror.argtypes = [ctypes.c_int]
         _lib = L
@@ -293,3 +295,12 @@ def moe_combine(Y: torch.Tensor, topk_weights: Optional[torch.Tensor], T: int, k
 
 def moe_debug_streaming(mode: int) -> None:
     lib().moe_debug_streaming(int(mode))
+
+
+def moe_debug_mfma_probe(block: int, random_operands: bool, iters: int, sink, check: bool = True) -> int:
+    """One launch of the pure-MFMA probe; FLOPs = 256 * 8 * iters * 524288.  `sink`: device tensor of >= 4 bytes."""
+    rc = lib().moe_debug_mfma_probe(int(block), int(bool(random_operands)), int(iters), _ptr(sink),
+                                    _stream() if sink is not None else None)
+    if check and rc != MOE_OK:
+        raise MoeError(rc, "moe_debug_mfma_probe")
+    return rc

@@ -807,4 +807,64 @@ __global__ __launch_bounds__(C::NT) void moe_gemm_stream_kernel(GemmArgs a) {
     pipe_tile<C, true>(a, map, L, tc, smem, &ts);
 }
 
+// Measurement aid: bf16 MFMAs on register operands and nothing else, two wavefronts per SIMD (512 threads, one
+// workgroup per CU).  Per loop trip and wavefront 512 KFLOP: 32 MFMAs of 16x16x32 or 16 of 32x32x16, every
+// accumulator independent of the others, 128 accumulator registers either way.
+template <int BLOCK, bool RANDOM>
+__global__ void __launch_bounds__(512) mfma_probe_kernel(int iters, float* sink) {
+    auto bits = [](uint32_t i) {   // two bf16 values of magnitude 2^-3 .. 2, random sign and mantissa
+        uint32_t h = i * 2654435761u;
+        h ^= h >> 15; h *= 2246822519u; h ^= h >> 13; h *= 3266489917u; h ^= h >> 16;
+        const uint32_t lo = (h & 0x807fu) | (0x3e00u + ((h >> 16) & 0x0180u));
+        const uint32_t hi = ((h >> 8) & 0x807fu) | (0x3e00u + ((h >> 20) & 0x0180u));
+        return RANDOM ? (lo | (hi << 16)) : 0x3f803f80u;
+    };
+    const uint32_t seed = (blockIdx.x * 977u + threadIdx.x) * 64u;
+    bf16x8_t fa[4], fb[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const u32x4_t v = {bits(seed + 4 * i), bits(seed + 4 * i + 1), bits(seed + 4 * i + 2), bits(seed + 4 * i + 3)};
+        fa[i] = __builtin_bit_cast(bf16x8_t, v);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const u32x4_t v = {bits(seed + 16 + 4 * i), bits(seed + 17 + 4 * i), bits(seed + 18 + 4 * i), bits(seed + 19 + 4 * i)};
+        fb[i] = __builtin_bit_cast(bf16x8_t, v);
+    }
+    float sum = 0.f;
+    if constexpr (BLOCK == 16) {
+        f32x4_t acc[32];
+#pragma unroll
+        for (int i = 0; i < 32; ++i) acc[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[i * 8 + j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb[j], acc[i * 8 + j], 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 32; ++i) sum += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
+    } else {
+        f32x16_t acc[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        acc[i * 4 + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i + 2 * h], fb[j + 4 * h], acc[i * 4 + j], 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) sum += acc[i][j];
+    }
+    if (sum == 12345.f) sink[0] = sum;   // keeps the loop alive; practically never true
+}
+
 }  // namespace moe

@@ -427,6 +427,20 @@ int moe_combine(const void* Y, const float* topk_weights, int T, int k, int N, v
 
 void moe_debug_streaming(int mode) { g_stream_mode = mode < 0 ? 0 : mode; }
 
+int moe_debug_mfma_probe(int block, int random_operands, int iters, void* sink, void* stream) {
+    if ((block != 16 && block != 32) || iters < 1 || !sink) return MOE_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float* out = static_cast<float*>(sink);
+    if (block == 16) {
+        if (random_operands) moe::mfma_probe_kernel<16, true><<<256, 512, 0, s>>>(iters, out);
+        else moe::mfma_probe_kernel<16, false><<<256, 512, 0, s>>>(iters, out);
+    } else {
+        if (random_operands) moe::mfma_probe_kernel<32, true><<<256, 512, 0, s>>>(iters, out);
+        else moe::mfma_probe_kernel<32, false><<<256, 512, 0, s>>>(iters, out);
+    }
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
 const char* moe_strerror(int code) {
     switch (code) {
         case MOE_OK: return "ok";

@@ -80,6 +80,13 @@ def test_null_arguments_rejected_on_host():
     assert lib.moe_task_map_expand(None, 8, None, 0, None) == mb.MOE_ERR_INVALID_ARG
 
 
+def test_mfma_probe_rejects_bad_arguments_before_any_launch():
+    lib = mb.lib()
+    assert lib.moe_debug_mfma_probe(8, 1, 10, None, None) == mb.MOE_ERR_INVALID_ARG
+    assert lib.moe_debug_mfma_probe(16, 1, 10, None, None) == mb.MOE_ERR_INVALID_ARG   # no sink
+    assert lib.moe_debug_mfma_probe(32, 0, 0, 1, None) == mb.MOE_ERR_INVALID_ARG        # no iterations
+
+
 def test_default_tiling_is_supported_and_matches_the_benchmark_choices():
     """Host-only: the heuristic returns a tiling a kernel exists for, and reproduces the tilings the benchmark
     points were tuned to (slack rows aside, where the heuristic always enables them for 256-row tiles)."""

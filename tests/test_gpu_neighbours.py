@@ -337,3 +337,13 @@ def test_step_captured_in_a_graph_replays_exactly(dev):
         torch.cuda.synchronize()
         assert torch.equal(Y.view(torch.int16), want_Y.view(torch.int16)), f"replay {it}: Y differs"
         assert torch.equal(out.view(torch.int16), want_out.view(torch.int16)), f"replay {it}: combine differs"
+
+
+def test_mfma_probe_runs(dev):
+    """The measurement probe launches and completes for both block shapes and operand kinds."""
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    for block in (16, 32):
+        for rnd in (False, True):
+            assert mb.moe_debug_mfma_probe(block, rnd, 50, sink) == mb.MOE_OK
+    torch.cuda.synchronize()
+    assert float(sink.abs().sum()) == 0.0
