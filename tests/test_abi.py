@@ -105,3 +105,22 @@ def test_default_tiling_is_supported_and_matches_the_benchmark_choices():
         mb.moe_default_tiling(mb.MOE_DTYPE_BF16, 8, 2, 16, 256, 100)
     with pytest.raises(mb.MoeError):
         mb.moe_default_tiling(mb.MOE_DTYPE_BF16, 8, 20, 16, 256, 128)
+
+
+def test_every_scalar_load_in_inline_asm_waits_in_the_same_statement():
+    """Host-only source check.  The compiler takes an asm statement's outputs as available when the statement
+    ends; a scalar load left in flight across statements can have its destination registers spilled and
+    reused before the data arrives (this produced wild row ids once).  So every asm string that issues a
+    scalar load must also contain the wait for it."""
+    import os
+    import re
+    root = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2501_16103_amd", "csrc")
+    seen = 0
+    for name in sorted(os.listdir(root)):
+        text = open(os.path.join(root, name)).read()
+        for m in re.finditer(r"asm\s+volatile\s*\((.*?)\)\s*;", text, re.S):
+            body = m.group(1)
+            if "s_load" in body or "s_buffer_load" in body:
+                seen += 1
+                assert "s_waitcnt lgkmcnt(0)" in body, f"{name}: scalar load without its wait in the same asm statement"
+    assert seen >= 1
