@@ -103,7 +103,7 @@ using Pb_256x256s32 = PipeCfg<256, 256, 64, 2, 4, 2, false, 2, 32, false, 16>;
 using Pb_128x256 = PipeCfg<128, 256, 64, 1, 4, 3>;
 using Pb_128x128 = PipeCfg<128, 128, 64, 2, 2, 4>;
 using Pb_64x256 = PipeCfg<64, 256, 64, 1, 4, 3>;
-using Pb_64x128 = PipeCfg<64, 128, 64, 1, 4, 4>;
+using Pb_64x128 = PipeCfg<64, 128, 64, 1, 4, 3>;   // 72 KB: two workgroups per CU
 using Pb_32x256 = PipeCfg<32, 256, 64, 1, 4, 4>;
 using Pb_32x128 = PipeCfg<32, 128, 64, 1, 4, 6>;
 // Narrow task functions that share the launch shape (512 threads, 256-wide n-tiles) of Pb_256x256: used for its
@@ -252,6 +252,10 @@ int moe_default_tiling(int dtype, int T, int k, int E, int K, int N, moe_tiling*
         const double t256 = (hit + (double)(R / 16)) * ((N + 255) / 256);
         g.tile_m = 16;
         g.tile_n = (N % 256 == 0 && t256 >= cus && t256 <= 2 * cus) ? 256 : 128;
+    } else if (mean_rows <= 48 && active * ((N + 255) / 256) < cus && N % 128 == 0) {
+        // too few 256-wide tiles to give every CU one: halve the tile width; 128 rows also hold a skewed
+        // routing's busiest expert in one tile
+        g.tile_m = 128; g.tile_n = 128;
     } else if (mean_rows <= 8) {
         // nearly every expert's rows fit one 16-row tile (count ~ mean +- 3 sqrt(mean))
         g.tile_m = 16; g.tile_n = 256;
