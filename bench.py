@@ -389,6 +389,11 @@ def main():
             points.append(p.report(max(10, args.steps // 2), max(3, args.warmup // 2)))
             del p
             torch.cuda.empty_cache()
+            # labelled extra: the fp8 layer of the decode points at a prefill size (256-row fp8 tiles)
+            p = Point(wk.decode_fp8(4096))
+            points.append(p.report(max(10, args.steps // 2), max(3, args.warmup // 2)))
+            del p
+            torch.cuda.empty_cache()
             # labelled extra: the same products with the weights pre-packed as [E][N][K]
             for w in (wl, wk.mixtral_up(256), wk.mixtral_up(16), wk.decode_fp8(32), wk.decode_fp8(8)):
                 copies = 1

@@ -203,7 +203,8 @@ int moe_build_task_map_ex(const int32_t* topk_ids, int T, int k, int E, int N, c
 /*
  * A reasonable tiling for a problem shape, from the measurements behind this library (HOST, pure; the routing
  * itself is not known to the host, so the choice goes by the mean rows per expert T*k/E):
- *   fp8 (the decode regime): 16-row tiles, 256 wide when that gives between one and two workgroups per CU, else 128;
+ *   fp8: up to 24 rows per expert (the decode regime) 16-row tiles, 256 wide when that gives between one and two
+ *   workgroups per CU, else 128; up to 96 rows 64 x 256; above that 256 x 256;
  *   bf16: up to 48 rows per expert 128 x 128 when 256-wide tiles would leave CUs without one; else up to
  *   8 rows 16 x 256; from 48 to 96 rows 128 x 256 when there are enough n-tiles to fill
  *   the chip three times over, else 64 x 256; otherwise 256 x 256 (its launch handles tiles of at most 64 and

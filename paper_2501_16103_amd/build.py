@@ -3,7 +3,9 @@ from __future__ import annotations
 
 import os
 import re
+import shutil
 import subprocess
+import tempfile
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB = os.path.join(HERE, "libmoe_sb.so")
@@ -16,32 +18,41 @@ HIPCC_FLAGS = [
 ]
 
 
-# The GEMM kernels count their global->LDS DMA instructions in vmcnt by hand, and register spills are vector
-# memory instructions that count there too: a spill inside a kernel whose waits allow DMAs in flight would let a
-# wait pass too early.  Only kernels whose every DMA wait is vmcnt(0) may spill (two-stage rings: the 256 x 256
-# tile with 32 slack rows, which sits at the 256-register limit).
-SPILL_TOLERANT = ("PipeCfgILi256ELi256ELi64ELi2ELi4ELi2ELb0ELi2ELi32E",)
-
-
-def check_spills(remarks: str) -> None:
-    name = None
-    for line in remarks.splitlines():
-        m = re.search(r"remark: Function Name: (\S+)", line)
-        if m:
-            name = m.group(1)
-            continue
-        m = re.search(r"remark:\s+VGPRs Spill: (\d+)", line)
-        if m and int(m.group(1)) > 0 and name and "gemm" in name and not any(t in name for t in SPILL_TOLERANT):
-            raise RuntimeError(f"{name} spills {m.group(1)} vector registers: its hand-counted vmcnt waits would be wrong")
+# A register spill inside a k loop is a vector memory instruction among the hand-counted global->LDS DMAs: the
+# compiler waits for its reload with vmcnt(0), which drains the whole DMA ring every iteration (measured: a
+# third of the throughput gone).  The build therefore reads the device assembly and refuses a GEMM kernel that
+# has a scratch access inside a loop that also holds MFMAs.  (Spills outside the loops only cost their own time;
+# they cannot let a DMA wait pass early: loads retire in order and extra entries in vmcnt make a wait stricter.)
+def check_no_spill_in_k_loops(asm_text: str) -> None:
+    for m in re.finditer(r"^(_ZN3moe\S*gemm\S*):\s*(?:;.*)?$", asm_text, re.M):
+        name = m.group(1)
+        end = asm_text.find(".Lfunc_end", m.end())
+        lines = asm_text[m.end():end].splitlines()
+        label_at = {ln.split(":")[0]: k for k, ln in enumerate(lines) if ln.startswith(".LBB")}
+        for k, ln in enumerate(lines):
+            b = re.search(r"s_cbranch\w*\s+(\.LBB\d+_\d+)", ln)
+            if not b or label_at.get(b.group(1), len(lines)) >= k:
+                continue
+            body = lines[label_at[b.group(1)]:k]
+            if sum("v_mfma" in x for x in body) >= 16 and any("scratch_" in x for x in body):
+                raise RuntimeError(f"{name}: register spill inside a k loop (it would drain the DMA ring every iteration)")
 
 
 def build_library(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-Rpass-analysis=kernel-resource-usage", SRC, "-o", LIB]
-    res = subprocess.run(cmd, cwd=HERE, capture_output=True, text=True)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
-    check_spills(res.stderr)
+    with tempfile.TemporaryDirectory() as tmp:
+        out = os.path.join(tmp, "libmoe_sb.so")
+        cmd = [hipcc] + HIPCC_FLAGS + ["-save-temps=obj", SRC, "-o", out]
+        res = subprocess.run(cmd, cwd=tmp, capture_output=True, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
+        asm = [f for f in os.listdir(tmp) if f.endswith(".s") and "amdgcn" in f]
+        if not asm:
+            raise RuntimeError("no device assembly found next to the built library")
+        with open(os.path.join(tmp, asm[0])) as f:
+            check_no_spill_in_k_loops(f.read())
+        shutil.copyfile(out, LIB)
+        os.chmod(LIB, 0o755)
     if verbose:
         print(" ".join(cmd))
     return LIB

@@ -110,8 +110,12 @@ struct PipeCfg {
     static constexpr int MBW_BODY = BM / WM / MF;              // row blocks per wavefront without the slack rows
     static constexpr int ACC = MF == 32 ? 16 : 4;              // accumulator registers per block
     // Large tiles on 16-row MFMA blocks hold twice as many fragments per k-step: the token fragments are then
-    // single-buffered, each reloaded for the next k-step as soon as the MFMAs of its row block are issued.
-    static constexpr bool XROLL = MFO_ == 16;
+    // single-buffered, each reloaded for the next k-step as soon as the MFMAs of its row block are issued (XROLL).
+    // Tiles of several 16-row blocks per wavefront: every wavefront runs the loop copy compiled for its own
+    // number of live blocks (a run-time test around every MFMA defeats the software pipelining there).
+    static constexpr bool PERWAVE = MF == 16 && MBW_BODY >= 4;
+    // ... and with at least four weight blocks per wavefront the fragments are reloaded in place (see reads_after)
+    static constexpr bool XROLL = PERWAVE && WTN / MF >= 4 && !WKC_;
     static constexpr int XROW = BK * ES, CPR = XROW / 16;
     static constexpr int WROW = BN * ES, CPRW = WROW / 16;
     // the token tile in LDS is rounded up so that every wavefront issues the same number of DMA instructions
@@ -404,7 +408,7 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
             } else if constexpr (C::FP8) {
                 const int nb = r - 1;
                 const char* p = ws + w_rd[nb] + (kk * 32) * C::WROW;
-                wq[buf][nb][0] = __builtin_bit_cast(u32x2_t, __builtin_amdgcn_ds_read_tr8_b64_v2i32((MOE_LDS(i32x2_t)*)(p)));
+                wq[wbuf(buf, nb)][nb][0] = __builtin_bit_cast(u32x2_t, __builtin_amdgcn_ds_read_tr8_b64_v2i32((MOE_LDS(i32x2_t)*)(p)));
             } else {
                 const int nb = (r - 1) >> 1, half = (r - 1) & 1;
                 const char* p = ws + w_rd[nb] + (kk * C::KS + half * 4) * C::WROW;
@@ -432,7 +436,7 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
         if (tail && mb >= mb_live) return;
         if constexpr (C::FP8) {
             const u32x2_t xv = {xq[C::XROLL ? 0 : buf][mb].x, xq[C::XROLL ? 0 : buf][mb].y};
-            acc[nb][mb] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(__builtin_bit_cast(long, wq[buf][nb][0]),
+            acc[nb][mb] = __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(__builtin_bit_cast(long, wq[wbuf(buf, nb)][nb][0]),
                                                                      __builtin_bit_cast(long, xv), acc[nb][mb], 0, 0, 0);
         } else {
             const int wb = wbuf(buf, nb);
@@ -487,14 +491,14 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
                 // first half of the step: the second-half weight blocks for the next step (into the other buffer);
                 // second half: the first-half weight blocks (in place, their last use is over) and, behind the
                 // last MFMA of each row block, that block's token fragment (in place)
-                constexpr int HB = NBW / 2, H = HB * NMB;
-                static_assert(!C::XROLL || (NBW % 2 == 0 && H >= NBW && NMB * (HB - 1) >= NBW), "reads fit their slots");
+                constexpr int HB = NBW / 2, H = HB * NMB, HR = WREADS / 2;   // HR: weight reads of one half
+                static_assert(!C::XROLL || (NBW % 2 == 0 && H >= HR && NMB * (HB - 1) >= HR), "reads fit their slots");
                 if (i < H) {
-                    if (i < NBW) read_one(1 + NBW + i, sx, sw, kk, buf, TAIL);
+                    if (i < HR) read_one(1 + HR + i, sx, sw, kk, buf, TAIL);
                 } else {
                     const int mb = (i - H) / HB, p = (i - H) % HB;
                     if (p == HB - 1) read_one(mb == 0 ? 0 : WREADS + mb, sx, sw, kk, buf, TAIL);
-                    else if (mb * (HB - 1) + p < NBW) read_one(1 + mb * (HB - 1) + p, sx, sw, kk, buf, TAIL);
+                    else if (mb * (HB - 1) + p < HR) read_one(1 + mb * (HB - 1) + p, sx, sw, kk, buf, TAIL);
                 }
             } else {
 #pragma unroll
@@ -581,7 +585,7 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
         auto run_nt = [&](auto nmb_tag, auto xil_tag, auto tail_tag) __attribute__((always_inline)) {
             run(nmb_tag, xil_tag, tail_tag, integral_constant<int, C::BM <= 128 ? 2 : 0>{});
         };
-        if constexpr (C::XROLL) {
+        if constexpr (C::PERWAVE) {
             // 16-row blocks: every wavefront runs the copy of the loop compiled for its own number of live blocks
             // (the copies agree in their barriers and DMA instructions, so wavefronts of one workgroup may differ);
             // fewer than half the body's blocks only happens when the launch has no narrower task function.

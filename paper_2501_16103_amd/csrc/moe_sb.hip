@@ -117,6 +117,11 @@ using P8_16x256 = PipeCfg<16, 256, 128, 1, 2, 2, true>;
 using P8_16x128 = PipeCfg<16, 128, 128, 1, 2, 4, true>;
 using P8_16x64 = PipeCfg<16, 64, 128, 1, 2, 4, true>;
 using P8_32x128 = PipeCfg<32, 128, 128, 1, 2, 4, true>;
+// fp8 at prefill sizes: the 256 x 256 launch shape with its two narrow task functions, and a 64-row tile
+using P8_256x256 = PipeCfg<256, 256, 128, 2, 4, 2, true, 3>;
+using P8s_64x256 = PipeCfg<64, 256, 128, 1, 8, 3, true>;
+using P8s_128x256 = PipeCfg<128, 256, 128, 1, 8, 2, true>;
+using P8_64x256 = PipeCfg<64, 256, 128, 1, 4, 3, true>;
 
 // The pre-packed weight layout [E][N][K] (K contiguous): the shapes the benchmark uses
 using Pk_256x256 = PipeCfg<256, 256, 64, 2, 4, 2, false, 3, 0, true>;
@@ -150,6 +155,8 @@ const GemmVariant kVariants[] = {
     {MOE_DTYPE_FP8_E4M3, 16, 128, 128, &launch_pipe<P8_16x128>, 0, 0, MOE_W_LAYOUT_KN, &launch_stream<P8_16x128>, P8_16x128::NS},
     {MOE_DTYPE_FP8_E4M3, 16, 64, 128, &launch_pipe<P8_16x64>, 0, 0, MOE_W_LAYOUT_KN, &launch_stream<P8_16x64>, P8_16x64::NS},
     {MOE_DTYPE_FP8_E4M3, 32, 128, 128, &launch_pipe<P8_32x128>},
+    {MOE_DTYPE_FP8_E4M3, 256, 256, 128, &launch_pipe<P8_256x256, P8s_64x256, P8s_128x256>},
+    {MOE_DTYPE_FP8_E4M3, 64, 256, 128, &launch_pipe<P8_64x256>},
 };
 
 const GemmVariant kPairVariants[] = {
@@ -246,7 +253,10 @@ int moe_default_tiling(int dtype, int T, int k, int E, int K, int N, moe_tiling*
     const int64_t active = R < E ? R : E;   // experts that can have rows at all
     const int cus = 256;
     moe_tiling g = {16, 128, MOE_ORDER_ASCENDING, 0, 0, 0};
-    if (dtype == MOE_DTYPE_FP8_E4M3) {
+    if (dtype == MOE_DTYPE_FP8_E4M3 && mean_rows > 24) {
+        // prefill sizes
+        g.tile_m = mean_rows > 96 ? 256 : 64; g.tile_n = 256;
+    } else if (dtype == MOE_DTYPE_FP8_E4M3) {
         // expected tiles under a uniform routing: E * (1 - (1 - 1/E)^R) experts are hit, plus full extra m-tiles
         const double hit = E * (1.0 - pow(1.0 - 1.0 / E, (double)R));
         const double t256 = (hit + (double)(R / 16)) * ((N + 255) / 256);

@@ -86,6 +86,8 @@ def fine_grained(T: int) -> Workload:
 
 
 def decode_fp8(T: int) -> Workload:
+    if T >= 1024:   # the same layer at prefill sizes
+        return Workload("decode_fp8", T, 64, 6, 2048, 2816, "fp8", "uniform_topk", 256, 256)
     return Workload("decode_fp8", T, 64, 6, 2048, 2816, "fp8", "uniform_topk", 16, 256 if T == 8 else 128)
 
 

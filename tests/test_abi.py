@@ -54,7 +54,8 @@ def test_host_only_entry_points():
     assert not mb.moe_tile_pair_supported(mb.MOE_DTYPE_FP8_E4M3, 256, 256, 64)
     assert mb.moe_tile_supported(mb.MOE_DTYPE_BF16, 256, 256)
     assert mb.moe_tile_supported(mb.MOE_DTYPE_FP8_E4M3, 16, 128)
-    assert not mb.moe_tile_supported(mb.MOE_DTYPE_FP8_E4M3, 256, 256)
+    assert mb.moe_tile_supported(mb.MOE_DTYPE_FP8_E4M3, 256, 256)
+    assert not mb.moe_tile_supported(mb.MOE_DTYPE_FP8_E4M3, 128, 128)
     assert mb.strerror(mb.MOE_ERR_ROUTING).startswith("routing id")
     assert mb.strerror(0) == "ok"
 

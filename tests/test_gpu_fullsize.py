@@ -109,6 +109,7 @@ FULL = [
     (wk.mixtral_up(4096).with_T(4096, tile_m_slack=0), 8, 64, 0),   # the same point with the plain ceil tiling
     (wk.mixtral_up(4096).with_T(4096, tile_m_slack=64), 8, 64, 0),  # and with 64 slack rows (32-row MFMA blocks)
     (wk.mixtral_up(256), 8, 32, 0),
+    (wk.decode_fp8(4096), 4, 32, 0),                                # the fp8 layer at a prefill size: 256-row tiles
     (wk.mixtral_up(16), 8, 32, 0),
     (wk.mixtral_down_zipf(4096), 8, 64, 0),
     (wk.mixtral_down_zipf(256), 8, 32, 0),

@@ -333,6 +333,10 @@ FP8_CASES = [
     (16, 256, 32, 64, 6, 384, 512, "uniform_topk"),
     (16, 128, 100, 8, 2, 128, 256, "zipf"),           # several m-tiles per expert
     (32, 128, 100, 8, 2, 256, 256, "zipf"),
+    (64, 256, 300, 8, 2, 256, 512, "zipf"),           # fp8 at prefill sizes: 64- and 256-row tiles
+    (256, 256, 700, 8, 2, 256, 512, "zipf"),
+    (256, 256, 1200, 8, 2, 384, 256, "gauss_topk"),
+    (256, 256, 257, 3, 1, 128, 256, "worst"),
 ]
 
 

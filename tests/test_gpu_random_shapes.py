@@ -17,7 +17,7 @@ pytestmark = pytest.mark.gpu
 
 POISON = 0x7FC1
 BF16_TILES = [(256, 256), (128, 256), (128, 128), (64, 256), (64, 128), (32, 256), (32, 128), (16, 256), (16, 128)]
-FP8_TILES = [(16, 256), (16, 128), (16, 64), (32, 128)]
+FP8_TILES = [(16, 256), (16, 128), (16, 64), (32, 128), (64, 256), (256, 256)]
 
 
 def _case(seed):
