@@ -149,20 +149,6 @@ __device__ __forceinline__ int pswz_w(int krow) {
     return s & (C::CPRW - 1);
 }
 
-// One tile of the batch: everything after the task-map decode.  A task function in the sense of Alg. 3.
-//
-// LDS holds two rings: NS stages of token tiles and NSW >= NS stages of weight tiles.
-// Main loop, per k-tile kt (token stage kt % NS, weight stage kt % NSW):
-//   k-steps 0 .. KSTEPS-2 : MFMA of the step, interleaved with the LDS reads of the next step
-//   wait for tile kt+1's DMA, workgroup barrier  (every wavefront has now read all of tile kt)
-//   last k-step           : its MFMAs, interleaved with the first LDS reads of tile kt+1 and with the DMA
-//                           instructions that refill the two stages with token tile kt+NS and weight tile kt+NSW
-// so neither the barrier nor the DMA issue leaves the MFMA pipe without queued work, and NSW-1 tiles of
-// weights per workgroup are in flight from HBM at any time.
-//
-// Rows: MF-row block b of the tile belongs to wavefront row b % WM (its block b / WM), so a partly filled tile
-// spreads its live blocks evenly over the wavefront rows.  The loop exists in copies for a compile-time number of
-// blocks per wavefront (all of them, or all but the slack block) and in one copy that tests each block at run time.
 // A workgroup's run of consecutive tiles for the streaming kernel: the task records stay in registers, so the
 // tile after the current one is known without touching memory and its loads can be issued while the current
 // tile still multiplies.
@@ -222,6 +208,20 @@ __device__ __forceinline__ void scalar_load16(const int32_t* p, i32x8_t& lo, i32
 
 // One tile of the batch (STREAM = false), or a run of tiles taken from `ts` (STREAM = true; 16-row tiles only):
 // everything after the task-map decode.  A task function in the sense of Alg. 3.
+//
+// LDS holds two rings: NS stages of token tiles and NSW >= NS stages of weight tiles.
+// Main loop, per k-tile kt (token stage kt % NS, weight stage kt % NSW):
+//   k-steps 0 .. KSTEPS-2 : MFMA of the step, interleaved with the LDS reads of the next step
+//   wait for tile kt+1's DMA, workgroup barrier  (every wavefront has now read all of tile kt)
+//   last k-step           : its MFMAs, interleaved with the first LDS reads of tile kt+1 and with the DMA
+//                           instructions that refill the two stages with token tile kt+NS and weight tile kt+NSW
+// so neither the barrier nor the DMA issue leaves the MFMA pipe without queued work, and NSW-1 tiles of
+// weights per workgroup are in flight from HBM at any time.
+//
+// Rows: MF-row block b of the tile belongs to wavefront row b % WM (its block b / WM), so a partly filled tile
+// spreads its live blocks evenly over the wavefront rows.  The loop exists in copies for a compile-time number of
+// blocks per wavefront and in one copy that tests each block at run time; tiles of many 16-row blocks (PERWAVE)
+// have a copy for every live-block count and each wavefront runs its own.
 template <class C, bool STREAM = false>
 __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __restrict__ map, const MapLayout& L,
                                           TileCoord tc, char* smem, TileStream* ts = nullptr) {
