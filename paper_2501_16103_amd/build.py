@@ -15,6 +15,9 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed-FP32 instructions are switched off for all device code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # The k loops are unrolled completely by pragma; at the default size limit for pragma-unrolled loops the largest
+    # copies sit at the edge, and a loop left rolled indexes the accumulators dynamically, which puts them in memory.
+    "-mllvm", "-pragma-unroll-threshold=100000",
 ]
 
 
@@ -24,17 +27,30 @@ HIPCC_FLAGS = [
 # has a scratch access inside a loop that also holds MFMAs.  (Spills outside the loops only cost their own time;
 # they cannot let a DMA wait pass early: loads retire in order and extra entries in vmcnt make a wait stricter.)
 def check_no_spill_in_k_loops(asm_text: str) -> None:
+    # accumulators or fragments that were not promoted to registers show up as a large private segment
+    for m in re.finditer(r"\.name:\s+(\S+)\n(?:.*\n)*?\s+\.private_segment_fixed_size:\s+(\d+)", asm_text):
+        if "gemm" in m.group(1) and int(m.group(2)) > 256:
+            raise RuntimeError(f"{m.group(1)}: {m.group(2)} bytes of private memory per lane (an array left in memory?)")
     for m in re.finditer(r"^(_ZN3moe\S*gemm\S*):\s*(?:;.*)?$", asm_text, re.M):
         name = m.group(1)
         end = asm_text.find(".Lfunc_end", m.end())
         lines = asm_text[m.end():end].splitlines()
         label_at = {ln.split(":")[0]: k for k, ln in enumerate(lines) if ln.startswith(".LBB")}
+        loops = []   # (first line, last line) of every backward branch's span
         for k, ln in enumerate(lines):
             b = re.search(r"s_cbranch\w*\s+(\.LBB\d+_\d+)", ln)
-            if not b or label_at.get(b.group(1), len(lines)) >= k:
+            if b and label_at.get(b.group(1), len(lines)) < k:
+                loops.append((label_at[b.group(1)], k))
+        for k, ln in enumerate(lines):
+            if "scratch_" not in ln:
                 continue
-            body = lines[label_at[b.group(1)]:k]
-            if sum("v_mfma" in x for x in body) >= 16 and any("scratch_" in x for x in body):
+            around = [lp for lp in loops if lp[0] <= k <= lp[1]]
+            if not around:
+                continue
+            lo, hi = min(around, key=lambda lp: lp[1] - lp[0])          # the innermost loop around the access
+            inner = [lp for lp in loops if lo <= lp[0] and lp[1] <= hi and lp != (lo, hi)]
+            own = sum("v_mfma" in lines[x] for x in range(lo, hi + 1) if not any(a <= x <= b for a, b in inner))
+            if own >= 16:
                 raise RuntimeError(f"{name}: register spill inside a k loop (it would drain the DMA ring every iteration)")
 
 

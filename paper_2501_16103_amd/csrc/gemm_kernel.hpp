@@ -94,10 +94,16 @@ __device__ __forceinline__ void wait_vmcnt() {
 // (K contiguous, a pre-packed layout) instead of [E][K][N]: the weight tile then has the token tile's geometry
 // and needs no transposing LDS reads.
 template <int BM_, int BN_, int BK_, int WM_, int WN_, int NS_, bool FP8_ = false, int NSW_ = NS_, int SLACK_ = 0,
-          bool WKC_ = false, int MFO_ = 0>
+          bool WKC_ = false, int MFO_ = 0, int NSWH_ = 0>
 struct PipeCfg {
     static constexpr bool WKC = WKC_;
-    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, NS = NS_, NSW = NSW_, SLACK = SLACK_;
+    // NSWH_ > 0: the weight ring is NSWH_ stages of HALF a k-tile (when whole stages do not divide the LDS left
+    // beside the token ring): k-tile kt lives in half-stages (2 kt) % NSWH_ and (2 kt + 1) % NSWH_, and the loop's
+    // reach ahead is that of ceil(NSWH_ / 2) whole stages.
+    static constexpr bool WHALF = NSWH_ > 0;
+    static constexpr int NSWH = NSWH_;
+    static constexpr int BM = BM_, BN = BN_, BK = BK_, WM = WM_, WN = WN_, NS = NS_, SLACK = SLACK_;
+    static constexpr int NSW = WHALF ? (NSWH_ + 1) / 2 : NSW_;
     static constexpr int BMC = BM + SLACK;                     // row capacity of the tile in LDS and registers
     static constexpr bool FP8 = FP8_;
     static constexpr int ES = FP8 ? 1 : 2;
@@ -122,7 +128,10 @@ struct PipeCfg {
     static constexpr int XS_BYTES = (BMC * XROW + 16 * NT - 1) / (16 * NT) * (16 * NT);
     static constexpr int WS_BYTES = BK * WROW;                 // (BN rows of XROW bytes when WKC: same size)
     static constexpr int W_RING = NS * XS_BYTES;               // byte offset of the weight ring
-    static constexpr int LDS_BYTES = NS * XS_BYTES + NSW * WS_BYTES;
+    static constexpr int WH_BYTES = WS_BYTES / 2;
+    static constexpr int LDS_BYTES = NS * XS_BYTES + (WHALF ? NSWH * WH_BYTES : NSW * WS_BYTES);
+    static_assert(!WHALF || (NS_ == 2 && !FP8_ && !WKC_ && BK_ / (MFO_ == 16 ? 32 : 16) == 2 && NSWH_ % 2 == 1),
+                  "half-stage weight ring: two k-steps per k-tile, two token stages, an odd number of half-stages");
     // weight-fragment LDS reads per k-step (two 4-k halves for bf16, one 8-k piece for fp8)
     static constexpr int WREADS = NBW * ((FP8 || WKC) ? 1 : 2);
     // memory-bound tiles start the weight stream before the token rows are known
@@ -306,13 +315,30 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
         else dma16(voff, src, dst);
     };
 
+    // half-stage weight ring: jj-th instruction of this wave for half-k-tile q (k rows [q BK/2, (q+1) BK/2)) into
+    // half-stage hs
+    static_assert(!C::WHALF || (W_FOLD && C::EARLY_W && WI % 2 == 0 && !STREAM), "half-stage weight ring");
+    auto dma_wh = [&](int jj, int q, int hs) __attribute__((always_inline)) {
+        const char* src = Wt + (size_t)q * (w_kt_stride / 2) + (size_t)(jj * NW * WROWS_PER_INST) * w_row_bytes;
+        dma16(dw_off[0], src, lds0 + C::W_RING + hs * C::WH_BYTES + (jj * NW + wave) * 1024);
+    };
+
     if (C::EARLY_W) {
+        if constexpr (C::WHALF) {
 #pragma unroll
-        for (int s = 0; s < NSW; ++s)
-            if (s < KT) {
+            for (int q = 0; q < C::NSWH; ++q)
+                if (q < 2 * KT) {
 #pragma unroll
-                for (int j = 0; j < WI; ++j) dma_w(j, s, s, false, 2);
-            }
+                    for (int jj = 0; jj < WI / 2; ++jj) dma_wh(jj, q, q);
+                }
+        } else {
+#pragma unroll
+            for (int s = 0; s < NSW; ++s)
+                if (s < KT) {
+#pragma unroll
+                    for (int j = 0; j < WI; ++j) dma_w(j, s, s, false, 2);
+                }
+        }
     }
 
     // ---- per-tile row information
@@ -391,7 +417,11 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
     // r-th LDS read of k-step kk, ordered by first use in the MFMA sequence (token block 0, weights, token blocks 1..)
     auto read_one = [&](int r, int sx, int sw, int kk, int buf, bool tail) __attribute__((always_inline)) {
         const char* xs = smem + sx * C::XS_BYTES;
-        const char* ws = smem + sw * C::WS_BYTES;   // w_rd holds the ring's offset
+        // w_rd holds the ring's offset; with half-stages sw is the tile's first half-stage and k-step kk lives in the
+        // kk-th one after it, starting at its row 0
+        int hs = sw + kk;
+        if (hs >= C::NSWH) hs -= C::NSWH;
+        const char* ws = C::WHALF ? smem + hs * C::WH_BYTES - (kk * C::KS) * C::WROW : smem + sw * C::WS_BYTES;
         if (r >= 1 && r <= WREADS) {
             if constexpr (C::WKC) {
                 const int nb = r - 1;
@@ -462,6 +492,13 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
             if (d < XIL) {
                 if (all_in_range || ktx < KT) dma_x(d, ktx, sx, false);
                 else if (STREAM && has_next) dma_x(d, ktx - KT, sx, true);
+            } else if constexpr (C::WHALF) {
+                // the two half-stages of the k-tile just read take half-k-tiles 2 kt + NSWH and 2 kt + NSWH + 1
+                const int h = (d - XIL) / (WI / 2), jj = (d - XIL) % (WI / 2);
+                const int q = 2 * (ktx - NS) + C::NSWH + h;
+                int hs = sw + h;
+                if (hs >= C::NSWH) hs -= C::NSWH;
+                if (all_in_range || q < 2 * KT) dma_wh(jj, q, hs);
             } else {
                 if (all_in_range || ktw < KT) dma_w(d - XIL, ktw, sw, false, NTM);
                 else if (STREAM && has_next) dma_w(d - XIL, ktw - KT, sw, true, NTM);
@@ -509,7 +546,7 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
             constexpr bool STEADY = decltype(steady_tag)::value;  // kt + NSW < KT: every fetch below is in range
             const bool more = STEADY || (STREAM && has_next);     // every fetch below has a target
             const int nxt = cur + 1 == NS ? 0 : cur + 1;
-            const int nxtw = curw + 1 == NSW ? 0 : curw + 1;
+            const int nxtw = C::WHALF ? (curw + 2 >= C::NSWH ? curw + 2 - C::NSWH : curw + 2) : (curw + 1 == NSW ? 0 : curw + 1);
 #pragma unroll
             for (int kk = 0; kk < KSTEPS - 1; ++kk) {
 #pragma unroll
@@ -522,7 +559,10 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
             // Tile kt+1 must have landed.  Issue order is [X(j+NS) W(j+NSW)] per iteration j, so what may still
             // be in flight is the NS-2 iterations' worth issued after X(kt+1), plus, with a deeper weight ring,
             // the weight rows issued right behind X(kt+1).
-            if (more || kt + NSW - 1 < KT) wait_vmcnt<(NS - 2) * ND + (NSW > NS ? WI : 0)>(); else wait_vmcnt<0>();
+            // (Half-stage ring: the iteration before issued X(kt+1), then half-k-tiles 2 kt + 3 and 2 kt + 4; only
+            // the last of them is not part of tile kt+1.)
+            constexpr int NEWER = C::WHALF ? WI / 2 : (NS - 2) * ND + (NSW > NS ? WI : 0);
+            if (more || kt + NSW - 1 < KT) wait_vmcnt<NEWER>(); else wait_vmcnt<0>();
             __syncthreads();
             MOE_SCHED_FENCE();
 #pragma unroll

@@ -99,7 +99,8 @@ struct GemmVariant {
 using Pb_256x256 = PipeCfg<256, 256, 64, 2, 4, 2, false, 3, 0, false, 16>;
 // same, for maps whose last m-tiles hold up to 64 slack rows
 using Pb_256x256s = PipeCfg<256, 256, 64, 2, 4, 2, false, 2, 64>;
-using Pb_256x256s32 = PipeCfg<256, 256, 64, 2, 4, 2, false, 2, 32, false, 16>;
+// (token ring 2 x 40 KB; the 80 KB left hold five half-stages of weights: 2.5 k-tiles instead of 2)
+using Pb_256x256s32 = PipeCfg<256, 256, 64, 2, 4, 2, false, 2, 32, false, 16, 5>;
 using Pb_128x256 = PipeCfg<128, 256, 64, 1, 4, 3>;
 using Pb_128x128 = PipeCfg<128, 128, 64, 2, 2, 4>;
 using Pb_64x256 = PipeCfg<64, 256, 64, 1, 4, 3>;
