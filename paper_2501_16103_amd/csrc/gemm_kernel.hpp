@@ -246,7 +246,7 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
     constexpr int XI_TOT = C::XS_BYTES / 1024, WI_TOT = C::WS_BYTES / 1024;
     static_assert(XI_TOT % NW == 0 && WI_TOT % NW == 0, "every wave issues the same number of DMA instructions");
     constexpr int XI = XI_TOT / NW, WI = WI_TOT / NW;
-    constexpr int XI_BODY = C::BM * C::XROW / 1024 / NW;   // instructions that cover rows < BM
+    constexpr int XI_BODY = C::SLACK == 0 ? XI : C::BM * C::XROW / 1024 / NW;   // instructions that cover rows < BM
     static_assert(C::SLACK == 0 || (C::BM * C::XROW) % (1024 * NW) == 0, "slack rows start at a DMA instruction boundary");
     constexpr int XROWS_PER_INST = 1024 / C::XROW, WROWS_PER_INST = 1024 / C::WROW;
     static_assert((NS - 1) * XI + (NSW - 1) * WI < 64, "vmcnt range");
