@@ -121,7 +121,7 @@ struct PipeCfg {
     // number of live blocks (a run-time test around every MFMA defeats the software pipelining there).
     static constexpr bool PERWAVE = MF == 16 && MBW_BODY >= 4;
     // ... and with at least four weight blocks per wavefront the fragments are reloaded in place (see reads_after)
-    static constexpr bool XROLL = PERWAVE && WTN / MF >= 4 && !WKC_;
+    static constexpr bool XROLL = PERWAVE && WTN / MF >= 4;
     static constexpr int XROW = BK * ES, CPR = XROW / 16;
     static constexpr int WROW = BN * ES, CPRW = WROW / 16;
     // the token tile in LDS is rounded up so that every wavefront issues the same number of DMA instructions
@@ -429,11 +429,12 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
                 const char* wrow = ws + C::W_RING + row * C::XROW;
                 if constexpr (C::FP8) {
                     const int c = kk * 2 + (g >> 1);
-                    wq[buf][nb][0] = *reinterpret_cast<const u32x2_t*>(wrow + ((c ^ pswz_x<C>(row)) << 4) + (g & 1) * 8);
+                    wq[wbuf(buf, nb)][nb][0] = *reinterpret_cast<const u32x2_t*>(wrow + ((c ^ pswz_x<C>(row)) << 4) + (g & 1) * 8);
                 } else {
                     const int c = MF == 32 ? kk * 2 + (lane >> 5) : kk * 4 + g;
                     const u32x4_t v = *reinterpret_cast<const u32x4_t*>(wrow + ((c ^ pswz_x<C>(row)) << 4));
-                    wq[buf][nb][0].x = v.x; wq[buf][nb][0].y = v.y; wq[buf][nb][1].x = v.z; wq[buf][nb][1].y = v.w;
+                    const int wb = wbuf(buf, nb);
+                    wq[wb][nb][0].x = v.x; wq[wb][nb][0].y = v.y; wq[wb][nb][1].x = v.z; wq[wb][nb][1].y = v.w;
                 }
             } else if constexpr (C::FP8) {
                 const int nb = r - 1;

@@ -125,7 +125,7 @@ using P8s_128x256 = PipeCfg<128, 256, 128, 1, 8, 2, true>;
 using P8_64x256 = PipeCfg<64, 256, 128, 1, 4, 3, true>;
 
 // The pre-packed weight layout [E][N][K] (K contiguous): the shapes the benchmark uses
-using Pk_256x256 = PipeCfg<256, 256, 64, 2, 4, 2, false, 3, 0, true>;
+using Pk_256x256 = PipeCfg<256, 256, 64, 2, 4, 2, false, 3, 0, true, 16>;
 using Pk_256x256s = PipeCfg<256, 256, 64, 2, 4, 2, false, 2, 64, true>;
 using Pks_64x256 = PipeCfg<64, 256, 64, 1, 8, 3, false, 3, 0, true>;
 using Pks_128x256 = PipeCfg<128, 256, 64, 1, 8, 2, false, 2, 0, true>;
