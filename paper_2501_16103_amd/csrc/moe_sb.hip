@@ -31,15 +31,22 @@ int nchunks_for(int64_t R) { return (int)((R + kChunkRows - 1) / kChunkRows); }
 
 typedef int (*gemm_launch_fn)(const GemmArgs&, int64_t grid, hipStream_t);
 
+// The large-LDS attribute of a kernel is set once per device (bit d of *done: device d, d < 64).
+inline int ensure_lds_attr(const void* fn, int lds, unsigned long long* done) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return MOE_ERR_HIP;
+    const unsigned long long bit = dev >= 0 && dev < 64 ? 1ull << dev : 0;
+    if (bit && (*done & bit)) return MOE_OK;
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return MOE_ERR_HIP;
+    *done |= bit;
+    return MOE_OK;
+}
+
 template <class C, class... Tails>
 int launch_pipe(const GemmArgs& a, int64_t grid, hipStream_t s) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&moe_gemm_pipe_kernel<C, Tails...>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES) != hipSuccess)
-            return MOE_ERR_HIP;
-        attr_set = true;
-    }
+    static unsigned long long attr_done = 0;
+    if (ensure_lds_attr(reinterpret_cast<const void*>(&moe_gemm_pipe_kernel<C, Tails...>), C::LDS_BYTES, &attr_done) != MOE_OK)
+        return MOE_ERR_HIP;
     moe_gemm_pipe_kernel<C, Tails...><<<dim3((unsigned)grid), dim3(C::NT), C::LDS_BYTES, s>>>(a);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
@@ -48,8 +55,10 @@ int launch_pipe(const GemmArgs& a, int64_t grid, hipStream_t s) {
 template <class C>
 int launch_stream(const GemmArgs& a, int64_t grid, hipStream_t s) {
     const int lds = C::LDS_BYTES + (C::FP8 ? 4 * (a.T + a.E) : 0);
-    static int lds_set = -1, resident = 0;
-    if (lds != lds_set) {
+    static int lds_set = -1, dev_set = -1, resident = 0;
+    int dev_now = 0;
+    if (hipGetDevice(&dev_now) != hipSuccess) return MOE_ERR_HIP;
+    if (lds != lds_set || dev_now != dev_set) {
         const void* fn = reinterpret_cast<const void*>(&moe_gemm_stream_kernel<C>);
         int dev = 0, cus = 0, per_cu = 0;
         if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess ||
@@ -59,6 +68,7 @@ int launch_stream(const GemmArgs& a, int64_t grid, hipStream_t s) {
             return MOE_ERR_HIP;
         resident = per_cu * cus / 8 * 8;
         lds_set = lds;
+        dev_set = dev_now;
     }
     // with fewer than two tiles per resident workgroup there is nothing to stream across: one workgroup per tile
     if (g_stream_mode == 0 && grid < 2 * (int64_t)resident) return launch_pipe<C>(a, grid, s);
@@ -71,13 +81,9 @@ int launch_stream(const GemmArgs& a, int64_t grid, hipStream_t s) {
 template <class CBIG, class CSMALL, class... Tails>
 int launch_pipe2(const GemmArgs& a, int64_t grid, hipStream_t s) {
     constexpr int lds = CBIG::LDS_BYTES > CSMALL::LDS_BYTES ? CBIG::LDS_BYTES : CSMALL::LDS_BYTES;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&moe_gemm_pipe2_kernel<CBIG, CSMALL, Tails...>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
-            return MOE_ERR_HIP;
-        attr_set = true;
-    }
+    static unsigned long long attr_done = 0;
+    if (ensure_lds_attr(reinterpret_cast<const void*>(&moe_gemm_pipe2_kernel<CBIG, CSMALL, Tails...>), lds, &attr_done) != MOE_OK)
+        return MOE_ERR_HIP;
     moe_gemm_pipe2_kernel<CBIG, CSMALL, Tails...><<<dim3((unsigned)grid), dim3(CBIG::NT), lds, s>>>(a);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
