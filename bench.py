@@ -231,6 +231,39 @@ def combine_point(T: int, k: int, N: int, steps: int, warmup: int, dev="cuda:0")
                 gbs=round(gbs, 1), frac_hbm=round(gbs / PEAK_HBM_GBS, 4), bound="hbm", alg_bytes=nbytes)
 
 
+def layer_point(T: int, steps: int, warmup: int, dev="cuda:0") -> dict:
+    """One whole bf16 feed-forward layer at the Mixtral-8x7B sizes (Sec. 2.2): two task maps, the gate+up product
+    with the fused gated activation, the down product and the weighted sum, five library calls per step."""
+    up = wk.mixtral_up(T)
+    k, E, hidden, inter = up.k, up.E, up.K, up.N // 2
+    ids = wk.make_routing(up).to(dev)
+    g = torch.Generator(device=dev).manual_seed(wk.BASE_SEED + 31 * T)
+    X = torch.randn((T, hidden), generator=g, device=dev).to(torch.bfloat16)
+    W1 = torch.empty((E, hidden, 2 * inter), dtype=torch.bfloat16, device=dev)
+    W2 = torch.empty((E, inter, hidden), dtype=torch.bfloat16, device=dev)
+    for e in range(E):
+        W1[e] = (torch.randn((hidden, 2 * inter), generator=g, device=dev) * hidden ** -0.5).to(torch.bfloat16)
+        W2[e] = (torch.randn((inter, hidden), generator=g, device=dev) * inter ** -0.5).to(torch.bfloat16)
+    wts = torch.softmax(torch.randn((T, k), generator=g, device=dev), dim=1)
+    plan = mb.MoeLayerPlan(T, k, E, hidden, inter, dev)
+    for _ in range(warmup):
+        plan.forward(X, W1, W2, ids, wts)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(steps)]
+    torch.cuda._sleep(int(4e6))
+    for i in range(steps):
+        ev[i][0].record()
+        plan.forward(X, W1, W2, ids, wts)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    flops = 6 * T * k * hidden * inter
+    return dict(workload=f"mixtral_layer_T{T}", dtype="bf16", T=T, k=k, E=E, hidden=hidden, inter=inter,
+                layer_ms=round(ms, 4), tflops=round(flops / (ms * 1e-3) / 1e12, 2),
+                tokens_per_s=round(T / (ms * 1e-3), 1),
+                tilings={"gate_up": [plan.g1.tile_m, plan.g1.tile_n, plan.g1.tile_m_slack],
+                         "down": [plan.g2.tile_m, plan.g2.tile_n, plan.g2.tile_m_slack]})
+
+
 def all_points():
     pts = [wk.tiny(64)]
     pts += [wk.mixtral_up(T) for T in (16, 256, 4096)]
@@ -406,6 +439,11 @@ def main():
                 torch.cuda.empty_cache()
             for (T, k, N) in ((4096, 2, 4096), (8192, 8, 4096), (32, 6, 2816)):
                 points.append(combine_point(T, k, N, max(10, args.steps // 2), max(3, args.warmup // 2)))
+                torch.cuda.empty_cache()
+        if want is None or "layer" in want:
+            # labelled extra: the whole feed-forward layer composed from the library's calls
+            for T in (4096, 256, 16):
+                points.append(layer_point(T, max(10, args.steps // 2), max(3, args.warmup // 2)))
                 torch.cuda.empty_cache()
         out["points"] = points
     print(json.dumps(out))

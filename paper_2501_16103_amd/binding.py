@@ -304,3 +304,43 @@ def moe_debug_mfma_probe(block: int, random_operands: bool, iters: int, sink, ch
     if check and rc != MOE_OK:
         raise MoeError(rc, "moe_debug_mfma_probe")
     return rc
+
+
+class MoeLayerPlan:
+    """Buffers and tilings for one bf16 MoE feed-forward layer (Sec. 2.2) run with the library's calls only:
+
+        map(T, k) -> gate+up product with the fused gated activation -> map(T*k, 1) -> down product -> weighted sum.
+
+    The second product sees the T*k activated rows as tokens of their own, each routed to exactly one expert
+    (the flattened routing with k = 1), so the same two entry points serve both products.  Nothing here computes:
+    the plan holds caller-visible device buffers and issues calls on the current stream."""
+
+    def __init__(self, T: int, k: int, E: int, hidden: int, inter: int, device="cuda:0"):
+        self.T, self.k, self.E, self.hidden, self.inter = T, k, E, hidden, inter
+        R = T * k
+        self.g1 = moe_default_tiling(MOE_DTYPE_BF16, T, k, E, hidden, 2 * inter)
+        self.g2 = moe_default_tiling(MOE_DTYPE_BF16, R, 1, E, inter, hidden)
+        self.map1 = alloc_task_map(T, k, E, self.g1.tile_m, self.g1.tile_n, 2 * inter, device)
+        self.map2 = alloc_task_map(R, 1, E, self.g2.tile_m, self.g2.tile_n, hidden, device)
+        self.act = torch.empty((R, inter), dtype=torch.bfloat16, device=device)       # [T, k, inter]
+        self.down = torch.empty((R, hidden), dtype=torch.bfloat16, device=device)     # [T, k, hidden]
+        self.out = torch.empty((T, hidden), dtype=torch.bfloat16, device=device)
+        self.d1 = GemmDesc(MOE_DTYPE_BF16, T, k, E, hidden, 2 * inter, self.g1.tile_m, self.g1.tile_n,
+                           tile_m_small=self.g1.tile_m_small, small_max_rows=self.g1.small_max_rows,
+                           tile_m_slack=self.g1.tile_m_slack, epilogue=MOE_EPILOGUE_SWIGLU)
+        self.d2 = GemmDesc(MOE_DTYPE_BF16, R, 1, E, inter, hidden, self.g2.tile_m, self.g2.tile_n,
+                           tile_m_small=self.g2.tile_m_small, small_max_rows=self.g2.small_max_rows,
+                           tile_m_slack=self.g2.tile_m_slack)
+
+    def forward(self, X: torch.Tensor, W_gate_up: torch.Tensor, W_down: torch.Tensor, topk_ids: torch.Tensor,
+                topk_weights: Optional[torch.Tensor]) -> torch.Tensor:
+        """X [T, hidden]; W_gate_up [E, hidden, 2*inter] (gate columns first); W_down [E, inter, hidden];
+        topk_ids int32 [T, k]; topk_weights fp32 [T, k] or None.  Returns out [T, hidden] (the plan's buffer)."""
+        T, k, E = self.T, self.k, self.E
+        flat = topk_ids.reshape(T * k, 1)
+        moe_build_task_map_ex(topk_ids, T, k, E, 2 * self.inter, self.g1, self.map1)
+        moe_grouped_gemm(X, W_gate_up, topk_ids, self.map1, self.act, self.d1)
+        moe_build_task_map_ex(flat, T * k, 1, E, self.hidden, self.g2, self.map2)
+        moe_grouped_gemm(self.act, W_down, flat, self.map2, self.down, self.d2)
+        moe_combine(self.down, topk_weights, T, k, self.hidden, self.out)
+        return self.out

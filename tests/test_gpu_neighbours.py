@@ -347,3 +347,50 @@ def test_mfma_probe_runs(dev):
             assert mb.moe_debug_mfma_probe(block, rnd, 50, sink) == mb.MOE_OK
     torch.cuda.synchronize()
     assert float(sink.abs().sum()) == 0.0
+
+
+LAYER_CASES = [
+    # T, k, E, hidden, inter, routing, weighted
+    (300, 2, 8, 256, 384, "zipf", True),
+    (40, 2, 8, 128, 256, "gauss_topk", True),          # weight-streaming tiles for both products
+    (700, 1, 4, 256, 256, "uniform_topk", False),      # k = 1: the second map equals the first one's routing
+]
+
+
+@pytest.mark.parametrize("T,k,E,hidden,inter,routing,weighted", LAYER_CASES)
+def test_moe_layer_composition(dev, oracle_mod, T, k, E, hidden, inter, routing, weighted):
+    """The whole feed-forward layer of Sec. 2.2 from library calls only.  Each stage is checked against the oracle
+    applied to the previous stage's device output, so every comparison keeps the single-stage tolerance."""
+    from tests.test_gpu_parity import _check_y
+    wl1 = wk.Workload("layer_up", T, E, k, hidden, 2 * inter, "bf16", routing, 16, 128)
+    wl2 = wk.Workload("layer_down", T * k, E, 1, inter, hidden, "bf16", routing, 16, 128)
+    ids = wk.make_routing(wl1)
+    X, W1, W2 = wk.make_x(wl1), wk.make_w(wl1) * 4.0, wk.make_w(wl2)
+    g = torch.Generator().manual_seed(77 + T)
+    wts = torch.rand((T, k), generator=g, dtype=torch.float32) if weighted else None
+    plan = mb.MoeLayerPlan(T, k, E, hidden, inter, dev)
+    for buf in (plan.act, plan.down, plan.out):
+        buf.view(torch.int16).fill_(POISON)
+    out = plan.forward(X.to(dev), W1.to(dev), W2.to(dev), ids.to(dev), None if wts is None else wts.to(dev))
+    torch.cuda.synchronize()
+    assert out.data_ptr() == plan.out.data_ptr()
+    act_bits = plan.act.cpu().view(torch.int16).numpy().view(np.uint16)
+    down_bits = plan.down.cpu().view(torch.int16).numpy().view(np.uint16)
+    out_bits = plan.out.cpu().view(torch.int16).numpy().view(np.uint16)
+    idn = ids.numpy()
+    # stage 1: gate+up product with the fused gated activation
+    res1 = oracle_mod.grouped_gemm_bf16(wk.bits(X), wk.bits(W1), idn)
+    _check_swiglu(oracle_mod, act_bits, res1, X.double().numpy(), W1.double().numpy(), idn, k, hidden)
+    # stage 2: the activated rows as T*k tokens with one expert each
+    flat = idn.reshape(T * k, 1)
+    res2 = oracle_mod.grouped_gemm_bf16(act_bits, wk.bits(W2), flat)
+    _check_y(down_bits, res2, H.bf16_bits_to_f64(act_bits), W2.double().numpy(), flat, 1, inter, H.tol_bf16(inter))
+    # stage 3: weighted sum over the k slots of each token
+    out64, outbf = oracle_mod.combine(down_bits, None if wts is None else wts.numpy(), T, k)
+    yabs = np.abs(H.bf16_bits_to_f64(down_bits)).reshape(T, k, hidden)
+    wabs = np.ones((T, k)) if wts is None else np.abs(wts.double().numpy())
+    A = np.einsum("tj,tjn->tn", wabs, yabs)
+    tight = 2.0 ** -8 * np.abs(out64) * 1.001 + (k + 1) * 2.0 ** -24 * A + 1e-30
+    err = np.abs(H.bf16_bits_to_f64(out_bits) - out64)
+    assert np.all(err <= tight), f"max err/tight = {(err / tight).max():.3f}"
+    assert (H.ulp_distance(out_bits, outbf) == 0).mean() > 0.97
