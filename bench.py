@@ -370,6 +370,21 @@ def main():
                 ms = ev[0].elapsed_time(ev[1])
                 res.append({"block": f"{block}x{block}x{512 // block}", "operands": "random" if rnd else "constant",
                             "ms": round(ms, 3), "tflops": round(flops / (ms * 1e-3) / 1e12, 1)})
+        # the 256x256x64 tile's loop, one ingredient at a time (LDS reads, barrier, DMA from cache, half of it from HBM)
+        src = (torch.randn((513 << 20) // 2, device="cuda:0") * 0.5).to(torch.bfloat16)
+        for mode, what in ((1, "MFMA + LDS fragment reads"), (2, "+ barrier per k-tile"), (3, "+ DMA from cache"),
+                           (4, "+ half of the DMA bytes from HBM")):
+            mb.moe_debug_pipeline_probe(mode, 1000, src, sink)
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            torch.cuda.synchronize()
+            ev[0].record()
+            mb.moe_debug_pipeline_probe(mode, iters, src, sink)
+            ev[1].record()
+            torch.cuda.synchronize()
+            ms = ev[0].elapsed_time(ev[1])
+            res.append({"block": "16x16x32", "operands": "random", "loop": what,
+                        "ms": round(ms, 3), "tflops": round(flops / (ms * 1e-3) / 1e12, 1)})
+        del src
         out["mfma_probe"] = res
     if args.dense_reference:
         A = torch.randn((wl.R, wl.K), device="cuda:0").to(torch.bfloat16)

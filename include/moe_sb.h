@@ -305,6 +305,19 @@ void moe_debug_streaming(int mode);
  * may write.  Returns MOE_ERR_INVALID_ARG for another block size, iters < 1 or a NULL sink. */
 int moe_debug_mfma_probe(int block, int random_operands, int iters, void* sink, void* stream);
 
+/* Measurement aid: the inner loop of the 256x256x64 bf16 tile (eight wavefronts, 16x16x32 MFMAs on a 128x64
+ * accumulator block each) assembled one ingredient at a time, to price each against the pure-MFMA rate above.
+ *   mode 1: MFMAs + the LDS fragment reads of every k-step;  2: + one workgroup barrier per 64-deep k-tile;
+ *   3: + the k-tile's 64 KB of global->LDS DMA from a cache-resident source;
+ *   4: as 3 with half of those bytes from lines never touched before (about the real kernel's HBM share).
+ * Enqueues one kernel of 256 workgroups x 512 threads; FLOPs of the launch = 256 * 8 * iters * 524288
+ * (iters counts k-steps: even, >= 2).  `src`: DEVICE memory, 16-byte aligned, read only, at least 1 MiB
+ * (mode 4: 513 MiB); its first 64 KiB become the fragments, so fill it with bf16 values of the magnitude of
+ * real operands.  `sink`: DEVICE memory of at least 4 bytes that the kernel may write.  Nothing is allocated.
+ * Returns MOE_ERR_INVALID_ARG for another mode, an odd or too small iters, a NULL or misaligned pointer or a
+ * src_bytes below the stated minimum. */
+int moe_debug_pipeline_probe(int mode, int iters, const void* src, size_t src_bytes, void* sink, void* stream);
+
 /* Static string for a return code. */
 const char* moe_strerror(int code);
 

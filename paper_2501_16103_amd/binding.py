@@ -44,7 +44,7 @@ EXPORTS = [
     "moe_build_task_map_ordered", "moe_build_task_map_tiled", "moe_grid_upper_bound_tiled", "moe_tile_pair_supported",
     "moe_build_task_map_ex", "moe_tiling_supported", "moe_w_layout_supported", "moe_default_tiling",
     "moe_task_map_status", "moe_task_map_expand", "moe_grouped_gemm", "moe_tile_supported", "moe_combine",
-    "moe_debug_streaming", "moe_debug_mfma_probe", "moe_strerror",
+    "moe_debug_streaming", "moe_debug_mfma_probe", "moe_debug_pipeline_probe", "moe_strerror",
 ]
 
 
@@ -120,6 +120,9 @@ def lib() -> ctypes.CDLL:
         L.moe_debug_streaming.argtypes = [ctypes.c_int]
         L.moe_debug_mfma_probe.restype = ctypes.c_int
         L.moe_debug_mfma_probe.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+        L.moe_debug_pipeline_probe.restype = ctypes.c_int
+        L.moe_debug_pipeline_probe.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
+                                               ctypes.c_void_p]
         L.moe_strerror.restype = ctypes.c_char_p
         L.moe_strerror.argtypes = [ctypes.c_int]
         _lib = L
@@ -303,6 +306,17 @@ def moe_debug_mfma_probe(block: int, random_operands: bool, iters: int, sink, ch
                                     _stream() if sink is not None else None)
     if check and rc != MOE_OK:
         raise MoeError(rc, "moe_debug_mfma_probe")
+    return rc
+
+
+def moe_debug_pipeline_probe(mode: int, iters: int, src, sink, check: bool = True) -> int:
+    """One launch of the tile-loop probe (1: LDS reads, 2: + barrier, 3: + DMA from cache, 4: + half of it from HBM);
+    FLOPs = 256 * 8 * iters * 524288.  `src`: device tensor of >= 1 MiB (mode 4: 513 MiB) holding bf16 values."""
+    nbytes = 0 if src is None else src.numel() * src.element_size()
+    rc = lib().moe_debug_pipeline_probe(int(mode), int(iters), _ptr(src), ctypes.c_size_t(nbytes), _ptr(sink),
+                                        _stream() if sink is not None and src is not None else None)
+    if check and rc != MOE_OK:
+        raise MoeError(rc, "moe_debug_pipeline_probe")
     return rc
 
 

@@ -462,6 +462,29 @@ int moe_debug_mfma_probe(int block, int random_operands, int iters, void* sink, 
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
+int moe_debug_pipeline_probe(int mode, int iters, const void* src, size_t src_bytes, void* sink, void* stream) {
+    const size_t need = mode == 4 ? (size_t(513) << 20) : (size_t(1) << 20);
+    if (mode < 1 || mode > 4 || iters < 2 || (iters & 1) || !src || !sink || src_bytes < need ||
+        (reinterpret_cast<uintptr_t>(src) & 15))
+        return MOE_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const char* in = static_cast<const char*>(src);
+    float* out = static_cast<float*>(sink);
+    constexpr int lds = 96 * 1024;   // one workgroup per CU, as for the tile it imitates
+    static unsigned long long done[4] = {0, 0, 0, 0};
+    auto go = [&](auto kernel, unsigned long long* d) {
+        if (ensure_lds_attr(reinterpret_cast<const void*>(kernel), lds, d) != MOE_OK) return int(MOE_ERR_HIP);
+        kernel<<<256, 512, lds, s>>>(iters, in, out);
+        return hipGetLastError() == hipSuccess ? int(MOE_OK) : int(MOE_ERR_HIP);
+    };
+    switch (mode) {
+        case 1: return go(&moe::pipeline_probe_kernel<1>, &done[0]);
+        case 2: return go(&moe::pipeline_probe_kernel<2>, &done[1]);
+        case 3: return go(&moe::pipeline_probe_kernel<3>, &done[2]);
+        default: return go(&moe::pipeline_probe_kernel<4>, &done[3]);
+    }
+}
+
 const char* moe_strerror(int code) {
     switch (code) {
         case MOE_OK: return "ok";

@@ -349,6 +349,19 @@ def test_mfma_probe_runs(dev):
     assert float(sink.abs().sum()) == 0.0
 
 
+def test_pipeline_probe_runs(dev):
+    """Every mode of the tile-loop probe launches and completes; the source buffer is left as it was."""
+    g = torch.Generator().manual_seed(5)
+    src = torch.randn((513 << 20) // 2, generator=g).to(torch.bfloat16).to(dev)
+    before = src[: 1 << 20].clone()
+    sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    for mode in (1, 2, 3, 4):
+        assert mb.moe_debug_pipeline_probe(mode, 64, src, sink) == mb.MOE_OK
+    assert mb.moe_debug_pipeline_probe(4, 64, src[: 1 << 20], sink, check=False) == mb.MOE_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+    assert torch.equal(src[: 1 << 20], before)
+
+
 LAYER_CASES = [
     # T, k, E, hidden, inter, routing, weighted
     (300, 2, 8, 256, 384, "zipf", True),
