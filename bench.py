@@ -384,6 +384,19 @@ def main():
             ms = ev[0].elapsed_time(ev[1])
             res.append({"block": "16x16x32", "operands": "random", "loop": what,
                         "ms": round(ms, 3), "tflops": round(flops / (ms * 1e-3) / 1e12, 1)})
+        # the LDS pipe alone: bytes per wavefront and k-step of each mode, reported per CU and nanosecond
+        for mode, what, nbytes in ((5, "16-byte fragment reads only", 8192), (6, "transposing 8-byte reads only", 4096),
+                                   (7, "both kinds of reads", 12288), (8, "DMA writes only", 4096)):
+            mb.moe_debug_pipeline_probe(mode, 1000, src, sink)
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            torch.cuda.synchronize()
+            ev[0].record()
+            mb.moe_debug_pipeline_probe(mode, iters, src, sink)
+            ev[1].record()
+            torch.cuda.synchronize()
+            ms = ev[0].elapsed_time(ev[1])
+            res.append({"lds_only": what, "ms": round(ms, 3), "lds_bytes_per_ns_per_cu": round(8 * iters * nbytes / (ms * 1e6), 1),
+                        "ns_per_k_step": round(ms * 1e6 / iters, 1)})
         del src
         out["mfma_probe"] = res
     if args.dense_reference:

@@ -208,7 +208,9 @@ int moe_build_task_map_ex(const int32_t* topk_ids, int T, int k, int E, int N, c
  *   bf16: up to 48 rows per expert 128 x 128 when 256-wide tiles would leave CUs without one; else up to
  *   8 rows 16 x 256; from 48 to 96 rows 128 x 256 when there are enough n-tiles to fill
  *   the chip three times over, else 64 x 256; otherwise 256 x 256 (its launch handles tiles of at most 64 and
- *   128 rows with narrower task functions), with 32 slack rows above 192 rows per expert.
+ *   128 rows with narrower task functions), with 32 slack rows above 192 rows per expert.  Where that choice
+ *   would give fewer than three quarters of the CUs a tile under a balanced routing (few experts and a narrow N:
+ *   a down projection at a few hundred tokens), the largest of 128 x 256, 128 x 128, 64 x 128 that does.
  * Always ascending order, one strategy.  The result satisfies moe_tiling_supported when N % tile_n == 0 allows
  * it (tile_n falls back to 128 or 64).  Returns MOE_ERR_INVALID_ARG on bad arguments, MOE_ERR_UNSUPPORTED when
  * no kernel fits (N not a multiple of 64).
@@ -309,7 +311,10 @@ int moe_debug_mfma_probe(int block, int random_operands, int iters, void* sink, 
  * accumulator block each) assembled one ingredient at a time, to price each against the pure-MFMA rate above.
  *   mode 1: MFMAs + the LDS fragment reads of every k-step;  2: + one workgroup barrier per 64-deep k-tile;
  *   3: + the k-tile's 64 KB of global->LDS DMA from a cache-resident source;
- *   4: as 3 with half of those bytes from lines never touched before (about the real kernel's HBM share).
+ *   4: as 3 with half of those bytes from lines never touched before (about the real kernel's HBM share);
+ *   5-8: no MFMAs, the LDS pipe alone (no FLOPs): 5 the 16-byte fragment reads of every k-step (8 per lane,
+ *   8 KiB per wavefront), 6 the transposing 8-byte reads (8 per lane, 4 KiB), 7 both, 8 the DMA writes
+ *   (4 instructions of 1 KiB per wavefront and k-step).
  * Enqueues one kernel of 256 workgroups x 512 threads; FLOPs of the launch = 256 * 8 * iters * 524288
  * (iters counts k-steps: even, >= 2).  `src`: DEVICE memory, 16-byte aligned, read only, at least 1 MiB
  * (mode 4: 513 MiB); its first 64 KiB become the fragments, so fill it with bf16 values of the magnitude of

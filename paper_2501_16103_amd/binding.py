@@ -310,8 +310,8 @@ def moe_debug_mfma_probe(block: int, random_operands: bool, iters: int, sink, ch
 
 
 def moe_debug_pipeline_probe(mode: int, iters: int, src, sink, check: bool = True) -> int:
-    """One launch of the tile-loop probe (1: LDS reads, 2: + barrier, 3: + DMA from cache, 4: + half of it from HBM);
-    FLOPs = 256 * 8 * iters * 524288.  `src`: device tensor of >= 1 MiB (mode 4: 513 MiB) holding bf16 values."""
+    """One launch of the tile-loop probe (1: LDS reads, 2: + barrier, 3: + DMA from cache, 4: + half of it from HBM;
+    5-8: the LDS pipe alone: 16-byte reads, transposing reads, both, DMA writes); FLOPs (modes 1-4) = 256 * 8 * iters * 524288.  `src`: device tensor of >= 1 MiB (mode 4: 513 MiB) holding bf16 values."""
     nbytes = 0 if src is None else src.numel() * src.element_size()
     rc = lib().moe_debug_pipeline_probe(int(mode), int(iters), _ptr(src), ctypes.c_size_t(nbytes), _ptr(sink),
                                         _stream() if sink is not None and src is not None else None)

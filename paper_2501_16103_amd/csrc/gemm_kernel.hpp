@@ -965,6 +965,7 @@ __global__ void __launch_bounds__(512) mfma_probe_kernel(int iters, float* sink)
 //   MODE 3: + the k-tile's 64 KB of global->LDS DMA (8 instructions per thread), source resident in cache
 //   MODE 4: as 3, but half of the bytes come from lines not touched before (a new 32 KB chunk of `src` per k-tile,
 //           shared by two workgroups), about the weight traffic the real kernel draws from HBM
+//   MODE 5-8: no MFMAs, the LDS pipe alone: the 16-byte reads, the transposing reads, both, the DMA writes
 // `src`: at least 1 MB (MODE 4: 513 MB) of device memory; its first 64 KB fill the LDS region the fragments are
 // read from, so bf16 values there make the operands realistic.  Per loop trip (two k-steps) and wavefront 1 MFLOP.
 template <int MODE>
@@ -985,14 +986,18 @@ __global__ void __launch_bounds__(512) pipeline_probe_kernel(int iters, const ch
     auto load = [&](int buf, int it) __attribute__((always_inline)) {
         int base = (it & 3) * 16384 + (wave & 1) * 8192;
         asm volatile("" : "+v"(base));
+        if (MODE != 6) {
 #pragma unroll
-        for (int i = 0; i < MB; ++i) xq[buf][i] = *reinterpret_cast<const u32x4_t*>(smem + base + lane * 16 + i * 1024);
+            for (int i = 0; i < MB; ++i) xq[buf][i] = *reinterpret_cast<const u32x4_t*>(smem + base + lane * 16 + i * 1024);
+        }
+        if (MODE != 5) {
 #pragma unroll
-        for (int j = 0; j < NB; ++j)
+            for (int j = 0; j < NB; ++j)
 #pragma unroll
-            for (int h = 0; h < 2; ++h)
-                wq[buf][j][h] = __builtin_bit_cast(u32x2_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (MOE_LDS(s16x4_t)*)(smem + ((base + lane * 8 + (j * 2 + h) * 512) & 65535))));
+                for (int h = 0; h < 2; ++h)
+                    wq[buf][j][h] = __builtin_bit_cast(u32x2_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                        (MOE_LDS(s16x4_t)*)(smem + ((base + lane * 8 + (j * 2 + h) * 512) & 65535))));
+        }
     };
     auto mma = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
@@ -1015,6 +1020,28 @@ __global__ void __launch_bounds__(512) pipeline_probe_kernel(int iters, const ch
         for (int r = 0; r < 4; ++r)
             dma16(lane * 16 + wave * 1024 + r * 8192, half ? src_w : src_x, lds0 + 65536 + r * 8192 + wave * 1024);
     };
+    if constexpr (MODE >= 5) {
+        // no MFMAs: the LDS pipe alone.  5: the 16-byte reads of a k-step, 6: its transposing 8-byte reads,
+        // 7: both, 8: the k-tile's DMA writes (cache-resident source)
+        for (int it = 0; it < iters; it += 2) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                if (MODE <= 7) load(h, it + h);
+                if (MODE == 5 || MODE == 7) {
+#pragma unroll
+                    for (int i = 0; i < MB; ++i) asm volatile("" ::"v"(xq[h][i]));
+                }
+                if (MODE == 6 || MODE == 7) {
+#pragma unroll
+                    for (int j = 0; j < NB; ++j) asm volatile("" ::"v"(wq[h][j][0]), "v"(wq[h][j][1]));
+                }
+                if (MODE == 8) { dmas(it, h); wait_vmcnt<4>(); }
+            }
+        }
+        if (MODE == 8) wait_vmcnt<0>();
+        if (iters < 0) sink[0] = 0.f;
+        return;
+    }
     load(0, 0);
     for (int it = 0; it < iters; it += 2) {
         load(1, it + 1);

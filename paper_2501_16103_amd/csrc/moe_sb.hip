@@ -276,14 +276,35 @@ int moe_default_tiling(int dtype, int T, int k, int E, int K, int N, moe_tiling*
     } else if (mean_rows <= 8) {
         // nearly every expert's rows fit one 16-row tile (count ~ mean +- 3 sqrt(mean))
         g.tile_m = 16; g.tile_n = 256;
-    } else if (mean_rows > 48 && mean_rows <= 96) {
-        // counts straddle 64: the four-wave 64- and 128-row functions of the 128-row launch
-        g.tile_m = active * ((N + 255) / 256) >= 3 * cus ? 128 : 64;
-        g.tile_n = 256;
     } else {
-        // 256-row tiles; their launch runs tiles of at most 64 / 128 rows with narrower task functions, which
-        // covers the small counts too.  Slack rows pay once experts hold several tiles.
-        g.tile_m = 256; g.tile_n = 256; g.tile_m_slack = mean_rows > 192 ? 32 : 0;
+        // expected tiles of a tiling under a balanced routing: counts spread around the mean, so an expert takes
+        // mean / tile_m + 1/2 m-tiles on average, and at least one
+        auto tiles = [&](int tm, int tn) {
+            const double mt = mean_rows / tm + 0.5;
+            return (double)active * (mt < 1.0 ? 1.0 : mt) * ((N + tn - 1) / tn);
+        };
+        bool short_grid;
+        if (mean_rows > 48 && mean_rows <= 96) {
+            // counts straddle 64: the four-wave 64- and 128-row functions of the 128-row launch
+            g.tile_m = active * ((N + 255) / 256) >= 3 * cus ? 128 : 64;
+            g.tile_n = 256;
+            short_grid = active * ((N + 255) / 256) < cus;
+        } else {
+            // 256-row tiles; their launch runs tiles of at most 64 / 128 rows with narrower task functions, which
+            // covers the small counts too.  Slack rows pay once experts hold several tiles.
+            g.tile_m = 256; g.tile_n = 256; g.tile_m_slack = mean_rows > 192 ? 32 : 0;
+            short_grid = tiles(256, 256) < 0.75 * cus;
+        }
+        if (short_grid) {
+            // few experts and a narrow N (a down projection at a few hundred tokens): the launch would leave CUs
+            // idle through a long k loop.  Take the largest tile that still gives three quarters of the CUs one.
+            const int cand[3][2] = {{128, 256}, {128, 128}, {64, 128}};
+            for (int c = 0; c < 3; ++c) {
+                if (N % cand[c][1] != 0) continue;
+                g.tile_m = cand[c][0]; g.tile_n = cand[c][1]; g.tile_m_slack = 0;
+                if (tiles(cand[c][0], cand[c][1]) >= 0.75 * cus) break;
+            }
+        }
     }
     // the n-tile must divide N; narrower tiles keep the same row tiling where a kernel exists
     for (int tn = g.tile_n; tn >= 64; tn >>= 1) {
@@ -464,14 +485,14 @@ int moe_debug_mfma_probe(int block, int random_operands, int iters, void* sink, 
 
 int moe_debug_pipeline_probe(int mode, int iters, const void* src, size_t src_bytes, void* sink, void* stream) {
     const size_t need = mode == 4 ? (size_t(513) << 20) : (size_t(1) << 20);
-    if (mode < 1 || mode > 4 || iters < 2 || (iters & 1) || !src || !sink || src_bytes < need ||
+    if (mode < 1 || mode > 8 || iters < 2 || (iters & 1) || !src || !sink || src_bytes < need ||
         (reinterpret_cast<uintptr_t>(src) & 15))
         return MOE_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const char* in = static_cast<const char*>(src);
     float* out = static_cast<float*>(sink);
     constexpr int lds = 96 * 1024;   // one workgroup per CU, as for the tile it imitates
-    static unsigned long long done[4] = {0, 0, 0, 0};
+    static unsigned long long done[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     auto go = [&](auto kernel, unsigned long long* d) {
         if (ensure_lds_attr(reinterpret_cast<const void*>(kernel), lds, d) != MOE_OK) return int(MOE_ERR_HIP);
         kernel<<<256, 512, lds, s>>>(iters, in, out);
@@ -481,7 +502,11 @@ int moe_debug_pipeline_probe(int mode, int iters, const void* src, size_t src_by
         case 1: return go(&moe::pipeline_probe_kernel<1>, &done[0]);
         case 2: return go(&moe::pipeline_probe_kernel<2>, &done[1]);
         case 3: return go(&moe::pipeline_probe_kernel<3>, &done[2]);
-        default: return go(&moe::pipeline_probe_kernel<4>, &done[3]);
+        case 4: return go(&moe::pipeline_probe_kernel<4>, &done[3]);
+        case 5: return go(&moe::pipeline_probe_kernel<5>, &done[4]);
+        case 6: return go(&moe::pipeline_probe_kernel<6>, &done[5]);
+        case 7: return go(&moe::pipeline_probe_kernel<7>, &done[6]);
+        default: return go(&moe::pipeline_probe_kernel<8>, &done[7]);
     }
 }
 

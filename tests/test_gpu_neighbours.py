@@ -355,7 +355,7 @@ def test_pipeline_probe_runs(dev):
     src = torch.randn((513 << 20) // 2, generator=g).to(torch.bfloat16).to(dev)
     before = src[: 1 << 20].clone()
     sink = torch.zeros(4, dtype=torch.float32, device=dev)
-    for mode in (1, 2, 3, 4):
+    for mode in range(1, 9):
         assert mb.moe_debug_pipeline_probe(mode, 64, src, sink) == mb.MOE_OK
     assert mb.moe_debug_pipeline_probe(4, 64, src[: 1 << 20], sink, check=False) == mb.MOE_ERR_INVALID_ARG
     torch.cuda.synchronize()
