@@ -679,10 +679,33 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
 
         // ---- epilogue: fp32 -> bf16 (RNE), scatter to Y[r, n]; fp8 applies the two scales first
         if constexpr (STAGED) __syncthreads();   // every wavefront has read its last fragments and all DMAs have landed
+        // Every row id the epilogue needs is fetched here, in one batch and without branches (rows past the tile's
+        // count read row 0's id and are never stored).  Loads and stores share one in-order counter: a load placed
+        // between the stores waits for the store before it to be acknowledged, once per row group (measured: 6.5 us
+        // of an 18-group epilogue).
+        constexpr int PASSES = STAGED ? C::WTM * CPROF / 64 : 1;
+        int r_pass[PASSES], r_mb[MBW];
+        const int cu_ = a.swiglu ? CPROF / 2 : CPROF;   // 16-byte chunks per staged row; 64 / cu_ rows per instruction
+        if constexpr (STAGED) {
+#pragma unroll
+            for (int pass = 0; pass < PASSES; ++pass) {
+                const int lr = pass * (64 / cu_) + lane / cu_;
+                const int m_local = ((lr / MF) * C::WM + wm) * MF + (lr % MF);
+                const bool live = lr < C::WTM && m_local < tc.rows;
+                const int r = rows_of_tile[live ? m_local : 0];
+                r_pass[pass] = live ? r : -1;
+            }
+        } else if constexpr (!STREAM) {
+#pragma unroll
+            for (int mb = 0; mb < MBW; ++mb) {
+                const int m_local = (mb * C::WM + wm) * MF + lrow;
+                r_mb[mb] = rows_of_tile[m_local < tc.rows ? m_local : 0];
+            }
+        }
 #pragma unroll
         for (int mb = 0; mb < MBW; ++mb) {
             const int m_local = (mb * C::WM + wm) * MF + lrow;
-            int r;
+            int r = 0;
             float xsc = 1.f, wsc = 1.f;
             if constexpr (STREAM) {
                 r = __shfl(rows_v, m_local);
@@ -690,7 +713,7 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
                 if (m_local >= tc.rows) continue;
             } else {
                 if (m_local >= tc.rows) continue;
-                r = rows_of_tile[m_local];
+                if constexpr (!STAGED) r = r_mb[mb];
                 if constexpr (C::FP8) { xsc = a.x_scale[r / a.k]; wsc = a.w_scale[tc.e]; }
             }
             if (!a.swiglu) {
@@ -739,20 +762,18 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
         }
         if constexpr (STAGED) {
             // read the corner back row by row: cu 16-byte chunks per row, 64 / cu rows per instruction
-            const int cu = a.swiglu ? CPROF / 2 : CPROF;
+            wait_vmcnt<0>();   // the row ids, long since there; told here so that no wait lands between the stores
+            const int cu = cu_;
             const int rpi = 64 / cu;
             const int c = lane & (cu - 1), lr0 = lane / cu;
             const size_t col_bytes = (size_t)(a.swiglu ? (n0 + wn * C::WTN) >> 1 : n0 + wn * C::WTN) * 2 + c * 16;
 #pragma unroll
-            for (int pass = 0; pass < C::WTM * CPROF / 64; ++pass) {
+            for (int pass = 0; pass < PASSES; ++pass) {
                 const int lr = pass * rpi + lr0;
-                if (lr < C::WTM) {
-                    const int m_local = ((lr / MF) * C::WM + wm) * MF + (lr % MF);
-                    if (m_local < tc.rows) {
-                        const int r = rows_of_tile[m_local];
-                        const u32x4_t v = *reinterpret_cast<const u32x4_t*>(stage + lr * RBMAX + ((c ^ (lr & (CPROF - 1))) << 4));
-                        *reinterpret_cast<u32x4_t*>(Yb + (size_t)r * y_row_bytes + col_bytes) = v;
-                    }
+                const int r = r_pass[pass];
+                if (r >= 0) {
+                    const u32x4_t v = *reinterpret_cast<const u32x4_t*>(stage + lr * RBMAX + ((c ^ (lr & (CPROF - 1))) << 4));
+                    *reinterpret_cast<u32x4_t*>(Yb + (size_t)r * y_row_bytes + col_bytes) = v;
                 }
             }
         }
