@@ -261,7 +261,7 @@ def layer_point(T: int, steps: int, warmup: int, dev="cuda:0") -> dict:
                 layer_ms=round(ms, 4), tflops=round(flops / (ms * 1e-3) / 1e12, 2),
                 tokens_per_s=round(T / (ms * 1e-3), 1),
                 tilings={"gate_up": [plan.g1.tile_m, plan.g1.tile_n, plan.g1.tile_m_slack],
-                         "down": [plan.g2.tile_m, plan.g2.tile_n, plan.g2.tile_m_slack]})
+                         "down": [plan.g2.tile_m, plan.g2.tile_n, plan.g2.tile_m_slack], "down_k_parts": plan.k_parts})
 
 
 def all_points():
@@ -470,7 +470,7 @@ def main():
                 torch.cuda.empty_cache()
         if want is None or "layer" in want:
             # labelled extra: the whole feed-forward layer composed from the library's calls
-            for T in (4096, 256, 16):
+            for T in (4096, 512, 256, 16):
                 points.append(layer_point(T, max(10, args.steps // 2), max(3, args.warmup // 2)))
                 torch.cuda.empty_cache()
         out["points"] = points

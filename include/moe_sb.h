@@ -274,6 +274,33 @@ typedef struct moe_gemm_desc {
 int moe_grouped_gemm(const void* X, const void* W, const int32_t* topk_ids, const void* task_map, void* Y,
                      const moe_gemm_desc* desc, void* stream);
 
+/*
+ * The same product for launches too short to give every CU a tile (few experts, a narrow N and a long K: a down
+ * projection at several hundred tokens), split along K: every tile of the map (Sec. 3.1: the map is unchanged, a
+ * workgroup finds its tile as always) is run by k_parts workgroups, each over one k_parts-th of K; their fp32 sums
+ * go to `workspace` and a second kernel adds them in ascending order of the parts, rounds once to bf16 and scatters
+ * the rows to Y.  Same result definition and tolerance as moe_grouped_gemm; the summation order differs.
+ *   workspace  DEVICE, 16-byte aligned, at least moe_splitk_workspace_bytes(T, k, N, k_parts) bytes
+ *              (k_parts * T*k * N fp32); owned by the caller, contents undefined afterwards; calls that share a
+ *              workspace must not overlap.
+ * Supported: bf16, MOE_W_LAYOUT_KN, MOE_EPILOGUE_NONE, tile 256 x 256 without slack rows and with one tiling
+ * strategy, k_parts 2 or 4 with (K / 64) % k_parts == 0 and K / 64 / k_parts >= 8, N % 256 == 0; anything else
+ * returns MOE_ERR_UNSUPPORTED.  MOE_ERR_INVALID_ARG for NULL or misaligned pointers or a workspace that is too small.
+ */
+int moe_grouped_gemm_splitk(const void* X, const void* W, const void* task_map, void* Y, const moe_gemm_desc* desc,
+                            int k_parts, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace moe_grouped_gemm_splitk needs (0 for k_parts < 2 or bad sizes).  HOST, pure. */
+size_t moe_splitk_workspace_bytes(int T, int k, int N, int k_parts);
+
+/* Whether to split, for a bf16 product over 256 x 256 tiles (HOST, pure): 1 = no (use moe_grouped_gemm with
+ * moe_default_tiling), else the k_parts (2 or 4) to pass to moe_grouped_gemm_splitk with a plain 256 x 256
+ * tiling.  It says yes where, under a balanced
+ * routing, 256 x 256 tiles would cover fewer than three quarters of the CUs, the experts hold at least 120 rows on
+ * average and every part keeps at least 16 k-tiles (the fewest parts that cover
+ * three quarters of the CUs, else four, else two).  MOE_ERR_INVALID_ARG (negative) on bad arguments. */
+int moe_default_k_parts(int T, int k, int E, int K, int N);
+
 /* 1 if a GEMM kernel exists for this (dtype, tile_m, tile_n), else 0.  HOST, pure. */
 int moe_tile_supported(int dtype, int tile_m, int tile_n);
 /* 1 if a GEMM kernel exists for this dtype, tiling and weight layout, else 0.  HOST, pure. */

@@ -44,6 +44,7 @@ EXPORTS = [
     "moe_build_task_map_ordered", "moe_build_task_map_tiled", "moe_grid_upper_bound_tiled", "moe_tile_pair_supported",
     "moe_build_task_map_ex", "moe_tiling_supported", "moe_w_layout_supported", "moe_default_tiling",
     "moe_task_map_status", "moe_task_map_expand", "moe_grouped_gemm", "moe_tile_supported", "moe_combine",
+    "moe_grouped_gemm_splitk", "moe_splitk_workspace_bytes", "moe_default_k_parts",
     "moe_debug_streaming", "moe_debug_mfma_probe", "moe_debug_pipeline_probe", "moe_strerror",
 ]
 
@@ -120,6 +121,14 @@ def lib() -> ctypes.CDLL:
         L.moe_debug_streaming.argtypes = [ctypes.c_int]
         L.moe_debug_mfma_probe.restype = ctypes.c_int
         L.moe_debug_mfma_probe.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+        L.moe_grouped_gemm_splitk.restype = ctypes.c_int
+        L.moe_grouped_gemm_splitk.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                              ctypes.POINTER(moe_gemm_desc), ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t,
+                                              ctypes.c_void_p]
+        L.moe_splitk_workspace_bytes.restype = ctypes.c_size_t
+        L.moe_splitk_workspace_bytes.argtypes = [ctypes.c_int] * 4
+        L.moe_default_k_parts.restype = ctypes.c_int
+        L.moe_default_k_parts.argtypes = [ctypes.c_int] * 5
         L.moe_debug_pipeline_probe.restype = ctypes.c_int
         L.moe_debug_pipeline_probe.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
                                                ctypes.c_void_p]
@@ -296,6 +305,29 @@ def moe_combine(Y: torch.Tensor, topk_weights: Optional[torch.Tensor], T: int, k
     return rc
 
 
+def moe_splitk_workspace_bytes(T: int, k: int, N: int, k_parts: int) -> int:
+    return int(lib().moe_splitk_workspace_bytes(T, k, N, k_parts))
+
+
+def moe_default_k_parts(T: int, k: int, E: int, K: int, N: int) -> int:
+    rc = lib().moe_default_k_parts(T, k, E, K, N)
+    if rc < 1:
+        raise MoeError(rc, "moe_default_k_parts")
+    return rc
+
+
+def moe_grouped_gemm_splitk(X: torch.Tensor, W: torch.Tensor, task_map: torch.Tensor, Y: torch.Tensor, desc: "GemmDesc",
+                            k_parts: int, workspace: Optional[torch.Tensor], check: bool = True) -> int:
+    """Split-k form of moe_grouped_gemm; `workspace`: device tensor of >= moe_splitk_workspace_bytes(...) bytes."""
+    c = desc.c_struct()
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib().moe_grouped_gemm_splitk(_ptr(X), _ptr(W), _ptr(task_map), _ptr(Y), ctypes.byref(c), int(k_parts),
+                                       _ptr(workspace), ctypes.c_size_t(nbytes), _stream() if X is not None else None)
+    if check and rc != MOE_OK:
+        raise MoeError(rc, "moe_grouped_gemm_splitk")
+    return rc
+
+
 def moe_debug_streaming(mode: int) -> None:
     lib().moe_debug_streaming(int(mode))
 
@@ -326,14 +358,19 @@ class MoeLayerPlan:
         map(T, k) -> gate+up product with the fused gated activation -> map(T*k, 1) -> down product -> weighted sum.
 
     The second product sees the T*k activated rows as tokens of their own, each routed to exactly one expert
-    (the flattened routing with k = 1), so the same two entry points serve both products.  Nothing here computes:
+    (the flattened routing with k = 1), so the same two entry points serve both products (the second one in its
+    split-k form, with a workspace held here, where moe_default_k_parts says so).  Nothing here computes:
     the plan holds caller-visible device buffers and issues calls on the current stream."""
 
     def __init__(self, T: int, k: int, E: int, hidden: int, inter: int, device="cuda:0"):
         self.T, self.k, self.E, self.hidden, self.inter = T, k, E, hidden, inter
         R = T * k
         self.g1 = moe_default_tiling(MOE_DTYPE_BF16, T, k, E, hidden, 2 * inter)
-        self.g2 = moe_default_tiling(MOE_DTYPE_BF16, R, 1, E, inter, hidden)
+        # the down product is the short-grid case (few experts, N = hidden): split along K where that pays
+        self.k_parts = moe_default_k_parts(R, 1, E, inter, hidden) if R > 0 else 1
+        self.g2 = Tiling(256, 256) if self.k_parts > 1 else moe_default_tiling(MOE_DTYPE_BF16, R, 1, E, inter, hidden)
+        self.workspace = (torch.empty(moe_splitk_workspace_bytes(R, 1, hidden, self.k_parts) // 4, dtype=torch.float32, device=device)
+                          if self.k_parts > 1 else None)
         self.map1 = alloc_task_map(T, k, E, self.g1.tile_m, self.g1.tile_n, 2 * inter, device)
         self.map2 = alloc_task_map(R, 1, E, self.g2.tile_m, self.g2.tile_n, hidden, device)
         self.act = torch.empty((R, inter), dtype=torch.bfloat16, device=device)       # [T, k, inter]
@@ -355,6 +392,9 @@ class MoeLayerPlan:
         moe_build_task_map_ex(topk_ids, T, k, E, 2 * self.inter, self.g1, self.map1)
         moe_grouped_gemm(X, W_gate_up, topk_ids, self.map1, self.act, self.d1)
         moe_build_task_map_ex(flat, T * k, 1, E, self.hidden, self.g2, self.map2)
-        moe_grouped_gemm(self.act, W_down, flat, self.map2, self.down, self.d2)
+        if self.k_parts > 1:
+            moe_grouped_gemm_splitk(self.act, W_down, self.map2, self.down, self.d2, self.k_parts, self.workspace)
+        else:
+            moe_grouped_gemm(self.act, W_down, flat, self.map2, self.down, self.d2)
         moe_combine(self.down, topk_weights, T, k, self.hidden, self.out)
         return self.out

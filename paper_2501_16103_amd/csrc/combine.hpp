@@ -50,4 +50,29 @@ __global__ __launch_bounds__(256) void moe_combine_kernel(const u32x4_t* __restr
     }
 }
 
+// Second half of a split-k product: Y[r(p), n] = bf16( sum_s partial[s][p][n] ), s ascending, for every position p of
+// sorted_rows (r(p) = sorted_rows[p]); each lane owns 8 consecutive n of one position.  A map that is invalid or
+// empty (status != 0: no tile ran, the workspace holds nothing) makes this a no-op, like the product itself.
+__global__ __launch_bounds__(256) void moe_splitk_reduce_kernel(const float* __restrict__ partial, const int32_t* __restrict__ map,
+                                                                const int32_t* __restrict__ sorted_rows, u32x4_t* __restrict__ Y,
+                                                                int R, int N, int parts) {
+    if (map[MOE_HDR_STATUS] != 0 || map[MOE_HDR_TOTAL_TILES] == 0) return;
+    const int cpr = N >> 3;
+    const long long total = (long long)R * cpr;
+    const size_t part_stride = (size_t)R * N;
+    for (long long c = (long long)blockIdx.x * 256 + threadIdx.x; c < total; c += (long long)gridDim.x * 256) {
+        const int p = (int)(c / cpr), col = (int)(c - (long long)p * cpr);
+        const float* src = partial + (size_t)p * N + (size_t)col * 8;
+        f32x4_t lo = *reinterpret_cast<const f32x4_t*>(src), hi = *reinterpret_cast<const f32x4_t*>(src + 4);
+        for (int sp = 1; sp < parts; ++sp) {
+            lo += *reinterpret_cast<const f32x4_t*>(src + sp * part_stride);
+            hi += *reinterpret_cast<const f32x4_t*>(src + sp * part_stride + 4);
+        }
+        u32x4_t o;
+        o.x = pack_bf16(lo[0], lo[1]); o.y = pack_bf16(lo[2], lo[3]);
+        o.z = pack_bf16(hi[0], hi[1]); o.w = pack_bf16(hi[2], hi[3]);
+        Y[(size_t)sorted_rows[p] * cpr + col] = o;
+    }
+}
+
 }  // namespace moe

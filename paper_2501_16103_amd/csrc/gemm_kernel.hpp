@@ -47,6 +47,7 @@ struct GemmArgs {
     int tile_m_small, small_max_rows;  // second tiling strategy of the map (0, 0 = none)
     int tile_m_slack;                  // slack rows of the map's last m-tiles
     int swiglu;                        // 1: W = [gate | up] halves of N, Y[r, i] = silu(gate_i) * up_i, Y is [R, N/2]
+    float* partial;                    // split-k launches: fp32 partial sums [gridDim.y][R (sorted row position)][N]
 };
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
@@ -96,6 +97,7 @@ __device__ __forceinline__ void wait_vmcnt() {
 template <int BM_, int BN_, int BK_, int WM_, int WN_, int NS_, bool FP8_ = false, int NSW_ = NS_, int SLACK_ = 0,
           bool WKC_ = false, int MFO_ = 0, int NSWH_ = 0>
 struct PipeCfg {
+    static constexpr bool SPLITK = false;
     static constexpr bool WKC = WKC_;
     // NSWH_ > 0: the weight ring is NSWH_ stages of HALF a k-tile (when whole stages do not divide the LDS left
     // beside the token ring): k-tile kt lives in half-stages (2 kt) % NSWH_ and (2 kt + 1) % NSWH_, and the loop's
@@ -143,6 +145,14 @@ struct PipeCfg {
     static_assert(XS_BYTES % 1024 == 0 && WS_BYTES % 1024 == 0, "DMA granularity");
     static_assert(NSW >= NS && NS >= 2, "the weight ring is at least as deep as the token ring");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS");
+};
+
+// The same tile function as one of gridDim.y workgroups that share a tile: workgroup y runs the y-th part of the
+// k loop and leaves its fp32 sums in the workspace (row = position in sorted_rows, so no scatter here); a reduction
+// kernel adds the parts, rounds once and scatters.  For launches too short to give every CU a tile.
+template <class C>
+struct SplitK : C {
+    static constexpr bool SPLITK = true;
 };
 
 template <class C>
@@ -283,17 +293,20 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
         }
         dw_off[j] = (uint32_t)krow * w_row_bytes + col_bytes;
     }
-    const char* Xb = static_cast<const char*>(a.X);
+    // split-k: this workgroup's part of K (the row pitch of X and the k stride of W are those of the whole K)
+    const int k_parts = C::SPLITK ? (int)gridDim.y : 1;
+    const int KT = a.K / BK / k_parts;
+    const int k_first = C::SPLITK ? (int)blockIdx.y * KT * BK : 0;
+    const char* Xb = static_cast<const char*>(a.X) + (size_t)k_first * ES;
     // weight base of a tile: expert, and the first column the tile reads (half as far with the fused activation)
     auto w_base = [&](const TileCoord& t) {
         const size_t col = (size_t)(a.swiglu ? (t.n_tile * BN) >> 1 : t.n_tile * BN);
-        return static_cast<const char*>(a.W) + ((size_t)t.e * a.K * a.N + (C::WKC ? col * a.K : col)) * ES;
+        return static_cast<const char*>(a.W) + ((size_t)t.e * a.K * a.N + (C::WKC ? col * a.K + k_first : col + (size_t)k_first * a.N)) * ES;
     };
     const char* Wt = w_base(tc);
     const char* Wt_next = Wt;
     const size_t w_kt_stride = C::WKC ? (size_t)BK * ES : (size_t)BK * w_row_bytes;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(MOE_LDS(char)*)smem;
-    const int KT = a.K / BK;
 
     // Weight panels that only this tile reads are fetched non-temporally -- when the grid is large enough to
     // stream from all CUs (measured: +10 % HBM throughput on the weight-streaming points, -9 % on a 132-tile grid).
@@ -612,7 +625,7 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
     constexpr int RBMAX = C::WTN * 2, CPROF = RBMAX / 16;
     // (the 64-row-slack tile is larger than its rings and keeps the direct stores,
     // and so do the K-contiguous layout and fp8, whose large-tile kernels the extra code pushed into register spills)
-    constexpr bool STAGED = !STREAM && C::BM >= 64 && NW * C::WTM * RBMAX <= C::LDS_BYTES && !C::WKC && !C::FP8;
+    constexpr bool STAGED = !STREAM && C::BM >= 64 && NW * C::WTM * RBMAX <= C::LDS_BYTES && !C::WKC && !C::FP8 && !C::SPLITK;
     static_assert(!STAGED || (C::WTM * (CPROF / 2)) % 64 == 0, "staging area");
     char* const stage = smem + wave * (C::WTM * RBMAX);
     // 4 values of tile row block mb (this lane's row in it), tile columns n_out .. n_out + 3 of the OUTPUT row
@@ -695,6 +708,26 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
                 const int r = rows_of_tile[live ? m_local : 0];
                 r_pass[pass] = live ? r : -1;
             }
+        } else if constexpr (C::SPLITK) {
+            static_assert(!C::SPLITK || (!STREAM && !C::FP8 && !C::WKC), "split-k: bf16, weights as [E][K][N]");
+            // fp32 partial sums, 16 bytes (4 columns of one row) per lane and block; no row ids needed
+            float* const part = a.partial + (size_t)blockIdx.y * ((size_t)a.T * a.k) * a.N;
+#pragma unroll
+            for (int mb = 0; mb < MBW; ++mb) {
+                const int m_local = (mb * C::WM + wm) * MF + lrow;
+                if (m_local >= tc.rows) continue;
+                float* prow = part + (size_t)(tc.row_base + m_local) * a.N + n0;
+#pragma unroll
+                for (int nb = 0; nb < NBW; ++nb) {
+#pragma unroll
+                    for (int jq = 0; jq < C::ACC / 4; ++jq) {
+                        const int n_local = MF == 32 ? wn * C::WTN + nb * 32 + 8 * jq + 4 * (lane >> 5) : wn * C::WTN + nb * 16 + 4 * g;
+                        const f32x4_t v = {acc[nb][mb][4 * jq + 0], acc[nb][mb][4 * jq + 1], acc[nb][mb][4 * jq + 2], acc[nb][mb][4 * jq + 3]};
+                        *reinterpret_cast<f32x4_t*>(prow + n_local) = v;
+                    }
+                }
+            }
+            break;
         } else if constexpr (!STREAM) {
 #pragma unroll
             for (int mb = 0; mb < MBW; ++mb) {

@@ -51,6 +51,16 @@ int launch_pipe(const GemmArgs& a, int64_t grid, hipStream_t s) {
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
+// Split-k launch: `parts` workgroups per tile (grid.y), fp32 partial sums into a.partial.
+template <class C, class... Tails>
+int launch_splitk(const GemmArgs& a, int64_t grid, int parts, hipStream_t s) {
+    static unsigned long long attr_done = 0;
+    if (ensure_lds_attr(reinterpret_cast<const void*>(&moe_gemm_pipe_kernel<SplitK<C>, SplitK<Tails>...>), C::LDS_BYTES, &attr_done) != MOE_OK)
+        return MOE_ERR_HIP;
+    moe_gemm_pipe_kernel<SplitK<C>, SplitK<Tails>...><<<dim3((unsigned)grid, (unsigned)parts), dim3(C::NT), C::LDS_BYTES, s>>>(a);
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
 // Streaming launch: as many workgroups as stay resident at once (grid is only an upper bound here).
 template <class C>
 int launch_stream(const GemmArgs& a, int64_t grid, hipStream_t s) {
@@ -434,6 +444,7 @@ int moe_grouped_gemm(const void* X, const void* W, const int32_t* topk_ids, cons
     a.T = d->T; a.k = d->k; a.E = d->E; a.K = d->K; a.N = d->N;
     a.tile_m_small = d->tile_m_small; a.small_max_rows = d->small_max_rows; a.tile_m_slack = d->tile_m_slack;
     a.swiglu = d->epilogue == MOE_EPILOGUE_SWIGLU;
+    a.partial = nullptr;
     int64_t grid = moe_grid_upper_bound_tiled(d->T, d->k, d->E, d->tile_m, d->tile_n, d->N, d->tile_m_small,
                                               d->small_max_rows);
     if (grid == 0) return MOE_OK;
@@ -443,6 +454,69 @@ int moe_grouped_gemm(const void* X, const void* W, const int32_t* topk_ids, cons
     const bool can_stream = v->fn_stream && d->E <= 256 && d->K / v->bk >= v->ring &&
                             (d->dtype != MOE_DTYPE_FP8_E4M3 || d->T + d->E <= 2048) && g_stream_mode != 1;
     return (can_stream ? v->fn_stream : v->fn)(a, grid, static_cast<hipStream_t>(stream));
+}
+
+size_t moe_splitk_workspace_bytes(int T, int k, int N, int k_parts) {
+    if (T < 0 || k < 1 || N < 1 || k_parts < 2) return 0;
+    return (size_t)k_parts * (size_t)T * k * N * sizeof(float);
+}
+
+int moe_default_k_parts(int T, int k, int E, int K, int N) {
+    if (T < 0 || k < 1 || E < 1 || k > E || K < 1 || N < 1) return MOE_ERR_INVALID_ARG;
+    if (K % 64 != 0 || N % 256 != 0) return 1;
+    const int64_t R = (int64_t)T * k;
+    const double mean_rows = (double)R / E;
+    const int64_t active = R < E ? R : E;
+    const double mt = mean_rows / 256 + 0.5;
+    const double tiles = (double)active * (mt < 1.0 ? 1.0 : mt) * (N / 256);
+    const int cus = 256, kt = K / 64;
+    // worth it where 256 x 256 tiles would leave CUs idle through a long k loop and the experts are not tiny
+    // (measured on 8 experts, N = 4096, K = 14336, us with map build and reduction: 1024 rows 255 -> 198, 1536 rows
+    // 294 -> 224; at 768 rows the 128 x 128 tiles of moe_default_tiling are faster, 171 against 190)
+    if (mean_rows < 120 || tiles >= 0.75 * cus) return 1;
+    // the fewest parts that cover three quarters of the CUs, else the most that keep 16 k-tiles each
+    int best = 1;
+    for (int parts = 2; parts <= 4; parts *= 2) {
+        if (kt % parts != 0 || kt / parts < 16) break;
+        best = parts;
+        if (tiles * parts >= 0.75 * cus) break;
+    }
+    return best;
+}
+
+int moe_grouped_gemm_splitk(const void* X, const void* W, const void* task_map, void* Y, const moe_gemm_desc* d,
+                            int k_parts, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!d) return MOE_ERR_INVALID_ARG;
+    if (d->T < 0 || d->k < 1 || d->E < 1 || d->E > kMaxE || d->k > d->E || d->K < 1 || d->N < 1) return MOE_ERR_INVALID_ARG;
+    if (d->dtype != MOE_DTYPE_BF16 || d->w_layout != MOE_W_LAYOUT_KN || d->epilogue != MOE_EPILOGUE_NONE ||
+        d->tile_m != 256 || d->tile_n != 256 || d->tile_m_small != 0 || d->small_max_rows != 0 || d->tile_m_slack != 0)
+        return MOE_ERR_UNSUPPORTED;
+    if (k_parts != 2 && k_parts != 4) return MOE_ERR_UNSUPPORTED;
+    if (d->K % 64 != 0 || (d->K / 64) % k_parts != 0 || d->K / 64 / k_parts < 8 || d->N % 256 != 0) return MOE_ERR_UNSUPPORTED;
+    if (d->T == 0) return MOE_OK;
+    if (!X || !W || !task_map || !Y || !workspace) return MOE_ERR_INVALID_ARG;
+    if (((uintptr_t)X & 15) || ((uintptr_t)W & 15) || ((uintptr_t)Y & 15) || ((uintptr_t)workspace & 15)) return MOE_ERR_INVALID_ARG;
+    if (workspace_bytes < moe_splitk_workspace_bytes(d->T, d->k, d->N, k_parts)) return MOE_ERR_INVALID_ARG;
+    GemmArgs a{};
+    a.X = X; a.W = W; a.map = static_cast<const int32_t*>(task_map); a.Y = Y;
+    a.T = d->T; a.k = d->k; a.E = d->E; a.K = d->K; a.N = d->N;
+    a.tile_m_slack = d->tile_m_slack;
+    a.partial = static_cast<float*>(workspace);
+    int64_t grid = moe_grid_upper_bound_tiled(d->T, d->k, d->E, 256, 256, d->N, 0, 0);
+    if (grid == 0) return MOE_OK;
+    grid = (grid + 7) / 8 * 8 + 8;
+    if (grid > 0x7fffffff) return MOE_ERR_UNSUPPORTED;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int rc = launch_splitk<Pb_256x256, Ps_64x256, Ps_128x256>(a, grid, k_parts, s);
+    if (rc != MOE_OK) return rc;
+    const int64_t R = (int64_t)d->T * d->k;
+    const long long chunks = (long long)R * (d->N / 8);
+    long long blocks = (chunks + 255) / 256;
+    if (blocks > 256 * 64) blocks = 256 * 64;
+    const MapLayout L = map_layout(d->E);
+    moe_splitk_reduce_kernel<<<(unsigned)blocks, 256, 0, s>>>(a.partial, a.map, a.map + L.off_rows, static_cast<u32x4_t*>(Y), (int)R,
+                                                             d->N, k_parts);
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
 int moe_combine(const void* Y, const float* topk_weights, int T, int k, int N, void* out, void* stream) {

@@ -102,6 +102,27 @@ def test_pipeline_probe_rejects_bad_arguments_before_any_launch():
     assert lib.moe_debug_pipeline_probe(4, 10, 16, small, 16, None) == mb.MOE_ERR_INVALID_ARG   # mode 4 needs 513 MiB
 
 
+def test_splitk_host_functions():
+    assert mb.moe_splitk_workspace_bytes(1024, 1, 4096, 2) == 2 * 1024 * 4096 * 4
+    assert mb.moe_splitk_workspace_bytes(1024, 1, 4096, 1) == 0
+    # 8 experts, N = 4096, K = 14336: split where 256 x 256 tiles would leave CUs idle and experts are not tiny
+    assert mb.moe_default_k_parts(1024, 1, 8, 14336, 4096) == 2
+    assert mb.moe_default_k_parts(1536, 1, 8, 14336, 4096) == 2
+    assert mb.moe_default_k_parts(2048, 1, 8, 14336, 4096) == 1      # 192 tiles expected: enough
+    assert mb.moe_default_k_parts(512, 1, 8, 14336, 4096) == 1       # 64 rows per expert: narrower tiles instead
+    assert mb.moe_default_k_parts(768, 1, 8, 14336, 4096) == 1
+    assert mb.moe_default_k_parts(4096, 2, 8, 4096, 28672) == 1      # the headline shape is never split
+    assert mb.moe_default_k_parts(1024, 1, 8, 1024, 4096) == 1       # too few k-tiles to share
+    with pytest.raises(mb.MoeError):
+        mb.moe_default_k_parts(8, 20, 16, 256, 128)
+    # argument checks happen before any launch
+    lib = mb.lib()
+    d = mb.GemmDesc(mb.MOE_DTYPE_BF16, 512, 1, 2, 1024, 256, 256, 256).c_struct()
+    assert lib.moe_grouped_gemm_splitk(None, None, None, None, ctypes.byref(d), 2, None, 0, None) == mb.MOE_ERR_INVALID_ARG
+    assert lib.moe_grouped_gemm_splitk(16, 16, 16, 16, ctypes.byref(d), 3, 16, 1 << 30, None) == mb.MOE_ERR_UNSUPPORTED
+    assert lib.moe_grouped_gemm_splitk(16, 16, 16, 16, None, 2, 16, 1 << 30, None) == mb.MOE_ERR_INVALID_ARG
+
+
 def test_default_tiling_is_supported_and_matches_the_benchmark_choices():
     """Host-only: the heuristic returns a tiling a kernel exists for, and reproduces the tilings the benchmark
     points were tuned to (slack rows aside, where the heuristic always enables them for 256-row tiles)."""

@@ -362,11 +362,72 @@ def test_pipeline_probe_runs(dev):
     assert torch.equal(src[: 1 << 20], before)
 
 
+SPLITK_CASES = [
+    # per-expert row counts (k = 1), K, N, order, k_parts
+    ([300, 256, 288, 31, 0, 513, 257, 700], 1024, 512, 0, 2),     # full, partly filled and empty experts; 8 k-tiles per part
+    ([130, 64, 1, 255], 2048, 256, 1, 4),                          # only the narrow task functions; spread order
+    ([600, 90], 1536, 768, 0, 2),                                  # 12 k-tiles per part
+]
+
+
+@pytest.mark.parametrize("counts,K,N,order,parts", SPLITK_CASES)
+def test_splitk_parity(dev, oracle_mod, counts, K, N, order, parts):
+    """The product with every tile split along K over `parts` workgroups and a reduction kernel: same definition,
+    same tolerance; rows outside Y untouched; the workspace is the caller's."""
+    from tests.test_gpu_parity import _check_y
+    E, T = len(counts), sum(counts)
+    wl = wk.Workload("parity_splitk", T, E, 1, K, N, "bf16", "gauss_topk", 256, 256)
+    g = torch.Generator().manual_seed(777 + T)
+    ids = torch.repeat_interleave(torch.arange(E, dtype=torch.int32), torch.tensor(counts))[torch.randperm(T, generator=g)].reshape(T, 1).contiguous()
+    X, W = wk.make_x(wl), wk.make_w(wl)
+    pad = 3
+    buf = torch.empty((T + 2 * pad, N), dtype=torch.int16, device=dev)
+    buf.fill_(POISON)
+    Y = buf[pad: pad + T]
+    tmap = mb.alloc_task_map(T, 1, E, 256, 256, N)
+    mb.moe_build_task_map_ex(ids.to(dev), T, 1, E, N, mb.Tiling(256, 256, order, 0, 0, 0), tmap)
+    nbytes = mb.moe_splitk_workspace_bytes(T, 1, N, parts)
+    assert nbytes == parts * T * N * 4
+    guard = 64
+    ws = torch.full((nbytes // 4 + 2 * guard,), float("nan"), dtype=torch.float32, device=dev)
+    desc = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 256, 256)
+    mb.moe_grouped_gemm_splitk(X.to(dev), W.to(dev), tmap, Y, desc, parts, ws[guard: guard + nbytes // 4])
+    torch.cuda.synchronize()
+    assert torch.isnan(ws[:guard]).all() and torch.isnan(ws[guard + nbytes // 4:]).all(), "wrote outside the workspace"
+    allbits = buf.cpu().numpy().view(np.uint16)
+    assert np.all(allbits[:pad] == POISON) and np.all(allbits[pad + T:] == POISON), "wrote outside Y"
+    res = oracle_mod.grouped_gemm_bf16(wk.bits(X), wk.bits(W), ids.numpy())
+    _check_y(allbits[pad: pad + T], res, X.double().numpy(), W.double().numpy(), ids.numpy(), 1, K, H.tol_bf16(K))
+
+
+def test_splitk_argument_errors(dev):
+    T, E, K, N = 512, 2, 1024, 256
+    X = torch.zeros((T, K), dtype=torch.bfloat16, device=dev)
+    W = torch.zeros((E, K, N), dtype=torch.bfloat16, device=dev)
+    Y = torch.zeros((T, N), dtype=torch.bfloat16, device=dev)
+    ids = torch.zeros((T, 1), dtype=torch.int32, device=dev)
+    tmap = mb.alloc_task_map(T, 1, E, 256, 256, N)
+    mb.moe_build_task_map(ids, T, 1, E, 256, 256, N, tmap)
+    ws = torch.zeros(2 * T * N, dtype=torch.float32, device=dev)
+    d = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 256, 256)
+    assert mb.moe_grouped_gemm_splitk(X, W, tmap, Y, d, 2, ws, check=False) == mb.MOE_OK
+    assert mb.moe_grouped_gemm_splitk(X, W, tmap, Y, d, 3, ws, check=False) == mb.MOE_ERR_UNSUPPORTED
+    assert mb.moe_grouped_gemm_splitk(X, W, tmap, Y, d, 4, ws, check=False) == mb.MOE_ERR_UNSUPPORTED      # 4 k-tiles per part
+    assert mb.moe_grouped_gemm_splitk(X, W, tmap, Y, d, 2, ws[: T * N], check=False) == mb.MOE_ERR_INVALID_ARG   # too small
+    assert mb.moe_grouped_gemm_splitk(X, W, tmap, Y, d, 2, None, check=False) == mb.MOE_ERR_INVALID_ARG
+    d128 = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 128, 256)
+    assert mb.moe_grouped_gemm_splitk(X, W, tmap, Y, d128, 2, ws, check=False) == mb.MOE_ERR_UNSUPPORTED
+    dsl = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 256, 256, tile_m_slack=32)
+    assert mb.moe_grouped_gemm_splitk(X, W, tmap, Y, dsl, 2, ws, check=False) == mb.MOE_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+
+
 LAYER_CASES = [
     # T, k, E, hidden, inter, routing, weighted
     (300, 2, 8, 256, 384, "zipf", True),
     (40, 2, 8, 128, 256, "gauss_topk", True),          # weight-streaming tiles for both products
     (700, 1, 4, 256, 256, "uniform_topk", False),      # k = 1: the second map equals the first one's routing
+    (600, 2, 8, 256, 2048, "gauss_topk", True),        # down product split along K (150 rows per expert, one n-tile)
 ]
 
 
@@ -382,6 +443,7 @@ def test_moe_layer_composition(dev, oracle_mod, T, k, E, hidden, inter, routing,
     g = torch.Generator().manual_seed(77 + T)
     wts = torch.rand((T, k), generator=g, dtype=torch.float32) if weighted else None
     plan = mb.MoeLayerPlan(T, k, E, hidden, inter, dev)
+    assert (plan.k_parts > 1) == (inter == 2048), "the case meant for the split-k path must take it"
     for buf in (plan.act, plan.down, plan.out):
         buf.view(torch.int16).fill_(POISON)
     out = plan.forward(X.to(dev), W1.to(dev), W2.to(dev), ids.to(dev), None if wts is None else wts.to(dev))
