@@ -29,7 +29,7 @@ def _gather_columns(W, experts, cols):
     return torch.cat(out)
 
 
-def _run_full(wl, dev, order=0):
+def _run_full(wl, dev, order=0, k_parts=1):
     ids = wk.make_routing(wl)
     if wl.dtype == "fp8":
         X, xs = wk.make_x(wl, dev)
@@ -43,8 +43,12 @@ def _run_full(wl, dev, order=0):
     tmap = mb.alloc_task_map(wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N, dev)
     mb.moe_build_task_map_ex(ids.to(dev), wl.T, wl.k, wl.E, wl.N, mb.Tiling(wl.tile_m, wl.tile_n, order, 0, 0, wl.tile_m_slack), tmap)
     dt = mb.MOE_DTYPE_FP8_E4M3 if wl.dtype == "fp8" else mb.MOE_DTYPE_BF16
-    mb.moe_grouped_gemm(X, W, ids.to(dev), tmap, Y,
-                        mb.GemmDesc(dt, wl.T, wl.k, wl.E, wl.K, wl.N, wl.tile_m, wl.tile_n, xs, ws, tile_m_slack=wl.tile_m_slack))
+    desc = mb.GemmDesc(dt, wl.T, wl.k, wl.E, wl.K, wl.N, wl.tile_m, wl.tile_n, xs, ws, tile_m_slack=wl.tile_m_slack)
+    if k_parts > 1:
+        work = torch.empty(mb.moe_splitk_workspace_bytes(wl.T, wl.k, wl.N, k_parts) // 4, dtype=torch.float32, device=dev)
+        mb.moe_grouped_gemm_splitk(X, W, tmap, Y, desc, k_parts, work)
+    else:
+        mb.moe_grouped_gemm(X, W, ids.to(dev), tmap, Y, desc)
     torch.cuda.synchronize()
     assert mb.moe_task_map_status(tmap) == mb.MOE_OK
     # properties that hold at any size
@@ -156,6 +160,27 @@ def test_full_size_sampled(oracle_mod, wl, per_tile, nrows, order):
     rr = np.repeat(rows, len(cols))
     nn = np.tile(cols, len(rows))
     _check_elements(oracle_mod, wl, ids, X, W, xs, ws, Y, rr, nn)
+
+
+def test_split_k_full_size_sampled(oracle_mod):
+    """The down projection of a Mixtral-sized layer at 512 tokens (1024 routed rows, 8 experts, K = 14336, N = 4096)
+    in the split-k launch the layer plan picks for it: samples in every tile and complete rows."""
+    wl = wk.Workload("mixtral_down_layer", 1024, 8, 1, 14336, 4096, "bf16", "gauss_topk", 256, 256)
+    k_parts = mb.moe_default_k_parts(wl.T, wl.k, wl.E, wl.K, wl.N)
+    assert k_parts == 2
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(512)
+    ids, X, W, xs, ws, Y, tmap = _run_full(wl, dev, 0, k_parts)
+    tm = oracle_mod.build_task_map(ids.numpy(), wl.T, wl.k, wl.E, 256, 256, wl.N)
+    want = H.expected_blob(tm)
+    np.testing.assert_array_equal(tmap.cpu().numpy()[: len(want)], want)
+    table = oracle_mod.full_table(tm.counts, 256, 256, wl.N)
+    rr, nn = _sample_points(tm, table, rng, 8)
+    _check_elements(oracle_mod, wl, ids, X, W, xs, ws, Y, rr, nn)
+    rows = rng.choice(wl.R, size=24, replace=False).astype(np.int32)
+    cols = rng.choice(wl.N, size=128, replace=False).astype(np.int32)
+    cols[:2] = (0, wl.N - 1)
+    _check_elements(oracle_mod, wl, ids, X, W, xs, ws, Y, np.repeat(rows, len(cols)), np.tile(cols, len(rows)))
 
 
 def test_fine_grained_full_size_sampled(oracle_mod):

@@ -95,3 +95,39 @@ def test_random_case(oracle_mod, seed):
         _check_swiglu(oracle_mod, got, res, Xf, Wf, ids.numpy(), k, K, sx, sw)
     else:
         _check_y(got, res, Xf, Wf, ids.numpy(), k, K, H.tol_fp8(K) if fp8 else H.tol_bf16(K), sx, sw)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_split_k_case(oracle_mod, seed):
+    """Seeded random shapes for the split-k launch: expert counts from empty to several tiles, 2 or 4 parts."""
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(7700 + seed)
+    parts = int(rng.choice([2, 4]))
+    E = int(rng.choice([1, 2, 3, 8, 17]))
+    counts = [int(rng.choice([0, 1, 17, 64, 65, 128, 200, 256, 257, 300, 520])) for _ in range(E)]
+    if sum(counts) == 0:
+        counts[0] = 33
+    while sum(counts) > 1400:
+        counts[int(np.argmax(counts))] //= 2
+    T = sum(counts)
+    K = 64 * parts * int(rng.integers(8, 12))
+    N = 256 * int(rng.integers(1, 3))
+    order = int(rng.integers(0, 3))
+    print(f"case: parts={parts} counts={counts} K={K} N={N} order={order}", flush=True)
+    wl = wk.Workload("random_split_k", T, E, 1, K, N, "bf16", "gauss_topk", 256, 256)
+    g = torch.Generator().manual_seed(7700 + seed)
+    ids = torch.repeat_interleave(torch.arange(E, dtype=torch.int32), torch.tensor(counts))[torch.randperm(T, generator=g)].reshape(T, 1).contiguous()
+    X, W = wk.make_x(wl), wk.make_w(wl)
+    pad = 3
+    buf = torch.empty((T + 2 * pad, N), dtype=torch.int16, device=dev)
+    buf.fill_(POISON)
+    Y = buf[pad: pad + T]
+    tmap = mb.alloc_task_map(T, 1, E, 256, 256, N)
+    mb.moe_build_task_map_ex(ids.to(dev), T, 1, E, N, mb.Tiling(256, 256, order, 0, 0, 0), tmap)
+    work = torch.empty(mb.moe_splitk_workspace_bytes(T, 1, N, parts) // 4, dtype=torch.float32, device=dev)
+    mb.moe_grouped_gemm_splitk(X.to(dev), W.to(dev), tmap, Y, mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 256, 256), parts, work)
+    torch.cuda.synchronize()
+    allbits = buf.cpu().numpy().view(np.uint16)
+    assert np.all(allbits[:pad] == POISON) and np.all(allbits[pad + T:] == POISON), "wrote outside Y"
+    res = oracle_mod.grouped_gemm_bf16(wk.bits(X), wk.bits(W), ids.numpy())
+    _check_y(allbits[pad: pad + T], res, X.double().numpy(), W.double().numpy(), ids.numpy(), 1, K, H.tol_bf16(K))
