@@ -331,6 +331,10 @@ def main():
                      "kernel": "moe_gemm_pipe_kernel",
                      "kernel_ms": head["gemm_ms"], "map_ms": head["map_ms"], "alg_bytes": head["alg_bytes"]},
     }
+    # what the runtime reports for this device, beside the published peak the fractions are taken against
+    prop = torch.cuda.get_device_properties(0)
+    out["device"] = {"name": prop.name, "compute_units": prop.multi_processor_count,
+                     "gcn_arch": getattr(prop, "gcnArchName", None), "hbm_gib": round(prop.total_memory / 2 ** 30, 1)}
     if args.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
         dst = torch.empty_like(src)
