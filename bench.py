@@ -117,8 +117,10 @@ class Point:
             self.gemm(i)
             ev[i][2].record()
         torch.cuda.synchronize()
-        gemm_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+        g = [e[1].elapsed_time(e[2]) for e in ev]
+        gemm_ms = float(np.mean(g))
         map_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+        self.gemm_ms_median, self.gemm_ms_min = float(np.median(g)), float(np.min(g))
         return wall_ms, gemm_ms, map_ms
 
     def time_graph(self, steps: int) -> float:
@@ -159,6 +161,7 @@ class Point:
         return dict(workload=f"{wl.name}_T{wl.T}" + ("_swiglu" if self.swiglu else "") + ("_wNK" if self.w_nk else ""), dtype=wl.dtype, T=wl.T, E=wl.E, k=wl.k, K=wl.K, N=wl.N,
                     tile=[wl.tile_m, wl.tile_n], sigma_order=("ascending", "spread", "interleave")[self.order], small_strategy=list(self.small), tile_m_slack=self.slack, ms_per_step=round(wall_ms, 4),
                     ms_per_step_graph=(round(self.time_graph(steps), 4) if wall_ms < 0.5 else None), gemm_ms=round(gemm_ms, 4),
+                    gemm_ms_median=round(self.gemm_ms_median, 4), gemm_ms_min=round(self.gemm_ms_min, 4),
                     map_ms=round(map_ms, 4), tflops_step=round(tf_step, 2), tflops_gemm=round(tf_gemm, 2),
                     frac_mfma=round(tf_gemm / peak_t, 4), gbs_gemm=round(gbs, 1),
                     frac_hbm=round(gbs / PEAK_HBM_GBS, 4), bound=bound, alg_bytes=abytes, flops=wl.flops)
@@ -329,7 +332,8 @@ def main():
                      "frac": round(head["tflops_gemm"] / PEAK_BF16_TFLOPS, 4),
                      "traffic": MEASURED_TRAFFIC_BYTES.get(HEADLINE) if wl == wk.mixtral_up(4096) else None,
                      "kernel": "moe_gemm_pipe_kernel",
-                     "kernel_ms": head["gemm_ms"], "map_ms": head["map_ms"], "alg_bytes": head["alg_bytes"]},
+                     "kernel_ms": head["gemm_ms"], "kernel_ms_median": head["gemm_ms_median"], "kernel_ms_min": head["gemm_ms_min"],
+                     "map_ms": head["map_ms"], "alg_bytes": head["alg_bytes"]},
     }
     # what the runtime reports for this device, beside the published peak the fractions are taken against
     prop = torch.cuda.get_device_properties(0)
