@@ -117,8 +117,10 @@ using Pb_256x256 = PipeCfg<256, 256, 64, 2, 4, 2, false, 3, 0, false, 16>;
 using Pb_256x256s = PipeCfg<256, 256, 64, 2, 4, 2, false, 2, 64>;
 // (token ring 2 x 40 KB; the 80 KB left hold five half-stages of weights: 2.5 k-tiles instead of 2)
 using Pb_256x256s32 = PipeCfg<256, 256, 64, 2, 4, 2, false, 2, 32, false, 16, 5>;
-using Pb_128x256 = PipeCfg<128, 256, 64, 1, 4, 3>;
-using Pb_128x128 = PipeCfg<128, 128, 64, 2, 2, 4>;
+// (eight wavefronts of 128 x 32: two per SIMD keep MFMAs and LDS reads of different wavefronts overlapping;
+// against four wavefronts of 128 x 64: -1 % on mixtral_up T=256 / 384, -7 % on a 1536-row down projection)
+using Pb_128x256 = PipeCfg<128, 256, 64, 1, 8, 3>;
+using Pb_128x128 = PipeCfg<128, 128, 64, 2, 4, 4>;   // eight wavefronts of 64 x 32 (-1 ... -7 % against four of 64 x 64)
 using Pb_64x256 = PipeCfg<64, 256, 64, 1, 4, 3>;
 using Pb_64x128 = PipeCfg<64, 128, 64, 1, 4, 3>;   // 72 KB: two workgroups per CU
 using Pb_32x256 = PipeCfg<32, 256, 64, 1, 4, 4>;
@@ -160,7 +162,7 @@ const GemmVariant kVariants[] = {
     {MOE_DTYPE_BF16, 256, 256, 64, &launch_pipe<Pb_256x256, Ps_64x256, Ps_128x256>},
     {MOE_DTYPE_BF16, 256, 256, 64, &launch_pipe<Pb_256x256s, Ps_64x256, Ps_128x256>, 0, 64},
     {MOE_DTYPE_BF16, 256, 256, 64, &launch_pipe<Pb_256x256s32, Ps_64x256, Ps_128x256>, 0, 32},
-    {MOE_DTYPE_BF16, 128, 256, 64, &launch_pipe<Pb_128x256, Pb_64x256>},
+    {MOE_DTYPE_BF16, 128, 256, 64, &launch_pipe<Pb_128x256, Ps_64x256>},
     {MOE_DTYPE_BF16, 128, 128, 64, &launch_pipe<Pb_128x128>},
     {MOE_DTYPE_BF16, 64, 256, 64, &launch_pipe<Pb_64x256>},
     {MOE_DTYPE_BF16, 64, 128, 64, &launch_pipe<Pb_64x128>},
