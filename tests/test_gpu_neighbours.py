@@ -339,6 +339,43 @@ def test_step_captured_in_a_graph_replays_exactly(dev):
         assert torch.equal(out.view(torch.int16), want_out.view(torch.int16)), f"replay {it}: combine differs"
 
 
+def test_layer_with_split_k_in_a_graph_replays_exactly(dev):
+    """The whole layer (two maps, fused gate+up product, split-k down product with its reduction, weighted sum)
+    captured once and replayed on new tokens and routings: every replay equals the eager result bit for bit, i.e.
+    the split-k parts are added in a fixed order and nothing in the path needs the host."""
+    T, k, E, hidden, inter = 600, 2, 8, 256, 2048
+    plan = mb.MoeLayerPlan(T, k, E, hidden, inter, dev)
+    assert plan.k_parts > 1
+    g = torch.Generator(device=dev).manual_seed(9)
+    X = torch.randn((T, hidden), generator=g, device=dev).to(torch.bfloat16)
+    W1 = (torch.randn((E, hidden, 2 * inter), generator=g, device=dev) * hidden ** -0.5).to(torch.bfloat16)
+    W2 = (torch.randn((E, inter, hidden), generator=g, device=dev) * inter ** -0.5).to(torch.bfloat16)
+    ids = torch.stack([torch.randperm(E, generator=g, device=dev)[:k] for _ in range(T)]).to(torch.int32)
+    wts = torch.rand((T, k), generator=g, device=dev, dtype=torch.float32)
+    plan.forward(X, W1, W2, ids, wts)   # first call sets the kernels' launch attributes: not a thing to capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            plan.forward(X, W1, W2, ids, wts)
+    torch.cuda.synchronize()
+    for it in range(3):
+        X.copy_(torch.randn((T, hidden), generator=g, device=dev).to(torch.bfloat16))
+        ids.copy_(torch.stack([torch.randperm(E, generator=g, device=dev)[:k] for _ in range(T)]).to(torch.int32))
+        plan.forward(X, W1, W2, ids, wts)
+        torch.cuda.synchronize()
+        want = plan.out.clone()
+        assert bool(torch.isfinite(want.float()).all())
+        plan.out.fill_(float("nan"))
+        plan.down.fill_(float("nan"))
+        plan.workspace.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(plan.out.view(torch.int16), want.view(torch.int16)), f"replay {it}: the layer's output differs"
+
+
 def test_mfma_probe_runs(dev):
     """The measurement probe launches and completes for both block shapes and operand kinds."""
     sink = torch.zeros(4, dtype=torch.float32, device=dev)
