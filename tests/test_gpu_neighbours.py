@@ -459,6 +459,27 @@ def test_splitk_argument_errors(dev):
     torch.cuda.synchronize()
 
 
+def test_splitk_invalid_map_and_empty_input_are_noops(dev):
+    """A map whose routing held an id outside [0, E) makes both kernels of the split-k call do nothing (Y and the
+    workspace keep their contents), as it does for the plain product; T = 0 returns at once."""
+    T, E, K, N = 300, 4, 1024, 256
+    X = torch.ones((T, K), dtype=torch.bfloat16, device=dev)
+    W = torch.ones((E, K, N), dtype=torch.bfloat16, device=dev)
+    Y = torch.full((T, N), POISON, dtype=torch.int16, device=dev)
+    ids = torch.zeros((T, 1), dtype=torch.int32, device=dev)
+    ids[17, 0] = E      # out of range
+    tmap = mb.alloc_task_map(T, 1, E, 256, 256, N)
+    mb.moe_build_task_map(ids, T, 1, E, 256, 256, N, tmap, check=False)
+    assert mb.moe_task_map_status(tmap) == mb.MOE_ERR_ROUTING
+    ws = torch.full((2 * T * N,), 7.0, dtype=torch.float32, device=dev)
+    d = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 256, 256)
+    assert mb.moe_grouped_gemm_splitk(X, W, tmap, Y, d, 2, ws, check=False) == mb.MOE_OK
+    torch.cuda.synchronize()
+    assert bool((Y == POISON).all()) and bool((ws == 7.0).all())
+    d0 = mb.GemmDesc(mb.MOE_DTYPE_BF16, 0, 1, E, K, N, 256, 256)
+    assert mb.moe_grouped_gemm_splitk(None, None, None, None, d0, 2, None, check=False) == mb.MOE_OK
+
+
 LAYER_CASES = [
     # T, k, E, hidden, inter, routing, weighted
     (300, 2, 8, 256, 384, "zipf", True),
