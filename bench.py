@@ -121,6 +121,16 @@ class Point:
         gemm_ms = float(np.mean(g))
         map_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
         self.gemm_ms_median, self.gemm_ms_min = float(np.median(g)), float(np.min(g))
+        # the same launches back to back (one map, no event between them): what rocprofv3's per-kernel durations
+        # correspond to, since an event pair around a single short launch also sees its dispatch latency
+        b = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        torch.cuda._sleep(int(4e6))
+        b[0].record()
+        for i in range(steps):
+            self.gemm(i)
+        b[1].record()
+        torch.cuda.synchronize()
+        self.gemm_ms_b2b = b[0].elapsed_time(b[1]) / steps
         return wall_ms, gemm_ms, map_ms
 
     def time_graph(self, steps: int) -> float:
@@ -162,6 +172,8 @@ class Point:
                     tile=[wl.tile_m, wl.tile_n], sigma_order=("ascending", "spread", "interleave")[self.order], small_strategy=list(self.small), tile_m_slack=self.slack, ms_per_step=round(wall_ms, 4),
                     ms_per_step_graph=(round(self.time_graph(steps), 4) if wall_ms < 0.5 else None), gemm_ms=round(gemm_ms, 4),
                     gemm_ms_median=round(self.gemm_ms_median, 4), gemm_ms_min=round(self.gemm_ms_min, 4),
+                    gemm_ms_back_to_back=round(self.gemm_ms_b2b, 4),
+                    frac_hbm_back_to_back=round(abytes / (self.gemm_ms_b2b * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                     map_ms=round(map_ms, 4), tflops_step=round(tf_step, 2), tflops_gemm=round(tf_gemm, 2),
                     frac_mfma=round(tf_gemm / peak_t, 4), gbs_gemm=round(gbs, 1),
                     frac_hbm=round(gbs / PEAK_HBM_GBS, 4), bound=bound, alg_bytes=abytes, flops=wl.flops)
