@@ -33,7 +33,7 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per GEMM launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a
 # copy kernel of known size; see profiles/.  None where it has not been measured.
-MEASURED_TRAFFIC_BYTES = {"mixtral_up_T4096": 3.396e9}
+MEASURED_TRAFFIC_BYTES = {"mixtral_up_T4096": 3.402e9}
 
 
 def algorithmic_bytes(wl: wk.Workload, ids: torch.Tensor, swiglu: bool = False) -> int:
