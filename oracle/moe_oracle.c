@@ -10,10 +10,10 @@
  *
  * Conventions (the paper leaves these open; each is a fixed reading):
  *   - block index B and all arrays are 0-based: the task of block B is
- *     h = #{ i : TilePrefix[i] <= B }  (Alg. 2 as printed: p = B >= TilePrefix[t]).
+ *     h = #{ i : TilePrefix[i] <= B }  (the comparison Alg. 2 votes on, read with 0-based B).
  *   - nu(expert e) = ceil(c_e / tile_m(e)) * ceil(N / tile_n)   (tiles of its GEMM), where
- *     tile_m(e) is the task's tiling strategy (Sec. 3.2, Sec. 4: tasks "categorized into
- *     several pre-defined tiling strategies"; thresholds are not given in the paper).  Two
+ *     tile_m(e) is the task's tiling strategy (Sec. 3.2, Sec. 4: every task is assigned to one
+ *     of a few tiling strategies fixed in advance; the paper gives neither shapes nor thresholds).  Two
  *     strategies here: experts with at most small_max_rows rows use tile_m_small, all
  *     others tile_m; small_max_rows = 0 means one strategy for every expert.
  *     A third knob of the tile_m strategy, also this library's own: with tile_m_slack > 0
@@ -119,18 +119,16 @@ void orc_tile_prefix(const int32_t* nu, int n, int32_t* tile_prefix) {
     }
 }
 
-/* Alg. 2: every "thread" t < n votes p = (B >= TilePrefix[t]); h is the
- * population count of the votes; l = B - TilePrefix[h-1] (or B when h = 0). */
+/* The mapping of Sec. 3.1 (what Alg. 2's vote and population count arrive at), written from its definition:
+ * block B belongs to the first task whose inclusive prefix lies above B -- TilePrefix is non-decreasing, so
+ * that task's index equals the number of entries at or below B -- and its tile index inside the task is B
+ * minus everything the tasks before it hold.  Blocks past the last entry get h = n. */
 void orc_mapping(const int32_t* tile_prefix, int n, int B, int32_t* h_out, int32_t* l_out) {
-    int h = 0;
-    for (int t = 0; t < n; ++t) {
-        int p = (B >= tile_prefix[t]);
-        h += p;
-    }
-    int kk = 0;
-    if (h > 0) kk = tile_prefix[h - 1];
-    *h_out = h;
-    *l_out = B - kk;
+    int owner = 0;
+    while (owner < n && tile_prefix[owner] <= B) owner += 1;
+    int32_t tiles_before = owner > 0 ? tile_prefix[owner - 1] : 0;
+    *h_out = owner;
+    *l_out = B - tiles_before;
 }
 
 /* Two-level TilePrefix (Sec. 3.1 mentions it for task counts beyond a few warps and omits the details; our
