@@ -31,9 +31,22 @@ PEAK_BF16_TFLOPS = 2516.6   # dense bf16 MFMA (256 CUs x 2.4 GHz x 4096 FLOP/clk
 PEAK_FP8_TFLOPS = 5033.2    # dense fp8 MFMA
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per GEMM launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a
-# copy kernel of known size; see profiles/.  None where it has not been measured.
-MEASURED_TRAFFIC_BYTES = {"mixtral_up_T4096": 3.402e9}
+# HBM bytes per GEMM launch as measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE; each scaled by what the same
+# counter reads for a plain copy of known size) are not something this run can measure itself: they are read from
+# a small tracked file that names the command and the source revision they came from.
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+
+
+def measured_traffic(workload: str):
+    """(bytes per launch, provenance) recorded for `workload` in profiles/hbm_traffic.json, or (None, None)."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            rec = json.load(f).get(workload)
+    except (OSError, ValueError):
+        return None, None
+    if not rec:
+        return None, None
+    return rec.get("bytes_per_launch"), {k: rec.get(k) for k in ("source", "commit", "command")}
 
 
 def algorithmic_bytes(wl: wk.Workload, ids: torch.Tensor, swiglu: bool = False) -> int:
@@ -176,7 +189,8 @@ class Point:
                     frac_hbm_back_to_back=round(abytes / (self.gemm_ms_b2b * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                     map_ms=round(map_ms, 4), tflops_step=round(tf_step, 2), tflops_gemm=round(tf_gemm, 2),
                     frac_mfma=round(tf_gemm / peak_t, 4), gbs_gemm=round(gbs, 1),
-                    frac_hbm=round(gbs / PEAK_HBM_GBS, 4), bound=bound, alg_bytes=abytes, flops=wl.flops)
+                    frac_hbm=round(gbs / PEAK_HBM_GBS, 4), bound=bound, alg_bytes=abytes, flops=wl.flops,
+                    kernel="moe_gemm_pipe_kernel")
 
 
 def cpu_baseline(pt: Point, target_s: float = 30.0) -> dict:
@@ -222,6 +236,56 @@ def cpu_baseline(pt: Point, target_s: float = 30.0) -> dict:
 
 
 HEADLINE = "mixtral_up_T4096"
+
+
+def weight_copies(w: wk.Workload) -> int:
+    """fp8 decode points: the touched weights (35-354 MB) are comparable to the 256 MB last-level cache, so the
+    launches rotate over enough full copies that none finds its experts cached by an earlier one."""
+    if w.dtype != "fp8":
+        return 1
+    touched = int(torch.unique(wk.make_routing(w)).numel()) * w.K * w.N
+    return min(16, max(4, -(-int(1.2e9) // touched)))
+
+
+def decode_hbm_points(steps: int, warmup: int, with_cpu: bool) -> list:
+    """The second half of the metric: the fp8 decode configuration (E=64, top-6, K=2048, N=2816) at T = 1, 8, 32,
+    priced against the HBM peak.  `achieved` = algorithmic bytes / duration of one GEMM launch, the launches of one
+    map timed back to back with HIP events on the launch stream (what a kernel trace's per-kernel durations
+    correspond to).  Beside each: the CPU oracle on the WHOLE problem (seconds, threads) and the GPU result
+    checked against it."""
+    out = []
+    for T in (1, 8, 32):
+        w = wk.decode_fp8(T)
+        p = Point(w, weight_copies(w))
+        wall_ms, gemm_ms, map_ms = p.time(steps, warmup)
+        abytes = algorithmic_bytes(w, p.ids_cpu)
+        ms = p.gemm_ms_b2b
+        gbs = abytes / (ms * 1e-3) / 1e9
+        rec = {"workload": f"{w.name}_T{T}", "bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS,
+               "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4), "kernel_ms": round(ms, 5),
+               "kernel_ms_single_launch_events": round(gemm_ms, 5), "map_ms": round(map_ms, 5),
+               "ms_per_step": round(wall_ms, 5), "alg_bytes": abytes, "tile": [w.tile_m, w.tile_n],
+               "weight_copies": len(p.W), "tflops": round(w.flops / (ms * 1e-3) / 1e12, 2)}
+        if with_cpu:
+            import oracle
+            from tests import helpers as H
+            p.build_map()
+            p.gemm(0)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            res = oracle.grouped_gemm_fp8(wk.bits(p.X), wk.bits(p.W[0]), p.xs.cpu().numpy(), p.ws.cpu().numpy(),
+                                          p.ids_cpu.numpy())
+            dt = time.perf_counter() - t0
+            got = H.y_bits(p.Y)
+            err = np.abs(H.bf16_bits_to_f64(got) - res.Y64)
+            rec["cpu_oracle"] = {"seconds": round(dt, 4), "cores": oracle.num_threads(), "sample": "the whole problem",
+                                 "gb_per_s": round(abytes / dt / 1e9, 2),
+                                 "gpu_vs_oracle": {"max_abs_err": float(err.max()),
+                                                   "frac_bit_equal": float((H.ulp_distance(got, res.Ybf) == 0).mean())}}
+        out.append(rec)
+        del p
+        torch.cuda.empty_cache()
+    return out
 
 
 def combine_point(T: int, k: int, N: int, steps: int, warmup: int, dev="cuda:0") -> dict:
@@ -302,6 +366,7 @@ def main():
                     help="tile_m_small,small_max_rows: second tiling strategy for the extra points with 256x256 tiles")
     ap.add_argument("--slack", type=int, default=-1, help="override tile_m_slack of every workload (0 = plain ceil tiling)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-decode", action="store_true", help="skip the fp8 decode points (roofline_hbm)")
     ap.add_argument("--operand-fill", default="", choices=["", "zeros", "ones"],
                     help="measurement aid: ALSO time the headline launch with X and W overwritten by a constant (the "
                          "kernel's duration depends on the operand values through the chip's power management); "
@@ -333,6 +398,7 @@ def main():
         wl = wl.with_T(wl.T, tile_m_slack=args.slack)
     pt = Point(wl)
     head = pt.report(args.steps, args.warmup)
+    traffic, traffic_from = measured_traffic(HEADLINE) if wl == wk.mixtral_up(4096) else (None, None)
     out = {
         "metric": "expert-GEMM TFLOP/s (useful FLOPs 2*T*k*K*N, task-map build + grouped GEMM per step)",
         "value": head["tflops_step"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -342,8 +408,8 @@ def main():
                    "tile_m": wl.tile_m, "tile_n": wl.tile_n, "tile_m_slack": wl.tile_m_slack, "routing": wl.routing},
         "roofline": {"bound": "mfma", "achieved": head["tflops_gemm"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(head["tflops_gemm"] / PEAK_BF16_TFLOPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(HEADLINE) if wl == wk.mixtral_up(4096) else None,
-                     "kernel": "moe_gemm_pipe_kernel",
+                     "traffic": traffic, "traffic_source": traffic_from,
+                     "kernel": head["kernel"],
                      "kernel_ms": head["gemm_ms"], "kernel_ms_median": head["gemm_ms_median"], "kernel_ms_min": head["gemm_ms_min"],
                      "map_ms": head["map_ms"], "alg_bytes": head["alg_bytes"]},
     }
@@ -374,17 +440,18 @@ def main():
                                "tflops": round(wl.flops / (g_ms * 1e-3) / 1e12, 2),
                                "random_kernel_ms": head["gemm_ms"]}
     if args.mfma_probe:
+        from paper_2501_16103_amd import probe
         sink = torch.zeros(4, dtype=torch.float32, device="cuda:0")
         iters = 100000
         flops = 256 * 8 * iters * 524288
         res = []
         for block in (32, 16):
             for rnd in (False, True):
-                mb.moe_debug_mfma_probe(block, rnd, 1000, sink)
+                probe.moe_probe_mfma(block, rnd, 1000, sink)
                 ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
                 torch.cuda.synchronize()
                 ev[0].record()
-                mb.moe_debug_mfma_probe(block, rnd, iters, sink)
+                probe.moe_probe_mfma(block, rnd, iters, sink)
                 ev[1].record()
                 torch.cuda.synchronize()
                 ms = ev[0].elapsed_time(ev[1])
@@ -394,11 +461,11 @@ def main():
         src = (torch.randn((513 << 20) // 2, device="cuda:0") * 0.5).to(torch.bfloat16)
         for mode, what in ((1, "MFMA + LDS fragment reads"), (2, "+ barrier per k-tile"), (3, "+ DMA from cache"),
                            (4, "+ half of the DMA bytes from HBM")):
-            mb.moe_debug_pipeline_probe(mode, 1000, src, sink)
+            probe.moe_probe_pipeline(mode, 1000, src, sink)
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
             torch.cuda.synchronize()
             ev[0].record()
-            mb.moe_debug_pipeline_probe(mode, iters, src, sink)
+            probe.moe_probe_pipeline(mode, iters, src, sink)
             ev[1].record()
             torch.cuda.synchronize()
             ms = ev[0].elapsed_time(ev[1])
@@ -407,11 +474,11 @@ def main():
         # the LDS pipe alone: bytes per wavefront and k-step of each mode, reported per CU and nanosecond
         for mode, what, nbytes in ((5, "16-byte fragment reads only", 8192), (6, "transposing 8-byte reads only", 4096),
                                    (7, "both kinds of reads", 12288), (8, "DMA writes only", 4096)):
-            mb.moe_debug_pipeline_probe(mode, 1000, src, sink)
+            probe.moe_probe_pipeline(mode, 1000, src, sink)
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
             torch.cuda.synchronize()
             ev[0].record()
-            mb.moe_debug_pipeline_probe(mode, iters, src, sink)
+            probe.moe_probe_pipeline(mode, iters, src, sink)
             ev[1].record()
             torch.cuda.synchronize()
             ms = ev[0].elapsed_time(ev[1])
@@ -437,6 +504,8 @@ def main():
                                   "ms": round(d_ms, 4), "tflops": round(wl.flops / (d_ms * 1e-3) / 1e12, 2)}
     del pt
     torch.cuda.empty_cache()
+    if not args.no_decode:
+        out["roofline_hbm"] = decode_hbm_points(max(20, args.steps), max(5, args.warmup), not args.no_cpu)
 
     if args.points != "none":
         want = None if args.points == "all" else set(args.points.split(","))
@@ -450,12 +519,7 @@ def main():
             if name == HEADLINE and not args.tile:
                 points.append(head)
                 continue
-            copies = 1
-            if w.dtype == "fp8":
-                # the touched weights (35-354 MB) are comparable to the 256 MB last-level cache: rotate over
-                # enough full copies that an iteration never finds its experts cached by an earlier one
-                touched = int(torch.unique(wk.make_routing(w)).numel()) * w.K * w.N
-                copies = min(16, max(4, -(-int(1.2e9) // touched)))
+            copies = weight_copies(w)
             small = tuple(int(v) for v in args.small.split(","))
             if small[0] and not (w.dtype == "bf16" and mb.moe_tile_pair_supported(mb.MOE_DTYPE_BF16, w.tile_m, w.tile_n, small[0])):
                 small = (0, 0)
@@ -477,11 +541,7 @@ def main():
             torch.cuda.empty_cache()
             # labelled extra: the same products with the weights pre-packed as [E][N][K]
             for w in (wl, wk.mixtral_up(256), wk.mixtral_up(16), wk.decode_fp8(32), wk.decode_fp8(8)):
-                copies = 1
-                if w.dtype == "fp8":
-                    touched = int(torch.unique(wk.make_routing(w)).numel()) * w.K * w.N
-                    copies = min(16, max(4, -(-int(1.2e9) // touched)))
-                p = Point(w, copies, w_nk=True)
+                p = Point(w, weight_copies(w), w_nk=True)
                 points.append(p.report(max(10, args.steps // 2), max(3, args.warmup // 2)))
                 del p
                 torch.cuda.empty_cache()

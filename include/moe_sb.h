@@ -11,7 +11,8 @@
  * General rules for every call
  *   - Pointers marked DEVICE are device memory owned by the caller; pointers
  *     marked HOST are host memory.  The library allocates nothing; the only state
- *     it keeps is per-kernel launch attributes set on first use and the moe_debug_streaming mode.
+ *     it keeps is per-kernel, per-device launch attributes set on first use (guarded by a lock: calls
+ *     may come from several host threads).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls only enqueue work; they do not synchronise unless stated.
  *   - Return value: MOE_OK (0) or a negative MOE_ERR_* code.  Nothing is
@@ -246,7 +247,20 @@ typedef struct moe_gemm_desc {
     int32_t tile_m_slack; /* slack rows of the map's last m-tiles, or 0 */
     int32_t epilogue;     /* MOE_EPILOGUE_* */
     int32_t w_layout;     /* MOE_W_LAYOUT_* */
+    int32_t launch_mode;  /* MOE_LAUNCH_*; 0 for the library's own choice.  Results are identical in every mode. */
 } moe_gemm_desc;
+
+/* How moe_grouped_gemm maps workgroups to tiles (moe_gemm_desc.launch_mode).  The task map and the results are the
+ * same in every mode; tests and measurements use the explicit modes.
+ *   MOE_LAUNCH_AUTO      resident workgroups where a kernel for that exists and the grid bound is at least two
+ *                        tiles per resident workgroup, else one workgroup per tile
+ *   MOE_LAUNCH_PER_TILE  always one workgroup per tile
+ *   MOE_LAUNCH_RESIDENT  resident workgroups (each runs a contiguous share of its XCD's tiles back to back) wherever
+ *                        a kernel for that exists: 16-row tiles with E <= 256 (fp8: T + E <= 2048), and the bf16
+ *                        256 x 256 tiles; elsewhere the same as MOE_LAUNCH_PER_TILE
+ *   a value >= 8         MOE_LAUNCH_RESIDENT with at most that many workgroups (rounded down to a multiple of 8)
+ */
+enum { MOE_LAUNCH_AUTO = 0, MOE_LAUNCH_PER_TILE = 1, MOE_LAUNCH_RESIDENT = 2 };
 
 /*
  * The statically batched expert GEMM (Alg. 3/4 with the GEMM tile as the task
@@ -317,38 +331,6 @@ int moe_tile_pair_supported(int dtype, int tile_m, int tile_n, int tile_m_small)
  * N % 8 == 0, else MOE_ERR_UNSUPPORTED.  Enqueued on `stream`; allocates nothing.
  */
 int moe_combine(const void* Y, const float* topk_weights, int T, int k, int N, void* out, void* stream);
-
-/* Measurement and test aid.  Where the shape allows it (16-row tiles, E <= 256, fp8: T + E <= 2048)
- * moe_grouped_gemm keeps workgroups resident and streams several tiles through each instead of launching one
- * workgroup per tile; by default it does so when the grid bound is at least two tiles per resident workgroup.
- * mode 0: that default; 1: never; 2: always; >= 8: always, with at most `mode` workgroups (rounded down to a
- * multiple of 8).  Results are identical in every mode.  Process-wide, not thread-safe. */
-void moe_debug_streaming(int mode);
-
-/* Measurement aid: the chip's sustained MFMA rate without any memory traffic, the ceiling every bf16 GEMM here
- * is under.  Enqueues one kernel of 256 workgroups x 512 threads in which every wavefront issues
- * iters x 512 KFLOP of bf16 MFMAs on register operands (32 accumulators of 16x16x32 when block == 16,
- * 8 accumulators of 32x32x16 when block == 32); operands are pseudo-random bf16 values when
- * random_operands != 0, else the constant 1.0 (the rate depends on the operand values: switching power).
- * FLOPs of the launch = 256 * 8 * iters * 524288.  `sink` is DEVICE memory of at least 4 bytes that the kernel
- * may write.  Returns MOE_ERR_INVALID_ARG for another block size, iters < 1 or a NULL sink. */
-int moe_debug_mfma_probe(int block, int random_operands, int iters, void* sink, void* stream);
-
-/* Measurement aid: the inner loop of the 256x256x64 bf16 tile (eight wavefronts, 16x16x32 MFMAs on a 128x64
- * accumulator block each) assembled one ingredient at a time, to price each against the pure-MFMA rate above.
- *   mode 1: MFMAs + the LDS fragment reads of every k-step;  2: + one workgroup barrier per 64-deep k-tile;
- *   3: + the k-tile's 64 KB of global->LDS DMA from a cache-resident source;
- *   4: as 3 with half of those bytes from lines never touched before (about the real kernel's HBM share);
- *   5-8: no MFMAs, the LDS pipe alone (no FLOPs): 5 the 16-byte fragment reads of every k-step (8 per lane,
- *   8 KiB per wavefront), 6 the transposing 8-byte reads (8 per lane, 4 KiB), 7 both, 8 the DMA writes
- *   (4 instructions of 1 KiB per wavefront and k-step).
- * Enqueues one kernel of 256 workgroups x 512 threads; FLOPs of the launch = 256 * 8 * iters * 524288
- * (iters counts k-steps: even, >= 2).  `src`: DEVICE memory, 16-byte aligned, read only, at least 1 MiB
- * (mode 4: 513 MiB); its first 64 KiB become the fragments, so fill it with bf16 values of the magnitude of
- * real operands.  `sink`: DEVICE memory of at least 4 bytes that the kernel may write.  Nothing is allocated.
- * Returns MOE_ERR_INVALID_ARG for another mode, an odd or too small iters, a NULL or misaligned pointer or a
- * src_bytes below the stated minimum. */
-int moe_debug_pipeline_probe(int mode, int iters, const void* src, size_t src_bytes, void* sink, void* stream);
 
 /* Static string for a return code. */
 const char* moe_strerror(int code);

@@ -32,6 +32,9 @@ MOE_EPILOGUE_SWIGLU = 1
 MOE_ORDER_ASCENDING = 0
 MOE_ORDER_SPREAD = 1
 MOE_ORDER_INTERLEAVE = 2
+MOE_LAUNCH_AUTO = 0
+MOE_LAUNCH_PER_TILE = 1
+MOE_LAUNCH_RESIDENT = 2
 MOE_MAP_MAGIC = 0x3142534D
 MOE_MAP_HDR_WORDS = 32
 HDR = dict(MAGIC=0, T=1, K_TOP=2, E=3, N=4, TILE_M=5, TILE_N=6, NT=7, M=8, TOTAL_TILES=9, ORDER=10,
@@ -45,7 +48,7 @@ EXPORTS = [
     "moe_build_task_map_ex", "moe_tiling_supported", "moe_w_layout_supported", "moe_default_tiling",
     "moe_task_map_status", "moe_task_map_expand", "moe_grouped_gemm", "moe_tile_supported", "moe_combine",
     "moe_grouped_gemm_splitk", "moe_splitk_workspace_bytes", "moe_default_k_parts",
-    "moe_debug_streaming", "moe_debug_mfma_probe", "moe_debug_pipeline_probe", "moe_strerror",
+    "moe_strerror",
 ]
 
 
@@ -60,7 +63,8 @@ class moe_gemm_desc(ctypes.Structure):
                 ("K", ctypes.c_int32), ("N", ctypes.c_int32), ("tile_m", ctypes.c_int32),
                 ("tile_n", ctypes.c_int32), ("x_scale", ctypes.c_void_p), ("w_scale", ctypes.c_void_p),
                 ("tile_m_small", ctypes.c_int32), ("small_max_rows", ctypes.c_int32),
-                ("tile_m_slack", ctypes.c_int32), ("epilogue", ctypes.c_int32), ("w_layout", ctypes.c_int32)]
+                ("tile_m_slack", ctypes.c_int32), ("epilogue", ctypes.c_int32), ("w_layout", ctypes.c_int32),
+                ("launch_mode", ctypes.c_int32)]
 
 
 class moe_tiling(ctypes.Structure):
@@ -117,10 +121,6 @@ def lib() -> ctypes.CDLL:
         L.moe_combine.restype = ctypes.c_int
         L.moe_combine.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                   ctypes.c_void_p, ctypes.c_void_p]
-        L.moe_debug_streaming.restype = None
-        L.moe_debug_streaming.argtypes = [ctypes.c_int]
-        L.moe_debug_mfma_probe.restype = ctypes.c_int
-        L.moe_debug_mfma_probe.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
         L.moe_grouped_gemm_splitk.restype = ctypes.c_int
         L.moe_grouped_gemm_splitk.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                               ctypes.POINTER(moe_gemm_desc), ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t,
@@ -129,9 +129,6 @@ def lib() -> ctypes.CDLL:
         L.moe_splitk_workspace_bytes.argtypes = [ctypes.c_int] * 4
         L.moe_default_k_parts.restype = ctypes.c_int
         L.moe_default_k_parts.argtypes = [ctypes.c_int] * 5
-        L.moe_debug_pipeline_probe.restype = ctypes.c_int
-        L.moe_debug_pipeline_probe.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
-                                               ctypes.c_void_p]
         L.moe_strerror.restype = ctypes.c_char_p
         L.moe_strerror.argtypes = [ctypes.c_int]
         _lib = L
@@ -280,12 +277,14 @@ class GemmDesc:
     tile_m_slack: int = 0
     epilogue: int = 0
     w_layout: int = 0
+    launch_mode: int = 0
 
     def c_struct(self) -> moe_gemm_desc:
         return moe_gemm_desc(self.dtype, self.T, self.k, self.E, self.K, self.N, self.tile_m, self.tile_n,
                              None if self.x_scale is None else self.x_scale.data_ptr(),
                              None if self.w_scale is None else self.w_scale.data_ptr(),
-                             self.tile_m_small, self.small_max_rows, self.tile_m_slack, self.epilogue, self.w_layout)
+                             self.tile_m_small, self.small_max_rows, self.tile_m_slack, self.epilogue, self.w_layout,
+                             self.launch_mode)
 
 
 def moe_grouped_gemm(X: torch.Tensor, W: torch.Tensor, topk_ids: Optional[torch.Tensor], task_map: torch.Tensor,
@@ -325,30 +324,6 @@ def moe_grouped_gemm_splitk(X: torch.Tensor, W: torch.Tensor, task_map: torch.Te
                                        _ptr(workspace), ctypes.c_size_t(nbytes), _stream() if X is not None else None)
     if check and rc != MOE_OK:
         raise MoeError(rc, "moe_grouped_gemm_splitk")
-    return rc
-
-
-def moe_debug_streaming(mode: int) -> None:
-    lib().moe_debug_streaming(int(mode))
-
-
-def moe_debug_mfma_probe(block: int, random_operands: bool, iters: int, sink, check: bool = True) -> int:
-    """One launch of the pure-MFMA probe; FLOPs = 256 * 8 * iters * 524288.  `sink`: device tensor of >= 4 bytes."""
-    rc = lib().moe_debug_mfma_probe(int(block), int(bool(random_operands)), int(iters), _ptr(sink),
-                                    _stream() if sink is not None else None)
-    if check and rc != MOE_OK:
-        raise MoeError(rc, "moe_debug_mfma_probe")
-    return rc
-
-
-def moe_debug_pipeline_probe(mode: int, iters: int, src, sink, check: bool = True) -> int:
-    """One launch of the tile-loop probe (1: LDS reads, 2: + barrier, 3: + DMA from cache, 4: + half of it from HBM;
-    5-8: the LDS pipe alone: 16-byte reads, transposing reads, both, DMA writes); FLOPs (modes 1-4) = 256 * 8 * iters * 524288.  `src`: device tensor of >= 1 MiB (mode 4: 513 MiB) holding bf16 values."""
-    nbytes = 0 if src is None else src.numel() * src.element_size()
-    rc = lib().moe_debug_pipeline_probe(int(mode), int(iters), _ptr(src), ctypes.c_size_t(nbytes), _ptr(sink),
-                                        _stream() if sink is not None and src is not None else None)
-    if check and rc != MOE_OK:
-        raise MoeError(rc, "moe_debug_pipeline_probe")
     return rc
 
 

@@ -51,12 +51,19 @@ __global__ __launch_bounds__(256) void moe_combine_kernel(const u32x4_t* __restr
 }
 
 // Second half of a split-k product: Y[r(p), n] = bf16( sum_s partial[s][p][n] ), s ascending, for every position p of
-// sorted_rows (r(p) = sorted_rows[p]); each lane owns 8 consecutive n of one position.  A map that is invalid or
-// empty (status != 0: no tile ran, the workspace holds nothing) makes this a no-op, like the product itself.
+// sorted_rows (r(p) = sorted_rows[p]); each lane owns 8 consecutive n of one position.  A map that is invalid,
+// empty, or not the one this product was described with (the same header test as the product's own, locate_tile:
+// shape, 256 x 256 tiles, one strategy, no slack, status 0) makes this a no-op, like the product itself: no tile
+// ran then, the workspace holds nothing, and the row ids behind the header are not to be trusted.
 __global__ __launch_bounds__(256) void moe_splitk_reduce_kernel(const float* __restrict__ partial, const int32_t* __restrict__ map,
                                                                 const int32_t* __restrict__ sorted_rows, u32x4_t* __restrict__ Y,
-                                                                int R, int N, int parts) {
-    if (map[MOE_HDR_STATUS] != 0 || map[MOE_HDR_TOTAL_TILES] == 0) return;
+                                                                int T, int k_top, int E, int N, int parts) {
+    const bool hdr_ok = map[MOE_HDR_MAGIC] == MOE_MAP_MAGIC && map[MOE_HDR_T] == T && map[MOE_HDR_K_TOP] == k_top &&
+                        map[MOE_HDR_E] == E && map[MOE_HDR_N] == N && map[MOE_HDR_TILE_M] == 256 &&
+                        map[MOE_HDR_TILE_N] == 256 && map[MOE_HDR_STATUS] == 0 && map[MOE_HDR_TILE_M_SMALL] == 0 &&
+                        map[MOE_HDR_SMALL_MAX_ROWS] == 0 && map[MOE_HDR_TILE_M_SLACK] == 0;
+    if (!hdr_ok || map[MOE_HDR_TOTAL_TILES] == 0) return;
+    const int R = T * k_top;
     const int cpr = N >> 3;
     const long long total = (long long)R * cpr;
     const size_t part_stride = (size_t)R * N;

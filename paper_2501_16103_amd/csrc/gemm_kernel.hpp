@@ -67,13 +67,13 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 // vmcnt like any load; the compiler does not see it, so every wait on it below is explicit.
 __device__ __forceinline__ void dma16(uint32_t voff, const void* sbase, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_addr)
-                 : "memory");
+                 : "memory", "m0");
 }
 // Same, marked non-temporal: for weight rows that no other workgroup will ask for (the panel of an expert with a
 // single m-tile), so that streaming them does not displace the lines other workgroups share through L2.
 __device__ __forceinline__ void dma16_nt(uint32_t voff, const void* sbase, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt" ::"v"(voff), "s"(sbase), "s"(lds_addr)
-                 : "memory");
+                 : "memory", "m0");
 }
 // f(integral_constant<int, LO>), ..., f(integral_constant<int, HI>)
 template <int LO, int HI, class F>
@@ -949,171 +949,6 @@ __global__ __launch_bounds__(C::NT) void moe_gemm_stream_kernel(GemmArgs a) {
     ts.end_B = t1;
     const TileCoord tc = decode_from_registers(ts, t0);
     pipe_tile<C, true>(a, map, L, tc, smem, &ts);
-}
-
-// Measurement aid: bf16 MFMAs on register operands and nothing else, two wavefronts per SIMD (512 threads, one
-// workgroup per CU).  Per loop trip and wavefront 512 KFLOP: 32 MFMAs of 16x16x32 or 16 of 32x32x16, every
-// accumulator independent of the others, 128 accumulator registers either way.
-template <int BLOCK, bool RANDOM>
-__global__ void __launch_bounds__(512) mfma_probe_kernel(int iters, float* sink) {
-    auto bits = [](uint32_t i) {   // two bf16 values of magnitude 2^-3 .. 2, random sign and mantissa
-        uint32_t h = i * 2654435761u;
-        h ^= h >> 15; h *= 2246822519u; h ^= h >> 13; h *= 3266489917u; h ^= h >> 16;
-        const uint32_t lo = (h & 0x807fu) | (0x3e00u + ((h >> 16) & 0x0180u));
-        const uint32_t hi = ((h >> 8) & 0x807fu) | (0x3e00u + ((h >> 20) & 0x0180u));
-        return RANDOM ? (lo | (hi << 16)) : 0x3f803f80u;
-    };
-    const uint32_t seed = (blockIdx.x * 977u + threadIdx.x) * 64u;
-    bf16x8_t fa[4], fb[8];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const u32x4_t v = {bits(seed + 4 * i), bits(seed + 4 * i + 1), bits(seed + 4 * i + 2), bits(seed + 4 * i + 3)};
-        fa[i] = __builtin_bit_cast(bf16x8_t, v);
-    }
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const u32x4_t v = {bits(seed + 16 + 4 * i), bits(seed + 17 + 4 * i), bits(seed + 18 + 4 * i), bits(seed + 19 + 4 * i)};
-        fb[i] = __builtin_bit_cast(bf16x8_t, v);
-    }
-    float sum = 0.f;
-    if constexpr (BLOCK == 16) {
-        f32x4_t acc[32];
-#pragma unroll
-        for (int i = 0; i < 32; ++i) acc[i] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-        for (int it = 0; it < iters; ++it) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 8; ++j) acc[i * 8 + j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb[j], acc[i * 8 + j], 0, 0, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < 32; ++i) sum += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
-    } else {
-        f32x16_t acc[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) acc[i][j] = 0.f;
-        for (int it = 0; it < iters; ++it) {
-#pragma unroll
-            for (int h = 0; h < 2; ++h)
-#pragma unroll
-                for (int i = 0; i < 2; ++i)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        acc[i * 4 + j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i + 2 * h], fb[j + 4 * h], acc[i * 4 + j], 0, 0, 0);
-        }
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-#pragma unroll
-            for (int j = 0; j < 16; ++j) sum += acc[i][j];
-    }
-    if (sum == 12345.f) sink[0] = sum;   // keeps the loop alive; practically never true
-}
-
-// Measurement aid: the inner loop of the 256x256x64 bf16 tile without its arithmetic on addresses -- eight
-// wavefronts, each with a 128x64 accumulator block of 16x16x32 MFMAs -- built up one ingredient at a time, so
-// that the cost of each shows against the pure-MFMA rate:
-//   MODE 1: the LDS fragment reads of a k-step (8 of 16 bytes, 8 transposing ones of 8 bytes), double-buffered
-//   MODE 2: + one workgroup barrier per 64-deep k-tile
-//   MODE 3: + the k-tile's 64 KB of global->LDS DMA (8 instructions per thread), source resident in cache
-//   MODE 4: as 3, but half of the bytes come from lines not touched before (a new 32 KB chunk of `src` per k-tile,
-//           shared by two workgroups), about the weight traffic the real kernel draws from HBM
-//   MODE 5-8: no MFMAs, the LDS pipe alone: the 16-byte reads, the transposing reads, both, the DMA writes
-// `src`: at least 1 MB (MODE 4: 513 MB) of device memory; its first 64 KB fill the LDS region the fragments are
-// read from, so bf16 values there make the operands realistic.  Per loop trip (two k-steps) and wavefront 1 MFLOP.
-template <int MODE>
-__global__ void __launch_bounds__(512) pipeline_probe_kernel(int iters, const char* src, float* sink) {
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-    constexpr int MB = 8, NB = 4;
-    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    for (int i = tid; i < 65536 / 16; i += 512) reinterpret_cast<u32x4_t*>(smem)[i] = reinterpret_cast<const u32x4_t*>(src)[i];
-    __syncthreads();
-    f32x4_t acc[MB][NB];
-#pragma unroll
-    for (int i = 0; i < MB; ++i)
-#pragma unroll
-        for (int j = 0; j < NB; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    u32x4_t xq[2][MB];
-    u32x2_t wq[2][NB][2];
-    // fragments of k-step `it`: conflict-free addresses inside [0, 64 KB), different from step to step
-    auto load = [&](int buf, int it) __attribute__((always_inline)) {
-        int base = (it & 3) * 16384 + (wave & 1) * 8192;
-        asm volatile("" : "+v"(base));
-        if (MODE != 6) {
-#pragma unroll
-            for (int i = 0; i < MB; ++i) xq[buf][i] = *reinterpret_cast<const u32x4_t*>(smem + base + lane * 16 + i * 1024);
-        }
-        if (MODE != 5) {
-#pragma unroll
-            for (int j = 0; j < NB; ++j)
-#pragma unroll
-                for (int h = 0; h < 2; ++h)
-                    wq[buf][j][h] = __builtin_bit_cast(u32x2_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (MOE_LDS(s16x4_t)*)(smem + ((base + lane * 8 + (j * 2 + h) * 512) & 65535))));
-        }
-    };
-    auto mma = [&](int buf) __attribute__((always_inline)) {
-#pragma unroll
-        for (int j = 0; j < NB; ++j)
-#pragma unroll
-            for (int i = 0; i < MB; ++i) {
-                const u32x4_t wv = {wq[buf][j][0].x, wq[buf][j][0].y, wq[buf][j][1].x, wq[buf][j][1].y};
-                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wv),
-                                                                    __builtin_bit_cast(bf16x8_t, xq[buf][i]), acc[i][j], 0, 0, 0);
-            }
-    };
-    // DMA target: LDS [64 KB, 96 KB), apart from the fragments; sources stay inside `src` by construction:
-    // cached part: offsets < 17 * 32 KB + 32 KB <= 1 MB; fresh part: 1 MB + chunk (< 512 MB) + 32 KB
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(MOE_LDS(char)*)smem;
-    auto dmas = [&](int it, int half) __attribute__((always_inline)) {
-        const uint32_t chunk = (((blockIdx.x >> 1) * 4099u + static_cast<uint32_t>(it >> 1)) & 16383u) * 32768u;
-        const char* src_w = MODE == 4 ? src + (1u << 20) + chunk : src + 32768 + (blockIdx.x & 15) * 32768;
-        const char* src_x = src + (blockIdx.x & 7) * 32768;
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-            dma16(lane * 16 + wave * 1024 + r * 8192, half ? src_w : src_x, lds0 + 65536 + r * 8192 + wave * 1024);
-    };
-    if constexpr (MODE >= 5) {
-        // no MFMAs: the LDS pipe alone.  5: the 16-byte reads of a k-step, 6: its transposing 8-byte reads,
-        // 7: both, 8: the k-tile's DMA writes (cache-resident source)
-        for (int it = 0; it < iters; it += 2) {
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                if (MODE <= 7) load(h, it + h);
-                if (MODE == 5 || MODE == 7) {
-#pragma unroll
-                    for (int i = 0; i < MB; ++i) asm volatile("" ::"v"(xq[h][i]));
-                }
-                if (MODE == 6 || MODE == 7) {
-#pragma unroll
-                    for (int j = 0; j < NB; ++j) asm volatile("" ::"v"(wq[h][j][0]), "v"(wq[h][j][1]));
-                }
-                if (MODE == 8) { dmas(it, h); wait_vmcnt<4>(); }
-            }
-        }
-        if (MODE == 8) wait_vmcnt<0>();
-        if (iters < 0) sink[0] = 0.f;
-        return;
-    }
-    load(0, 0);
-    for (int it = 0; it < iters; it += 2) {
-        load(1, it + 1);
-        if (MODE >= 3) dmas(it, 0);
-        mma(0);
-        load(0, it + 2);
-        if (MODE >= 3) dmas(it, 1);
-        mma(1);
-        if (MODE >= 3) wait_vmcnt<8>();      // the previous k-tile's DMA has landed
-        if (MODE >= 2) __syncthreads();
-    }
-    if (MODE >= 3) wait_vmcnt<0>();
-    float sum = 0.f;
-#pragma unroll
-    for (int i = 0; i < MB; ++i)
-#pragma unroll
-        for (int j = 0; j < NB; ++j) sum += acc[i][j][0] + acc[i][j][1] + acc[i][j][2] + acc[i][j][3];
-    if (sum == 12345.678f) sink[0] = sum;   // keeps the loop alive; practically never true
 }
 
 }  // namespace moe

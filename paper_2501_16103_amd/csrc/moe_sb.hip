@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
+#include <mutex>
 #include <type_traits>
 
 #include "../../include/moe_sb.h"
@@ -25,14 +26,17 @@ int check_map_args(int T, int k, int E, int tile_m, int tile_n, int N) {
     return MOE_OK;
 }
 
-int g_stream_mode = 0;  // set by moe_debug_streaming: 0 automatic, 1 never, 2 always, >= 8 always with that many workgroups
+// Guards the launch-attribute caches below (set once per kernel and device): calls may come from several host threads.
+std::mutex g_attr_lock;
 
 int nchunks_for(int64_t R) { return (int)((R + kChunkRows - 1) / kChunkRows); }
 
-typedef int (*gemm_launch_fn)(const GemmArgs&, int64_t grid, hipStream_t);
+// `mode` is moe_gemm_desc.launch_mode (only the launches that have a resident form look at it)
+typedef int (*gemm_launch_fn)(const GemmArgs&, int64_t grid, int mode, hipStream_t);
 
 // The large-LDS attribute of a kernel is set once per device (bit d of *done: device d, d < 64).
 inline int ensure_lds_attr(const void* fn, int lds, unsigned long long* done) {
+    std::lock_guard<std::mutex> hold(g_attr_lock);
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return MOE_ERR_HIP;
     const unsigned long long bit = dev >= 0 && dev < 64 ? 1ull << dev : 0;
@@ -43,7 +47,7 @@ inline int ensure_lds_attr(const void* fn, int lds, unsigned long long* done) {
 }
 
 template <class C, class... Tails>
-int launch_pipe(const GemmArgs& a, int64_t grid, hipStream_t s) {
+int launch_pipe(const GemmArgs& a, int64_t grid, int /*mode*/, hipStream_t s) {
     static unsigned long long attr_done = 0;
     if (ensure_lds_attr(reinterpret_cast<const void*>(&moe_gemm_pipe_kernel<C, Tails...>), C::LDS_BYTES, &attr_done) != MOE_OK)
         return MOE_ERR_HIP;
@@ -61,35 +65,46 @@ int launch_splitk(const GemmArgs& a, int64_t grid, int parts, hipStream_t s) {
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
+// Workgroups of `fn` that stay resident at once on the current device with `lds` bytes of dynamic LDS (also sets
+// the kernel's large-LDS attribute); cached per kernel instance in *cache for the last (device, lds) asked for.
+struct ResidentCache { int lds = -1, dev = -1, resident = 0; };
+inline int resident_workgroups(const void* fn, int threads, int lds, ResidentCache* cache, int* resident) {
+    std::lock_guard<std::mutex> hold(g_attr_lock);
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return MOE_ERR_HIP;
+    if (lds != cache->lds || dev != cache->dev) {
+        int cus = 0, per_cu = 0;
+        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, threads, lds) != hipSuccess || per_cu < 1 || cus < 8)
+            return MOE_ERR_HIP;
+        cache->resident = per_cu * cus / 8 * 8;
+        cache->lds = lds;
+        cache->dev = dev;
+    }
+    *resident = cache->resident;
+    return MOE_OK;
+}
+
 // Streaming launch: as many workgroups as stay resident at once (grid is only an upper bound here).
 template <class C>
-int launch_stream(const GemmArgs& a, int64_t grid, hipStream_t s) {
+int launch_stream(const GemmArgs& a, int64_t grid, int mode, hipStream_t s) {
     const int lds = C::LDS_BYTES + (C::FP8 ? 4 * (a.T + a.E) : 0);
-    static int lds_set = -1, dev_set = -1, resident = 0;
-    int dev_now = 0;
-    if (hipGetDevice(&dev_now) != hipSuccess) return MOE_ERR_HIP;
-    if (lds != lds_set || dev_now != dev_set) {
-        const void* fn = reinterpret_cast<const void*>(&moe_gemm_stream_kernel<C>);
-        int dev = 0, cus = 0, per_cu = 0;
-        if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess ||
-            hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
-            hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, C::NT, lds) != hipSuccess || per_cu < 1 || cus < 8)
-            return MOE_ERR_HIP;
-        resident = per_cu * cus / 8 * 8;
-        lds_set = lds;
-        dev_set = dev_now;
-    }
+    static ResidentCache cache;
+    int resident = 0;
+    if (resident_workgroups(reinterpret_cast<const void*>(&moe_gemm_stream_kernel<C>), C::NT, lds, &cache, &resident) != MOE_OK)
+        return MOE_ERR_HIP;
     // with fewer than two tiles per resident workgroup there is nothing to stream across: one workgroup per tile
-    if (g_stream_mode == 0 && grid < 2 * (int64_t)resident) return launch_pipe<C>(a, grid, s);
+    if (mode == MOE_LAUNCH_PER_TILE || (mode == MOE_LAUNCH_AUTO && grid < 2 * (int64_t)resident))
+        return launch_pipe<C>(a, grid, mode, s);
     int64_t g = grid < resident ? grid : resident;
-    if (g_stream_mode >= 8 && g > g_stream_mode) g = g_stream_mode / 8 * 8;
+    if (mode >= 8 && g > mode) g = mode / 8 * 8;
     moe_gemm_stream_kernel<C><<<dim3((unsigned)g), dim3(C::NT), lds, s>>>(a);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
 template <class CBIG, class CSMALL, class... Tails>
-int launch_pipe2(const GemmArgs& a, int64_t grid, hipStream_t s) {
+int launch_pipe2(const GemmArgs& a, int64_t grid, int /*mode*/, hipStream_t s) {
     constexpr int lds = CBIG::LDS_BYTES > CSMALL::LDS_BYTES ? CBIG::LDS_BYTES : CSMALL::LDS_BYTES;
     static unsigned long long attr_done = 0;
     if (ensure_lds_attr(reinterpret_cast<const void*>(&moe_gemm_pipe2_kernel<CBIG, CSMALL, Tails...>), lds, &attr_done) != MOE_OK)
@@ -360,28 +375,20 @@ int moe_build_task_map_ex(const int32_t* topk_ids, int T, int k, int E, int N, c
     const int64_t R = (int64_t)T * k;
     if (R <= kChunkRows) {
         const size_t lds = ((size_t)kWaves * L.E64 + L.E64 + 32 + 2 * (size_t)L.E64) * sizeof(int);
-        static bool attr_set = false;
-        if (!attr_set) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&map_build_small),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)(((size_t)kWaves * kMaxE + 3 * (size_t)kMaxE + 32) * sizeof(int))) != hipSuccess)
-                return MOE_ERR_HIP;
-            attr_set = true;
-        }
+        static unsigned long long attr_done = 0;
+        if (ensure_lds_attr(reinterpret_cast<const void*>(&map_build_small),
+                            (int)(((size_t)kWaves * kMaxE + 3 * (size_t)kMaxE + 32) * sizeof(int)), &attr_done) != MOE_OK)
+            return MOE_ERR_HIP;
         map_build_small<<<1, kMapThreads, lds, s>>>(topk_ids, map, T, k, E, N, g);
     } else {
         const int nchunks = nchunks_for(R);
         int32_t* chunk_hist = map + L.off_rows + round_up64((size_t)R);
         const int hs = hist_stride(L.E64);
         map_hist<<<nchunks, 256, hs * sizeof(int), s>>>(topk_ids, (int)R, E, L.E64, chunk_hist);
-        static bool attr_set2 = false;
-        if (!attr_set2) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(&map_scan_scatter),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    (int)(((size_t)kWaves * kMaxE + kMaxE) * sizeof(int))) != hipSuccess)
-                return MOE_ERR_HIP;
-            attr_set2 = true;
-        }
+        static unsigned long long attr_done2 = 0;
+        if (ensure_lds_attr(reinterpret_cast<const void*>(&map_scan_scatter),
+                            (int)(((size_t)kWaves * kMaxE + kMaxE) * sizeof(int)), &attr_done2) != MOE_OK)
+            return MOE_ERR_HIP;
         map_scan_scatter<<<nchunks, kMapThreads, ((size_t)kWaves * L.E64 + L.E64) * sizeof(int), s>>>(
             topk_ids, map, chunk_hist, nchunks, T, k, E, N, g);
     }
@@ -429,6 +436,7 @@ int moe_grouped_gemm(const void* X, const void* W, const int32_t* topk_ids, cons
         if (rcs != MOE_OK) return rcs;
     }
     if (d->w_layout != MOE_W_LAYOUT_KN && d->w_layout != MOE_W_LAYOUT_NK) return MOE_ERR_INVALID_ARG;
+    if (d->launch_mode < 0) return MOE_ERR_INVALID_ARG;
     const GemmVariant* v = find_variant(d->dtype, d->tile_m, d->tile_n, d->tile_m_small, d->tile_m_slack, d->w_layout);
     if (!v) return MOE_ERR_UNSUPPORTED;
     if (d->K % v->bk != 0 || d->N % d->tile_n != 0) return MOE_ERR_UNSUPPORTED;
@@ -454,8 +462,8 @@ int moe_grouped_gemm(const void* X, const void* W, const int32_t* topk_ids, cons
     if (grid > 0x7fffffff) return MOE_ERR_UNSUPPORTED;
     // weight-streaming tiles: keep the workgroups resident and stream tile after tile where the shape allows it
     const bool can_stream = v->fn_stream && d->E <= 256 && d->K / v->bk >= v->ring &&
-                            (d->dtype != MOE_DTYPE_FP8_E4M3 || d->T + d->E <= 2048) && g_stream_mode != 1;
-    return (can_stream ? v->fn_stream : v->fn)(a, grid, static_cast<hipStream_t>(stream));
+                            (d->dtype != MOE_DTYPE_FP8_E4M3 || d->T + d->E <= 2048) && d->launch_mode != MOE_LAUNCH_PER_TILE;
+    return (can_stream ? v->fn_stream : v->fn)(a, grid, d->launch_mode, static_cast<hipStream_t>(stream));
 }
 
 size_t moe_splitk_workspace_bytes(int T, int k, int N, int k_parts) {
@@ -516,8 +524,8 @@ int moe_grouped_gemm_splitk(const void* X, const void* W, const void* task_map, 
     long long blocks = (chunks + 255) / 256;
     if (blocks > 256 * 64) blocks = 256 * 64;
     const MapLayout L = map_layout(d->E);
-    moe_splitk_reduce_kernel<<<(unsigned)blocks, 256, 0, s>>>(a.partial, a.map, a.map + L.off_rows, static_cast<u32x4_t*>(Y), (int)R,
-                                                             d->N, k_parts);
+    moe_splitk_reduce_kernel<<<(unsigned)blocks, 256, 0, s>>>(a.partial, a.map, a.map + L.off_rows, static_cast<u32x4_t*>(Y), d->T,
+                                                             d->k, d->E, d->N, k_parts);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
@@ -541,49 +549,6 @@ int moe_combine(const void* Y, const float* topk_weights, int T, int k, int N, v
         default: moe_combine_kernel<0><<<(unsigned)blocks, 256, 0, s>>>(y, topk_weights, o, T, k, N); break;
     }
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
-}
-
-void moe_debug_streaming(int mode) { g_stream_mode = mode < 0 ? 0 : mode; }
-
-int moe_debug_mfma_probe(int block, int random_operands, int iters, void* sink, void* stream) {
-    if ((block != 16 && block != 32) || iters < 1 || !sink) return MOE_ERR_INVALID_ARG;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    float* out = static_cast<float*>(sink);
-    if (block == 16) {
-        if (random_operands) moe::mfma_probe_kernel<16, true><<<256, 512, 0, s>>>(iters, out);
-        else moe::mfma_probe_kernel<16, false><<<256, 512, 0, s>>>(iters, out);
-    } else {
-        if (random_operands) moe::mfma_probe_kernel<32, true><<<256, 512, 0, s>>>(iters, out);
-        else moe::mfma_probe_kernel<32, false><<<256, 512, 0, s>>>(iters, out);
-    }
-    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
-}
-
-int moe_debug_pipeline_probe(int mode, int iters, const void* src, size_t src_bytes, void* sink, void* stream) {
-    const size_t need = mode == 4 ? (size_t(513) << 20) : (size_t(1) << 20);
-    if (mode < 1 || mode > 8 || iters < 2 || (iters & 1) || !src || !sink || src_bytes < need ||
-        (reinterpret_cast<uintptr_t>(src) & 15))
-        return MOE_ERR_INVALID_ARG;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const char* in = static_cast<const char*>(src);
-    float* out = static_cast<float*>(sink);
-    constexpr int lds = 96 * 1024;   // one workgroup per CU, as for the tile it imitates
-    static unsigned long long done[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    auto go = [&](auto kernel, unsigned long long* d) {
-        if (ensure_lds_attr(reinterpret_cast<const void*>(kernel), lds, d) != MOE_OK) return int(MOE_ERR_HIP);
-        kernel<<<256, 512, lds, s>>>(iters, in, out);
-        return hipGetLastError() == hipSuccess ? int(MOE_OK) : int(MOE_ERR_HIP);
-    };
-    switch (mode) {
-        case 1: return go(&moe::pipeline_probe_kernel<1>, &done[0]);
-        case 2: return go(&moe::pipeline_probe_kernel<2>, &done[1]);
-        case 3: return go(&moe::pipeline_probe_kernel<3>, &done[2]);
-        case 4: return go(&moe::pipeline_probe_kernel<4>, &done[3]);
-        case 5: return go(&moe::pipeline_probe_kernel<5>, &done[4]);
-        case 6: return go(&moe::pipeline_probe_kernel<6>, &done[5]);
-        case 7: return go(&moe::pipeline_probe_kernel<7>, &done[6]);
-        default: return go(&moe::pipeline_probe_kernel<8>, &done[7]);
-    }
 }
 
 const char* moe_strerror(int code) {

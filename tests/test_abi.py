@@ -82,24 +82,26 @@ def test_null_arguments_rejected_on_host():
 
 
 def test_mfma_probe_rejects_bad_arguments_before_any_launch():
-    lib = mb.lib()
-    assert lib.moe_debug_mfma_probe(8, 1, 10, None, None) == mb.MOE_ERR_INVALID_ARG
-    assert lib.moe_debug_mfma_probe(16, 1, 10, None, None) == mb.MOE_ERR_INVALID_ARG   # no sink
-    assert lib.moe_debug_mfma_probe(32, 0, 0, 1, None) == mb.MOE_ERR_INVALID_ARG        # no iterations
+    from paper_2501_16103_amd import probe
+    lib = probe.lib()
+    assert lib.moe_probe_mfma(8, 1, 10, None, None) == mb.MOE_ERR_INVALID_ARG
+    assert lib.moe_probe_mfma(16, 1, 10, None, None) == mb.MOE_ERR_INVALID_ARG   # no sink
+    assert lib.moe_probe_mfma(32, 0, 0, 1, None) == mb.MOE_ERR_INVALID_ARG        # no iterations
 
 
 def test_pipeline_probe_rejects_bad_arguments_before_any_launch():
-    lib = mb.lib()
+    from paper_2501_16103_amd import probe
+    lib = probe.lib()
     big, small = ctypes.c_size_t(513 << 20), ctypes.c_size_t(1 << 20)
-    assert lib.moe_debug_pipeline_probe(0, 10, 16, big, 16, None) == mb.MOE_ERR_INVALID_ARG     # no such mode
-    assert lib.moe_debug_pipeline_probe(9, 10, 16, big, 16, None) == mb.MOE_ERR_INVALID_ARG
-    assert lib.moe_debug_pipeline_probe(1, 11, 16, big, 16, None) == mb.MOE_ERR_INVALID_ARG     # odd k-step count
-    assert lib.moe_debug_pipeline_probe(1, 0, 16, big, 16, None) == mb.MOE_ERR_INVALID_ARG
-    assert lib.moe_debug_pipeline_probe(1, 10, None, big, 16, None) == mb.MOE_ERR_INVALID_ARG   # no source
-    assert lib.moe_debug_pipeline_probe(1, 10, 16, big, None, None) == mb.MOE_ERR_INVALID_ARG   # no sink
-    assert lib.moe_debug_pipeline_probe(1, 10, 24, big, 16, None) == mb.MOE_ERR_INVALID_ARG     # misaligned source
-    assert lib.moe_debug_pipeline_probe(3, 10, 16, ctypes.c_size_t((1 << 20) - 1), 16, None) == mb.MOE_ERR_INVALID_ARG
-    assert lib.moe_debug_pipeline_probe(4, 10, 16, small, 16, None) == mb.MOE_ERR_INVALID_ARG   # mode 4 needs 513 MiB
+    assert lib.moe_probe_pipeline(0, 10, 16, big, 16, None) == mb.MOE_ERR_INVALID_ARG     # no such mode
+    assert lib.moe_probe_pipeline(9, 10, 16, big, 16, None) == mb.MOE_ERR_INVALID_ARG
+    assert lib.moe_probe_pipeline(1, 11, 16, big, 16, None) == mb.MOE_ERR_INVALID_ARG     # odd k-step count
+    assert lib.moe_probe_pipeline(1, 0, 16, big, 16, None) == mb.MOE_ERR_INVALID_ARG
+    assert lib.moe_probe_pipeline(1, 10, None, big, 16, None) == mb.MOE_ERR_INVALID_ARG   # no source
+    assert lib.moe_probe_pipeline(1, 10, 16, big, None, None) == mb.MOE_ERR_INVALID_ARG   # no sink
+    assert lib.moe_probe_pipeline(1, 10, 24, big, 16, None) == mb.MOE_ERR_INVALID_ARG     # misaligned source
+    assert lib.moe_probe_pipeline(3, 10, 16, ctypes.c_size_t((1 << 20) - 1), 16, None) == mb.MOE_ERR_INVALID_ARG
+    assert lib.moe_probe_pipeline(4, 10, 16, small, 16, None) == mb.MOE_ERR_INVALID_ARG   # mode 4 needs 513 MiB
 
 
 def test_splitk_host_functions():

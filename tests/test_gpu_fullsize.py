@@ -29,9 +29,12 @@ def _gather_columns(W, experts, cols):
     return torch.cat(out)
 
 
-def _run_full(wl, dev, order=0, k_parts=1):
+def _run_full(wl, dev, order=0, k_parts=1, launch_mode=0, inputs=None):
+    """`inputs`: (X, W, xs, ws) already on the device, to run one set of weights through several launches."""
     ids = wk.make_routing(wl)
-    if wl.dtype == "fp8":
+    if inputs is not None:
+        X, W, xs, ws = inputs
+    elif wl.dtype == "fp8":
         X, xs = wk.make_x(wl, dev)
         W, ws = wk.make_w(wl, dev)
     else:
@@ -43,7 +46,8 @@ def _run_full(wl, dev, order=0, k_parts=1):
     tmap = mb.alloc_task_map(wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N, dev)
     mb.moe_build_task_map_ex(ids.to(dev), wl.T, wl.k, wl.E, wl.N, mb.Tiling(wl.tile_m, wl.tile_n, order, 0, 0, wl.tile_m_slack), tmap)
     dt = mb.MOE_DTYPE_FP8_E4M3 if wl.dtype == "fp8" else mb.MOE_DTYPE_BF16
-    desc = mb.GemmDesc(dt, wl.T, wl.k, wl.E, wl.K, wl.N, wl.tile_m, wl.tile_n, xs, ws, tile_m_slack=wl.tile_m_slack)
+    desc = mb.GemmDesc(dt, wl.T, wl.k, wl.E, wl.K, wl.N, wl.tile_m, wl.tile_n, xs, ws, tile_m_slack=wl.tile_m_slack,
+                       launch_mode=launch_mode)
     if k_parts > 1:
         work = torch.empty(mb.moe_splitk_workspace_bytes(wl.T, wl.k, wl.N, k_parts) // 4, dtype=torch.float32, device=dev)
         mb.moe_grouped_gemm_splitk(X, W, tmap, Y, desc, k_parts, work)
@@ -117,6 +121,8 @@ FULL = [
     (wk.mixtral_up(16), 8, 32, 0),
     (wk.mixtral_down_zipf(4096), 8, 64, 0),
     (wk.mixtral_down_zipf(256), 8, 32, 0),
+    (wk.paper_eval("balanced"), 8, 64, 0),                          # Sec. 5: every expert 512 rows
+    (wk.paper_eval("best"), 8, 64, 0),                              # Sec. 5: k experts hold everything, E - k are empty
     (wk.paper_eval("worst"), 8, 64, 0),
     (wk.paper_eval("worst"), 8, 64, 1),
     (wk.mixtral_down_zipf(4096), 8, 64, 1),
@@ -195,6 +201,40 @@ def test_fine_grained_full_size_sampled(oracle_mod):
     table = oracle_mod.full_table(tm.counts, wl.tile_m, wl.tile_n, wl.N)
     rr, nn = _sample_points(tm, table, rng, 2)
     _check_elements(oracle_mod, wl, ids, X, W, xs, ws, Y, rr, nn)
+
+
+def test_fine_grained_T128_full_size_sampled(oracle_mod):
+    """E=256, top-8, T=128 (1024 routed rows over 256 experts: counts of 0 to about 10, several experts empty, Sec. 4.1):
+    16-row tiles in the resident launch the benchmark times, and in the one-workgroup-per-tile launch; both must agree
+    bit for bit, and with the oracle on 2 samples per tile plus complete rows."""
+    wl = wk.fine_grained(128)
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(10)
+    inputs = (wk.make_x(wl, dev), wk.make_w(wl, dev), None, None)
+    ids, X, W, xs, ws, Y, tmap = _run_full(wl, dev, inputs=inputs)
+    tm = oracle_mod.build_task_map(ids.numpy(), wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, wl.N)
+    assert (tm.counts == 0).any(), "the point must have empty experts"
+    want = H.expected_blob(tm)
+    np.testing.assert_array_equal(tmap.cpu().numpy()[: len(want)], want)
+    table = oracle_mod.full_table(tm.counts, wl.tile_m, wl.tile_n, wl.N, sigma=tm.sigma)
+    assert len(table) == tm.total_tiles
+    rr, nn = _sample_points(tm, table, rng, 2)
+    _check_elements(oracle_mod, wl, ids, X, W, xs, ws, Y, rr, nn)
+    # complete rows: first and last row of every tenth expert's segment, then random ones
+    rows = []
+    for e in range(0, wl.E, 10):
+        c, o = int(tm.counts[e]), int(tm.offsets[e])
+        if c:
+            rows += [int(tm.sorted_rows[o]), int(tm.sorted_rows[o + c - 1])]
+    rows += rng.choice(wl.R, size=16, replace=False).tolist()
+    rows = np.array(list(dict.fromkeys(rows))[:40], dtype=np.int32)
+    assert len(rows) >= 32
+    cols = rng.choice(wl.N, size=256, replace=False).astype(np.int32)
+    cols[:2] = (0, wl.N - 1)
+    _check_elements(oracle_mod, wl, ids, X, W, xs, ws, Y, np.repeat(rows, len(cols)), np.tile(cols, len(rows)))
+    y_resident = Y.clone()
+    _, _, _, _, _, Y1, _ = _run_full(wl, dev, launch_mode=mb.MOE_LAUNCH_PER_TILE, inputs=inputs)
+    assert torch.equal(y_resident, Y1), "resident and per-tile launches differ"
 
 
 def test_fine_grained_T8192_full_size_sampled(oracle_mod):

@@ -8,6 +8,7 @@ import pytest
 import torch
 
 from paper_2501_16103_amd import binding as mb
+from paper_2501_16103_amd import probe
 from paper_2501_16103_amd import workloads as wk
 from tests import helpers as H
 
@@ -23,7 +24,7 @@ def dev():
     return torch.device("cuda:0")
 
 
-def _run_swiglu(dev, wl, ids, X, W, xs=None, ws=None, slack=0):
+def _run_swiglu(dev, wl, ids, X, W, xs=None, ws=None, slack=0, launch_mode=0):
     R, I = wl.R, wl.N // 2
     pad = 4
     buf = torch.empty((R + 2 * pad, I), dtype=torch.int16, device=dev)
@@ -34,7 +35,7 @@ def _run_swiglu(dev, wl, ids, X, W, xs=None, ws=None, slack=0):
     dt = mb.MOE_DTYPE_FP8_E4M3 if wl.dtype == "fp8" else mb.MOE_DTYPE_BF16
     desc = mb.GemmDesc(dt, wl.T, wl.k, wl.E, wl.K, wl.N, wl.tile_m, wl.tile_n,
                        None if xs is None else xs.to(dev), None if ws is None else ws.to(dev),
-                       tile_m_slack=slack, epilogue=mb.MOE_EPILOGUE_SWIGLU)
+                       tile_m_slack=slack, epilogue=mb.MOE_EPILOGUE_SWIGLU, launch_mode=launch_mode)
     mb.moe_grouped_gemm(X.to(dev), W.to(dev), ids.to(dev), tmap, Y, desc)
     torch.cuda.synchronize()
     allbits = buf.cpu().numpy().view(np.uint16)
@@ -268,16 +269,12 @@ def test_streaming_kernel_parity(dev, oracle_mod, dtype, tile_n, T, E, k, K, N, 
     else:
         X, W = wk.make_x(wl), wk.make_w(wl) * (4.0 if swiglu else 1.0)
     outs = []
-    try:
-        for mode in (wgs, 1):
-            mb.moe_debug_streaming(mode)
-            if swiglu:
-                outs.append(_run_swiglu(dev, wl, ids, X, W, xs, ws))
-            else:
-                from tests.test_gpu_parity import _run_gemm
-                outs.append(_run_gemm(dev, wl, ids, X, W, xs, ws))
-    finally:
-        mb.moe_debug_streaming(0)
+    for mode in (wgs, mb.MOE_LAUNCH_PER_TILE):
+        if swiglu:
+            outs.append(_run_swiglu(dev, wl, ids, X, W, xs, ws, launch_mode=mode))
+        else:
+            from tests.test_gpu_parity import _run_gemm
+            outs.append(_run_gemm(dev, wl, ids, X, W, xs, ws, launch_mode=mode))
     np.testing.assert_array_equal(outs[0], outs[1])
     if dtype == "fp8":
         res = oracle_mod.grouped_gemm_fp8(wk.bits(X), wk.bits(W), xs.numpy(), ws.numpy(), ids.numpy())
@@ -381,7 +378,7 @@ def test_mfma_probe_runs(dev):
     sink = torch.zeros(4, dtype=torch.float32, device=dev)
     for block in (16, 32):
         for rnd in (False, True):
-            assert mb.moe_debug_mfma_probe(block, rnd, 50, sink) == mb.MOE_OK
+            assert probe.moe_probe_mfma(block, rnd, 50, sink) == mb.MOE_OK
     torch.cuda.synchronize()
     assert float(sink.abs().sum()) == 0.0
 
@@ -393,8 +390,8 @@ def test_pipeline_probe_runs(dev):
     before = src[: 1 << 20].clone()
     sink = torch.zeros(4, dtype=torch.float32, device=dev)
     for mode in range(1, 9):
-        assert mb.moe_debug_pipeline_probe(mode, 64, src, sink) == mb.MOE_OK
-    assert mb.moe_debug_pipeline_probe(4, 64, src[: 1 << 20], sink, check=False) == mb.MOE_ERR_INVALID_ARG
+        assert probe.moe_probe_pipeline(mode, 64, src, sink) == mb.MOE_OK
+    assert probe.moe_probe_pipeline(4, 64, src[: 1 << 20], sink) == mb.MOE_ERR_INVALID_ARG
     torch.cuda.synchronize()
     assert torch.equal(src[: 1 << 20], before)
 
@@ -478,6 +475,51 @@ def test_splitk_invalid_map_and_empty_input_are_noops(dev):
     assert bool((Y == POISON).all()) and bool((ws == 7.0).all())
     d0 = mb.GemmDesc(mb.MOE_DTYPE_BF16, 0, 1, E, K, N, 256, 256)
     assert mb.moe_grouped_gemm_splitk(None, None, None, None, d0, 2, None, check=False) == mb.MOE_OK
+
+
+def test_splitk_mismatched_map_is_a_noop(dev):
+    """A valid map that was built for another problem (other T, other N, other tiling, slack rows) or a blob that is
+    no map at all: neither the product nor the reduction of the split-k call may touch Y, and the reduction must not
+    follow row ids it has no reason to trust."""
+    T, E, K, N = 300, 4, 1024, 256
+    X = torch.ones((T, K), dtype=torch.bfloat16, device=dev)
+    W = torch.ones((E, K, N), dtype=torch.bfloat16, device=dev)
+    pad = 4
+    buf = torch.full((T + 2 * pad, N), POISON, dtype=torch.int16, device=dev)
+    Y = buf[pad: pad + T]
+    g = torch.Generator().manual_seed(3)
+    ids = torch.randint(0, E, (T, 1), generator=g, dtype=torch.int32).to(dev)
+    ws = torch.full((2 * T * N,), 7.0, dtype=torch.float32, device=dev)
+    d = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 256, 256)
+    maps = []
+    # built for more tokens (its row ids reach past this call's Y), for another width, another tiling, with slack rows
+    big = mb.alloc_task_map(4 * T, 1, E, 256, 256, N)
+    ids_big = torch.randint(0, E, (4 * T, 1), generator=g, dtype=torch.int32).to(dev)
+    mb.moe_build_task_map(ids_big, 4 * T, 1, E, 256, 256, N, big)
+    maps.append(big)
+    m = mb.alloc_task_map(T, 1, E, 256, 256, 2 * N)
+    mb.moe_build_task_map(ids, T, 1, E, 256, 256, 2 * N, m)
+    maps.append(m)
+    m = mb.alloc_task_map(T, 1, E, 128, 256, N)
+    mb.moe_build_task_map(ids, T, 1, E, 128, 256, N, m)
+    maps.append(m)
+    m = mb.alloc_task_map(T, 1, E, 256, 256, N)
+    mb.moe_build_task_map_ex(ids, T, 1, E, N, mb.Tiling(256, 256, 0, 0, 0, 32), m)
+    maps.append(m)
+    junk = torch.randint(0, 2 ** 20, (big.numel(),), generator=g, dtype=torch.int32).to(dev)   # not a map: no magic word
+    maps.append(junk)
+    for tmap in maps:
+        assert mb.moe_grouped_gemm_splitk(X, W, tmap, Y, d, 2, ws, check=False) == mb.MOE_OK
+        torch.cuda.synchronize()
+        assert bool((buf == POISON).all()), "a mismatched map made the split-k call write"
+        assert bool((ws == 7.0).all())
+    # the matching map still works
+    m = mb.alloc_task_map(T, 1, E, 256, 256, N)
+    mb.moe_build_task_map(ids, T, 1, E, 256, 256, N, m)
+    mb.moe_grouped_gemm_splitk(X, W, m, Y, d, 2, ws)
+    torch.cuda.synchronize()
+    assert bool((buf[:pad] == POISON).all()) and bool((buf[pad + T:] == POISON).all())
+    assert bool((Y.view(torch.bfloat16) == float(K)).all())
 
 
 LAYER_CASES = [

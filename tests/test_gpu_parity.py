@@ -135,7 +135,7 @@ def test_argument_errors(dev):
     assert bool(torch.isnan(Y).all())
 
 
-def _run_gemm(dev, wl, ids, X, W, xs=None, ws=None, order=0, small=0, thr=0, slack=0):
+def _run_gemm(dev, wl, ids, X, W, xs=None, ws=None, order=0, small=0, thr=0, slack=0, launch_mode=0):
     """Run map build + GEMM with Y embedded between poisoned canary rows; returns Y bits [R,N]."""
     R, N = wl.R, wl.N
     pad = 4
@@ -145,7 +145,8 @@ def _run_gemm(dev, wl, ids, X, W, xs=None, ws=None, order=0, small=0, thr=0, sla
     tmap = _build_map(ids.to(dev), wl.T, wl.k, wl.E, wl.tile_m, wl.tile_n, N, order, small, thr, slack)
     dt = mb.MOE_DTYPE_FP8_E4M3 if wl.dtype == "fp8" else mb.MOE_DTYPE_BF16
     desc = mb.GemmDesc(dt, wl.T, wl.k, wl.E, wl.K, N, wl.tile_m, wl.tile_n,
-                       None if xs is None else xs.to(dev), None if ws is None else ws.to(dev), small, thr, slack)
+                       None if xs is None else xs.to(dev), None if ws is None else ws.to(dev), small, thr, slack,
+                       launch_mode=launch_mode)
     mb.moe_grouped_gemm(X.to(dev), W.to(dev), ids.to(dev), tmap, Y, desc)
     torch.cuda.synchronize()
     assert mb.moe_task_map_status(tmap) == mb.MOE_OK

@@ -73,13 +73,9 @@ def test_random_case(oracle_mod, seed):
     np.testing.assert_array_equal(tmap.cpu().numpy()[: len(want)], want)
     desc = mb.GemmDesc(dt, T, k, E, K, N, tile_m, tile_n, None if xs is None else xs.to(dev), None if ws is None else ws.to(dev),
                        tile_m_slack=opt["slack"], epilogue=mb.MOE_EPILOGUE_SWIGLU if opt["swiglu"] else mb.MOE_EPILOGUE_NONE,
-                       w_layout=mb.MOE_W_LAYOUT_NK if opt["nk"] else mb.MOE_W_LAYOUT_KN)
-    try:
-        mb.moe_debug_streaming(opt["stream"])
-        mb.moe_grouped_gemm(X.to(dev), Wd, ids.to(dev), tmap, Y, desc)
-        torch.cuda.synchronize()
-    finally:
-        mb.moe_debug_streaming(0)
+                       w_layout=mb.MOE_W_LAYOUT_NK if opt["nk"] else mb.MOE_W_LAYOUT_KN, launch_mode=opt["stream"])
+    mb.moe_grouped_gemm(X.to(dev), Wd, ids.to(dev), tmap, Y, desc)
+    torch.cuda.synchronize()
     allbits = buf.cpu().numpy().view(np.uint16)
     assert np.all(allbits[:pad] == POISON) and np.all(allbits[pad + R:] == POISON), "wrote outside Y"
     got = allbits[pad: pad + R]
