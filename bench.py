@@ -487,21 +487,28 @@ def main():
         del src
         out["mfma_probe"] = res
     if args.dense_reference:
+        # the tensor library's dense GEMM of the same size: with the weight stored as here ([K, N], N contiguous) and
+        # with a K-contiguous weight ([N, K], the layout linear layers are usually stored in)
         A = torch.randn((wl.R, wl.K), device="cuda:0").to(torch.bfloat16)
-        B = torch.randn((wl.K, wl.N), device="cuda:0").to(torch.bfloat16)
-        for _ in range(3):
-            C = A @ B
-        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-        torch.cuda.synchronize()
-        ev[0].record()
-        for _ in range(10):
-            C = A @ B
-        ev[1].record()
-        torch.cuda.synchronize()
-        d_ms = ev[0].elapsed_time(ev[1]) / 10
-        del A, B, C
-        out["dense_reference"] = {"what": f"torch.matmul bf16 [{wl.R},{wl.K}] x [{wl.K},{wl.N}] row-major, random data",
-                                  "ms": round(d_ms, 4), "tflops": round(wl.flops / (d_ms * 1e-3) / 1e12, 2)}
+        ref = []
+        for layout in ("KN", "NK"):
+            B = torch.randn((wl.K, wl.N) if layout == "KN" else (wl.N, wl.K), device="cuda:0").to(torch.bfloat16)
+            Bm = B if layout == "KN" else B.t()
+            for _ in range(3):
+                C = A @ Bm
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+            torch.cuda.synchronize()
+            ev[0].record()
+            for _ in range(10):
+                C = A @ Bm
+            ev[1].record()
+            torch.cuda.synchronize()
+            d_ms = ev[0].elapsed_time(ev[1]) / 10
+            ref.append({"what": f"torch.matmul bf16 [{wl.R},{wl.K}] x weight stored [{'K,N' if layout == 'KN' else 'N,K'}], random data",
+                        "ms": round(d_ms, 4), "tflops": round(wl.flops / (d_ms * 1e-3) / 1e12, 2)})
+            del B, Bm, C
+        del A
+        out["dense_reference"] = ref
     del pt
     torch.cuda.empty_cache()
     if not args.no_decode:

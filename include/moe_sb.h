@@ -33,7 +33,8 @@ enum {
     MOE_ERR_INVALID_ARG = -1, /* null pointer, negative size, k > E, misaligned pointer */
     MOE_ERR_UNSUPPORTED = -2, /* tile shape / dtype / divisibility the kernels do not cover */
     MOE_ERR_ROUTING = -3,     /* a routing id outside [0,E) was found on the device */
-    MOE_ERR_HIP = -4          /* a HIP runtime call failed */
+    MOE_ERR_HIP = -4,         /* a HIP runtime call failed */
+    MOE_ERR_TOO_LARGE = -5    /* the problem needs more scratch memory than the library's static array holds */
 };
 
 enum { MOE_DTYPE_BF16 = 0, MOE_DTYPE_FP8_E4M3 = 1 };
@@ -303,6 +304,25 @@ int moe_grouped_gemm(const void* X, const void* W, const int32_t* topk_ids, cons
  */
 int moe_grouped_gemm_splitk(const void* X, const void* W, const void* task_map, void* Y, const moe_gemm_desc* desc,
                             int k_parts, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * moe_grouped_gemm_splitk for callers that cannot allocate device memory and have no workspace to hand in: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (without the
+ * workspace), same kernels, same results bit for bit; the fp32 partial sums go to a static device array inside the
+ * library instead: moe_splitk_static_scratch_bytes() = 32 MiB per GPU, held by every GPU the library runs on until
+ * the process ends.  The call allocates and frees nothing (its first call on a device looks the array's address up).
+ *   - MOE_ERR_TOO_LARGE when moe_splitk_workspace_bytes(T, k, N, k_parts) exceeds the array (nothing is enqueued);
+ *     all other errors as for moe_grouped_gemm_splitk.
+ *   - All calls on one GPU share that GPU's array, which keeps the last call's contents.  Nothing in it has to start
+ *     at zero: every partial sum the reduction reads was written by the product launch of the same call.  Calls that
+ *     may overlap on one GPU (different streams without ordering, several host threads) race on it: order them, or
+ *     use moe_grouped_gemm_splitk with a workspace each.
+ */
+int moe_grouped_gemm_splitk_static(const void* X, const void* W, const void* task_map, void* Y,
+                                   const moe_gemm_desc* desc, int k_parts, void* stream);
+
+/* Size of that static array in bytes.  HOST, pure. */
+size_t moe_splitk_static_scratch_bytes(void);
 
 /* Bytes of workspace moe_grouped_gemm_splitk needs (0 for k_parts < 2 or bad sizes).  HOST, pure. */
 size_t moe_splitk_workspace_bytes(int T, int k, int N, int k_parts);

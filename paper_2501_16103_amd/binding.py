@@ -23,6 +23,7 @@ MOE_ERR_INVALID_ARG = -1
 MOE_ERR_UNSUPPORTED = -2
 MOE_ERR_ROUTING = -3
 MOE_ERR_HIP = -4
+MOE_ERR_TOO_LARGE = -5
 MOE_DTYPE_BF16 = 0
 MOE_DTYPE_FP8_E4M3 = 1
 MOE_W_LAYOUT_KN = 0
@@ -48,6 +49,7 @@ EXPORTS = [
     "moe_build_task_map_ex", "moe_tiling_supported", "moe_w_layout_supported", "moe_default_tiling",
     "moe_task_map_status", "moe_task_map_expand", "moe_grouped_gemm", "moe_tile_supported", "moe_combine",
     "moe_grouped_gemm_splitk", "moe_splitk_workspace_bytes", "moe_default_k_parts",
+    "moe_grouped_gemm_splitk_static", "moe_splitk_static_scratch_bytes",
     "moe_strerror",
 ]
 
@@ -125,6 +127,11 @@ def lib() -> ctypes.CDLL:
         L.moe_grouped_gemm_splitk.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                               ctypes.POINTER(moe_gemm_desc), ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t,
                                               ctypes.c_void_p]
+        L.moe_grouped_gemm_splitk_static.restype = ctypes.c_int
+        L.moe_grouped_gemm_splitk_static.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                                     ctypes.POINTER(moe_gemm_desc), ctypes.c_int, ctypes.c_void_p]
+        L.moe_splitk_static_scratch_bytes.restype = ctypes.c_size_t
+        L.moe_splitk_static_scratch_bytes.argtypes = []
         L.moe_splitk_workspace_bytes.restype = ctypes.c_size_t
         L.moe_splitk_workspace_bytes.argtypes = [ctypes.c_int] * 4
         L.moe_default_k_parts.restype = ctypes.c_int
@@ -324,6 +331,21 @@ def moe_grouped_gemm_splitk(X: torch.Tensor, W: torch.Tensor, task_map: torch.Te
                                        _ptr(workspace), ctypes.c_size_t(nbytes), _stream() if X is not None else None)
     if check and rc != MOE_OK:
         raise MoeError(rc, "moe_grouped_gemm_splitk")
+    return rc
+
+
+def moe_splitk_static_scratch_bytes() -> int:
+    return int(lib().moe_splitk_static_scratch_bytes())
+
+
+def moe_grouped_gemm_splitk_static(X: torch.Tensor, W: torch.Tensor, task_map: torch.Tensor, Y: torch.Tensor,
+                                   desc: "GemmDesc", k_parts: int, check: bool = True) -> int:
+    """moe_grouped_gemm_splitk without a workspace: the partial sums go to the library's static device array."""
+    c = desc.c_struct()
+    rc = lib().moe_grouped_gemm_splitk_static(_ptr(X), _ptr(W), _ptr(task_map), _ptr(Y), ctypes.byref(c), int(k_parts),
+                                              _stream() if X is not None else None)
+    if check and rc != MOE_OK:
+        raise MoeError(rc, "moe_grouped_gemm_splitk_static")
     return rc
 
 

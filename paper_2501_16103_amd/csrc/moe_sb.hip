@@ -13,6 +13,12 @@
 
 using namespace moe;
 
+// Scratch memory of moe_grouped_gemm_splitk_static, the entry point for callers that cannot allocate: the fp32
+// partial sums of a split-k product.  One copy per GPU, held until the process ends; host code reaches it only
+// through the pointer hipGetSymbolAddress returns for the current device (static_scratch below).
+constexpr size_t kStaticScratchBytes = size_t(32) << 20;
+static __device__ __align__(256) float scratch[kStaticScratchBytes / sizeof(float)];
+
 namespace {
 
 bool tile_m_ok(int v) { return v == 16 || v == 32 || v == 64 || v == 128 || v == 256; }
@@ -220,6 +226,64 @@ int check_small_args(int tile_m, int tile_m_small, int small_max_rows, int tile_
     if (tile_m_small != 16 && tile_m_small != 32 && tile_m_small != 64 && tile_m_small != 128) return MOE_ERR_UNSUPPORTED;
     if (tile_m_small >= tile_m) return MOE_ERR_INVALID_ARG;
     if (small_max_rows < 1 || small_max_rows > 4 * tile_m_small) return MOE_ERR_INVALID_ARG;
+    return MOE_OK;
+}
+
+// ---- split-k: shared by the entry point that takes a workspace and by the one that allocates nothing
+
+int check_splitk_args(const moe_gemm_desc* d, int k_parts) {
+    if (!d) return MOE_ERR_INVALID_ARG;
+    if (d->T < 0 || d->k < 1 || d->E < 1 || d->E > kMaxE || d->k > d->E || d->K < 1 || d->N < 1) return MOE_ERR_INVALID_ARG;
+    if (d->dtype != MOE_DTYPE_BF16 || d->w_layout != MOE_W_LAYOUT_KN || d->epilogue != MOE_EPILOGUE_NONE ||
+        d->tile_m != 256 || d->tile_n != 256 || d->tile_m_small != 0 || d->small_max_rows != 0 || d->tile_m_slack != 0)
+        return MOE_ERR_UNSUPPORTED;
+    if (k_parts != 2 && k_parts != 4) return MOE_ERR_UNSUPPORTED;
+    if (d->K % 64 != 0 || (d->K / 64) % k_parts != 0 || d->K / 64 / k_parts < 8 || d->N % 256 != 0) return MOE_ERR_UNSUPPORTED;
+    return MOE_OK;
+}
+
+// The two launches of a split-k product (arguments already checked by check_splitk_args, T > 0): the product with
+// k_parts workgroups per tile leaves fp32 partial sums in `ws`, the reduction adds them and scatters.
+int run_splitk(const void* X, const void* W, const void* task_map, void* Y, const moe_gemm_desc* d, int k_parts, float* ws,
+               hipStream_t s) {
+    if (!X || !W || !task_map || !Y || !ws) return MOE_ERR_INVALID_ARG;
+    if (((uintptr_t)X & 15) || ((uintptr_t)W & 15) || ((uintptr_t)Y & 15) || ((uintptr_t)task_map & 15)) return MOE_ERR_INVALID_ARG;
+    GemmArgs a{};
+    a.X = X; a.W = W; a.map = static_cast<const int32_t*>(task_map); a.Y = Y;
+    a.T = d->T; a.k = d->k; a.E = d->E; a.K = d->K; a.N = d->N;
+    a.tile_m_slack = d->tile_m_slack;
+    a.partial = ws;
+    int64_t grid = moe_grid_upper_bound_tiled(d->T, d->k, d->E, 256, 256, d->N, 0, 0);
+    if (grid == 0) return MOE_OK;
+    grid = (grid + 7) / 8 * 8 + 8;
+    if (grid > 0x7fffffff) return MOE_ERR_UNSUPPORTED;
+    const int rc = launch_splitk<Pb_256x256, Ps_64x256, Ps_128x256>(a, grid, k_parts, s);
+    if (rc != MOE_OK) return rc;
+    const int64_t R = (int64_t)d->T * d->k;
+    const long long chunks = (long long)R * (d->N / 8);
+    long long blocks = (chunks + 255) / 256;
+    if (blocks > 256 * 64) blocks = 256 * 64;
+    const MapLayout L = map_layout(d->E);
+    moe_splitk_reduce_kernel<<<(unsigned)blocks, 256, 0, s>>>(a.partial, a.map, a.map + L.off_rows, static_cast<u32x4_t*>(Y), d->T,
+                                                             d->k, d->E, d->N, k_parts);
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
+// This device's address of the static scratch array, looked up once per device (with that device current) and
+// kept: every GPU the library runs on holds its own copy of the array at its own address.  In host code the
+// array's name is only a handle for this lookup, never a device address.
+int static_scratch(float** out) {
+    static float* ptr_of_device[64] = {};
+    std::lock_guard<std::mutex> hold(g_attr_lock);
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return MOE_ERR_HIP;
+    if (dev < 0 || dev >= 64) return MOE_ERR_UNSUPPORTED;
+    if (!ptr_of_device[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return MOE_ERR_HIP;
+        ptr_of_device[dev] = static_cast<float*>(p);
+    }
+    *out = ptr_of_device[dev];
     return MOE_OK;
 }
 
@@ -496,37 +560,26 @@ int moe_default_k_parts(int T, int k, int E, int K, int N) {
 
 int moe_grouped_gemm_splitk(const void* X, const void* W, const void* task_map, void* Y, const moe_gemm_desc* d,
                             int k_parts, void* workspace, size_t workspace_bytes, void* stream) {
-    if (!d) return MOE_ERR_INVALID_ARG;
-    if (d->T < 0 || d->k < 1 || d->E < 1 || d->E > kMaxE || d->k > d->E || d->K < 1 || d->N < 1) return MOE_ERR_INVALID_ARG;
-    if (d->dtype != MOE_DTYPE_BF16 || d->w_layout != MOE_W_LAYOUT_KN || d->epilogue != MOE_EPILOGUE_NONE ||
-        d->tile_m != 256 || d->tile_n != 256 || d->tile_m_small != 0 || d->small_max_rows != 0 || d->tile_m_slack != 0)
-        return MOE_ERR_UNSUPPORTED;
-    if (k_parts != 2 && k_parts != 4) return MOE_ERR_UNSUPPORTED;
-    if (d->K % 64 != 0 || (d->K / 64) % k_parts != 0 || d->K / 64 / k_parts < 8 || d->N % 256 != 0) return MOE_ERR_UNSUPPORTED;
-    if (d->T == 0) return MOE_OK;
-    if (!X || !W || !task_map || !Y || !workspace) return MOE_ERR_INVALID_ARG;
-    if (((uintptr_t)X & 15) || ((uintptr_t)W & 15) || ((uintptr_t)Y & 15) || ((uintptr_t)workspace & 15)) return MOE_ERR_INVALID_ARG;
-    if (workspace_bytes < moe_splitk_workspace_bytes(d->T, d->k, d->N, k_parts)) return MOE_ERR_INVALID_ARG;
-    GemmArgs a{};
-    a.X = X; a.W = W; a.map = static_cast<const int32_t*>(task_map); a.Y = Y;
-    a.T = d->T; a.k = d->k; a.E = d->E; a.K = d->K; a.N = d->N;
-    a.tile_m_slack = d->tile_m_slack;
-    a.partial = static_cast<float*>(workspace);
-    int64_t grid = moe_grid_upper_bound_tiled(d->T, d->k, d->E, 256, 256, d->N, 0, 0);
-    if (grid == 0) return MOE_OK;
-    grid = (grid + 7) / 8 * 8 + 8;
-    if (grid > 0x7fffffff) return MOE_ERR_UNSUPPORTED;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const int rc = launch_splitk<Pb_256x256, Ps_64x256, Ps_128x256>(a, grid, k_parts, s);
+    const int rc = check_splitk_args(d, k_parts);
     if (rc != MOE_OK) return rc;
-    const int64_t R = (int64_t)d->T * d->k;
-    const long long chunks = (long long)R * (d->N / 8);
-    long long blocks = (chunks + 255) / 256;
-    if (blocks > 256 * 64) blocks = 256 * 64;
-    const MapLayout L = map_layout(d->E);
-    moe_splitk_reduce_kernel<<<(unsigned)blocks, 256, 0, s>>>(a.partial, a.map, a.map + L.off_rows, static_cast<u32x4_t*>(Y), d->T,
-                                                             d->k, d->E, d->N, k_parts);
-    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+    if (d->T == 0) return MOE_OK;
+    if (!workspace || ((uintptr_t)workspace & 15)) return MOE_ERR_INVALID_ARG;
+    if (workspace_bytes < moe_splitk_workspace_bytes(d->T, d->k, d->N, k_parts)) return MOE_ERR_INVALID_ARG;
+    return run_splitk(X, W, task_map, Y, d, k_parts, static_cast<float*>(workspace), static_cast<hipStream_t>(stream));
+}
+
+size_t moe_splitk_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int moe_grouped_gemm_splitk_static(const void* X, const void* W, const void* task_map, void* Y, const moe_gemm_desc* d,
+                                   int k_parts, void* stream) {
+    const int rc = check_splitk_args(d, k_parts);
+    if (rc != MOE_OK) return rc;
+    if (moe_splitk_workspace_bytes(d->T, d->k, d->N, k_parts) > kStaticScratchBytes) return MOE_ERR_TOO_LARGE;
+    if (d->T == 0) return MOE_OK;
+    float* ws = nullptr;
+    const int rs = static_scratch(&ws);
+    if (rs != MOE_OK) return rs;
+    return run_splitk(X, W, task_map, Y, d, k_parts, ws, static_cast<hipStream_t>(stream));
 }
 
 int moe_combine(const void* Y, const float* topk_weights, int T, int k, int N, void* out, void* stream) {
@@ -558,6 +611,7 @@ const char* moe_strerror(int code) {
         case MOE_ERR_UNSUPPORTED: return "unsupported size, tile shape or dtype";
         case MOE_ERR_ROUTING: return "routing id outside [0, E)";
         case MOE_ERR_HIP: return "HIP runtime error";
+        case MOE_ERR_TOO_LARGE: return "problem needs more scratch memory than the library's static array holds";
         default: return "unknown error";
     }
 }

@@ -27,6 +27,19 @@ def test_library_exports_every_declared_symbol():
     assert sorted(mb.EXPORTS) == names
 
 
+def test_probe_library_exports_every_declared_symbol():
+    """include/moe_probe.h: the measurement kernels live in a library of their own."""
+    from paper_2501_16103_amd import probe
+    text = open(os.path.join(ROOT, "include", "moe_probe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = sorted(set(re.findall(r"\b(moe_probe_[a-z0-9_]+)\s*\(", text)))
+    assert names == sorted(probe.EXPORTS)
+    for n in names:
+        assert hasattr(probe.lib(), n)
+    for n in names:
+        assert not hasattr(mb.lib(), n), "the product library must not export measurement kernels"
+
+
 def test_host_only_entry_points():
     assert mb.moe_task_map_bytes(-1, 2, 8, 16, 128, 256) == 0
     assert mb.moe_task_map_bytes(4, 9, 8, 16, 128, 256) == 0        # k > E
