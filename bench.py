@@ -63,7 +63,7 @@ class Point:
     """Device buffers of one workload (optionally several weight copies to defeat the caches)."""
 
     def __init__(self, wl: wk.Workload, copies: int = 1, dev="cuda:0", order: int = 0, small=(0, 0), swiglu: bool = False,
-                 w_nk: bool = False):
+                 w_nk: bool = False, launch_mode: int = 0):
         self.wl = wl
         self.w_nk = w_nk      # weights pre-packed as [E][N][K] (a labelled extra, never the headline)
         self.swiglu = swiglu  # fused gated activation: Y is [R, N/2]
@@ -94,7 +94,8 @@ class Point:
         dt = mb.MOE_DTYPE_FP8_E4M3 if wl.dtype == "fp8" else mb.MOE_DTYPE_BF16
         self.desc = mb.GemmDesc(dt, wl.T, wl.k, wl.E, wl.K, wl.N, wl.tile_m, wl.tile_n, self.xs, self.ws, *small, self.slack,
                                 mb.MOE_EPILOGUE_SWIGLU if swiglu else mb.MOE_EPILOGUE_NONE,
-                                mb.MOE_W_LAYOUT_NK if w_nk else mb.MOE_W_LAYOUT_KN)
+                                mb.MOE_W_LAYOUT_NK if w_nk else mb.MOE_W_LAYOUT_KN, launch_mode)
+        self.launch_mode = launch_mode
         self.tiling = mb.Tiling(wl.tile_m, wl.tile_n, order, small[0], small[1], self.slack)
 
     def build_map(self):
@@ -190,6 +191,7 @@ class Point:
                     map_ms=round(map_ms, 4), tflops_step=round(tf_step, 2), tflops_gemm=round(tf_gemm, 2),
                     frac_mfma=round(tf_gemm / peak_t, 4), gbs_gemm=round(gbs, 1),
                     frac_hbm=round(gbs / PEAK_HBM_GBS, 4), bound=bound, alg_bytes=abytes, flops=wl.flops,
+                    launch_mode=self.launch_mode,
                     kernel="moe_gemm_pipe_kernel")
 
 
@@ -365,6 +367,10 @@ def main():
     ap.add_argument("--small", default="0,0",
                     help="tile_m_small,small_max_rows: second tiling strategy for the extra points with 256x256 tiles")
     ap.add_argument("--slack", type=int, default=-1, help="override tile_m_slack of every workload (0 = plain ceil tiling)")
+    ap.add_argument("--launch-mode", type=int, default=-1,
+                    help="moe_gemm_desc.launch_mode of every point: 0 the library's choice, 1 one workgroup per tile, "
+                         "2 resident workgroups where a kernel exists, >= 8 resident with at most that many workgroups "
+                         "(default: each point's own default)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-decode", action="store_true", help="skip the fp8 decode points (roofline_hbm)")
     ap.add_argument("--operand-fill", default="", choices=["", "zeros", "ones"],
@@ -396,7 +402,8 @@ def main():
         wl = wl.with_T(wl.T, tile_m=tm, tile_n=tn, tile_m_slack=0)
     if args.slack >= 0:
         wl = wl.with_T(wl.T, tile_m_slack=args.slack)
-    pt = Point(wl)
+    lm = max(0, args.launch_mode)
+    pt = Point(wl, launch_mode=lm)
     head = pt.report(args.steps, args.warmup)
     traffic, traffic_from = measured_traffic(HEADLINE) if wl == wk.mixtral_up(4096) else (None, None)
     out = {
@@ -405,7 +412,8 @@ def main():
         "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": HEADLINE, "T": wl.T, "E": wl.E, "top_k": wl.k, "K": wl.K, "N": wl.N,
-                   "tile_m": wl.tile_m, "tile_n": wl.tile_n, "tile_m_slack": wl.tile_m_slack, "routing": wl.routing},
+                   "tile_m": wl.tile_m, "tile_n": wl.tile_n, "tile_m_slack": wl.tile_m_slack, "routing": wl.routing,
+                   "launch_mode": lm},
         "roofline": {"bound": "mfma", "achieved": head["tflops_gemm"], "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(head["tflops_gemm"] / PEAK_BF16_TFLOPS, 4),
                      "traffic": traffic, "traffic_source": traffic_from,
@@ -531,7 +539,7 @@ def main():
             if small[0] and not (w.dtype == "bf16" and mb.moe_tile_pair_supported(mb.MOE_DTYPE_BF16, w.tile_m, w.tile_n, small[0])):
                 small = (0, 0)
             for order in {"both": [0, 1], "all": [0, 1, 2], "spread": [1], "interleave": [2]}.get(args.order, [0]):
-                p = Point(w, copies, order=order, small=small)
+                p = Point(w, copies, order=order, small=small, launch_mode=lm)
                 points.append(p.report(max(10, args.steps // 2), max(3, args.warmup // 2)))
                 del p
                 torch.cuda.empty_cache()

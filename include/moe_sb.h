@@ -257,8 +257,8 @@ typedef struct moe_gemm_desc {
  *                        tiles per resident workgroup, else one workgroup per tile
  *   MOE_LAUNCH_PER_TILE  always one workgroup per tile
  *   MOE_LAUNCH_RESIDENT  resident workgroups (each runs a contiguous share of its XCD's tiles back to back) wherever
- *                        a kernel for that exists: 16-row tiles with E <= 256 (fp8: T + E <= 2048), and the bf16
- *                        256 x 256 tiles; elsewhere the same as MOE_LAUNCH_PER_TILE
+ *                        a kernel for that exists: 16-row tiles with E <= 256 (fp8: T + E <= 2048); elsewhere the
+ *                        same as MOE_LAUNCH_PER_TILE
  *   a value >= 8         MOE_LAUNCH_RESIDENT with at most that many workgroups (rounded down to a multiple of 8)
  */
 enum { MOE_LAUNCH_AUTO = 0, MOE_LAUNCH_PER_TILE = 1, MOE_LAUNCH_RESIDENT = 2 };

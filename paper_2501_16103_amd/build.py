@@ -40,10 +40,21 @@ def check_no_spill_in_k_loops(asm_text: str) -> None:
         lines = asm_text[m.end():end].splitlines()
         label_at = {ln.split(":")[0]: k for k, ln in enumerate(lines) if ln.startswith(".LBB")}
         loops = []   # (first line, last line) of every backward branch's span
+
+        def exits(k):   # the block at line k does nothing but end the program (an early-placed exit, not a loop head)
+            for ln in lines[k + 1:]:
+                ln = ln.strip()
+                if ln and not ln.startswith(";"):
+                    return ln.startswith("s_endpgm")
+            return False
+
         for k, ln in enumerate(lines):
             b = re.search(r"s_cbranch\w*\s+(\.LBB\d+_\d+)", ln)
-            if b and label_at.get(b.group(1), len(lines)) < k:
+            if b and label_at.get(b.group(1), len(lines)) < k and not exits(label_at[b.group(1)]):
                 loops.append((label_at[b.group(1)], k))
+        def mfmas(lo, hi):
+            return sum("v_mfma" in lines[x] for x in range(lo, hi + 1))
+
         for k, ln in enumerate(lines):
             if "scratch_" not in ln:
                 continue
@@ -52,6 +63,13 @@ def check_no_spill_in_k_loops(asm_text: str) -> None:
                 continue
             lo, hi = min(around, key=lambda lp: lp[1] - lp[0])          # the innermost loop around the access
             inner = [lp for lp in loops if lo <= lp[0] and lp[1] <= hi and lp != (lo, hi)]
+            if any(mfmas(a, b) >= 16 for a, b in inner):
+                # a loop over tiles (resident kernels) with the k loops inside it: a reload between two tiles costs
+                # its own time only -- unless it sits in the middle of a straight run of MFMAs (the unrolled last
+                # iterations of a tile, which still have DMAs in flight)
+                if mfmas(max(lo, k - 40), k) >= 8 and mfmas(k, min(hi, k + 40)) >= 8:
+                    raise RuntimeError(f"{name}: register spill among the MFMAs of a tile's last iterations")
+                continue
             own = sum("v_mfma" in lines[x] for x in range(lo, hi + 1) if not any(a <= x <= b for a, b in inner))
             if own >= 16:
                 raise RuntimeError(f"{name}: register spill inside a k loop (it would drain the DMA ring every iteration)")
