@@ -78,6 +78,7 @@ __global__ void __launch_bounds__(512) mfma_probe_kernel(int iters, float* sink)
 //   MODE 4: as 3, but half of the bytes come from lines not touched before (a new 32 KB chunk of `src` per k-tile,
 //           shared by two workgroups), about the weight traffic the real kernel draws from HBM
 //   MODE 5-8: no MFMAs, the LDS pipe alone: the 16-byte reads, the transposing reads, both, the DMA writes
+//   MODE 9: no MFMAs, both kinds of reads AND the DMA writes together (do they share the LDS pipe's time or overlap?)
 // `src`: at least 1 MB (MODE 4: 513 MB) of device memory; its first 64 KB fill the LDS region the fragments are
 // read from, so bf16 values there make the operands realistic.  Per loop trip (two k-steps) and wavefront 1 MFLOP.
 template <int MODE>
@@ -138,19 +139,19 @@ __global__ void __launch_bounds__(512) pipeline_probe_kernel(int iters, const ch
         for (int it = 0; it < iters; it += 2) {
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                if (MODE <= 7) load(h, it + h);
-                if (MODE == 5 || MODE == 7) {
+                if (MODE <= 7 || MODE == 9) load(h, it + h);
+                if (MODE == 5 || MODE == 7 || MODE == 9) {
 #pragma unroll
                     for (int i = 0; i < MB; ++i) asm volatile("" ::"v"(xq[h][i]));
                 }
-                if (MODE == 6 || MODE == 7) {
+                if (MODE == 6 || MODE == 7 || MODE == 9) {
 #pragma unroll
                     for (int j = 0; j < NB; ++j) asm volatile("" ::"v"(wq[h][j][0]), "v"(wq[h][j][1]));
                 }
-                if (MODE == 8) { dmas(it, h); wait_vmcnt<4>(); }
+                if (MODE == 8 || MODE == 9) { dmas(it, h); wait_vmcnt<4>(); }
             }
         }
-        if (MODE == 8) wait_vmcnt<0>();
+        if (MODE == 8 || MODE == 9) wait_vmcnt<0>();
         if (iters < 0) sink[0] = 0.f;
         return;
     }

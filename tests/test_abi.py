@@ -107,7 +107,7 @@ def test_pipeline_probe_rejects_bad_arguments_before_any_launch():
     lib = probe.lib()
     big, small = ctypes.c_size_t(513 << 20), ctypes.c_size_t(1 << 20)
     assert lib.moe_probe_pipeline(0, 10, 16, big, 16, None) == mb.MOE_ERR_INVALID_ARG     # no such mode
-    assert lib.moe_probe_pipeline(9, 10, 16, big, 16, None) == mb.MOE_ERR_INVALID_ARG
+    assert lib.moe_probe_pipeline(10, 10, 16, big, 16, None) == mb.MOE_ERR_INVALID_ARG
     assert lib.moe_probe_pipeline(1, 11, 16, big, 16, None) == mb.MOE_ERR_INVALID_ARG     # odd k-step count
     assert lib.moe_probe_pipeline(1, 0, 16, big, 16, None) == mb.MOE_ERR_INVALID_ARG
     assert lib.moe_probe_pipeline(1, 10, None, big, 16, None) == mb.MOE_ERR_INVALID_ARG   # no source
