@@ -212,6 +212,25 @@ def full_table(counts, tile_m: int, tile_n: int, N: int, sigma=None, tile_m_smal
     return table[:n]
 
 
+def heterogeneous_batch_table(tm: TaskMap, reduce_tiles: int) -> np.ndarray:
+    """A batch of two task types in one launch (Sec. 3.2, Alg. 3): the GEMM tasks of `tm` followed by ONE reduction
+    task of `reduce_tiles` tiles.  The batch's TilePrefix (Alg. 1) runs over nu = [tiles of every non-empty expert in
+    sigma order ..., reduce_tiles]; every block is mapped with Alg. 2.  Returns [total + reduce_tiles, 3] rows
+    (type, task, l): type 0 = GEMM tile l of expert `task`, type 1 = tile l of the reduction task (task = -1)."""
+    nu = [int(tm.tile_prefix[i] - (tm.tile_prefix[i - 1] if i else 0)) for i in range(tm.M)] + [int(reduce_tiles)]
+    prefix = tile_prefix(nu)
+    out = np.zeros((int(prefix[-1]) if len(prefix) else 0, 3), dtype=np.int32)
+    for B in range(len(out)):
+        h, l = mapping(prefix, B)
+        out[B] = (0, int(tm.sigma[h]), l) if h < tm.M else (1, -1, l)
+    return out
+
+
+def reduce_task_tiles(T: int, N: int, chunks_per_tile: int = 4096) -> int:
+    """nu of the reduction task: its output [T, N] in chunks of 8 columns, chunks_per_tile chunks per tile."""
+    return -(-(T * (N // 8)) // chunks_per_tile)
+
+
 # ------------------------------------------------------------------ result
 @dataclass
 class GemmResult:

@@ -70,3 +70,35 @@ def test_combine_random_against_einsum(oracle_mod):
     np.testing.assert_allclose(out64, want, rtol=1e-14, atol=1e-14)
     got_bf = H.bf16_bits_to_f64(outbf)
     assert np.all(np.abs(got_bf - out64) <= 2.0 ** -8 * np.abs(out64))
+
+
+# ------------------------------------------------------------------ heterogeneous batch (Sec. 3.2, Alg. 3)
+def test_heterogeneous_batch_mapping_against_nested_loops(oracle_mod):
+    """GEMM tasks plus one reduction task in one batch: Alg. 1 + 2 over the extended list of tile counts must give, for
+    every block, what plain nested loops over (task, tile) give -- the prior-art full table of Sec. 2.1 with one more
+    task at its end -- and the GEMM part must be the GEMM map's own decode, untouched by the extra task."""
+    rng = np.random.default_rng(77)
+    for (T, E, k, N, red) in ((300, 8, 2, 512, 5), (64, 70, 3, 256, 1), (10, 4, 1, 256, 0), (0, 4, 2, 256, 3)):
+        ids = np.stack([rng.choice(E, size=k, replace=False) for _ in range(T)]).astype(np.int32) if T else np.zeros((0, k), np.int32)
+        tm = oracle_mod.build_task_map(ids, T, k, E, 64, 128, N)
+        got = oracle_mod.heterogeneous_batch_table(tm, red)
+        want = []
+        nt = -(-N // 128)
+        for e in range(E):                      # GEMM tasks in ascending expert order, empty ones have no tiles
+            for l in range(-(-int(tm.counts[e]) // 64) * nt):
+                want.append((0, e, l))
+        for l in range(red):                    # then the reduction task
+            want.append((1, -1, l))
+        assert got.tolist() == [list(w) for w in want]
+        assert len(got) == tm.total_tiles + red
+        for B in range(tm.total_tiles):         # the GEMM blocks decode as without the extra task
+            e, m_tile, n_tile, _ = oracle_mod.decode_block(tm, B)
+            mt = -(-int(tm.counts[e]) // 64)
+            assert got[B].tolist() == [0, e, n_tile * mt + m_tile]
+
+
+def test_reduce_task_tiles_closed_form(oracle_mod):
+    assert oracle_mod.reduce_task_tiles(4096, 4096) == 4096 * 512 // 4096
+    assert oracle_mod.reduce_task_tiles(1, 8) == 1
+    assert oracle_mod.reduce_task_tiles(0, 4096) == 0
+    assert oracle_mod.reduce_task_tiles(33, 1024) == -(-33 * 128 // 4096)
