@@ -312,6 +312,41 @@ def combine_point(T: int, k: int, N: int, steps: int, warmup: int, dev="cuda:0")
                 gbs=round(gbs, 1), frac_hbm=round(gbs / PEAK_HBM_GBS, 4), bound="hbm", alg_bytes=nbytes)
 
 
+def batched_point(wl: wk.Workload, rT: int, rk: int, rN: int, steps: int, warmup: int, dev="cuda:0") -> dict:
+    """Heterogeneous batching (Sec. 3.2): the GEMM of `wl` with a reduction task (the weighted sum over [rT, rk, rN]
+    finished products of an earlier call) in the same launch, against the two separate calls back to back."""
+    p = Point(wl)
+    g = torch.Generator(device=dev).manual_seed(wk.BASE_SEED + rT)
+    Yin = torch.randn((rT * rk, rN), generator=g, device=dev).to(torch.bfloat16)
+    w = torch.rand((rT, rk), generator=g, device=dev, dtype=torch.float32)
+    out = torch.empty((rT, rN), dtype=torch.bfloat16, device=dev)
+    p.build_map()
+
+    def both():
+        mb.moe_grouped_gemm(p.X, p.W[0], p.ids, p.tmap, p.Y, p.desc)
+        mb.moe_combine(Yin, w, rT, rk, rN, out)
+
+    def batched():
+        mb.moe_grouped_gemm_batched(p.X, p.W[0], p.tmap, p.Y, p.desc, Yin, w, rT, rk, rN, out)
+
+    res = {}
+    for name, fn in (("separate", both), ("batched", batched), ("separate_again", both), ("batched_again", batched)):
+        for _ in range(warmup):
+            fn()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        torch.cuda._sleep(int(4e6))
+        ev[0].record()
+        for _ in range(steps):
+            fn()
+        ev[1].record()
+        torch.cuda.synchronize()
+        res[name] = ev[0].elapsed_time(ev[1]) / steps
+    sep, bat = min(res["separate"], res["separate_again"]), min(res["batched"], res["batched_again"])
+    return dict(workload=f"{wl.name}_T{wl.T}_batched_with_combine_T{rT}_k{rk}_N{rN}", dtype="bf16",
+                separate_ms=round(sep, 4), batched_ms=round(bat, 4), reduce_tiles=mb.moe_reduce_task_tiles(rT, rN),
+                tflops_batched=round(wl.flops / (bat * 1e-3) / 1e12, 2), tflops_separate=round(wl.flops / (sep * 1e-3) / 1e12, 2))
+
+
 def layer_point(T: int, steps: int, warmup: int, dev="cuda:0") -> dict:
     """One whole bf16 feed-forward layer at the Mixtral-8x7B sizes (Sec. 2.2): two task maps, the gate+up product
     with the fused gated activation, the down product and the weighted sum, five library calls per step."""
@@ -562,6 +597,11 @@ def main():
                 torch.cuda.empty_cache()
             for (T, k, N) in ((4096, 2, 4096), (8192, 8, 4096), (32, 6, 2816)):
                 points.append(combine_point(T, k, N, max(10, args.steps // 2), max(3, args.warmup // 2)))
+                torch.cuda.empty_cache()
+        if want is None or "batched" in want or "neighbours" in want:
+            # heterogeneous batch: the headline product with the previous layer's weighted sum in the same launch
+            for (rT, rk, rN) in ((4096, 2, 4096), (8192, 8, 4096)):
+                points.append(batched_point(wl, rT, rk, rN, max(10, args.steps // 2), max(3, args.warmup // 2)))
                 torch.cuda.empty_cache()
         if want is None or "layer" in want:
             # labelled extra: the whole feed-forward layer composed from the library's calls

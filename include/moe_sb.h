@@ -352,6 +352,38 @@ int moe_tile_pair_supported(int dtype, int tile_m, int tile_n, int tile_m_small)
  */
 int moe_combine(const void* Y, const float* topk_weights, int T, int k, int N, void* out, void* stream);
 
+/*
+ * Heterogeneous batching (Sec. 3.2, Alg. 3: tasks of different kinds -- the paper names a GEMM and a reduction -- in
+ * ONE kernel): moe_grouped_gemm with a reduction task added to the batch.  The reduction is moe_combine's,
+ *     out[t, n] = bf16( sum_j topk_weights[t, j] * Y_in[t, j, n] ),
+ * over the finished products of an EARLIER call (another layer, another micro-batch: it must not depend on the Y
+ * this call writes).  Its nu = moe_reduce_task_tiles(T, N) tiles of 4096 eight-column chunks each are appended to
+ * the GEMM map's tiles: in the terms of Sec. 3.1 the batch's TilePrefix is the map's with one more entry,
+ * total_tiles + nu; a block at or beyond total_tiles belongs to the reduction task and runs its task function,
+ * every other block is decoded as in moe_grouped_gemm.  The reduction tiles only move memory; every XCD walks its
+ * share of them spread in proportion over its share of the GEMM blocks (the placement idea of Sec. 4.2), so they
+ * stream while the neighbouring workgroups multiply.
+ */
+typedef struct moe_reduce_task {
+    const void* Y;              /* DEVICE [T, k, N] bf16, 16-byte aligned */
+    const float* topk_weights;  /* DEVICE [T, k] fp32, or NULL for the plain sum */
+    int32_t T, k, N;            /* N % 8 == 0 */
+    void* out;                  /* DEVICE [T, N] bf16, 16-byte aligned, must not overlap Y or the GEMM's buffers */
+} moe_reduce_task;
+
+/* Tiles of such a reduction task: ceil(T * (N / 8) / 4096).  HOST, pure; 0 on invalid sizes. */
+int64_t moe_reduce_task_tiles(int T, int N);
+
+/*
+ * X, W, task_map, Y, desc as for moe_grouped_gemm (same results bit for bit); `red` is a HOST pointer, read before
+ * return.  out is what moe_combine(red->Y, red->topk_weights, red->T, red->k, red->N, red->out) gives, bit for bit.
+ * Supported where a batched kernel exists: bf16, [E][K][N] weights, 256 x 256 tiles without slack rows or with 32,
+ * one tiling strategy; anything else MOE_ERR_UNSUPPORTED.  A map that does not match `desc` makes the whole call a
+ * no-op (the reduction included).  MOE_ERR_INVALID_ARG for a NULL red or bad pointers.
+ */
+int moe_grouped_gemm_batched(const void* X, const void* W, const void* task_map, void* Y, const moe_gemm_desc* desc,
+                             const moe_reduce_task* red, void* stream);
+
 /* Static string for a return code. */
 const char* moe_strerror(int code);
 

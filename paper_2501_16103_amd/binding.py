@@ -50,6 +50,7 @@ EXPORTS = [
     "moe_task_map_status", "moe_task_map_expand", "moe_grouped_gemm", "moe_tile_supported", "moe_combine",
     "moe_grouped_gemm_splitk", "moe_splitk_workspace_bytes", "moe_default_k_parts",
     "moe_grouped_gemm_splitk_static", "moe_splitk_static_scratch_bytes",
+    "moe_grouped_gemm_batched", "moe_reduce_task_tiles",
     "moe_strerror",
 ]
 
@@ -67,6 +68,11 @@ class moe_gemm_desc(ctypes.Structure):
                 ("tile_m_small", ctypes.c_int32), ("small_max_rows", ctypes.c_int32),
                 ("tile_m_slack", ctypes.c_int32), ("epilogue", ctypes.c_int32), ("w_layout", ctypes.c_int32),
                 ("launch_mode", ctypes.c_int32)]
+
+
+class moe_reduce_task(ctypes.Structure):
+    _fields_ = [("Y", ctypes.c_void_p), ("topk_weights", ctypes.c_void_p), ("T", ctypes.c_int32), ("k", ctypes.c_int32),
+                ("N", ctypes.c_int32), ("out", ctypes.c_void_p)]
 
 
 class moe_tiling(ctypes.Structure):
@@ -132,6 +138,11 @@ def lib() -> ctypes.CDLL:
                                                      ctypes.POINTER(moe_gemm_desc), ctypes.c_int, ctypes.c_void_p]
         L.moe_splitk_static_scratch_bytes.restype = ctypes.c_size_t
         L.moe_splitk_static_scratch_bytes.argtypes = []
+        L.moe_grouped_gemm_batched.restype = ctypes.c_int
+        L.moe_grouped_gemm_batched.argtypes = [ctypes.c_void_p] * 4 + [ctypes.POINTER(moe_gemm_desc),
+                                                                       ctypes.POINTER(moe_reduce_task), ctypes.c_void_p]
+        L.moe_reduce_task_tiles.restype = ctypes.c_int64
+        L.moe_reduce_task_tiles.argtypes = [ctypes.c_int, ctypes.c_int]
         L.moe_splitk_workspace_bytes.restype = ctypes.c_size_t
         L.moe_splitk_workspace_bytes.argtypes = [ctypes.c_int] * 4
         L.moe_default_k_parts.restype = ctypes.c_int
@@ -331,6 +342,23 @@ def moe_grouped_gemm_splitk(X: torch.Tensor, W: torch.Tensor, task_map: torch.Te
                                        _ptr(workspace), ctypes.c_size_t(nbytes), _stream() if X is not None else None)
     if check and rc != MOE_OK:
         raise MoeError(rc, "moe_grouped_gemm_splitk")
+    return rc
+
+
+def moe_reduce_task_tiles(T: int, N: int) -> int:
+    return int(lib().moe_reduce_task_tiles(T, N))
+
+
+def moe_grouped_gemm_batched(X: torch.Tensor, W: torch.Tensor, task_map: torch.Tensor, Y: torch.Tensor, desc: "GemmDesc",
+                             red_Y: torch.Tensor, red_weights: Optional[torch.Tensor], red_T: int, red_k: int, red_N: int,
+                             red_out: torch.Tensor, check: bool = True) -> int:
+    """moe_grouped_gemm with a reduction task (moe_combine's sum over red_Y [red_T, red_k, red_N]) in the same launch."""
+    d = desc.c_struct()
+    r = moe_reduce_task(None if red_Y is None else red_Y.data_ptr(), None if red_weights is None else red_weights.data_ptr(),
+                        red_T, red_k, red_N, None if red_out is None else red_out.data_ptr())
+    rc = lib().moe_grouped_gemm_batched(_ptr(X), _ptr(W), _ptr(task_map), _ptr(Y), ctypes.byref(d), ctypes.byref(r), _stream())
+    if check and rc != MOE_OK:
+        raise MoeError(rc, "moe_grouped_gemm_batched")
     return rc
 
 

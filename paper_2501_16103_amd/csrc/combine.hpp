@@ -12,15 +12,15 @@ namespace moe {
 __device__ __forceinline__ float bf16_lo(uint32_t v) { return __uint_as_float(v << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t v) { return __uint_as_float(v & 0xffff0000u); }
 
-// grid.x covers chunks (8 columns) of all tokens: chunk index c -> token c / (N/8), column 8 * (c % (N/8)).
+// Chunks (8 columns) [c_begin, c_end) of all tokens, walked by `nthreads` threads of which this is number `tid`:
+// chunk index c -> token c / (N/8), column 8 * (c % (N/8)).
 // KU > 0: k is the compile-time KU and all k loads of a chunk are issued before the first is used.
 template <int KU>
-__global__ __launch_bounds__(256) void moe_combine_kernel(const u32x4_t* __restrict__ Y, const float* __restrict__ w,
-                                                          u32x4_t* __restrict__ out, int T, int k_rt, int N) {
+__device__ __forceinline__ void combine_range(const u32x4_t* __restrict__ Y, const float* __restrict__ w, u32x4_t* __restrict__ out,
+                                              int k_rt, int N, long long c_begin, long long c_end, long long tid, long long nthreads) {
     const int k = KU > 0 ? KU : k_rt;
     const int cpr = N >> 3;  // chunks per row
-    const long long total = (long long)T * cpr;
-    for (long long c = (long long)blockIdx.x * 256 + threadIdx.x; c < total; c += (long long)gridDim.x * 256) {
+    for (long long c = c_begin + tid; c < c_end; c += nthreads) {
         const int t = (int)(c / cpr), col = (int)(c - (long long)t * cpr);
         float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         const u32x4_t* src = Y + ((size_t)t * k) * cpr + col;
@@ -48,6 +48,65 @@ __global__ __launch_bounds__(256) void moe_combine_kernel(const u32x4_t* __restr
         o.z = pack_bf16(acc[4], acc[5]); o.w = pack_bf16(acc[6], acc[7]);
         out[(size_t)t * cpr + col] = o;
     }
+}
+
+template <int KU>
+__global__ __launch_bounds__(256) void moe_combine_kernel(const u32x4_t* __restrict__ Y, const float* __restrict__ w,
+                                                          u32x4_t* __restrict__ out, int T, int k_rt, int N) {
+    combine_range<KU>(Y, w, out, k_rt, N, 0, (long long)T * (N >> 3), (long long)blockIdx.x * 256 + threadIdx.x,
+                      (long long)gridDim.x * 256);
+}
+
+// ---- heterogeneous batching (Sec. 3.2, Alg. 3): GEMM tasks and one reduction task in the same launch
+
+// 8-column chunks of output per tile of the reduction task: nu(reduction) = ceil(T * N / 8 / kReduceTileChunks).
+constexpr int kReduceTileChunks = 4096;
+
+// Tile l of the reduction task: the sum over a token's experts (see combine_range) for chunks
+// [l * kReduceTileChunks, (l + 1) * kReduceTileChunks) of [red_T, red_N], run by all threads of the workgroup.
+__device__ __forceinline__ void reduce_tile(const GemmArgs& a, int l, int nthreads) {
+    const long long total = (long long)a.red_T * (a.red_N >> 3);
+    const long long c0 = (long long)l * kReduceTileChunks;
+    const long long c1 = c0 + kReduceTileChunks < total ? c0 + kReduceTileChunks : total;
+    const u32x4_t* y = static_cast<const u32x4_t*>(a.red_Y);
+    u32x4_t* o = static_cast<u32x4_t*>(a.red_out);
+    switch (a.red_k) {
+        case 2: combine_range<2>(y, a.red_w, o, 2, a.red_N, c0, c1, threadIdx.x, nthreads); break;
+        case 6: combine_range<6>(y, a.red_w, o, 6, a.red_N, c0, c1, threadIdx.x, nthreads); break;
+        case 8: combine_range<8>(y, a.red_w, o, 8, a.red_N, c0, c1, threadIdx.x, nthreads); break;
+        default: combine_range<0>(y, a.red_w, o, a.red_k, a.red_N, c0, c1, threadIdx.x, nthreads); break;
+    }
+}
+
+// One launch, two task types: the blocks of the GEMM tasks (all experts, as in moe_gemm_pipe_kernel) and the
+// a.red_tiles blocks of one reduction task.  In the terms of Sec. 3.1 the batch's TilePrefix is the GEMM map's with
+// one more entry, total_tiles + red_tiles, for the reduction task; a block at or beyond total_tiles belongs to it
+// (the vote of Alg. 2 on that last entry) and runs the other task function (Alg. 3).  The reduction tiles only move
+// memory, so every XCD walks its share of them spread in proportion over its share of the GEMM blocks (the
+// placement idea of Sec. 4.2): they stream while the neighbours multiply.
+template <class C, class... Tails>
+__global__ __launch_bounds__(C::NT) void moe_gemm_batched_kernel(GemmArgs a) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int32_t* __restrict__ map = a.map;
+    MapLayout L = map_layout(a.E);
+    const int4 first_record = reinterpret_cast<const int4*>(map + L.off_records)[__lane_id()];
+    const int total = map[MOE_HDR_TOTAL_TILES];
+    if (!map_matches<C::BM, C::BN, 0, C::SLACK>(a, map)) return;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int ng = slots_of_xcd(map, total, xcd);
+    const int r0 = (int)((long long)a.red_tiles * xcd >> 3), r1 = (int)((long long)a.red_tiles * (xcd + 1) >> 3);
+    const int nr = r1 - r0, n = ng + nr;
+    if (slot >= n) return;
+    const int before = (int)((long long)slot * nr / n), upto = (int)((long long)(slot + 1) * nr / n);
+    if (upto > before) {
+        reduce_tile(a, r0 + before, C::NT);
+        return;
+    }
+    int B;
+    if (!slot_to_block(map, total, xcd, slot - before, B)) return;
+    const moe_tiling g = {C::BM, C::BN, 0, 0, 0, C::SLACK};
+    const TileCoord tc = decode_block(map, L, g, B, first_record);
+    run_tile<C, Tails...>(a, map, L, tc, smem);
 }
 
 // Second half of a split-k product: Y[r(p), n] = bf16( sum_s partial[s][p][n] ), s ascending, for every position p of

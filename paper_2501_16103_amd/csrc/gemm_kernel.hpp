@@ -48,6 +48,11 @@ struct GemmArgs {
     int tile_m_slack;                  // slack rows of the map's last m-tiles
     int swiglu;                        // 1: W = [gate | up] halves of N, Y[r, i] = silu(gate_i) * up_i, Y is [R, N/2]
     float* partial;                    // split-k launches: fp32 partial sums [gridDim.y][R (sorted row position)][N]
+    // heterogeneous launches: a reduction task batched with the GEMM tasks (Alg. 3 with two task types), else red_tiles = 0
+    const void* red_Y;                 // [red_T][red_k][red_N] bf16, finished products of an earlier launch
+    const float* red_w;                // [red_T][red_k] or nullptr
+    void* red_out;                     // [red_T][red_N] bf16
+    int red_T, red_k, red_N, red_tiles;
 };
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
@@ -821,24 +826,22 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
     }
 }
 
-// Block index -> tile (Alg. 2 + 4), shared by the kernels below.  Returns false for surplus workgroups and for
-// a map that does not belong to this launch (wrong shape, tiling or status): those do nothing.
+// Whether the map belongs to this launch (shape, tiling, strategy, slack, status); a launch whose map does not
+// match does nothing.
 template <int BM_BIG, int BN, int BM_SMALL, int SLACK>
-__device__ __forceinline__ bool locate_tile(const GemmArgs& a, const int32_t* __restrict__ map, MapLayout& L, TileCoord& tc) {
-    // the first 64 task records travel together with the header: one memory round trip before the tile is known
-    L = map_layout(a.E);
-    const int4 first_record = reinterpret_cast<const int4*>(map + L.off_records)[__lane_id()];
-    const int total = map[MOE_HDR_TOTAL_TILES];
-    const bool hdr_ok = map[MOE_HDR_MAGIC] == MOE_MAP_MAGIC && map[MOE_HDR_T] == a.T && map[MOE_HDR_K_TOP] == a.k &&
-                        map[MOE_HDR_E] == a.E && map[MOE_HDR_N] == a.N && map[MOE_HDR_TILE_M] == BM_BIG &&
-                        map[MOE_HDR_TILE_N] == BN && map[MOE_HDR_STATUS] == 0 &&
-                        map[MOE_HDR_TILE_M_SMALL] == BM_SMALL && map[MOE_HDR_SMALL_MAX_ROWS] == a.small_max_rows &&
-                        a.tile_m_small == BM_SMALL && map[MOE_HDR_TILE_M_SLACK] == SLACK && a.tile_m_slack == SLACK;
-    if (!hdr_ok) return false;
-    // Workgroup ids are dealt round-robin to the 8 XCDs; give each XCD one contiguous run of block indices so
-    // that neighbours in the map share an L2.
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    int B;
+__device__ __forceinline__ bool map_matches(const GemmArgs& a, const int32_t* __restrict__ map) {
+    return map[MOE_HDR_MAGIC] == MOE_MAP_MAGIC && map[MOE_HDR_T] == a.T && map[MOE_HDR_K_TOP] == a.k &&
+           map[MOE_HDR_E] == a.E && map[MOE_HDR_N] == a.N && map[MOE_HDR_TILE_M] == BM_BIG &&
+           map[MOE_HDR_TILE_N] == BN && map[MOE_HDR_STATUS] == 0 &&
+           map[MOE_HDR_TILE_M_SMALL] == BM_SMALL && map[MOE_HDR_SMALL_MAX_ROWS] == a.small_max_rows &&
+           a.tile_m_small == BM_SMALL && map[MOE_HDR_TILE_M_SLACK] == SLACK && a.tile_m_slack == SLACK;
+}
+
+// Which block index slot `slot` of XCD `xcd` runs (the XCD-aware remap in front of Alg. 2 / 4: a bijection between
+// a launch's slots and the map's blocks, not part of the map).  Workgroup ids are dealt round-robin to the 8 XCDs;
+// every XCD gets one contiguous run of block indices so that neighbours in the map share an L2.  Returns false
+// for slots beyond the XCD's share (and then for every larger slot as well).
+__device__ __forceinline__ bool slot_to_block(const int32_t* __restrict__ map, int total, int xcd, int slot, int& B) {
     if (map[MOE_HDR_SIGMA_ORDER] == MOE_ORDER_INTERLEAVE) {
         // Sec. 4.2: blocks [0, heavy) are compute-bound, [heavy, total) only stream weights.  Every XCD gets a
         // contiguous share of each part and walks the two shares interleaved in proportion (slot s takes the
@@ -851,12 +854,36 @@ __device__ __forceinline__ bool locate_tile(const GemmArgs& a, const int32_t* __
         if (slot >= n) return false;
         const int before = (int)((long long)slot * nl / n), upto = (int)((long long)(slot + 1) * nl / n);
         B = upto > before ? heavy + l0 + before : h0 + slot - before;
-    } else {
-        const int per_xcd = (total + 7) >> 3;
-        if (slot >= per_xcd) return false;
-        B = xcd * per_xcd + slot;
-        if (B >= total) return false;
+        return true;
     }
+    const int per_xcd = (total + 7) >> 3;
+    if (slot >= per_xcd) return false;
+    B = xcd * per_xcd + slot;
+    return B < total;
+}
+// Slots of XCD `xcd` for which slot_to_block returns true.
+__device__ __forceinline__ int slots_of_xcd(const int32_t* __restrict__ map, int total, int xcd) {
+    if (map[MOE_HDR_SIGMA_ORDER] == MOE_ORDER_INTERLEAVE) {
+        const int heavy = map[MOE_HDR_HEAVY_TILES], light = total - heavy;
+        return (int)(((long long)heavy * (xcd + 1) >> 3) - ((long long)heavy * xcd >> 3)) +
+               (int)(((long long)light * (xcd + 1) >> 3) - ((long long)light * xcd >> 3));
+    }
+    const int per_xcd = (total + 7) >> 3;
+    const int left = total - xcd * per_xcd;
+    return left < 0 ? 0 : (left < per_xcd ? left : per_xcd);
+}
+
+// Block index -> tile (Alg. 2 + 4), shared by the kernels below.  Returns false for surplus workgroups and for
+// a map that does not belong to this launch (wrong shape, tiling or status): those do nothing.
+template <int BM_BIG, int BN, int BM_SMALL, int SLACK>
+__device__ __forceinline__ bool locate_tile(const GemmArgs& a, const int32_t* __restrict__ map, MapLayout& L, TileCoord& tc) {
+    // the first 64 task records travel together with the header: one memory round trip before the tile is known
+    L = map_layout(a.E);
+    const int4 first_record = reinterpret_cast<const int4*>(map + L.off_records)[__lane_id()];
+    const int total = map[MOE_HDR_TOTAL_TILES];
+    if (!map_matches<BM_BIG, BN, BM_SMALL, SLACK>(a, map)) return false;
+    int B;
+    if (!slot_to_block(map, total, blockIdx.x & 7, blockIdx.x >> 3, B)) return false;
     const moe_tiling g = {BM_BIG, BN, 0, BM_SMALL, a.small_max_rows, SLACK};
     tc = decode_block(map, L, g, B, first_record);
     return true;

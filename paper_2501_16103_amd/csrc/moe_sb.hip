@@ -71,6 +71,16 @@ int launch_splitk(const GemmArgs& a, int64_t grid, int parts, hipStream_t s) {
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
+// Heterogeneous launch: the GEMM tasks' blocks plus a.red_tiles blocks of the reduction task.
+template <class C, class... Tails>
+int launch_batched(const GemmArgs& a, int64_t grid, int /*mode*/, hipStream_t s) {
+    static unsigned long long attr_done = 0;
+    if (ensure_lds_attr(reinterpret_cast<const void*>(&moe_gemm_batched_kernel<C, Tails...>), C::LDS_BYTES, &attr_done) != MOE_OK)
+        return MOE_ERR_HIP;
+    moe_gemm_batched_kernel<C, Tails...><<<dim3((unsigned)grid), dim3(C::NT), C::LDS_BYTES, s>>>(a);
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
+
 // Workgroups of `fn` that stay resident at once on the current device with `lds` bytes of dynamic LDS (also sets
 // the kernel's large-LDS attribute); cached per kernel instance in *cache for the last (device, lds) asked for.
 struct ResidentCache { int lds = -1, dev = -1, resident = 0; };
@@ -128,6 +138,8 @@ struct GemmVariant {
     // the same tile as a streaming launch (resident workgroups run several tiles back to back), or nullptr
     gemm_launch_fn fn_stream = nullptr;
     int ring = 0;  // ring depth of the streaming kernel: it needs K / bk >= ring
+    // the same GEMM tasks batched with a reduction task in one launch (moe_grouped_gemm_batched), or nullptr
+    gemm_launch_fn fn_batched = nullptr;
 };
 
 // Pipelined bf16 kernels:  BM   BN   BK  WM WN  ring stages
@@ -180,9 +192,11 @@ const GemmVariant kVariants[] = {
     {MOE_DTYPE_BF16, 16, 256, 64, &launch_pipe<Pk_16x256>, 0, 0, MOE_W_LAYOUT_NK},
     {MOE_DTYPE_FP8_E4M3, 16, 256, 128, &launch_pipe<P8k_16x256>, 0, 0, MOE_W_LAYOUT_NK},
     {MOE_DTYPE_FP8_E4M3, 16, 128, 128, &launch_pipe<P8k_16x128>, 0, 0, MOE_W_LAYOUT_NK},
-    {MOE_DTYPE_BF16, 256, 256, 64, &launch_pipe<Pb_256x256, Ps_64x256, Ps_128x256>},
+    {MOE_DTYPE_BF16, 256, 256, 64, &launch_pipe<Pb_256x256, Ps_64x256, Ps_128x256>, 0, 0, MOE_W_LAYOUT_KN, nullptr, 0,
+     &launch_batched<Pb_256x256, Ps_64x256, Ps_128x256>},
     {MOE_DTYPE_BF16, 256, 256, 64, &launch_pipe<Pb_256x256s, Ps_64x256, Ps_128x256>, 0, 64},
-    {MOE_DTYPE_BF16, 256, 256, 64, &launch_pipe<Pb_256x256s32, Ps_64x256, Ps_128x256>, 0, 32},
+    {MOE_DTYPE_BF16, 256, 256, 64, &launch_pipe<Pb_256x256s32, Ps_64x256, Ps_128x256>, 0, 32, MOE_W_LAYOUT_KN, nullptr, 0,
+     &launch_batched<Pb_256x256s32, Ps_64x256, Ps_128x256>},
     {MOE_DTYPE_BF16, 128, 256, 64, &launch_pipe<Pb_128x256, Ps_64x256>},
     {MOE_DTYPE_BF16, 128, 128, 64, &launch_pipe<Pb_128x128>},
     {MOE_DTYPE_BF16, 64, 256, 64, &launch_pipe<Pb_64x256>},
@@ -227,6 +241,58 @@ int check_small_args(int tile_m, int tile_m_small, int small_max_rows, int tile_
     if (tile_m_small >= tile_m) return MOE_ERR_INVALID_ARG;
     if (small_max_rows < 1 || small_max_rows > 4 * tile_m_small) return MOE_ERR_INVALID_ARG;
     return MOE_OK;
+}
+
+// moe_grouped_gemm, optionally with a reduction task batched into the same launch (red != nullptr).
+int grouped_gemm_impl(const void* X, const void* W, const void* task_map, void* Y, const moe_gemm_desc* d,
+                      const moe_reduce_task* red, void* stream) {
+    if (!d || !task_map) return MOE_ERR_INVALID_ARG;
+    const int rc = check_map_args(d->T, d->k, d->E, d->tile_m, d->tile_n, d->N);
+    if (rc != MOE_OK) return rc;
+    if (d->K < 1) return MOE_ERR_INVALID_ARG;
+    if (d->dtype != MOE_DTYPE_BF16 && d->dtype != MOE_DTYPE_FP8_E4M3) return MOE_ERR_UNSUPPORTED;
+    {
+        const int rcs = check_small_args(d->tile_m, d->tile_m_small, d->small_max_rows, d->tile_m_slack);
+        if (rcs != MOE_OK) return rcs;
+    }
+    if (d->w_layout != MOE_W_LAYOUT_KN && d->w_layout != MOE_W_LAYOUT_NK) return MOE_ERR_INVALID_ARG;
+    if (d->launch_mode < 0) return MOE_ERR_INVALID_ARG;
+    const GemmVariant* v = find_variant(d->dtype, d->tile_m, d->tile_n, d->tile_m_small, d->tile_m_slack, d->w_layout);
+    if (!v) return MOE_ERR_UNSUPPORTED;
+    if (red && !v->fn_batched) return MOE_ERR_UNSUPPORTED;
+    if (d->K % v->bk != 0 || d->N % d->tile_n != 0) return MOE_ERR_UNSUPPORTED;
+    if (d->epilogue != MOE_EPILOGUE_NONE && d->epilogue != MOE_EPILOGUE_SWIGLU) return MOE_ERR_INVALID_ARG;
+    const int es = d->dtype == MOE_DTYPE_FP8_E4M3 ? 1 : 2;
+    if ((int64_t)d->T * d->K * es >= (int64_t)1 << 32) return MOE_ERR_UNSUPPORTED;
+    const int64_t red_tiles = red ? moe_reduce_task_tiles(red->T, red->N) : 0;
+    if (d->T == 0 && red_tiles == 0) return MOE_OK;
+    if (d->T > 0) {
+        if (!X || !W || !Y) return MOE_ERR_INVALID_ARG;
+        if (((uintptr_t)X & 15) || ((uintptr_t)W & 15) || ((uintptr_t)Y & 15)) return MOE_ERR_INVALID_ARG;
+        if (d->dtype == MOE_DTYPE_FP8_E4M3 && (!d->x_scale || !d->w_scale)) return MOE_ERR_INVALID_ARG;
+    }
+    if ((uintptr_t)task_map & 15) return MOE_ERR_INVALID_ARG;
+    GemmArgs a{};
+    a.X = X; a.W = W; a.map = static_cast<const int32_t*>(task_map); a.Y = Y;
+    a.x_scale = d->x_scale; a.w_scale = d->w_scale;
+    a.T = d->T; a.k = d->k; a.E = d->E; a.K = d->K; a.N = d->N;
+    a.tile_m_small = d->tile_m_small; a.small_max_rows = d->small_max_rows; a.tile_m_slack = d->tile_m_slack;
+    a.swiglu = d->epilogue == MOE_EPILOGUE_SWIGLU;
+    a.partial = nullptr;
+    if (red_tiles > 0) {
+        a.red_Y = red->Y; a.red_w = red->topk_weights; a.red_out = red->out;
+        a.red_T = red->T; a.red_k = red->k; a.red_N = red->N; a.red_tiles = (int)red_tiles;
+    }
+    int64_t grid = moe_grid_upper_bound_tiled(d->T, d->k, d->E, d->tile_m, d->tile_n, d->N, d->tile_m_small,
+                                              d->small_max_rows) + red_tiles;
+    if (grid == 0) return MOE_OK;
+    grid = (grid + 7) / 8 * 8 + 16;  // spare slots per XCD: the interleaved dealings round their shares up
+    if (grid > 0x7fffffff) return MOE_ERR_UNSUPPORTED;
+    if (red) return v->fn_batched(a, grid, d->launch_mode, static_cast<hipStream_t>(stream));
+    // weight-streaming tiles: keep the workgroups resident and stream tile after tile where the shape allows it
+    const bool can_stream = v->fn_stream && d->E <= 256 && d->K / v->bk >= v->ring &&
+                            (d->dtype != MOE_DTYPE_FP8_E4M3 || d->T + d->E <= 2048) && d->launch_mode != MOE_LAUNCH_PER_TILE;
+    return (can_stream ? v->fn_stream : v->fn)(a, grid, d->launch_mode, static_cast<hipStream_t>(stream));
 }
 
 // ---- split-k: shared by the entry point that takes a workspace and by the one that allocates nothing
@@ -490,44 +556,25 @@ int moe_w_layout_supported(int dtype, const moe_tiling* g, int w_layout) {
 int moe_grouped_gemm(const void* X, const void* W, const int32_t* topk_ids, const void* task_map, void* Y,
                      const moe_gemm_desc* d, void* stream) {
     (void)topk_ids;
-    if (!d || !task_map) return MOE_ERR_INVALID_ARG;
-    const int rc = check_map_args(d->T, d->k, d->E, d->tile_m, d->tile_n, d->N);
-    if (rc != MOE_OK) return rc;
-    if (d->K < 1) return MOE_ERR_INVALID_ARG;
-    if (d->dtype != MOE_DTYPE_BF16 && d->dtype != MOE_DTYPE_FP8_E4M3) return MOE_ERR_UNSUPPORTED;
-    {
-        const int rcs = check_small_args(d->tile_m, d->tile_m_small, d->small_max_rows, d->tile_m_slack);
-        if (rcs != MOE_OK) return rcs;
-    }
-    if (d->w_layout != MOE_W_LAYOUT_KN && d->w_layout != MOE_W_LAYOUT_NK) return MOE_ERR_INVALID_ARG;
-    if (d->launch_mode < 0) return MOE_ERR_INVALID_ARG;
-    const GemmVariant* v = find_variant(d->dtype, d->tile_m, d->tile_n, d->tile_m_small, d->tile_m_slack, d->w_layout);
-    if (!v) return MOE_ERR_UNSUPPORTED;
-    if (d->K % v->bk != 0 || d->N % d->tile_n != 0) return MOE_ERR_UNSUPPORTED;
-    if (d->epilogue != MOE_EPILOGUE_NONE && d->epilogue != MOE_EPILOGUE_SWIGLU) return MOE_ERR_INVALID_ARG;
-    const int es = d->dtype == MOE_DTYPE_FP8_E4M3 ? 1 : 2;
-    if ((int64_t)d->T * d->K * es >= (int64_t)1 << 32) return MOE_ERR_UNSUPPORTED;
-    if (d->T == 0) return MOE_OK;
-    if (!X || !W || !Y) return MOE_ERR_INVALID_ARG;
-    if (((uintptr_t)X & 15) || ((uintptr_t)W & 15) || ((uintptr_t)Y & 15) || ((uintptr_t)task_map & 15))
+    return grouped_gemm_impl(X, W, task_map, Y, d, nullptr, stream);
+}
+
+int64_t moe_reduce_task_tiles(int T, int N) {
+    if (T < 0 || N < 8 || N % 8 != 0) return 0;
+    const long long chunks = (long long)T * (N / 8);
+    return (chunks + kReduceTileChunks - 1) / kReduceTileChunks;
+}
+
+int moe_grouped_gemm_batched(const void* X, const void* W, const void* task_map, void* Y, const moe_gemm_desc* d,
+                             const moe_reduce_task* red, void* stream) {
+    if (!red) return MOE_ERR_INVALID_ARG;
+    if (red->T < 0 || red->k < 1 || red->N < 1) return MOE_ERR_INVALID_ARG;
+    if (red->N % 8 != 0) return MOE_ERR_UNSUPPORTED;
+    if (red->T > 0 && (!red->Y || !red->out || ((uintptr_t)red->Y & 15) || ((uintptr_t)red->out & 15) ||
+                       ((uintptr_t)red->topk_weights & 3)))
         return MOE_ERR_INVALID_ARG;
-    if (d->dtype == MOE_DTYPE_FP8_E4M3 && (!d->x_scale || !d->w_scale)) return MOE_ERR_INVALID_ARG;
-    GemmArgs a;
-    a.X = X; a.W = W; a.map = static_cast<const int32_t*>(task_map); a.Y = Y;
-    a.x_scale = d->x_scale; a.w_scale = d->w_scale;
-    a.T = d->T; a.k = d->k; a.E = d->E; a.K = d->K; a.N = d->N;
-    a.tile_m_small = d->tile_m_small; a.small_max_rows = d->small_max_rows; a.tile_m_slack = d->tile_m_slack;
-    a.swiglu = d->epilogue == MOE_EPILOGUE_SWIGLU;
-    a.partial = nullptr;
-    int64_t grid = moe_grid_upper_bound_tiled(d->T, d->k, d->E, d->tile_m, d->tile_n, d->N, d->tile_m_small,
-                                              d->small_max_rows);
-    if (grid == 0) return MOE_OK;
-    grid = (grid + 7) / 8 * 8 + 8;  // one spare slot per XCD: the interleaved dealing rounds two shares up
-    if (grid > 0x7fffffff) return MOE_ERR_UNSUPPORTED;
-    // weight-streaming tiles: keep the workgroups resident and stream tile after tile where the shape allows it
-    const bool can_stream = v->fn_stream && d->E <= 256 && d->K / v->bk >= v->ring &&
-                            (d->dtype != MOE_DTYPE_FP8_E4M3 || d->T + d->E <= 2048) && d->launch_mode != MOE_LAUNCH_PER_TILE;
-    return (can_stream ? v->fn_stream : v->fn)(a, grid, d->launch_mode, static_cast<hipStream_t>(stream));
+    if (moe_reduce_task_tiles(red->T, red->N) > (1 << 24)) return MOE_ERR_UNSUPPORTED;
+    return grouped_gemm_impl(X, W, task_map, Y, d, red, stream);
 }
 
 size_t moe_splitk_workspace_bytes(int T, int k, int N, int k_parts) {

@@ -522,6 +522,87 @@ def test_splitk_mismatched_map_is_a_noop(dev):
     assert bool((Y.view(torch.bfloat16) == float(K)).all())
 
 
+BATCHED_CASES = [
+    # per-expert row counts of the GEMM (k = 1), K, N, slack | reduction: T, k, N, weighted
+    ([257, 320, 321, 256, 1, 64, 65, 0, 576], 128, 256, 0, 300, 2, 512, True),
+    ([1025, 1040, 991, 1055], 192, 512, 32, 1000, 8, 4096, True),      # 125 reduction tiles among 64 GEMM tiles
+    ([300, 0, 0, 513, 129], 192, 512, 0, 70, 6, 264, False),            # plain sum, a ragged last reduction tile
+    ([512, 512], 128, 1024, 0, 0, 2, 256, True),                        # empty reduction task: the plain product
+    ([40], 128, 256, 32, 4096, 2, 1024, True),                          # one GEMM tile, 128 reduction tiles
+]
+
+
+@pytest.mark.parametrize("order", [0, 2], ids=["ascending", "interleave"])
+@pytest.mark.parametrize("counts,K,N,slack,rT,rk,rN,weighted", BATCHED_CASES)
+def test_heterogeneous_batch_parity(dev, oracle_mod, counts, K, N, slack, rT, rk, rN, weighted, order):
+    """Sec. 3.2 / Alg. 3: GEMM tasks and a reduction task in ONE launch.  The GEMM's Y must equal the oracle's and,
+    bit for bit, moe_grouped_gemm's; the reduction's output must equal the oracle's sum and, bit for bit,
+    moe_combine's; every element of both outputs is written, nothing outside them."""
+    from tests.test_gpu_parity import _build_map, _check_y, _ids_from_counts
+    E, T = len(counts), int(sum(counts))
+    wl = wk.Workload("parity_batched", T, E, 1, K, N, "bf16", "gauss_topk", 256, 256)
+    ids = _ids_from_counts(counts, 11 + E + K)
+    X, W = wk.make_x(wl), wk.make_w(wl)
+    g = torch.Generator().manual_seed(rT + rk)
+    Yin = torch.randn((rT * rk, rN), generator=g).to(torch.bfloat16)
+    wts = torch.rand((rT, rk), generator=g, dtype=torch.float32) if weighted else None
+    pad = 3
+    ybuf = torch.full((T + 2 * pad, N), POISON, dtype=torch.int16, device=dev)
+    obuf = torch.full((rT + 2 * pad, rN), POISON, dtype=torch.int16, device=dev)
+    Y, out = ybuf[pad: pad + T], obuf[pad: pad + rT]
+    tmap = _build_map(ids.to(dev), T, 1, E, 256, 256, N, order, slack=slack)
+    desc = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 256, 256, tile_m_slack=slack)
+    Yin_d, wts_d = Yin.to(dev), None if wts is None else wts.to(dev)
+    mb.moe_grouped_gemm_batched(X.to(dev), W.to(dev), tmap, Y, desc, Yin_d, wts_d, rT, rk, rN, out)
+    torch.cuda.synchronize()
+    yb, ob = ybuf.cpu().numpy().view(np.uint16), obuf.cpu().numpy().view(np.uint16)
+    assert np.all(yb[:pad] == POISON) and np.all(yb[pad + T:] == POISON), "wrote outside Y"
+    assert np.all(ob[:pad] == POISON) and np.all(ob[pad + rT:] == POISON), "wrote outside the reduction's output"
+    got_y, got_o = yb[pad: pad + T], ob[pad: pad + rT]
+    res = oracle_mod.grouped_gemm_bf16(wk.bits(X), wk.bits(W), ids.numpy())
+    _check_y(got_y, res, X.double().numpy(), W.double().numpy(), ids.numpy(), 1, K, H.tol_bf16(K))
+    # the same two results from the two separate calls
+    Y2 = torch.full((T, N), POISON, dtype=torch.int16, device=dev)
+    mb.moe_grouped_gemm(X.to(dev), W.to(dev), None, tmap, Y2, desc)
+    np.testing.assert_array_equal(got_y, H.y_bits(Y2))
+    if rT > 0:
+        assert not np.any(got_o == POISON), "an element of the reduction's output was never written"
+        o64, obf = oracle_mod.combine(wk.bits(Yin), None if wts is None else wts.numpy(), rT, rk)
+        err = np.abs(H.bf16_bits_to_f64(got_o) - o64)
+        A = np.abs(Yin.double().numpy().reshape(rT, rk, rN) * (1.0 if wts is None else wts.double().numpy()[:, :, None])).sum(axis=1)
+        assert np.all(err <= 2.0 ** -8 * np.abs(o64) * 1.001 + (rk + 1) * 2.0 ** -24 * A + 1e-30)
+        out2 = torch.full((rT, rN), POISON, dtype=torch.int16, device=dev)
+        mb.moe_combine(Yin_d, wts_d, rT, rk, rN, out2)
+        np.testing.assert_array_equal(got_o, H.y_bits(out2))
+
+
+def test_heterogeneous_batch_argument_errors(dev):
+    T, E, K, N = 300, 4, 128, 256
+    X = torch.ones((T, K), dtype=torch.bfloat16, device=dev)
+    W = torch.ones((E, K, N), dtype=torch.bfloat16, device=dev)
+    Y = torch.zeros((T, N), dtype=torch.bfloat16, device=dev)
+    ids = torch.zeros((T, 1), dtype=torch.int32, device=dev)
+    Yin = torch.ones((10 * 2, 64), dtype=torch.bfloat16, device=dev)
+    out = torch.zeros((10, 64), dtype=torch.bfloat16, device=dev)
+    tmap = mb.alloc_task_map(T, 1, E, 256, 256, N)
+    mb.moe_build_task_map(ids, T, 1, E, 256, 256, N, tmap)
+    d = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 256, 256)
+    assert mb.moe_grouped_gemm_batched(X, W, tmap, Y, d, Yin, None, 10, 2, 64, out, check=False) == mb.MOE_OK
+    assert mb.moe_grouped_gemm_batched(X, W, tmap, Y, d, Yin, None, 10, 2, 60, out, check=False) == mb.MOE_ERR_UNSUPPORTED   # N % 8
+    assert mb.moe_grouped_gemm_batched(X, W, tmap, Y, d, None, None, 10, 2, 64, out, check=False) == mb.MOE_ERR_INVALID_ARG
+    assert mb.moe_grouped_gemm_batched(X, W, tmap, Y, d, Yin, None, 10, 0, 64, out, check=False) == mb.MOE_ERR_INVALID_ARG
+    m128 = mb.alloc_task_map(T, 1, E, 128, 256, N)
+    mb.moe_build_task_map(ids, T, 1, E, 128, 256, N, m128)
+    d128 = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 128, 256)
+    assert mb.moe_grouped_gemm_batched(X, W, m128, Y, d128, Yin, None, 10, 2, 64, out, check=False) == mb.MOE_ERR_UNSUPPORTED   # no batched kernel
+    # a map that does not match makes the whole call a no-op, the reduction included
+    out.fill_(7.0)
+    Y.fill_(7.0)
+    assert mb.moe_grouped_gemm_batched(X, W, m128, Y, d, Yin, None, 10, 2, 64, out, check=False) == mb.MOE_OK
+    torch.cuda.synchronize()
+    assert bool((out == 7.0).all()) and bool((Y == 7.0).all())
+
+
 LAYER_CASES = [
     # T, k, E, hidden, inter, routing, weighted
     (300, 2, 8, 256, 384, "zipf", True),
