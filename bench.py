@@ -63,7 +63,7 @@ class Point:
     """Device buffers of one workload (optionally several weight copies to defeat the caches)."""
 
     def __init__(self, wl: wk.Workload, copies: int = 1, dev="cuda:0", order: int = 0, small=(0, 0), swiglu: bool = False,
-                 w_nk: bool = False, launch_mode: int = 0):
+                 w_nk: bool = False, launch_mode: int = 0, tail_split: bool = False):
         self.wl = wl
         self.w_nk = w_nk      # weights pre-packed as [E][N][K] (a labelled extra, never the headline)
         self.swiglu = swiglu  # fused gated activation: Y is [R, N/2]
@@ -96,6 +96,9 @@ class Point:
                                 mb.MOE_EPILOGUE_SWIGLU if swiglu else mb.MOE_EPILOGUE_NONE,
                                 mb.MOE_W_LAYOUT_NK if w_nk else mb.MOE_W_LAYOUT_KN, launch_mode)
         self.launch_mode = launch_mode
+        # the tiles of a partly filled last round split along K (moe_grouped_gemm_tail_split; 64 MiB workspace)
+        self.tail_ws = (torch.empty(mb.moe_tail_split_workspace_bytes() // 4, dtype=torch.float32, device=dev)
+                        if tail_split else None)
         self.tiling = mb.Tiling(wl.tile_m, wl.tile_n, order, small[0], small[1], self.slack)
 
     def build_map(self):
@@ -103,7 +106,10 @@ class Point:
         mb.moe_build_task_map_ex(self.ids, wl.T, wl.k, wl.E, wl.N, self.tiling, self.tmap)
 
     def gemm(self, i: int = 0):
-        mb.moe_grouped_gemm(self.X, self.W[i % len(self.W)], self.ids, self.tmap, self.Y, self.desc)
+        if self.tail_ws is not None:
+            mb.moe_grouped_gemm_tail_split(self.X, self.W[i % len(self.W)], self.tmap, self.Y, self.desc, self.tail_ws)
+        else:
+            mb.moe_grouped_gemm(self.X, self.W[i % len(self.W)], self.ids, self.tmap, self.Y, self.desc)
 
     def time(self, steps: int, warmup: int):
         """Returns (wall ms per step, mean GEMM-kernel ms, mean map-build ms) over `steps` steps.
@@ -191,7 +197,7 @@ class Point:
                     map_ms=round(map_ms, 4), tflops_step=round(tf_step, 2), tflops_gemm=round(tf_gemm, 2),
                     frac_mfma=round(tf_gemm / peak_t, 4), gbs_gemm=round(gbs, 1),
                     frac_hbm=round(gbs / PEAK_HBM_GBS, 4), bound=bound, alg_bytes=abytes, flops=wl.flops,
-                    launch_mode=self.launch_mode,
+                    launch_mode=self.launch_mode, tail_split=self.tail_ws is not None,
                     kernel="moe_gemm_pipe_kernel")
 
 
@@ -578,6 +584,15 @@ def main():
                 points.append(p.report(max(10, args.steps // 2), max(3, args.warmup // 2)))
                 del p
                 torch.cuda.empty_cache()
+                # plain 256 x 256 tilings whose tile count is not a whole number of rounds: also with the tail split
+                if (w.dtype == "bf16" and w.tile_m == 256 and w.tile_n == 256 and w.tile_m_slack == 0 and not small[0]
+                        and w.K % 64 == 0 and w.N % 256 == 0):
+                    p = Point(w, copies, order=order, launch_mode=lm, tail_split=True)
+                    r = p.report(max(10, args.steps // 2), max(3, args.warmup // 2))
+                    r["workload"] += "_tail_split"
+                    points.append(r)
+                    del p
+                    torch.cuda.empty_cache()
         if want is None or "neighbours" in want:
             # the fused gated activation on the headline shape, and the sum over a token's experts
             p = Point(wl, swiglu=True)

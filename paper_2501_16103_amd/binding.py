@@ -50,7 +50,7 @@ EXPORTS = [
     "moe_task_map_status", "moe_task_map_expand", "moe_grouped_gemm", "moe_tile_supported", "moe_combine",
     "moe_grouped_gemm_splitk", "moe_splitk_workspace_bytes", "moe_default_k_parts",
     "moe_grouped_gemm_splitk_static", "moe_splitk_static_scratch_bytes",
-    "moe_grouped_gemm_batched", "moe_reduce_task_tiles",
+    "moe_grouped_gemm_batched", "moe_reduce_task_tiles", "moe_grouped_gemm_tail_split", "moe_tail_split_workspace_bytes",
     "moe_strerror",
 ]
 
@@ -143,6 +143,11 @@ def lib() -> ctypes.CDLL:
                                                                        ctypes.POINTER(moe_reduce_task), ctypes.c_void_p]
         L.moe_reduce_task_tiles.restype = ctypes.c_int64
         L.moe_reduce_task_tiles.argtypes = [ctypes.c_int, ctypes.c_int]
+        L.moe_grouped_gemm_tail_split.restype = ctypes.c_int
+        L.moe_grouped_gemm_tail_split.argtypes = [ctypes.c_void_p] * 4 + [ctypes.POINTER(moe_gemm_desc), ctypes.c_void_p,
+                                                                          ctypes.c_size_t, ctypes.c_void_p]
+        L.moe_tail_split_workspace_bytes.restype = ctypes.c_size_t
+        L.moe_tail_split_workspace_bytes.argtypes = []
         L.moe_splitk_workspace_bytes.restype = ctypes.c_size_t
         L.moe_splitk_workspace_bytes.argtypes = [ctypes.c_int] * 4
         L.moe_default_k_parts.restype = ctypes.c_int
@@ -342,6 +347,23 @@ def moe_grouped_gemm_splitk(X: torch.Tensor, W: torch.Tensor, task_map: torch.Te
                                        _ptr(workspace), ctypes.c_size_t(nbytes), _stream() if X is not None else None)
     if check and rc != MOE_OK:
         raise MoeError(rc, "moe_grouped_gemm_splitk")
+    return rc
+
+
+def moe_tail_split_workspace_bytes() -> int:
+    return int(lib().moe_tail_split_workspace_bytes())
+
+
+def moe_grouped_gemm_tail_split(X: torch.Tensor, W: torch.Tensor, task_map: torch.Tensor, Y: torch.Tensor, desc: "GemmDesc",
+                                workspace: Optional[torch.Tensor], check: bool = True) -> int:
+    """moe_grouped_gemm with the tiles of a partly filled last round split along K; `workspace`: device tensor of
+    >= moe_tail_split_workspace_bytes() bytes."""
+    c = desc.c_struct()
+    nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    rc = lib().moe_grouped_gemm_tail_split(_ptr(X), _ptr(W), _ptr(task_map), _ptr(Y), ctypes.byref(c), _ptr(workspace),
+                                           ctypes.c_size_t(nbytes), _stream() if X is not None else None)
+    if check and rc != MOE_OK:
+        raise MoeError(rc, "moe_grouped_gemm_tail_split")
     return rc
 
 

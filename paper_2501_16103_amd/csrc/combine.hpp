@@ -57,6 +57,41 @@ __global__ __launch_bounds__(256) void moe_combine_kernel(const u32x4_t* __restr
                       (long long)gridDim.x * 256);
 }
 
+// Last step of a tail-split product: block (x, j) adds the parts of the x-th XCD's tail tile j (compact blocks
+// [x][j * P + p][BM][BN] of the workspace, p ascending), rounds once to bf16 and scatters the tile's rows to Y.
+template <int BM, int BN>
+__global__ __launch_bounds__(256) void moe_tail_reduce_kernel(GemmArgs a) {
+    const int32_t* __restrict__ map = a.map;
+    const MapLayout L = map_layout(a.E);
+    const int4 first_record = reinterpret_cast<const int4*>(map + L.off_records)[__lane_id()];
+    const int total = map[MOE_HDR_TOTAL_TILES];
+    if (!map_matches<BM, BN, 0, 0>(a, map)) return;
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    const TailSplit ts = tail_split(map, total, xcd, a.cus_per_xcd, a.K / 64);
+    if (ts.parts == 1 || j >= ts.tail) return;
+    int B;
+    if (!slot_to_block(map, total, xcd, ts.full + j, B)) return;
+    const moe_tiling g = {BM, BN, 0, 0, 0, 0};
+    const TileCoord tc = decode_block(map, L, g, B, first_record);
+    const float* base = a.partial + ((size_t)(xcd * a.cus_per_xcd + j * ts.parts) * BM) * BN;
+    const int32_t* rows = map + L.off_rows + tc.row_base;
+    u32x4_t* Y = static_cast<u32x4_t*>(a.Y);
+    constexpr int CPR = BN / 8;   // 8-column chunks per tile row
+    for (int c = threadIdx.x; c < tc.rows * CPR; c += 256) {
+        const int m = c / CPR, col = c - m * CPR;
+        const float* src = base + (size_t)m * BN + col * 8;
+        f32x4_t lo = *reinterpret_cast<const f32x4_t*>(src), hi = *reinterpret_cast<const f32x4_t*>(src + 4);
+        for (int p = 1; p < ts.parts; ++p) {
+            lo += *reinterpret_cast<const f32x4_t*>(src + (size_t)p * BM * BN);
+            hi += *reinterpret_cast<const f32x4_t*>(src + (size_t)p * BM * BN + 4);
+        }
+        u32x4_t o;
+        o.x = pack_bf16(lo[0], lo[1]); o.y = pack_bf16(lo[2], lo[3]);
+        o.z = pack_bf16(hi[0], hi[1]); o.w = pack_bf16(hi[2], hi[3]);
+        Y[((size_t)rows[m] * a.N + (size_t)tc.n_tile * BN) / 8 + col] = o;
+    }
+}
+
 // ---- heterogeneous batching (Sec. 3.2, Alg. 3): GEMM tasks and one reduction task in the same launch
 
 // 8-column chunks of output per tile of the reduction task: nu(reduction) = ceil(T * N / 8 / kReduceTileChunks).

@@ -48,6 +48,14 @@ struct GemmArgs {
     int tile_m_slack;                  // slack rows of the map's last m-tiles
     int swiglu;                        // 1: W = [gate | up] halves of N, Y[r, i] = silu(gate_i) * up_i, Y is [R, N/2]
     float* partial;                    // split-k launches: fp32 partial sums [gridDim.y][R (sorted row position)][N]
+    // split-k task functions: which part of K this workgroup runs, and where its partial sums go (set per workgroup
+    // by the kernel, not by the host): partial_tile != nullptr: row m of the tile at partial_tile + m * BN (a
+    // compact per-tile block); else row position p, column n at partial + (k_part * R + p) * N + n
+    int k_part, k_parts;
+    float* partial_tile;
+    // tail-split launches (cus_per_xcd > 0): the tiles of an XCD's last, partly filled round are left to the
+    // workgroups of the tail launch whenever those can split them (see tail_parts)
+    int cus_per_xcd;
     // heterogeneous launches: a reduction task batched with the GEMM tasks (Alg. 3 with two task types), else red_tiles = 0
     const void* red_Y;                 // [red_T][red_k][red_N] bf16, finished products of an earlier launch
     const float* red_w;                // [red_T][red_k] or nullptr
@@ -299,9 +307,9 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
         dw_off[j] = (uint32_t)krow * w_row_bytes + col_bytes;
     }
     // split-k: this workgroup's part of K (the row pitch of X and the k stride of W are those of the whole K)
-    const int k_parts = C::SPLITK ? (int)gridDim.y : 1;
+    const int k_parts = C::SPLITK ? a.k_parts : 1;
     const int KT = a.K / BK / k_parts;
-    const int k_first = C::SPLITK ? (int)blockIdx.y * KT * BK : 0;
+    const int k_first = C::SPLITK ? a.k_part * KT * BK : 0;
     const char* Xb = static_cast<const char*>(a.X) + (size_t)k_first * ES;
     // weight base of a tile: expert, and the first column the tile reads (half as far with the fused activation)
     auto w_base = [&](const TileCoord& t) {
@@ -716,12 +724,13 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
         } else if constexpr (C::SPLITK) {
             static_assert(!C::SPLITK || (!STREAM && !C::FP8 && !C::WKC), "split-k: bf16, weights as [E][K][N]");
             // fp32 partial sums, 16 bytes (4 columns of one row) per lane and block; no row ids needed
-            float* const part = a.partial + (size_t)blockIdx.y * ((size_t)a.T * a.k) * a.N;
+            float* const part = a.partial + (size_t)a.k_part * ((size_t)a.T * a.k) * a.N;
 #pragma unroll
             for (int mb = 0; mb < MBW; ++mb) {
                 const int m_local = (mb * C::WM + wm) * MF + lrow;
                 if (m_local >= tc.rows) continue;
-                float* prow = part + (size_t)(tc.row_base + m_local) * a.N + n0;
+                float* prow = a.partial_tile ? a.partial_tile + (size_t)m_local * BN
+                                             : part + (size_t)(tc.row_base + m_local) * a.N + n0;
 #pragma unroll
                 for (int nb = 0; nb < NBW; ++nb) {
 #pragma unroll
@@ -873,6 +882,26 @@ __device__ __forceinline__ int slots_of_xcd(const int32_t* __restrict__ map, int
     return left < 0 ? 0 : (left < per_xcd ? left : per_xcd);
 }
 
+// Tail split.  With one workgroup per tile an XCD's tiles run in rounds of `cus` (its CUs); when the last round is
+// only partly filled, the other CUs idle for a whole tile's duration.  If the t tiles of that round are few enough,
+// each is run by 2 or 4 workgroups instead, every one over a part of K (fp32 partial sums, added afterwards), so that
+// the last round is a half or a quarter as long.  The map is untouched: this is a property of the launch.
+__host__ __device__ inline int tail_parts(int t, int cus, int k_tiles) {
+    if (t <= 0) return 1;
+    if (4 * t <= cus && k_tiles % 4 == 0 && k_tiles / 4 >= 8) return 4;
+    if (2 * t <= cus && k_tiles % 2 == 0 && k_tiles / 2 >= 8) return 2;
+    return 1;
+}
+struct TailSplit { int full, tail, parts; };   // slots [0, full) run whole tiles, slots [full, full + tail) are split
+__device__ __forceinline__ TailSplit tail_split(const int32_t* __restrict__ map, int total, int xcd, int cus, int k_tiles) {
+    const int n_x = slots_of_xcd(map, total, xcd);
+    TailSplit ts;
+    ts.full = n_x / cus * cus;
+    ts.tail = n_x - ts.full;
+    ts.parts = tail_parts(ts.tail, cus, k_tiles);
+    return ts;
+}
+
 // Block index -> tile (Alg. 2 + 4), shared by the kernels below.  Returns false for surplus workgroups and for
 // a map that does not belong to this launch (wrong shape, tiling or status): those do nothing.
 template <int BM_BIG, int BN, int BM_SMALL, int SLACK>
@@ -884,6 +913,10 @@ __device__ __forceinline__ bool locate_tile(const GemmArgs& a, const int32_t* __
     if (!map_matches<BM_BIG, BN, BM_SMALL, SLACK>(a, map)) return false;
     int B;
     if (!slot_to_block(map, total, blockIdx.x & 7, blockIdx.x >> 3, B)) return false;
+    if (a.cus_per_xcd > 0) {
+        const TailSplit ts = tail_split(map, total, blockIdx.x & 7, a.cus_per_xcd, a.K / 64);
+        if (ts.parts > 1 && (int)(blockIdx.x >> 3) >= ts.full) return false;   // the tail launch runs this tile
+    }
     const moe_tiling g = {BM_BIG, BN, 0, BM_SMALL, a.small_max_rows, SLACK};
     tc = decode_block(map, L, g, B, first_record);
     return true;
@@ -913,7 +946,41 @@ __global__ __launch_bounds__(C::NT) void moe_gemm_pipe_kernel(GemmArgs a) {
     MapLayout L;
     TileCoord tc;
     if (!locate_tile<C::BM, C::BN, 0, C::SLACK>(a, a.map, L, tc)) return;
-    run_tile<C, Tails...>(a, a.map, L, tc, smem);
+    if constexpr (C::SPLITK) {
+        // one of gridDim.y workgroups that share the tile
+        GemmArgs b = a;
+        b.k_part = (int)blockIdx.y;
+        b.k_parts = (int)gridDim.y;
+        run_tile<C, Tails...>(b, a.map, L, tc, smem);
+    } else {
+        run_tile<C, Tails...>(a, a.map, L, tc, smem);
+    }
+}
+
+// The tail launch of a tail-split product: workgroup i of XCD x runs part i % P of the x-th XCD's tail tile i / P
+// (P = that XCD's number of parts) and leaves its fp32 sums in its own compact block of the workspace,
+// [x][i][BM][BN].  C and Tails are split-k task functions.
+template <class C, class... Tails>
+__global__ __launch_bounds__(C::NT) void moe_gemm_tail_kernel(GemmArgs a) {
+    static_assert(C::SPLITK && C::SLACK == 0, "split-k task functions");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int32_t* __restrict__ map = a.map;
+    const MapLayout L = map_layout(a.E);
+    const int4 first_record = reinterpret_cast<const int4*>(map + L.off_records)[__lane_id()];
+    const int total = map[MOE_HDR_TOTAL_TILES];
+    if (!map_matches<C::BM, C::BN, 0, 0>(a, map)) return;
+    const int xcd = blockIdx.x & 7, i = blockIdx.x >> 3;
+    const TailSplit ts = tail_split(map, total, xcd, a.cus_per_xcd, a.K / 64);
+    if (ts.parts == 1 || i >= ts.tail * ts.parts) return;
+    int B;
+    if (!slot_to_block(map, total, xcd, ts.full + i / ts.parts, B)) return;
+    const moe_tiling g = {C::BM, C::BN, 0, 0, 0, 0};
+    const TileCoord tc = decode_block(map, L, g, B, first_record);
+    GemmArgs b = a;
+    b.k_part = i % ts.parts;
+    b.k_parts = ts.parts;
+    b.partial_tile = a.partial + ((size_t)(xcd * a.cus_per_xcd + i) * C::BM) * C::BN;
+    run_tile<C, Tails...>(b, map, L, tc, smem);
 }
 
 // Two tiling strategies in one launch (Alg. 3 with K = 2 task types): the expert's row count picks the task

@@ -603,6 +603,128 @@ def test_heterogeneous_batch_argument_errors(dev):
     assert bool((out == 7.0).all()) and bool((Y == 7.0).all())
 
 
+def _tail_blocks(total, k_tiles, cus=32):
+    """Block indices that a tail-split launch runs in parts, and the number of parts, per the rule in moe_sb.h
+    (ascending sigma order: XCD x owns blocks [x * ceil(total / 8), ...))."""
+    per_xcd = (total + 7) // 8
+    out = {}
+    for x in range(8):
+        n_x = max(0, min(per_xcd, total - x * per_xcd))
+        full = n_x // cus * cus
+        t = n_x - full
+        parts = 1
+        if t > 0 and 4 * t <= cus and k_tiles % 4 == 0 and k_tiles // 4 >= 8:
+            parts = 4
+        elif t > 0 and 2 * t <= cus and k_tiles % 2 == 0 and k_tiles // 2 >= 8:
+            parts = 2
+        if parts > 1:
+            for B in range(x * per_xcd + full, x * per_xcd + n_x):
+                out[B] = parts
+    return out
+
+
+TAIL_CASES = [
+    # per-expert row counts (k = 1), K, N  (tile 256 x 256)                    tiles -> tail of each XCD
+    ([300, 0, 513, 129, 255, 700], 2048, 1024),        # 40 tiles: 5 per XCD, all of them tail, 4 parts
+    ([257, 320, 321, 256, 1, 64, 65, 0, 576], 1024, 512),   # 26 tiles, 4 per XCD (the last XCD fewer), K = 1024: 2 parts at most
+    ([9000, 6000, 4100], 2048, 1024),                  # 77 m-tiles x 4: 308 tiles, 39 per XCD: 32 whole + 7 tail tiles, 4 parts
+    ([5000, 5200, 3000], 1024, 1024),                  # 53 m-tiles x 4 = 212 tiles, 27 per XCD: too many tail tiles for any split
+    ([300, 200], 512, 256),                            # K too short to split: everything runs whole
+]
+
+
+@pytest.mark.parametrize("counts,K,N", TAIL_CASES)
+def test_tail_split_parity(dev, oracle_mod, counts, K, N):
+    """The tiles of a partly filled last round run in 2 or 4 parts along K: Y == oracle, nothing outside Y, every
+    element written; every tile outside the tails bit for bit what moe_grouped_gemm gives."""
+    from tests.test_gpu_parity import _build_map, _check_y, _ids_from_counts
+    E, T = len(counts), int(sum(counts))
+    wl = wk.Workload("parity_tail", T, E, 1, K, N, "bf16", "gauss_topk", 256, 256)
+    ids = _ids_from_counts(counts, 13 + E + K)
+    X, W = wk.make_x(wl), wk.make_w(wl)
+    pad = 3
+    buf = torch.full((T + 2 * pad, N), POISON, dtype=torch.int16, device=dev)
+    Y = buf[pad: pad + T]
+    tmap = _build_map(ids.to(dev), T, 1, E, 256, 256, N)
+    desc = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 256, 256)
+    guard = 1024
+    ws = torch.full((mb.moe_tail_split_workspace_bytes() // 4 + 2 * guard,), float("nan"), dtype=torch.float32, device=dev)
+    Xd, Wd = X.to(dev), W.to(dev)
+    mb.moe_grouped_gemm_tail_split(Xd, Wd, tmap, Y, desc, ws[guard: guard + mb.moe_tail_split_workspace_bytes() // 4])
+    torch.cuda.synchronize()
+    assert bool(torch.isnan(ws[:guard]).all()) and bool(torch.isnan(ws[-guard:]).all()), "wrote outside the workspace"
+    bits = buf.cpu().numpy().view(np.uint16)
+    assert np.all(bits[:pad] == POISON) and np.all(bits[pad + T:] == POISON), "wrote outside Y"
+    got = bits[pad: pad + T]
+    assert not np.any(got == POISON), "an output was never written"
+    tm = oracle_mod.build_task_map(ids.numpy(), T, 1, E, 256, 256, N)
+    table = oracle_mod.full_table(tm.counts, 256, 256, N)
+    tails = _tail_blocks(tm.total_tiles, K // 64)
+    if T <= 3000:
+        res = oracle_mod.grouped_gemm_bf16(wk.bits(X), wk.bits(W), ids.numpy())
+        _check_y(got, res, X.double().numpy(), W.double().numpy(), ids.numpy(), 1, K, H.tol_bf16(K))
+    else:
+        # the oracle on a sample of complete rows: the first and last row of every tail tile, and 300 others
+        rng = np.random.default_rng(5)
+        sel = [int(tm.sorted_rows[tm.offsets[e] + m * 256 + i]) for B, (e, m, n, rows) in enumerate(table) if B in tails for i in (0, rows - 1)]
+        sel = np.array(sorted(set(sel) | set(rng.choice(T, size=300, replace=False).tolist())), dtype=np.int32)
+        res = oracle_mod.grouped_gemm_bf16(wk.bits(X), wk.bits(W), ids.numpy(), rows=sel)
+        flat = ids.numpy().reshape(-1)
+        Xf, Wf = X.double().numpy(), W.double().numpy()
+        err = np.abs(H.bf16_bits_to_f64(got[sel]) - res.Y64)
+        A = np.zeros_like(err)
+        for e in range(E):
+            m = flat[sel] == e
+            if m.any():
+                A[m] = np.abs(Xf[sel[m]]) @ np.abs(Wf[e])
+        assert np.all(err <= 2.0 ** -8 * np.abs(res.Y64) * 1.001 + H.sum_err_coeff(K, False) * A + 1e-30)
+        assert (H.ulp_distance(got[sel], res.Ybf) == 0).mean() > 0.97
+    Y2 = torch.full((T, N), POISON, dtype=torch.int16, device=dev)
+    mb.moe_grouped_gemm(Xd, Wd, None, tmap, Y2, desc)
+    plain = H.y_bits(Y2)
+    whole = 0
+    for B, (e, m_tile, n_tile, rows) in enumerate(table):
+        if B in tails:
+            continue
+        rr = tm.sorted_rows[tm.offsets[e] + m_tile * 256: tm.offsets[e] + m_tile * 256 + rows]
+        np.testing.assert_array_equal(got[rr, n_tile * 256:(n_tile + 1) * 256], plain[rr, n_tile * 256:(n_tile + 1) * 256])
+        whole += 1
+    assert whole + len(tails) == tm.total_tiles
+    if K >= 1024 and tm.total_tiles in (40, 26, 308):
+        assert len(tails) > 0, "the case must exercise the split"
+    if not tails:
+        np.testing.assert_array_equal(got, plain)
+
+
+def test_tail_split_argument_errors(dev):
+    T, E, K, N = 300, 4, 1024, 256
+    X = torch.ones((T, K), dtype=torch.bfloat16, device=dev)
+    W = torch.ones((E, K, N), dtype=torch.bfloat16, device=dev)
+    Y = torch.full((T, N), 7.0, dtype=torch.bfloat16, device=dev)
+    ids = torch.zeros((T, 1), dtype=torch.int32, device=dev)
+    tmap = mb.alloc_task_map(T, 1, E, 256, 256, N)
+    mb.moe_build_task_map(ids, T, 1, E, 256, 256, N, tmap)
+    ws = torch.empty(mb.moe_tail_split_workspace_bytes() // 4, dtype=torch.float32, device=dev)
+    d = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 256, 256)
+    assert mb.moe_tail_split_workspace_bytes() == 8 * 32 * 256 * 256 * 4
+    assert mb.moe_grouped_gemm_tail_split(X, W, tmap, Y, d, ws, check=False) == mb.MOE_OK
+    assert mb.moe_grouped_gemm_tail_split(X, W, tmap, Y, d, ws[:1000], check=False) == mb.MOE_ERR_INVALID_ARG
+    assert mb.moe_grouped_gemm_tail_split(X, W, tmap, Y, d, None, check=False) == mb.MOE_ERR_INVALID_ARG
+    d128 = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 128, 256)
+    assert mb.moe_grouped_gemm_tail_split(X, W, tmap, Y, d128, ws, check=False) == mb.MOE_ERR_UNSUPPORTED
+    dsl = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 256, 256, tile_m_slack=32)
+    assert mb.moe_grouped_gemm_tail_split(X, W, tmap, Y, dsl, ws, check=False) == mb.MOE_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    assert bool((Y == float(K)).all())
+    # a map built for another problem: none of the three launches may write
+    other = mb.alloc_task_map(2 * T, 1, E, 256, 256, N)
+    mb.moe_build_task_map(torch.zeros((2 * T, 1), dtype=torch.int32, device=dev), 2 * T, 1, E, 256, 256, N, other)
+    Y.fill_(7.0)
+    assert mb.moe_grouped_gemm_tail_split(X, W, other, Y, d, ws, check=False) == mb.MOE_OK
+    torch.cuda.synchronize()
+    assert bool((Y == 7.0).all())
+
+
 LAYER_CASES = [
     # T, k, E, hidden, inter, routing, weighted
     (300, 2, 8, 256, 384, "zipf", True),
