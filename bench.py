@@ -97,7 +97,7 @@ class Point:
                                 mb.MOE_W_LAYOUT_NK if w_nk else mb.MOE_W_LAYOUT_KN, launch_mode)
         self.launch_mode = launch_mode
         # the tiles of a partly filled last round split along K (moe_grouped_gemm_tail_split; 64 MiB workspace)
-        self.tail_ws = (torch.empty(mb.moe_tail_split_workspace_bytes() // 4, dtype=torch.float32, device=dev)
+        self.tail_ws = (torch.empty(mb.moe_tail_split_workspace_bytes(wl.tile_m, wl.tile_n) // 4, dtype=torch.float32, device=dev)
                         if tail_split else None)
         self.tiling = mb.Tiling(wl.tile_m, wl.tile_n, order, small[0], small[1], self.slack)
 
@@ -584,8 +584,8 @@ def main():
                 points.append(p.report(max(10, args.steps // 2), max(3, args.warmup // 2)))
                 del p
                 torch.cuda.empty_cache()
-                # plain 256 x 256 tilings whose tile count is not a whole number of rounds: also with the tail split
-                if (w.dtype == "bf16" and w.tile_m == 256 and w.tile_n == 256 and w.tile_m_slack == 0 and not small[0]
+                # tilings that have a tail-split launch (it pays when the tile count is not a whole number of rounds)
+                if (w.dtype == "bf16" and w.tile_m in (64, 128, 256) and w.tile_n == 256 and w.tile_m_slack == 0 and not small[0]
                         and w.K % 64 == 0 and w.N % 256 == 0):
                     p = Point(w, copies, order=order, launch_mode=lm, tail_split=True)
                     r = p.report(max(10, args.steps // 2), max(3, args.warmup // 2))

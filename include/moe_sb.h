@@ -327,19 +327,23 @@ size_t moe_splitk_static_scratch_bytes(void);
 /*
  * moe_grouped_gemm for launches whose last round of tiles is only partly filled (Sec. 3.1's map is unchanged; this
  * is a property of the launch).  With one workgroup per tile an XCD's tiles run in rounds of its 32 CUs; when the
- * last round holds t <= 16 tiles the other CUs idle for a whole tile's duration.  Here those t tiles are run by
- * 4 (t <= 8) or 2 (t <= 16) workgroups each, every one over a part of K; their fp32 sums go to `workspace` and are
- * added in ascending order of the parts, rounded once to bf16 and scattered to Y.  All other tiles run exactly as in
- * moe_grouped_gemm (their results are bit for bit the same); the tail tiles differ from it in summation order only.
- * Three launches on `stream`.  The split happens per XCD and only if every part keeps at least 8 k-tiles.
- *   workspace  DEVICE, 16-byte aligned, at least moe_tail_split_workspace_bytes() = 64 MiB, owned by the caller,
- *              contents undefined afterwards; calls that share it must not overlap.
- * Supported: bf16, MOE_W_LAYOUT_KN, MOE_EPILOGUE_NONE, 256 x 256 tiles without slack rows, one tiling strategy,
- * K % 64 == 0, N % 256 == 0; anything else MOE_ERR_UNSUPPORTED.
+ * last round holds t < 32 tiles the other CUs idle for a whole tile's duration.  Here those t tiles are run by
+ * P workgroups each, every one over a part of K; their fp32 sums go to `workspace` and are added in ascending order
+ * of the parts, rounded once to bf16 and scattered to Y.  P is the smallest of 1, 2, 4 that minimises the last
+ * round's length ceil(t * P / 32) / P (e.g. t <= 8: 4 parts, a quarter; t = 16: 2 parts, a half; t = 22: 4 parts,
+ * three quarters; t = 27: no split), chosen per XCD on the device, and only if every part keeps at least 8 k-tiles.
+ * All other tiles run exactly as in moe_grouped_gemm (their results are bit for bit the same); the tail tiles differ
+ * from it in summation order only.  Three launches on `stream`.
+ *   workspace  DEVICE, 16-byte aligned, at least moe_tail_split_workspace_bytes(tile_m, tile_n) bytes
+ *              (8 * 128 * tile_m * tile_n * 4: 256 MiB for 256 x 256 tiles), owned by the caller, contents undefined
+ *              afterwards; calls that share it must not overlap.
+ * Supported: bf16, MOE_W_LAYOUT_KN, MOE_EPILOGUE_NONE, tiles 256 x 256, 128 x 256 or 64 x 256 without slack rows, one
+ * tiling strategy, K % 64 == 0, N % 256 == 0; anything else MOE_ERR_UNSUPPORTED.
  */
 int moe_grouped_gemm_tail_split(const void* X, const void* W, const void* task_map, void* Y, const moe_gemm_desc* desc,
                                 void* workspace, size_t workspace_bytes, void* stream);
-size_t moe_tail_split_workspace_bytes(void);
+/* HOST, pure; 0 for a tile shape without a tail-split launch. */
+size_t moe_tail_split_workspace_bytes(int tile_m, int tile_n);
 
 /* Bytes of workspace moe_grouped_gemm_splitk needs (0 for k_parts < 2 or bad sizes).  HOST, pure. */
 size_t moe_splitk_workspace_bytes(int T, int k, int N, int k_parts);

@@ -147,7 +147,7 @@ def lib() -> ctypes.CDLL:
         L.moe_grouped_gemm_tail_split.argtypes = [ctypes.c_void_p] * 4 + [ctypes.POINTER(moe_gemm_desc), ctypes.c_void_p,
                                                                           ctypes.c_size_t, ctypes.c_void_p]
         L.moe_tail_split_workspace_bytes.restype = ctypes.c_size_t
-        L.moe_tail_split_workspace_bytes.argtypes = []
+        L.moe_tail_split_workspace_bytes.argtypes = [ctypes.c_int, ctypes.c_int]
         L.moe_splitk_workspace_bytes.restype = ctypes.c_size_t
         L.moe_splitk_workspace_bytes.argtypes = [ctypes.c_int] * 4
         L.moe_default_k_parts.restype = ctypes.c_int
@@ -350,14 +350,14 @@ def moe_grouped_gemm_splitk(X: torch.Tensor, W: torch.Tensor, task_map: torch.Te
     return rc
 
 
-def moe_tail_split_workspace_bytes() -> int:
-    return int(lib().moe_tail_split_workspace_bytes())
+def moe_tail_split_workspace_bytes(tile_m: int = 256, tile_n: int = 256) -> int:
+    return int(lib().moe_tail_split_workspace_bytes(tile_m, tile_n))
 
 
 def moe_grouped_gemm_tail_split(X: torch.Tensor, W: torch.Tensor, task_map: torch.Tensor, Y: torch.Tensor, desc: "GemmDesc",
                                 workspace: Optional[torch.Tensor], check: bool = True) -> int:
     """moe_grouped_gemm with the tiles of a partly filled last round split along K; `workspace`: device tensor of
-    >= moe_tail_split_workspace_bytes() bytes."""
+    >= moe_tail_split_workspace_bytes(tile_m, tile_n) bytes."""
     c = desc.c_struct()
     nbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     rc = lib().moe_grouped_gemm_tail_split(_ptr(X), _ptr(W), _ptr(task_map), _ptr(Y), ctypes.byref(c), _ptr(workspace),

@@ -58,7 +58,7 @@ __global__ __launch_bounds__(256) void moe_combine_kernel(const u32x4_t* __restr
 }
 
 // Last step of a tail-split product: block (x, j) adds the parts of the x-th XCD's tail tile j (compact blocks
-// [x][j * P + p][BM][BN] of the workspace, p ascending), rounds once to bf16 and scatters the tile's rows to Y.
+// [x][j * P + p][BM][BN] of the workspace, kTailBlocksPerXcd blocks per XCD, p ascending), rounds once to bf16 and scatters the tile's rows to Y.
 template <int BM, int BN>
 __global__ __launch_bounds__(256) void moe_tail_reduce_kernel(GemmArgs a) {
     const int32_t* __restrict__ map = a.map;
@@ -73,7 +73,7 @@ __global__ __launch_bounds__(256) void moe_tail_reduce_kernel(GemmArgs a) {
     if (!slot_to_block(map, total, xcd, ts.full + j, B)) return;
     const moe_tiling g = {BM, BN, 0, 0, 0, 0};
     const TileCoord tc = decode_block(map, L, g, B, first_record);
-    const float* base = a.partial + ((size_t)(xcd * a.cus_per_xcd + j * ts.parts) * BM) * BN;
+    const float* base = a.partial + ((size_t)(xcd * kTailBlocksPerXcd + j * ts.parts) * BM) * BN;
     const int32_t* rows = map + L.off_rows + tc.row_base;
     u32x4_t* Y = static_cast<u32x4_t*>(a.Y);
     constexpr int CPR = BN / 8;   // 8-column chunks per tile row

@@ -883,15 +883,21 @@ __device__ __forceinline__ int slots_of_xcd(const int32_t* __restrict__ map, int
 }
 
 // Tail split.  With one workgroup per tile an XCD's tiles run in rounds of `cus` (its CUs); when the last round is
-// only partly filled, the other CUs idle for a whole tile's duration.  If the t tiles of that round are few enough,
-// each is run by 2 or 4 workgroups instead, every one over a part of K (fp32 partial sums, added afterwards), so that
-// the last round is a half or a quarter as long.  The map is untouched: this is a property of the launch.
+// only partly filled, the other CUs idle for a whole tile's duration.  The t tiles of that round can instead be run
+// by P = 2 or 4 workgroups each, every one over a part of K (fp32 partial sums, added afterwards): the t * P parts
+// then take ceil(t * P / cus) sub-rounds of 1 / P of a tile's duration.  P is the smallest of 1, 2, 4 that makes
+// this shortest (parts keep at least 8 k-tiles).  The map is untouched: this is a property of the launch.
 __host__ __device__ inline int tail_parts(int t, int cus, int k_tiles) {
     if (t <= 0) return 1;
-    if (4 * t <= cus && k_tiles % 4 == 0 && k_tiles / 4 >= 8) return 4;
-    if (2 * t <= cus && k_tiles % 2 == 0 && k_tiles / 2 >= 8) return 2;
-    return 1;
+    int best = 1, best_len = 4;                       // duration of the last round in quarters of a tile
+    for (int P = 2; P <= 4; P *= 2) {
+        if (k_tiles % P != 0 || k_tiles / P < 8) break;
+        const int len = (t * P + cus - 1) / cus * (4 / P);
+        if (len < best_len) { best = P; best_len = len; }
+    }
+    return best;
 }
+constexpr int kTailBlocksPerXcd = 128;   // upper bound on t * P (t < cus <= 32, P <= 4): blocks of the tail workspace per XCD
 struct TailSplit { int full, tail, parts; };   // slots [0, full) run whole tiles, slots [full, full + tail) are split
 __device__ __forceinline__ TailSplit tail_split(const int32_t* __restrict__ map, int total, int xcd, int cus, int k_tiles) {
     const int n_x = slots_of_xcd(map, total, xcd);
@@ -979,7 +985,7 @@ __global__ __launch_bounds__(C::NT) void moe_gemm_tail_kernel(GemmArgs a) {
     GemmArgs b = a;
     b.k_part = i % ts.parts;
     b.k_parts = ts.parts;
-    b.partial_tile = a.partial + ((size_t)(xcd * a.cus_per_xcd + i) * C::BM) * C::BN;
+    b.partial_tile = a.partial + ((size_t)(xcd * kTailBlocksPerXcd + i) * C::BM) * C::BN;
     run_tile<C, Tails...>(b, map, L, tc, smem);
 }
 

@@ -337,7 +337,26 @@ int run_splitk(const void* X, const void* W, const void* task_map, void* Y, cons
 
 // ---- tail split (see tail_parts in gemm_kernel.hpp); MI355X: 8 XCDs of 32 CUs
 constexpr int kCusPerXcd = 32;
-constexpr size_t kTailWorkspaceBytes = size_t(8) * kCusPerXcd * 256 * 256 * sizeof(float);
+static_assert(kTailBlocksPerXcd >= 4 * (kCusPerXcd - 1), "workspace blocks per XCD");
+
+size_t tail_workspace_bytes(int tile_m, int tile_n) {
+    return size_t(8) * kTailBlocksPerXcd * tile_m * tile_n * sizeof(float);
+}
+
+// The three launches of a tail-split product: whole tiles, the parts of the tail tiles, their sums.
+template <class C, class... Tails>
+int launch_tail_split(const GemmArgs& a, int64_t grid, hipStream_t s) {
+    const int r1 = launch_pipe<C, Tails...>(a, grid, 0, s);
+    if (r1 != MOE_OK) return r1;
+    using TailC = SplitK<C>;
+    static unsigned long long attr_done = 0;
+    const void* fn = reinterpret_cast<const void*>(&moe_gemm_tail_kernel<TailC, SplitK<Tails>...>);
+    if (ensure_lds_attr(fn, TailC::LDS_BYTES, &attr_done) != MOE_OK) return MOE_ERR_HIP;
+    moe_gemm_tail_kernel<TailC, SplitK<Tails>...><<<dim3(8 * kTailBlocksPerXcd), dim3(TailC::NT), TailC::LDS_BYTES, s>>>(a);
+    if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
+    moe_tail_reduce_kernel<C::BM, C::BN><<<dim3(8 * kCusPerXcd), dim3(256), 0, s>>>(a);
+    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+}
 
 // This device's address of the static scratch array, looked up once per device (with that device current) and
 // kept: every GPU the library runs on holds its own copy of the array at its own address.  In host code the
@@ -621,45 +640,42 @@ int moe_grouped_gemm_splitk(const void* X, const void* W, const void* task_map, 
 
 size_t moe_splitk_static_scratch_bytes(void) { return kStaticScratchBytes; }
 
-size_t moe_tail_split_workspace_bytes(void) { return kTailWorkspaceBytes; }
+size_t moe_tail_split_workspace_bytes(int tile_m, int tile_n) {
+    if ((tile_m != 64 && tile_m != 128 && tile_m != 256) || tile_n != 256) return 0;
+    return tail_workspace_bytes(tile_m, tile_n);
+}
 
 int moe_grouped_gemm_tail_split(const void* X, const void* W, const void* task_map, void* Y, const moe_gemm_desc* d,
                                 void* workspace, size_t workspace_bytes, void* stream) {
     if (!d) return MOE_ERR_INVALID_ARG;
     if (d->T < 0 || d->k < 1 || d->E < 1 || d->E > kMaxE || d->k > d->E || d->K < 1 || d->N < 1) return MOE_ERR_INVALID_ARG;
-    // the shapes of the split-k product (how many parts, if any, is decided per XCD on the device)
+    // the shapes the split-k task functions cover (how many parts, if any, is decided per XCD on the device)
     if (d->dtype != MOE_DTYPE_BF16 || d->w_layout != MOE_W_LAYOUT_KN || d->epilogue != MOE_EPILOGUE_NONE ||
-        d->tile_m != 256 || d->tile_n != 256 || d->tile_m_small != 0 || d->small_max_rows != 0 || d->tile_m_slack != 0)
+        (d->tile_m != 64 && d->tile_m != 128 && d->tile_m != 256) || d->tile_n != 256 || d->tile_m_small != 0 ||
+        d->small_max_rows != 0 || d->tile_m_slack != 0)
         return MOE_ERR_UNSUPPORTED;
     if (d->K % 64 != 0 || d->N % 256 != 0) return MOE_ERR_UNSUPPORTED;
     if (d->T == 0) return MOE_OK;
     if (!X || !W || !task_map || !Y || !workspace) return MOE_ERR_INVALID_ARG;
     if (((uintptr_t)X & 15) || ((uintptr_t)W & 15) || ((uintptr_t)Y & 15) || ((uintptr_t)task_map & 15) || ((uintptr_t)workspace & 15))
         return MOE_ERR_INVALID_ARG;
-    if (workspace_bytes < kTailWorkspaceBytes) return MOE_ERR_INVALID_ARG;
+    if (workspace_bytes < tail_workspace_bytes(d->tile_m, d->tile_n)) return MOE_ERR_INVALID_ARG;
     if ((int64_t)d->T * d->K * 2 >= (int64_t)1 << 32) return MOE_ERR_UNSUPPORTED;
     GemmArgs a{};
     a.X = X; a.W = W; a.map = static_cast<const int32_t*>(task_map); a.Y = Y;
     a.T = d->T; a.k = d->k; a.E = d->E; a.K = d->K; a.N = d->N;
     a.partial = static_cast<float*>(workspace);
     a.cus_per_xcd = kCusPerXcd;
-    int64_t grid = moe_grid_upper_bound_tiled(d->T, d->k, d->E, 256, 256, d->N, 0, 0);
+    int64_t grid = moe_grid_upper_bound_tiled(d->T, d->k, d->E, d->tile_m, d->tile_n, d->N, 0, 0);
     if (grid == 0) return MOE_OK;
     grid = (grid + 7) / 8 * 8 + 16;
     if (grid > 0x7fffffff) return MOE_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    // whole tiles of the full rounds (and of tails that are not split)
-    const int r1 = launch_pipe<Pb_256x256, Ps_64x256, Ps_128x256>(a, grid, 0, s);
-    if (r1 != MOE_OK) return r1;
-    // the parts of the tail tiles, then their sums
-    using TailC = SplitK<Pb_256x256>;
-    static unsigned long long attr_done = 0;
-    const void* fn = reinterpret_cast<const void*>(&moe_gemm_tail_kernel<TailC, SplitK<Ps_64x256>, SplitK<Ps_128x256>>);
-    if (ensure_lds_attr(fn, TailC::LDS_BYTES, &attr_done) != MOE_OK) return MOE_ERR_HIP;
-    moe_gemm_tail_kernel<TailC, SplitK<Ps_64x256>, SplitK<Ps_128x256>><<<dim3(8 * kCusPerXcd), dim3(TailC::NT), TailC::LDS_BYTES, s>>>(a);
-    if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
-    moe_tail_reduce_kernel<256, 256><<<dim3(8 * kCusPerXcd), dim3(256), 0, s>>>(a);
-    return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
+    switch (d->tile_m) {
+        case 256: return launch_tail_split<Pb_256x256, Ps_64x256, Ps_128x256>(a, grid, s);
+        case 128: return launch_tail_split<Pb_128x256, Ps_64x256>(a, grid, s);
+        default: return launch_tail_split<Pb_64x256>(a, grid, s);
+    }
 }
 
 int moe_grouped_gemm_splitk_static(const void* X, const void* W, const void* task_map, void* Y, const moe_gemm_desc* d,

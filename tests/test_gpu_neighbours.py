@@ -612,11 +612,13 @@ def _tail_blocks(total, k_tiles, cus=32):
         n_x = max(0, min(per_xcd, total - x * per_xcd))
         full = n_x // cus * cus
         t = n_x - full
-        parts = 1
-        if t > 0 and 4 * t <= cus and k_tiles % 4 == 0 and k_tiles // 4 >= 8:
-            parts = 4
-        elif t > 0 and 2 * t <= cus and k_tiles % 2 == 0 and k_tiles // 2 >= 8:
-            parts = 2
+        parts, best = 1, 4     # length of the last round in quarters of a tile
+        for P in (2, 4):
+            if t == 0 or k_tiles % P or k_tiles // P < 8:
+                break
+            length = -(-t * P // cus) * (4 // P)
+            if length < best:
+                parts, best = P, length
         if parts > 1:
             for B in range(x * per_xcd + full, x * per_xcd + n_x):
                 out[B] = parts
@@ -624,41 +626,46 @@ def _tail_blocks(total, k_tiles, cus=32):
 
 
 TAIL_CASES = [
-    # per-expert row counts (k = 1), K, N  (tile 256 x 256)                    tiles -> tail of each XCD
-    ([300, 0, 513, 129, 255, 700], 2048, 1024),        # 40 tiles: 5 per XCD, all of them tail, 4 parts
-    ([257, 320, 321, 256, 1, 64, 65, 0, 576], 1024, 512),   # 26 tiles, 4 per XCD (the last XCD fewer), K = 1024: 2 parts at most
-    ([9000, 6000, 4100], 2048, 1024),                  # 77 m-tiles x 4: 308 tiles, 39 per XCD: 32 whole + 7 tail tiles, 4 parts
-    ([5000, 5200, 3000], 1024, 1024),                  # 53 m-tiles x 4 = 212 tiles, 27 per XCD: too many tail tiles for any split
-    ([300, 200], 512, 256),                            # K too short to split: everything runs whole
+    # tile_m, per-expert row counts (k = 1), K, N  (tile_n = 256)                    tiles -> tail of each XCD
+    (256, [300, 0, 513, 129, 255, 700], 2048, 1024),        # 40 tiles: 5 per XCD, all of them tail, 4 parts
+    (256, [257, 320, 321, 256, 1, 64, 65, 0, 576], 1024, 512),   # 26 tiles, 4 per XCD (the last XCD fewer), K = 1024: 2 parts at most
+    (256, [9000, 6000, 4100], 2048, 1024),                  # 77 m-tiles x 4: 308 tiles, 39 per XCD: 32 whole + 7 tail tiles, 4 parts
+    (256, [5000, 5200, 3000], 2048, 1024),                  # 212 tiles, 27 per XCD: no split shortens the round
+    (256, [4000, 5200, 2000], 2048, 1024),                  # 180 tiles, 23 per XCD: 4 parts in three sub-rounds
+    (256, [300, 200], 512, 256),                            # K too short to split: everything runs whole
+    (128, [70, 3, 140, 129, 300], 2048, 1024),              # 128-row tiles (and the 64-row task function for the small ones)
+    (128, [2000, 2100, 900], 1024, 2048),                   # 41 m-tiles x 8 = 328 tiles: 32 whole + 9 tail per XCD, 2 parts
+    (64, [172, 107, 61, 39, 52, 23, 32, 26], 2048, 1024),   # 64-row tiles, the row counts of a skewed routing
 ]
 
 
-@pytest.mark.parametrize("counts,K,N", TAIL_CASES)
-def test_tail_split_parity(dev, oracle_mod, counts, K, N):
+@pytest.mark.parametrize("tile_m,counts,K,N", TAIL_CASES)
+def test_tail_split_parity(dev, oracle_mod, tile_m, counts, K, N):
     """The tiles of a partly filled last round run in 2 or 4 parts along K: Y == oracle, nothing outside Y, every
     element written; every tile outside the tails bit for bit what moe_grouped_gemm gives."""
     from tests.test_gpu_parity import _build_map, _check_y, _ids_from_counts
     E, T = len(counts), int(sum(counts))
-    wl = wk.Workload("parity_tail", T, E, 1, K, N, "bf16", "gauss_topk", 256, 256)
+    wl = wk.Workload("parity_tail", T, E, 1, K, N, "bf16", "gauss_topk", tile_m, 256)
     ids = _ids_from_counts(counts, 13 + E + K)
     X, W = wk.make_x(wl), wk.make_w(wl)
     pad = 3
     buf = torch.full((T + 2 * pad, N), POISON, dtype=torch.int16, device=dev)
     Y = buf[pad: pad + T]
-    tmap = _build_map(ids.to(dev), T, 1, E, 256, 256, N)
-    desc = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 256, 256)
+    tmap = _build_map(ids.to(dev), T, 1, E, tile_m, 256, N)
+    desc = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, tile_m, 256)
     guard = 1024
-    ws = torch.full((mb.moe_tail_split_workspace_bytes() // 4 + 2 * guard,), float("nan"), dtype=torch.float32, device=dev)
+    nws = mb.moe_tail_split_workspace_bytes(tile_m, 256) // 4
+    ws = torch.full((nws + 2 * guard,), float("nan"), dtype=torch.float32, device=dev)
     Xd, Wd = X.to(dev), W.to(dev)
-    mb.moe_grouped_gemm_tail_split(Xd, Wd, tmap, Y, desc, ws[guard: guard + mb.moe_tail_split_workspace_bytes() // 4])
+    mb.moe_grouped_gemm_tail_split(Xd, Wd, tmap, Y, desc, ws[guard: guard + nws])
     torch.cuda.synchronize()
     assert bool(torch.isnan(ws[:guard]).all()) and bool(torch.isnan(ws[-guard:]).all()), "wrote outside the workspace"
     bits = buf.cpu().numpy().view(np.uint16)
     assert np.all(bits[:pad] == POISON) and np.all(bits[pad + T:] == POISON), "wrote outside Y"
     got = bits[pad: pad + T]
     assert not np.any(got == POISON), "an output was never written"
-    tm = oracle_mod.build_task_map(ids.numpy(), T, 1, E, 256, 256, N)
-    table = oracle_mod.full_table(tm.counts, 256, 256, N)
+    tm = oracle_mod.build_task_map(ids.numpy(), T, 1, E, tile_m, 256, N)
+    table = oracle_mod.full_table(tm.counts, tile_m, 256, N)
     tails = _tail_blocks(tm.total_tiles, K // 64)
     if T <= 3000:
         res = oracle_mod.grouped_gemm_bf16(wk.bits(X), wk.bits(W), ids.numpy())
@@ -666,7 +673,7 @@ def test_tail_split_parity(dev, oracle_mod, counts, K, N):
     else:
         # the oracle on a sample of complete rows: the first and last row of every tail tile, and 300 others
         rng = np.random.default_rng(5)
-        sel = [int(tm.sorted_rows[tm.offsets[e] + m * 256 + i]) for B, (e, m, n, rows) in enumerate(table) if B in tails for i in (0, rows - 1)]
+        sel = [int(tm.sorted_rows[tm.offsets[e] + m * tile_m + i]) for B, (e, m, n, rows) in enumerate(table) if B in tails for i in (0, rows - 1)]
         sel = np.array(sorted(set(sel) | set(rng.choice(T, size=300, replace=False).tolist())), dtype=np.int32)
         res = oracle_mod.grouped_gemm_bf16(wk.bits(X), wk.bits(W), ids.numpy(), rows=sel)
         flat = ids.numpy().reshape(-1)
@@ -686,11 +693,11 @@ def test_tail_split_parity(dev, oracle_mod, counts, K, N):
     for B, (e, m_tile, n_tile, rows) in enumerate(table):
         if B in tails:
             continue
-        rr = tm.sorted_rows[tm.offsets[e] + m_tile * 256: tm.offsets[e] + m_tile * 256 + rows]
+        rr = tm.sorted_rows[tm.offsets[e] + m_tile * tile_m: tm.offsets[e] + m_tile * tile_m + rows]
         np.testing.assert_array_equal(got[rr, n_tile * 256:(n_tile + 1) * 256], plain[rr, n_tile * 256:(n_tile + 1) * 256])
         whole += 1
     assert whole + len(tails) == tm.total_tiles
-    if K >= 1024 and tm.total_tiles in (40, 26, 308):
+    if K >= 1024 and tm.total_tiles not in (212,):
         assert len(tails) > 0, "the case must exercise the split"
     if not tails:
         np.testing.assert_array_equal(got, plain)
@@ -704,14 +711,16 @@ def test_tail_split_argument_errors(dev):
     ids = torch.zeros((T, 1), dtype=torch.int32, device=dev)
     tmap = mb.alloc_task_map(T, 1, E, 256, 256, N)
     mb.moe_build_task_map(ids, T, 1, E, 256, 256, N, tmap)
-    ws = torch.empty(mb.moe_tail_split_workspace_bytes() // 4, dtype=torch.float32, device=dev)
+    ws = torch.empty(mb.moe_tail_split_workspace_bytes(256, 256) // 4, dtype=torch.float32, device=dev)
     d = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 256, 256)
-    assert mb.moe_tail_split_workspace_bytes() == 8 * 32 * 256 * 256 * 4
+    assert mb.moe_tail_split_workspace_bytes(256, 256) == 8 * 128 * 256 * 256 * 4
+    assert mb.moe_tail_split_workspace_bytes(64, 256) == 8 * 128 * 64 * 256 * 4
+    assert mb.moe_tail_split_workspace_bytes(32, 256) == 0 and mb.moe_tail_split_workspace_bytes(256, 128) == 0
     assert mb.moe_grouped_gemm_tail_split(X, W, tmap, Y, d, ws, check=False) == mb.MOE_OK
     assert mb.moe_grouped_gemm_tail_split(X, W, tmap, Y, d, ws[:1000], check=False) == mb.MOE_ERR_INVALID_ARG
     assert mb.moe_grouped_gemm_tail_split(X, W, tmap, Y, d, None, check=False) == mb.MOE_ERR_INVALID_ARG
-    d128 = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 128, 256)
-    assert mb.moe_grouped_gemm_tail_split(X, W, tmap, Y, d128, ws, check=False) == mb.MOE_ERR_UNSUPPORTED
+    d32 = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 32, 256)
+    assert mb.moe_grouped_gemm_tail_split(X, W, tmap, Y, d32, ws, check=False) == mb.MOE_ERR_UNSUPPORTED
     dsl = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 256, 256, tile_m_slack=32)
     assert mb.moe_grouped_gemm_tail_split(X, W, tmap, Y, dsl, ws, check=False) == mb.MOE_ERR_UNSUPPORTED
     torch.cuda.synchronize()
