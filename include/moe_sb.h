@@ -335,10 +335,10 @@ size_t moe_splitk_static_scratch_bytes(void);
  * All other tiles run exactly as in moe_grouped_gemm (their results are bit for bit the same); the tail tiles differ
  * from it in summation order only.  Three launches on `stream`.
  *   workspace  DEVICE, 16-byte aligned, at least moe_tail_split_workspace_bytes(tile_m, tile_n) bytes
- *              (8 * 128 * tile_m * tile_n * 4: 256 MiB for 256 x 256 tiles), owned by the caller, contents undefined
+ *              (8 * 128 * rows * tile_n * 4 with rows = tile_m, 288 for 256-row tiles: 288 MiB), owned by the caller, contents undefined
  *              afterwards; calls that share it must not overlap.
- * Supported: bf16, MOE_W_LAYOUT_KN, MOE_EPILOGUE_NONE, tiles 256 x 256, 128 x 256 or 64 x 256 without slack rows, one
- * tiling strategy, K % 64 == 0, N % 256 == 0; anything else MOE_ERR_UNSUPPORTED.
+ * Supported: bf16, MOE_W_LAYOUT_KN, MOE_EPILOGUE_NONE, tiles 256 x 256 (without slack rows or with 32), 128 x 256 or
+ * 64 x 256 (without), one tiling strategy, K % 64 == 0, N % 256 == 0; anything else MOE_ERR_UNSUPPORTED.
  */
 int moe_grouped_gemm_tail_split(const void* X, const void* W, const void* task_map, void* Y, const moe_gemm_desc* desc,
                                 void* workspace, size_t workspace_bytes, void* stream);

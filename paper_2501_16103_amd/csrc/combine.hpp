@@ -58,22 +58,23 @@ __global__ __launch_bounds__(256) void moe_combine_kernel(const u32x4_t* __restr
 }
 
 // Last step of a tail-split product: block (x, j) adds the parts of the x-th XCD's tail tile j (compact blocks
-// [x][j * P + p][BM][BN] of the workspace, kTailBlocksPerXcd blocks per XCD, p ascending), rounds once to bf16 and scatters the tile's rows to Y.
-template <int BM, int BN>
+// [x][j * P + p][BM + SLACK][BN] of the workspace, kTailBlocksPerXcd blocks per XCD, p ascending), rounds once to bf16 and scatters the tile's rows to Y.
+template <int BM, int BN, int SLACK>
 __global__ __launch_bounds__(256) void moe_tail_reduce_kernel(GemmArgs a) {
+    constexpr int BMC = BM + SLACK;   // rows of a workspace block
     const int32_t* __restrict__ map = a.map;
     const MapLayout L = map_layout(a.E);
     const int4 first_record = reinterpret_cast<const int4*>(map + L.off_records)[__lane_id()];
     const int total = map[MOE_HDR_TOTAL_TILES];
-    if (!map_matches<BM, BN, 0, 0>(a, map)) return;
+    if (!map_matches<BM, BN, 0, SLACK>(a, map)) return;
     const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
     const TailSplit ts = tail_split(map, total, xcd, a.cus_per_xcd, a.K / 64);
     if (ts.parts == 1 || j >= ts.tail) return;
     int B;
     if (!slot_to_block(map, total, xcd, ts.full + j, B)) return;
-    const moe_tiling g = {BM, BN, 0, 0, 0, 0};
+    const moe_tiling g = {BM, BN, 0, 0, 0, SLACK};
     const TileCoord tc = decode_block(map, L, g, B, first_record);
-    const float* base = a.partial + ((size_t)(xcd * kTailBlocksPerXcd + j * ts.parts) * BM) * BN;
+    const float* base = a.partial + ((size_t)(xcd * kTailBlocksPerXcd + j * ts.parts) * BMC) * BN;
     const int32_t* rows = map + L.off_rows + tc.row_base;
     u32x4_t* Y = static_cast<u32x4_t*>(a.Y);
     constexpr int CPR = BN / 8;   // 8-column chunks per tile row
@@ -82,8 +83,8 @@ __global__ __launch_bounds__(256) void moe_tail_reduce_kernel(GemmArgs a) {
         const float* src = base + (size_t)m * BN + col * 8;
         f32x4_t lo = *reinterpret_cast<const f32x4_t*>(src), hi = *reinterpret_cast<const f32x4_t*>(src + 4);
         for (int p = 1; p < ts.parts; ++p) {
-            lo += *reinterpret_cast<const f32x4_t*>(src + (size_t)p * BM * BN);
-            hi += *reinterpret_cast<const f32x4_t*>(src + (size_t)p * BM * BN + 4);
+            lo += *reinterpret_cast<const f32x4_t*>(src + (size_t)p * BMC * BN);
+            hi += *reinterpret_cast<const f32x4_t*>(src + (size_t)p * BMC * BN + 4);
         }
         u32x4_t o;
         o.x = pack_bf16(lo[0], lo[1]); o.y = pack_bf16(lo[2], lo[3]);

@@ -965,27 +965,27 @@ __global__ __launch_bounds__(C::NT) void moe_gemm_pipe_kernel(GemmArgs a) {
 
 // The tail launch of a tail-split product: workgroup i of XCD x runs part i % P of the x-th XCD's tail tile i / P
 // (P = that XCD's number of parts) and leaves its fp32 sums in its own compact block of the workspace,
-// [x][i][BM][BN].  C and Tails are split-k task functions.
+// [x][i][BM + SLACK][BN].  C and Tails are split-k task functions.
 template <class C, class... Tails>
 __global__ __launch_bounds__(C::NT) void moe_gemm_tail_kernel(GemmArgs a) {
-    static_assert(C::SPLITK && C::SLACK == 0, "split-k task functions");
+    static_assert(C::SPLITK, "split-k task functions");
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int32_t* __restrict__ map = a.map;
     const MapLayout L = map_layout(a.E);
     const int4 first_record = reinterpret_cast<const int4*>(map + L.off_records)[__lane_id()];
     const int total = map[MOE_HDR_TOTAL_TILES];
-    if (!map_matches<C::BM, C::BN, 0, 0>(a, map)) return;
+    if (!map_matches<C::BM, C::BN, 0, C::SLACK>(a, map)) return;
     const int xcd = blockIdx.x & 7, i = blockIdx.x >> 3;
     const TailSplit ts = tail_split(map, total, xcd, a.cus_per_xcd, a.K / 64);
     if (ts.parts == 1 || i >= ts.tail * ts.parts) return;
     int B;
     if (!slot_to_block(map, total, xcd, ts.full + i / ts.parts, B)) return;
-    const moe_tiling g = {C::BM, C::BN, 0, 0, 0, 0};
+    const moe_tiling g = {C::BM, C::BN, 0, 0, 0, C::SLACK};
     const TileCoord tc = decode_block(map, L, g, B, first_record);
     GemmArgs b = a;
     b.k_part = i % ts.parts;
     b.k_parts = ts.parts;
-    b.partial_tile = a.partial + ((size_t)(xcd * kTailBlocksPerXcd + i) * C::BM) * C::BN;
+    b.partial_tile = a.partial + ((size_t)(xcd * kTailBlocksPerXcd + i) * C::BMC) * C::BN;
     run_tile<C, Tails...>(b, map, L, tc, smem);
 }
 

@@ -339,8 +339,8 @@ int run_splitk(const void* X, const void* W, const void* task_map, void* Y, cons
 constexpr int kCusPerXcd = 32;
 static_assert(kTailBlocksPerXcd >= 4 * (kCusPerXcd - 1), "workspace blocks per XCD");
 
-size_t tail_workspace_bytes(int tile_m, int tile_n) {
-    return size_t(8) * kTailBlocksPerXcd * tile_m * tile_n * sizeof(float);
+size_t tail_workspace_bytes(int tile_m, int tile_n) {   // (256-row blocks with room for 32 slack rows)
+    return size_t(8) * kTailBlocksPerXcd * (tile_m == 256 ? 288 : tile_m) * tile_n * sizeof(float);
 }
 
 // The three launches of a tail-split product: whole tiles, the parts of the tail tiles, their sums.
@@ -354,7 +354,7 @@ int launch_tail_split(const GemmArgs& a, int64_t grid, hipStream_t s) {
     if (ensure_lds_attr(fn, TailC::LDS_BYTES, &attr_done) != MOE_OK) return MOE_ERR_HIP;
     moe_gemm_tail_kernel<TailC, SplitK<Tails>...><<<dim3(8 * kTailBlocksPerXcd), dim3(TailC::NT), TailC::LDS_BYTES, s>>>(a);
     if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
-    moe_tail_reduce_kernel<C::BM, C::BN><<<dim3(8 * kCusPerXcd), dim3(256), 0, s>>>(a);
+    moe_tail_reduce_kernel<C::BM, C::BN, C::SLACK><<<dim3(8 * kCusPerXcd), dim3(256), 0, s>>>(a);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
@@ -652,7 +652,7 @@ int moe_grouped_gemm_tail_split(const void* X, const void* W, const void* task_m
     // the shapes the split-k task functions cover (how many parts, if any, is decided per XCD on the device)
     if (d->dtype != MOE_DTYPE_BF16 || d->w_layout != MOE_W_LAYOUT_KN || d->epilogue != MOE_EPILOGUE_NONE ||
         (d->tile_m != 64 && d->tile_m != 128 && d->tile_m != 256) || d->tile_n != 256 || d->tile_m_small != 0 ||
-        d->small_max_rows != 0 || d->tile_m_slack != 0)
+        d->small_max_rows != 0 || (d->tile_m_slack != 0 && !(d->tile_m == 256 && d->tile_m_slack == 32)))
         return MOE_ERR_UNSUPPORTED;
     if (d->K % 64 != 0 || d->N % 256 != 0) return MOE_ERR_UNSUPPORTED;
     if (d->T == 0) return MOE_OK;
@@ -664,6 +664,7 @@ int moe_grouped_gemm_tail_split(const void* X, const void* W, const void* task_m
     GemmArgs a{};
     a.X = X; a.W = W; a.map = static_cast<const int32_t*>(task_map); a.Y = Y;
     a.T = d->T; a.k = d->k; a.E = d->E; a.K = d->K; a.N = d->N;
+    a.tile_m_slack = d->tile_m_slack;
     a.partial = static_cast<float*>(workspace);
     a.cus_per_xcd = kCusPerXcd;
     int64_t grid = moe_grid_upper_bound_tiled(d->T, d->k, d->E, d->tile_m, d->tile_n, d->N, 0, 0);
@@ -672,7 +673,8 @@ int moe_grouped_gemm_tail_split(const void* X, const void* W, const void* task_m
     if (grid > 0x7fffffff) return MOE_ERR_UNSUPPORTED;
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (d->tile_m) {
-        case 256: return launch_tail_split<Pb_256x256, Ps_64x256, Ps_128x256>(a, grid, s);
+        case 256: return d->tile_m_slack == 32 ? launch_tail_split<Pb_256x256s32, Ps_64x256, Ps_128x256>(a, grid, s)
+                                               : launch_tail_split<Pb_256x256, Ps_64x256, Ps_128x256>(a, grid, s);
         case 128: return launch_tail_split<Pb_128x256, Ps_64x256>(a, grid, s);
         default: return launch_tail_split<Pb_64x256>(a, grid, s);
     }

@@ -636,6 +636,8 @@ TAIL_CASES = [
     (128, [70, 3, 140, 129, 300], 2048, 1024),              # 128-row tiles (and the 64-row task function for the small ones)
     (128, [2000, 2100, 900], 1024, 2048),                   # 41 m-tiles x 8 = 328 tiles: 32 whole + 9 tail per XCD, 2 parts
     (64, [172, 107, 61, 39, 52, 23, 32, 26], 2048, 1024),   # 64-row tiles, the row counts of a skewed routing
+    (-256, [1025, 1040, 991, 1055, 280, 300], 2048, 512),   # (negative: 32 slack rows) tail tiles of 257 .. 287 rows
+    (-256, [9000, 6000, 4113], 2048, 1024),                 # slack rows, whole rounds and a tail
 ]
 
 
@@ -644,6 +646,8 @@ def test_tail_split_parity(dev, oracle_mod, tile_m, counts, K, N):
     """The tiles of a partly filled last round run in 2 or 4 parts along K: Y == oracle, nothing outside Y, every
     element written; every tile outside the tails bit for bit what moe_grouped_gemm gives."""
     from tests.test_gpu_parity import _build_map, _check_y, _ids_from_counts
+    slack = 32 if tile_m < 0 else 0
+    tile_m = abs(tile_m)
     E, T = len(counts), int(sum(counts))
     wl = wk.Workload("parity_tail", T, E, 1, K, N, "bf16", "gauss_topk", tile_m, 256)
     ids = _ids_from_counts(counts, 13 + E + K)
@@ -651,8 +655,8 @@ def test_tail_split_parity(dev, oracle_mod, tile_m, counts, K, N):
     pad = 3
     buf = torch.full((T + 2 * pad, N), POISON, dtype=torch.int16, device=dev)
     Y = buf[pad: pad + T]
-    tmap = _build_map(ids.to(dev), T, 1, E, tile_m, 256, N)
-    desc = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, tile_m, 256)
+    tmap = _build_map(ids.to(dev), T, 1, E, tile_m, 256, N, slack=slack)
+    desc = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, tile_m, 256, tile_m_slack=slack)
     guard = 1024
     nws = mb.moe_tail_split_workspace_bytes(tile_m, 256) // 4
     ws = torch.full((nws + 2 * guard,), float("nan"), dtype=torch.float32, device=dev)
@@ -664,8 +668,8 @@ def test_tail_split_parity(dev, oracle_mod, tile_m, counts, K, N):
     assert np.all(bits[:pad] == POISON) and np.all(bits[pad + T:] == POISON), "wrote outside Y"
     got = bits[pad: pad + T]
     assert not np.any(got == POISON), "an output was never written"
-    tm = oracle_mod.build_task_map(ids.numpy(), T, 1, E, tile_m, 256, N)
-    table = oracle_mod.full_table(tm.counts, tile_m, 256, N)
+    tm = oracle_mod.build_task_map(ids.numpy(), T, 1, E, tile_m, 256, N, tile_m_slack=slack)
+    table = oracle_mod.full_table(tm.counts, tile_m, 256, N, tile_m_slack=slack)
     tails = _tail_blocks(tm.total_tiles, K // 64)
     if T <= 3000:
         res = oracle_mod.grouped_gemm_bf16(wk.bits(X), wk.bits(W), ids.numpy())
@@ -713,7 +717,7 @@ def test_tail_split_argument_errors(dev):
     mb.moe_build_task_map(ids, T, 1, E, 256, 256, N, tmap)
     ws = torch.empty(mb.moe_tail_split_workspace_bytes(256, 256) // 4, dtype=torch.float32, device=dev)
     d = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 256, 256)
-    assert mb.moe_tail_split_workspace_bytes(256, 256) == 8 * 128 * 256 * 256 * 4
+    assert mb.moe_tail_split_workspace_bytes(256, 256) == 8 * 128 * 288 * 256 * 4
     assert mb.moe_tail_split_workspace_bytes(64, 256) == 8 * 128 * 64 * 256 * 4
     assert mb.moe_tail_split_workspace_bytes(32, 256) == 0 and mb.moe_tail_split_workspace_bytes(256, 128) == 0
     assert mb.moe_grouped_gemm_tail_split(X, W, tmap, Y, d, ws, check=False) == mb.MOE_OK
@@ -721,7 +725,7 @@ def test_tail_split_argument_errors(dev):
     assert mb.moe_grouped_gemm_tail_split(X, W, tmap, Y, d, None, check=False) == mb.MOE_ERR_INVALID_ARG
     d32 = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 32, 256)
     assert mb.moe_grouped_gemm_tail_split(X, W, tmap, Y, d32, ws, check=False) == mb.MOE_ERR_UNSUPPORTED
-    dsl = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 256, 256, tile_m_slack=32)
+    dsl = mb.GemmDesc(mb.MOE_DTYPE_BF16, T, 1, E, K, N, 256, 256, tile_m_slack=64)
     assert mb.moe_grouped_gemm_tail_split(X, W, tmap, Y, dsl, ws, check=False) == mb.MOE_ERR_UNSUPPORTED
     torch.cuda.synchronize()
     assert bool((Y == float(K)).all())
