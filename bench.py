@@ -508,8 +508,11 @@ def main():
                             "ms": round(ms, 3), "tflops": round(flops / (ms * 1e-3) / 1e12, 1)})
         # the 256x256x64 tile's loop, one ingredient at a time (LDS reads, barrier, DMA from cache, half of it from HBM)
         src = (torch.randn((513 << 20) // 2, device="cuda:0") * 0.5).to(torch.bfloat16)
+        # ... and the same ingredients in the schedule of the large tile's k loop (the two wavefronts of a SIMD alternate)
         for mode, what in ((1, "MFMA + LDS fragment reads"), (2, "+ barrier per k-tile"), (3, "+ DMA from cache"),
-                           (4, "+ half of the DMA bytes from HBM")):
+                           (4, "+ half of the DMA bytes from HBM"),
+                           (10, "alternating roles: MFMA + LDS fragment reads + 4 barriers per k-tile"),
+                           (11, "alternating roles: + DMA from cache"), (12, "alternating roles: + half of the DMA bytes from HBM")):
             probe.moe_probe_pipeline(mode, 1000, src, sink)
             ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
             torch.cuda.synchronize()

@@ -34,10 +34,14 @@ int moe_probe_mfma(int block, int random_operands, int iters, void* sink, void* 
  *   4: as 3 with half of those bytes from lines never touched before (about the real kernel's HBM share);
  *   5-8: no MFMAs, the LDS pipe alone (no FLOPs): 5 the 16-byte fragment reads of every k-step (8 per lane,
  *   8 KiB per wavefront), 6 the transposing 8-byte reads (8 per lane, 4 KiB), 7 both, 8 the DMA writes
- *   (4 instructions of 1 KiB per wavefront and k-step), 9 both kinds of reads and the DMA writes together.
+ *   (4 instructions of 1 KiB per wavefront and k-step), 9 both kinds of reads and the DMA writes together;
+ *   10-12: the ingredients of modes 2-4 scheduled as the large bf16 tile's k loop schedules them: the two wavefronts
+ *   of a SIMD alternate, one issuing a k-step's MFMAs back to back from registers while the other reloads its
+ *   fragments, four workgroup barriers per k-tile (10: MFMAs + LDS reads + barriers, 11: + DMA from cache,
+ *   12: + half of the DMA bytes from HBM).
  * Enqueues one kernel of 256 workgroups x 512 threads; FLOPs of the launch = 256 * 8 * iters * 524288
  * (iters counts k-steps: even, >= 2).  `src`: DEVICE memory, 16-byte aligned, read only, at least 1 MiB
- * (mode 4: 513 MiB); its first 64 KiB become the fragments, so fill it with bf16 values of the magnitude of
+ * (modes 4 and 12: 513 MiB); its first 64 KiB become the fragments, so fill it with bf16 values of the magnitude of
  * real operands.  `sink`: DEVICE memory of at least 4 bytes that the kernel may write.
  * Returns -1 for another mode, an odd or too small iters, a NULL or misaligned pointer or a
  * src_bytes below the stated minimum. */

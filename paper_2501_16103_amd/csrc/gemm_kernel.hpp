@@ -137,6 +137,8 @@ struct PipeCfg {
     static constexpr bool PERWAVE = MF == 16 && MBW_BODY >= 4;
     // ... and with at least four weight blocks per wavefront the fragments are reloaded in place (see reads_after)
     static constexpr bool XROLL = PERWAVE && WTN / MF >= 4;
+    // ... and the bf16 [K][N] ones run their k loop in two alternating roles (see run_pp in pipe_tile)
+    static constexpr bool PP = XROLL && !WKC_ && !FP8_ && NS_ == 2 && BK_ / KS == 2;
     static constexpr int XROW = BK * ES, CPR = XROW / 16;
     static constexpr int WROW = BN * ES, CPRW = WROW / 16;
     // the token tile in LDS is rounded up so that every wavefront issues the same number of DMA instructions
@@ -351,15 +353,16 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
 
     if (C::EARLY_W) {
         if constexpr (C::WHALF) {
+            // (alternating roles: the loop's first iteration fetches the ring's last stage like every other one)
 #pragma unroll
-            for (int q = 0; q < C::NSWH; ++q)
+            for (int q = 0; q < (C::PP ? 4 : C::NSWH); ++q)
                 if (q < 2 * KT) {
 #pragma unroll
                     for (int jj = 0; jj < WI / 2; ++jj) dma_wh(jj, q, q);
                 }
         } else {
 #pragma unroll
-            for (int s = 0; s < NSW; ++s)
+            for (int s = 0; s < (C::PP ? NS : NSW); ++s)
                 if (s < KT) {
 #pragma unroll
                     for (int j = 0; j < WI; ++j) dma_w(j, s, s, false, 2);
@@ -487,9 +490,7 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
     };
     // i-th MFMA of a k-step over nmb row blocks: row-block-major, or (XROLL) the first half of the weight blocks
     // for every row block and then the second half, which lets the first half's fragments be reloaded in place
-    auto mfma_one = [&](int i, int nmb, int buf, bool tail) __attribute__((always_inline)) {
-        const int mb = C::XROLL ? (i % (NBW / 2 * nmb)) / (NBW / 2) : i / NBW;
-        const int nb = C::XROLL ? i / (NBW / 2 * nmb) * (NBW / 2) + i % (NBW / 2) : i % NBW;
+    auto mfma_at = [&](int mb, int nb, int buf, bool tail) __attribute__((always_inline)) {
         if (tail && mb >= mb_live) return;
         if constexpr (C::FP8) {
             const u32x2_t xv = {xq[C::XROLL ? 0 : buf][mb].x, xq[C::XROLL ? 0 : buf][mb].y};
@@ -499,9 +500,21 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
             const int wb = wbuf(buf, nb);
             const u32x4_t wv = {wq[wb][nb][0].x, wq[wb][nb][0].y, wq[wb][nb][1].x, wq[wb][nb][1].y};
             const bf16x8_t wf = __builtin_bit_cast(bf16x8_t, wv), xf = __builtin_bit_cast(bf16x8_t, xq[C::XROLL ? 0 : buf][mb]);
-            if constexpr (MF == 32) acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[nb][mb], 0, 0, 0);
+            if constexpr (C::PP) {
+                // Written out so that the sum stays in its registers: left to itself the register allocator moves
+                // accumulators into fragment registers that have just become free and copies them back at the end
+                // of the loop (tens of moves per k-tile, and spills among the MFMAs).  The accumulator is only ever
+                // written by this instruction with the same destination, which may follow itself back to back; its
+                // first use outside the loop comes after a barrier and a wait.
+                asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(acc[nb][mb]) : "v"(wf), "v"(xf));
+            } else if constexpr (MF == 32) acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf, xf, acc[nb][mb], 0, 0, 0);
             else acc[nb][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf, xf, acc[nb][mb], 0, 0, 0);
         }
+    };
+    auto mfma_one = [&](int i, int nmb, int buf, bool tail) __attribute__((always_inline)) {
+        const int mb = C::XROLL ? (i % (NBW / 2 * nmb)) / (NBW / 2) : i / NBW;
+        const int nb = C::XROLL ? i / (NBW / 2 * nmb) * (NBW / 2) + i % (NBW / 2) : i % NBW;
+        mfma_at(mb, nb, buf, tail);
     };
 
     TileCoord tc_next = tc;       // streaming: the tile after the current one
@@ -620,6 +633,134 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
         for (; kt < KT; ++kt) iteration(kt, std::false_type{});
     };
 
+    // The k loop in two alternating roles (PP tiles; two k-steps per k-tile, two token stages).  The hardware places
+    // wavefronts w and w + NW/2 of a workgroup on the same SIMD; they take opposite roles.  Time is cut into slots
+    // by workgroup barriers, four per k-tile; in every slot one role issues a whole k-step's MFMAs back to back
+    // (M), all fragments already in registers, while the other (L) reloads its single-buffered fragments for its
+    // next k-step -- so no wavefront ever waits for an LDS read between two MFMAs, and the SIMD's MFMA pipe always
+    // has a wavefront that wants it:
+    //            slot 1        slot 2        slot 3             slot 4
+    //   role 0   M(kt, 0)      L(kt, 1)      M(kt, 1), wait     L(kt+1, 0)
+    //   role 1   L(kt, 0)      M(kt, 0)      L(kt, 1), wait     M(kt, 1)
+    // After slot 1 nobody reads the weights of k-step 0 of tile kt any more, after slot 3 nothing of tile kt; the
+    // wait in slot 3 is for the wavefront's own DMAs of tile kt+1, which the barrier behind it publishes.  Refills,
+    // per wavefront in this order: slot 1: first half of the weight instructions that become free with the barrier
+    // after slot 3 of tile kt-1; slot 2: the other half (half-stage ring: k-step 0 of tile kt, just read); slot 4:
+    // token tile kt+2.  At the wait only the weight instructions of slots 1 and 2 (WI of them) may be in flight.
+    // The prologue fills two stages of each ring; the last two iterations of a tile fetch nothing.
+    // In an M slot the DMA instructions go between the MFMAs, spread over the slot.
+    auto run_pp = [&](auto nmb_tag, auto xil_tag, auto tail_tag, auto role_tag) __attribute__((always_inline)) {
+        constexpr int NMB = decltype(nmb_tag)::value, ROLE = decltype(role_tag)::value;
+        constexpr bool TAIL = decltype(tail_tag)::value;
+        constexpr int NM = NBW * NMB, NREADS = WREADS + NMB, WH = WI / 2;
+        // token-row instructions of this role's wavefronts that cover at least one row of the tile (the tile in LDS
+        // is rounded up to whole instructions per wavefront; the upper wavefronts' last one may be all padding)
+        constexpr int XI_ROLE = (C::BMC + XROWS_PER_INST * NW - 1 - ROLE * (NW / 2) * XROWS_PER_INST) / (XROWS_PER_INST * NW);
+        constexpr int XIL = decltype(xil_tag)::value < XI_ROLE ? decltype(xil_tag)::value : XI_ROLE;
+        static_assert(KSTEPS == 2 && NS == 2 && NSW == 3 && WI % 2 == 0 && !STREAM && C::EARLY_W && C::XROLL, "alternating roles");
+        auto bar = []() __attribute__((always_inline)) {
+            MOE_SCHED_FENCE();
+            __builtin_amdgcn_s_barrier();
+            MOE_SCHED_FENCE();
+        };
+        auto lgkm0 = []() __attribute__((always_inline)) { __builtin_amdgcn_s_waitcnt(0xc07f); };
+        auto reads = [&](int sx, int sw, int kk) __attribute__((always_inline)) {
+            MOE_SCHED_FENCE();
+#pragma unroll
+            for (int r = 0; r < NREADS; ++r) read_one(r, sx, sw, kk, 0, TAIL);
+        };
+        // a k-step's MFMAs (row-block-major), with ND DMA instructions dma(0) .. dma(ND-1) spread between them
+        auto mma = [&](auto nd_tag, auto&& dma) __attribute__((always_inline)) {
+            constexpr int ND = decltype(nd_tag)::value, SP = ND > 0 ? NM / ND : NM;
+            static_assert(ND <= NM, "one DMA instruction per MFMA at most");
+            MOE_SCHED_FENCE();
+#pragma unroll
+            for (int i = 0; i < NM; ++i) {
+                mfma_at(i / NBW, i % NBW, 0, TAIL);
+                if (ND > 0 && i % SP == SP / 2 && i / SP < ND) dma(i / SP);
+                MOE_SCHED_FENCE();
+            }
+        };
+        if (first) {
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                if (s < KT) {
+#pragma unroll
+                    for (int d = 0; d < XIL; ++d) dma_x(d, s, s, false);
+                }
+            }
+            wait_vmcnt<0>();
+            __syncthreads();
+            if (ROLE == 0) {
+                reads(0, 0, 0);
+                lgkm0();
+            }
+        }
+        auto iteration = [&](int kt, auto steady_tag) __attribute__((always_inline)) {
+            constexpr bool STEADY = decltype(steady_tag)::value;   // kt + 2 < KT: the refills have a target (else there are none)
+            const int nxt = cur ^ 1;
+            const int nxtw = C::WHALF ? (curw + 2 >= C::NSWH ? curw + 2 - C::NSWH : curw + 2) : (curw + 1 == NSW ? 0 : curw + 1);
+            const int prevw = C::WHALF ? (curw == 0 ? C::NSWH - 1 : curw - 1) : (curw == 0 ? NSW - 1 : curw - 1);
+            // weight instructions into the stage that the barrier after slot 3 of tile kt-1 freed (whole stages: tile
+            // kt+2, first half of its instructions; half-stages: half-k-tile 2 kt + 4), then the second half (half-stages:
+            // half-k-tile 2 kt + 5 into the half-stage of k-step 0 of tile kt); the loop's first iteration fills the
+            // stage that the prologue left empty
+            auto wa = [&](int j) __attribute__((always_inline)) {
+                if constexpr (STEADY) {
+                    if constexpr (C::WHALF) dma_wh(j, 2 * kt + 4, prevw);
+                    else dma_w(j, kt + 2, prevw, false, 0);
+                }
+            };
+            auto wb = [&](int j) __attribute__((always_inline)) {
+                if constexpr (STEADY) {
+                    if constexpr (C::WHALF) dma_wh(j, 2 * kt + 5, curw);
+                    else dma_w(WH + j, kt + 2, prevw, false, 0);
+                }
+            };
+            auto xr = [&](int j) __attribute__((always_inline)) {
+                if constexpr (STEADY) dma_x(j, kt + 2, cur, false);
+            };
+            auto none = [](int) __attribute__((always_inline)) {};
+            using std::integral_constant;
+            if constexpr (ROLE == 0) {
+                mma(integral_constant<int, WH>{}, wa);
+                bar();
+                reads(cur, curw, 1);
+#pragma unroll
+                for (int j = 0; j < WH; ++j) wb(j);
+                lgkm0();
+                bar();
+                mma(integral_constant<int, 0>{}, none);
+                if (STEADY) wait_vmcnt<WI>(); else wait_vmcnt<0>();
+                bar();
+                if (STEADY || kt + 1 < KT) reads(nxt, nxtw, 0);
+#pragma unroll
+                for (int j = 0; j < XIL; ++j) xr(j);
+                lgkm0();
+                bar();
+            } else {
+                reads(cur, curw, 0);
+#pragma unroll
+                for (int j = 0; j < WH; ++j) wa(j);
+                lgkm0();
+                bar();
+                mma(integral_constant<int, WH>{}, wb);
+                bar();
+                reads(cur, curw, 1);
+                lgkm0();
+                if (STEADY) wait_vmcnt<WI>(); else wait_vmcnt<0>();
+                bar();
+                mma(integral_constant<int, XIL>{}, xr);
+                bar();
+            }
+            cur = nxt;
+            curw = nxtw;
+        };
+        int kt = 0;
+        for (; kt + 2 < KT; ++kt) iteration(kt, std::true_type{});
+        for (; kt < KT; ++kt) iteration(kt, std::false_type{});
+    };
+
     char* Yb = static_cast<char*>(a.Y);
     const size_t y_row_bytes = (size_t)(a.swiglu ? a.N >> 1 : a.N) * 2;
     auto store4 = [](char* p, float v0, float v1, float v2, float v3) {
@@ -675,7 +816,12 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
 
         using std::integral_constant;
         auto run_nt = [&](auto nmb_tag, auto xil_tag, auto tail_tag) __attribute__((always_inline)) {
-            run(nmb_tag, xil_tag, tail_tag, integral_constant<int, C::BM <= 128 ? 2 : 0>{});
+            if constexpr (C::PP) {
+                if (wave < NW / 2) run_pp(nmb_tag, xil_tag, tail_tag, integral_constant<int, 0>{});
+                else run_pp(nmb_tag, xil_tag, tail_tag, integral_constant<int, 1>{});
+            } else {
+                run(nmb_tag, xil_tag, tail_tag, integral_constant<int, C::BM <= 128 ? 2 : 0>{});
+            }
         };
         if constexpr (C::PERWAVE) {
             // 16-row blocks: every wavefront runs the copy of the loop compiled for its own number of live blocks
@@ -691,7 +837,12 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
                 }
             };
             for_each_int<C::MBW_BODY / 2, MBW>(try_nmb);
-            if (!done) run_nt(integral_constant<int, C::MBW_BODY>{}, integral_constant<int, XI_BODY>{}, std::true_type{});
+            if (!done) {
+                // (alternating roles: the copy for the fewest blocks instead; its surplus blocks multiply rows that
+                // are never stored, and every wavefront of the workgroup keeps the same barriers)
+                if constexpr (C::PP) run_nt(integral_constant<int, C::MBW_BODY / 2>{}, integral_constant<int, XI_BODY>{}, std::false_type{});
+                else run_nt(integral_constant<int, C::MBW_BODY>{}, integral_constant<int, XI_BODY>{}, std::true_type{});
+            }
         } else if (C::SLACK > 0 && tc.rows > C::BM) {
             // every wavefront moves its share of the slack rows; only those whose slack block holds a real row compute it
             if (mb_live == MBW) run_nt(integral_constant<int, MBW>{}, integral_constant<int, XI>{}, std::false_type{});

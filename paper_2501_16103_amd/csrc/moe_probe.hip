@@ -43,15 +43,15 @@ int moe_probe_mfma(int block, int random_operands, int iters, void* sink, void* 
 }
 
 int moe_probe_pipeline(int mode, int iters, const void* src, size_t src_bytes, void* sink, void* stream) {
-    const size_t need = mode == 4 ? (size_t(513) << 20) : (size_t(1) << 20);
-    if (mode < 1 || mode > 9 || iters < 2 || (iters & 1) || !src || !sink || src_bytes < need ||
+    const size_t need = (mode == 4 || mode == 12) ? (size_t(513) << 20) : (size_t(1) << 20);
+    if (mode < 1 || mode > 12 || iters < 2 || (iters & 1) || !src || !sink || src_bytes < need ||
         (reinterpret_cast<uintptr_t>(src) & 15))
         return kInvalid;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const char* in = static_cast<const char*>(src);
     float* out = static_cast<float*>(sink);
     constexpr int lds = 96 * 1024;   // one workgroup per CU, as for the tile it imitates
-    static unsigned long long done[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};
+    static unsigned long long done[12] = {0};
     auto go = [&](auto kernel, unsigned long long* d) {
         if (ensure_lds_attr(reinterpret_cast<const void*>(kernel), lds, d) != kOk) return int(kHip);
         kernel<<<256, 512, lds, s>>>(iters, in, out);
@@ -66,7 +66,10 @@ int moe_probe_pipeline(int mode, int iters, const void* src, size_t src_bytes, v
         case 6: return go(&moe::pipeline_probe_kernel<6>, &done[5]);
         case 7: return go(&moe::pipeline_probe_kernel<7>, &done[6]);
         case 8: return go(&moe::pipeline_probe_kernel<8>, &done[7]);
-        default: return go(&moe::pipeline_probe_kernel<9>, &done[8]);
+        case 9: return go(&moe::pipeline_probe_kernel<9>, &done[8]);
+        case 10: return go(&moe::pipeline_pingpong_kernel<10>, &done[9]);
+        case 11: return go(&moe::pipeline_pingpong_kernel<11>, &done[10]);
+        default: return go(&moe::pipeline_pingpong_kernel<12>, &done[11]);
     }
 }
 

@@ -175,4 +175,128 @@ __global__ void __launch_bounds__(512) pipeline_probe_kernel(int iters, const ch
     if (sum == 12345.678f) sink[0] = sum;   // keeps the loop alive; practically never true
 }
 
+// Measurement aid: the same ingredients as pipeline_probe_kernel, scheduled as two alternating roles instead of one
+// interleaved stream (the schedule of the large bf16 tile's k loop).  The two wavefronts of a SIMD take opposite
+// roles (decided from the hardware's SIMD id, first come first served); a k-step is two slots separated by
+// workgroup barriers, and in every slot one role issues its k-step's MFMAs back to back, all fragments already in
+// registers, while the other role does nothing but reload its (single-buffered) fragments for its next k-step.
+// Four barriers per 64-deep k-tile instead of one; no wavefront ever waits on an LDS read inside its MFMA run.
+//   MODE 10: MFMAs + LDS fragment reads;  11: + the k-tile's 64 KB of DMA, cache-resident source;  12: as 11 with
+//   half of the bytes from lines not touched before (the sources of modes 3 and 4 of the probe above)
+// DMA instructions: four per wavefront in the slot after the k-tile's third barrier, four in the wavefront's next
+// MFMA slot; inside an MFMA slot they follow the first MFMAs, one each.
+template <int MODE>
+__global__ void __launch_bounds__(512) pipeline_pingpong_kernel(int iters, const char* src, float* sink) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    __shared__ int waves_on_simd[4];
+    constexpr int MB = 8, NB = 4;
+    constexpr bool DMA = MODE >= 11;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    for (int i = tid; i < 65536 / 16; i += 512) reinterpret_cast<u32x4_t*>(smem)[i] = reinterpret_cast<const u32x4_t*>(src)[i];
+    if (tid < 4) waves_on_simd[tid] = 0;
+    __syncthreads();
+    // HW_ID bits 5:4: the SIMD this wavefront runs on
+    const int simd = __builtin_amdgcn_s_getreg((1 << 11) | (4 << 6) | 4) & 3;
+    int arrival = 0;
+    if (lane == 0) arrival = atomicAdd(&waves_on_simd[simd], 1);
+    const int role = __builtin_amdgcn_readfirstlane(arrival) & 1;
+    __syncthreads();
+
+    f32x4_t acc[MB][NB];
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    u32x4_t xq[MB];
+    u32x2_t wq[NB][2];
+    auto lgkm0 = []() __attribute__((always_inline)) { __builtin_amdgcn_s_waitcnt(0xc07f); };
+    // memory slot: fragments of k-step `it` (addresses as in the probe above)
+    auto load = [&](int it) __attribute__((always_inline)) {
+        __builtin_amdgcn_sched_barrier(0);
+        int base = (it & 3) * 16384 + (wave & 1) * 8192;
+        asm volatile("" : "+v"(base));
+#pragma unroll
+        for (int i = 0; i < MB; ++i) xq[i] = *reinterpret_cast<const u32x4_t*>(smem + base + lane * 16 + i * 1024);
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                wq[j][h] = __builtin_bit_cast(u32x2_t, __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (MOE_LDS(s16x4_t)*)(smem + ((base + lane * 8 + (j * 2 + h) * 512) & 65535))));
+    };
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(MOE_LDS(char)*)smem;
+    // d-th of a wavefront's 8 DMA instructions of a k-tile (0-3 token half, 4-7 weight half; targets and sources as
+    // in the probe above)
+    auto dma_one = [&](int it, int d) __attribute__((always_inline)) {
+        const uint32_t chunk = (((blockIdx.x >> 1) * 4099u + static_cast<uint32_t>(it >> 1)) & 16383u) * 32768u;
+        const char* src_w = MODE == 12 ? src + (1u << 20) + chunk : src + 32768 + (blockIdx.x & 15) * 32768;
+        const char* src_x = src + (blockIdx.x & 7) * 32768;
+        const int r = d & 3;
+        dma16(lane * 16 + wave * 1024 + r * 8192, (d & 4) ? src_w : src_x, lds0 + 65536 + r * 8192 + wave * 1024);
+    };
+    // compute slot: the k-step's 32 MFMAs, DMA instructions d0 .. d0 + nd - 1 behind the first nd of them
+    auto mma = [&](int it, int d0, int nd) __attribute__((always_inline)) {
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+#pragma unroll
+            for (int i = 0; i < MB; ++i) {
+                const u32x4_t wv = {wq[j][0].x, wq[j][0].y, wq[j][1].x, wq[j][1].y};
+                acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, wv),
+                                                                    __builtin_bit_cast(bf16x8_t, xq[i]), acc[i][j], 0, 0, 0);
+                if (DMA && j * MB + i < nd) { dma_one(it, d0 + j * MB + i); __builtin_amdgcn_sched_barrier(0); }
+            }
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto bar = []() __attribute__((always_inline)) {
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    // Both roles pass the same four barriers per trip.  The wait on the DMA ring sits before the third one in both
+    // (all but the newest half of a k-tile's instructions have landed: the token half of the tile before).
+    if (role == 0) {
+        load(0);
+        lgkm0();
+        for (int it = 0; it < iters; it += 2) {
+            mma(it, 4, 4);
+            bar();
+            load(it + 1);
+            lgkm0();
+            bar();
+            mma(it, 0, 0);
+            if (DMA) wait_vmcnt<4>();
+            bar();
+            load(it + 2);
+            if (DMA) {
+#pragma unroll
+                for (int d = 0; d < 4; ++d) dma_one(it, d);
+            }
+            lgkm0();
+            bar();
+        }
+    } else {
+        for (int it = 0; it < iters; it += 2) {
+            load(it);
+            lgkm0();
+            bar();
+            mma(it, 4, 4);
+            bar();
+            load(it + 1);
+            lgkm0();
+            if (DMA) wait_vmcnt<4>();
+            bar();
+            mma(it, 0, 4);
+            bar();
+        }
+    }
+    if (DMA) wait_vmcnt<0>();
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j) sum += acc[i][j][0] + acc[i][j][1] + acc[i][j][2] + acc[i][j][3];
+    if (sum == 12345.678f) sink[0] = sum;   // keeps the loop alive; practically never true
+}
+
 }  // namespace moe

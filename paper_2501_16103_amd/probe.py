@@ -43,8 +43,8 @@ def moe_probe_mfma(block: int, random_operands: bool, iters: int, sink) -> int:
 
 
 def moe_probe_pipeline(mode: int, iters: int, src, sink) -> int:
-    """One launch of the tile-loop probe (modes 1-8, see the header); `src`: device tensor of >= 1 MiB (mode 4:
-    513 MiB) holding bf16 values."""
+    """One launch of the tile-loop probe (modes 1-12, see the header); `src`: device tensor of >= 1 MiB (modes 4
+    and 12: 513 MiB) holding bf16 values."""
     nbytes = 0 if src is None else src.numel() * src.element_size()
     return int(lib().moe_probe_pipeline(int(mode), int(iters), _ptr(src), ctypes.c_size_t(nbytes), _ptr(sink),
                                         _stream() if sink is not None and src is not None else None))

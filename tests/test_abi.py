@@ -107,14 +107,15 @@ def test_pipeline_probe_rejects_bad_arguments_before_any_launch():
     lib = probe.lib()
     big, small = ctypes.c_size_t(513 << 20), ctypes.c_size_t(1 << 20)
     assert lib.moe_probe_pipeline(0, 10, 16, big, 16, None) == mb.MOE_ERR_INVALID_ARG     # no such mode
-    assert lib.moe_probe_pipeline(10, 10, 16, big, 16, None) == mb.MOE_ERR_INVALID_ARG
+    assert lib.moe_probe_pipeline(13, 10, 16, big, 16, None) == mb.MOE_ERR_INVALID_ARG
     assert lib.moe_probe_pipeline(1, 11, 16, big, 16, None) == mb.MOE_ERR_INVALID_ARG     # odd k-step count
     assert lib.moe_probe_pipeline(1, 0, 16, big, 16, None) == mb.MOE_ERR_INVALID_ARG
     assert lib.moe_probe_pipeline(1, 10, None, big, 16, None) == mb.MOE_ERR_INVALID_ARG   # no source
     assert lib.moe_probe_pipeline(1, 10, 16, big, None, None) == mb.MOE_ERR_INVALID_ARG   # no sink
     assert lib.moe_probe_pipeline(1, 10, 24, big, 16, None) == mb.MOE_ERR_INVALID_ARG     # misaligned source
     assert lib.moe_probe_pipeline(3, 10, 16, ctypes.c_size_t((1 << 20) - 1), 16, None) == mb.MOE_ERR_INVALID_ARG
-    assert lib.moe_probe_pipeline(4, 10, 16, small, 16, None) == mb.MOE_ERR_INVALID_ARG   # mode 4 needs 513 MiB
+    assert lib.moe_probe_pipeline(4, 10, 16, small, 16, None) == mb.MOE_ERR_INVALID_ARG   # modes 4 and 12 need 513 MiB
+    assert lib.moe_probe_pipeline(12, 10, 16, small, 16, None) == mb.MOE_ERR_INVALID_ARG
 
 
 def test_splitk_host_functions():

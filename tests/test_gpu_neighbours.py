@@ -389,9 +389,11 @@ def test_pipeline_probe_runs(dev):
     src = torch.randn((513 << 20) // 2, generator=g).to(torch.bfloat16).to(dev)
     before = src[: 1 << 20].clone()
     sink = torch.zeros(4, dtype=torch.float32, device=dev)
-    for mode in range(1, 10):
+    for mode in range(1, 13):
         assert probe.moe_probe_pipeline(mode, 64, src, sink) == mb.MOE_OK
-    assert probe.moe_probe_pipeline(4, 64, src[: 1 << 20], sink) == mb.MOE_ERR_INVALID_ARG
+    for mode in (4, 12):
+        assert probe.moe_probe_pipeline(mode, 64, src[: 1 << 20], sink) == mb.MOE_ERR_INVALID_ARG
+    assert probe.moe_probe_pipeline(13, 64, src, sink) == mb.MOE_ERR_INVALID_ARG
     torch.cuda.synchronize()
     assert torch.equal(src[: 1 << 20], before)
 
