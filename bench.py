@@ -507,22 +507,26 @@ def main():
                 res.append({"block": f"{block}x{block}x{512 // block}", "operands": "random" if rnd else "constant",
                             "ms": round(ms, 3), "tflops": round(flops / (ms * 1e-3) / 1e12, 1)})
         # the 256x256x64 tile's loop, one ingredient at a time (LDS reads, barrier, DMA from cache, half of it from HBM)
+        # ... and the same ingredients in the schedule of the large tile's k loop (the two wavefronts of a SIMD alternate);
+        # with --operand-fill zeros a second time on all-zero fragments (no switching power: what the schedule alone costs)
         src = (torch.randn((513 << 20) // 2, device="cuda:0") * 0.5).to(torch.bfloat16)
-        # ... and the same ingredients in the schedule of the large tile's k loop (the two wavefronts of a SIMD alternate)
-        for mode, what in ((1, "MFMA + LDS fragment reads"), (2, "+ barrier per k-tile"), (3, "+ DMA from cache"),
-                           (4, "+ half of the DMA bytes from HBM"),
-                           (10, "alternating roles: MFMA + LDS fragment reads + 4 barriers per k-tile"),
-                           (11, "alternating roles: + DMA from cache"), (12, "alternating roles: + half of the DMA bytes from HBM")):
-            probe.moe_probe_pipeline(mode, 1000, src, sink)
-            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
-            torch.cuda.synchronize()
-            ev[0].record()
-            probe.moe_probe_pipeline(mode, iters, src, sink)
-            ev[1].record()
-            torch.cuda.synchronize()
-            ms = ev[0].elapsed_time(ev[1])
-            res.append({"block": "16x16x32", "operands": "random", "loop": what,
-                        "ms": round(ms, 3), "tflops": round(flops / (ms * 1e-3) / 1e12, 1)})
+        for fill in ("random", "zeros") if args.operand_fill == "zeros" else ("random",):
+            if fill == "zeros":
+                src.zero_()
+            for mode, what in ((1, "MFMA + LDS fragment reads"), (2, "+ barrier per k-tile"), (3, "+ DMA from cache"),
+                               (4, "+ half of the DMA bytes from HBM"),
+                               (10, "alternating roles: MFMA + LDS fragment reads + 4 barriers per k-tile"),
+                               (11, "alternating roles: + DMA from cache"), (12, "alternating roles: + half of the DMA bytes from HBM")):
+                probe.moe_probe_pipeline(mode, 1000, src, sink)
+                ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+                torch.cuda.synchronize()
+                ev[0].record()
+                probe.moe_probe_pipeline(mode, iters, src, sink)
+                ev[1].record()
+                torch.cuda.synchronize()
+                ms = ev[0].elapsed_time(ev[1])
+                res.append({"block": "16x16x32", "operands": fill, "loop": what,
+                            "ms": round(ms, 3), "tflops": round(flops / (ms * 1e-3) / 1e12, 1)})
         # the LDS pipe alone: bytes per wavefront and k-step of each mode, reported per CU and nanosecond
         for mode, what, nbytes in ((5, "16-byte fragment reads only", 8192), (6, "transposing 8-byte reads only", 4096),
                                    (7, "both kinds of reads", 12288), (8, "DMA writes only", 4096)):
