@@ -775,7 +775,8 @@ __device__ __forceinline__ void pipe_tile(const GemmArgs& a, const int32_t* __re
         v.y = pack_bf16(v2, v3);
         *reinterpret_cast<u32x2_t*>(p) = v;
     };
-    auto silu_mul = [](float gate, float up) { return gate / (1.f + __expf(-gate)) * up; };
+    // (the hardware reciprocal is good to one unit in the last place of an fp32: far inside the bf16 rounding of the result)
+    auto silu_mul = [](float gate, float up) { return gate * __builtin_amdgcn_rcpf(1.f + __expf(-gate)) * up; };
     // Tiles of 64 rows and more leave through LDS: a lane's results are runs of 4 columns of one row (8 bytes), so
     // direct stores write every 128-byte line of Y in four pieces from four instructions.  Staged, each wavefront
     // writes its own WTM x WTN corner of the tile into the (now idle) rings and reads it back row-wise, 16 bytes

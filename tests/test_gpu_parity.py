@@ -192,6 +192,8 @@ BF16_CASES = [
     (128, 256, 600, 8, 2, 128, 512, "zipf"),
     (256, 256, 1200, 8, 2, 256, 512, "gauss_topk"),
     (256, 256, 700, 16, 2, 128, 256, "zipf"),         # empty experts, one > 2 tiles, ragged tails
+    (256, 256, 900, 8, 2, 64, 256, "gauss_topk"),     # one k-tile: prologue and the loop's last iteration only
+    (256, 256, 520, 4, 2, 320, 256, "zipf"),          # five k-tiles: three steady iterations and two that fetch nothing
     (16, 128, 40, 256, 8, 128, 256, "gauss_topk"),    # E = 256: four voting rounds
     (64, 128, 257, 3, 1, 64, 128, "worst"),
     (16, 128, 50, 300, 4, 128, 256, "gauss_topk"),    # E = 300: five groups of task records, no streaming launch
