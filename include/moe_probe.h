@@ -1,7 +1,7 @@
 /*
  * moe_probe -- measurement aids for the MI355X (gfx950) build of the statically batched MoE expert GEMM.
  *
- * Not part of the method and not part of libmoe_sb.so: two kernels that price the ingredients of the large bf16
+ * Not part of the method and not part of libmoe_sb.so: kernels that price the ingredients of the large bf16
  * tile's inner loop (Sec. 4.4 describes the pipeline they imitate) against the chip's sustained MFMA rate.  They
  * live in a library of their own, libmoe_probe.so, which only the benchmark's --mfma-probe leg and two tests load.
  * Same conventions as moe_sb.h: DEVICE pointers are caller-owned device memory, `stream` is a hipStream_t passed
@@ -46,6 +46,13 @@ int moe_probe_mfma(int block, int random_operands, int iters, void* sink, void* 
  * Returns -1 for another mode, an odd or too small iters, a NULL or misaligned pointer or a
  * src_bytes below the stated minimum. */
 int moe_probe_pipeline(int mode, int iters, const void* src, size_t src_bytes, void* sink, void* stream);
+
+/* Where the hardware places the eight wavefronts of a 512-thread workgroup that has a CU to itself (the launch shape
+ * of the large tiles, whose k loop gives wavefronts w and w + 4 opposite roles because they share a SIMD; Sec. 4.4's
+ * pipeline has no counterpart of this).  Enqueues one kernel of `workgroups` workgroups; out[8 * g + w] = SIMD (0..3)
+ * of wavefront w of workgroup g.  `out`: DEVICE memory of workgroups * 8 int32, written entirely.
+ * Returns -1 for workgroups outside [1, 65536] or a NULL out. */
+int moe_probe_wave_placement(int workgroups, int32_t* out, void* stream);
 
 #ifdef __cplusplus
 }

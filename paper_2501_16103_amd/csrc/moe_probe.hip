@@ -73,4 +73,13 @@ int moe_probe_pipeline(int mode, int iters, const void* src, size_t src_bytes, v
     }
 }
 
+int moe_probe_wave_placement(int workgroups, int32_t* out, void* stream) {
+    if (workgroups < 1 || workgroups > 65536 || !out) return kInvalid;
+    constexpr int lds = 150 * 1024;   // one workgroup per CU
+    static unsigned long long done = 0;
+    if (ensure_lds_attr(reinterpret_cast<const void*>(&moe::wave_placement_kernel), lds, &done) != kOk) return kHip;
+    moe::wave_placement_kernel<<<workgroups, 512, lds, static_cast<hipStream_t>(stream)>>>(out);
+    return hipGetLastError() == hipSuccess ? kOk : kHip;
+}
+
 }  // extern "C"

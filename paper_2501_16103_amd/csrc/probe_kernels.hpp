@@ -299,4 +299,15 @@ __global__ void __launch_bounds__(512) pipeline_pingpong_kernel(int iters, const
     if (sum == 12345.678f) sink[0] = sum;   // keeps the loop alive; practically never true
 }
 
+// Measurement aid: where the hardware puts the eight wavefronts of a 512-thread workgroup that has a CU to itself
+// (the large tiles' launch shape).  out[8 * workgroup + w] = SIMD (0..3) that wavefront w runs on.  The alternating
+// schedule of the large bf16 tiles gives wavefronts w and w + 4 opposite roles because they share a SIMD; if a
+// device placed them otherwise the results would be the same and only the schedule's benefit would be lost.
+__global__ void __launch_bounds__(512) wave_placement_kernel(int* out) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int simd = __builtin_amdgcn_s_getreg((1 << 11) | (4 << 6) | 4) & 3;   // HW_ID bits 5:4
+    if ((threadIdx.x & 63) == 0) out[blockIdx.x * 8 + (threadIdx.x >> 6)] = simd;
+    if (simd > 3) smem[threadIdx.x] = 1;   // never true: keeps the LDS allocation, which is what gives the workgroup its own CU
+}
+
 }  // namespace moe

@@ -8,7 +8,7 @@ import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmoe_probe.so")
-EXPORTS = ["moe_probe_mfma", "moe_probe_pipeline"]
+EXPORTS = ["moe_probe_mfma", "moe_probe_pipeline", "moe_probe_wave_placement"]
 
 _lib = None
 
@@ -24,6 +24,8 @@ def lib() -> ctypes.CDLL:
         L.moe_probe_pipeline.restype = ctypes.c_int
         L.moe_probe_pipeline.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p,
                                          ctypes.c_void_p]
+        L.moe_probe_wave_placement.restype = ctypes.c_int
+        L.moe_probe_wave_placement.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
         _lib = L
     return _lib
 
@@ -48,3 +50,11 @@ def moe_probe_pipeline(mode: int, iters: int, src, sink) -> int:
     nbytes = 0 if src is None else src.numel() * src.element_size()
     return int(lib().moe_probe_pipeline(int(mode), int(iters), _ptr(src), ctypes.c_size_t(nbytes), _ptr(sink),
                                         _stream() if sink is not None and src is not None else None))
+
+
+def moe_probe_wave_placement(workgroups: int, out) -> int:
+    """out[8 * g + w] = SIMD of wavefront w of workgroup g (512-thread workgroups, one per CU); `out`: int32 device
+    tensor of workgroups * 8 elements."""
+    if out is not None and (out.dtype != torch.int32 or out.numel() < workgroups * 8):
+        raise ValueError("out must be an int32 tensor of workgroups * 8 elements")
+    return int(lib().moe_probe_wave_placement(int(workgroups), _ptr(out), _stream() if out is not None else None))

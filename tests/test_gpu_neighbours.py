@@ -383,6 +383,19 @@ def test_mfma_probe_runs(dev):
     assert float(sink.abs().sum()) == 0.0
 
 
+def test_wavefronts_w_and_w_plus_4_share_a_simd(dev):
+    """What the alternating schedule of the large bf16 tiles relies on for its speed (not for its results): the
+    hardware puts wavefronts w and w + 4 of a 512-thread workgroup on the same SIMD, two per SIMD."""
+    n = 3584
+    out = torch.full((n * 8,), -1, dtype=torch.int32, device=dev)
+    assert probe.moe_probe_wave_placement(n, out) == mb.MOE_OK
+    assert probe.moe_probe_wave_placement(0, out) == mb.MOE_ERR_INVALID_ARG
+    simd = out.cpu().numpy().reshape(n, 8)
+    assert simd.min() >= 0 and simd.max() <= 3
+    assert np.array_equal(simd[:, :4], simd[:, 4:])
+    assert np.all(np.sort(simd[:, :4], axis=1) == np.arange(4))
+
+
 def test_pipeline_probe_runs(dev):
     """Every mode of the tile-loop probe launches and completes; the source buffer is left as it was."""
     g = torch.Generator().manual_seed(5)
