@@ -354,7 +354,7 @@ int launch_tail_split(const GemmArgs& a, int64_t grid, hipStream_t s) {
     if (ensure_lds_attr(fn, TailC::LDS_BYTES, &attr_done) != MOE_OK) return MOE_ERR_HIP;
     moe_gemm_tail_kernel<TailC, SplitK<Tails>...><<<dim3(8 * kTailBlocksPerXcd), dim3(TailC::NT), TailC::LDS_BYTES, s>>>(a);
     if (hipGetLastError() != hipSuccess) return MOE_ERR_HIP;
-    moe_tail_reduce_kernel<C::BM, C::BN, C::SLACK><<<dim3(8 * kCusPerXcd), dim3(256), 0, s>>>(a);
+    moe_tail_reduce_kernel<C::BM, C::BN, C::SLACK><<<dim3(8 * kCusPerXcd * kTailReduceSlices), dim3(256), 0, s>>>(a);
     return hipGetLastError() == hipSuccess ? MOE_OK : MOE_ERR_HIP;
 }
 
