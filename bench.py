@@ -592,7 +592,8 @@ def main():
                 del p
                 torch.cuda.empty_cache()
                 # tilings that have a tail-split launch (it pays when the tile count is not a whole number of rounds)
-                if (w.dtype == "bf16" and w.tile_m in (64, 128, 256) and w.tile_n == 256 and w.tile_m_slack == 0 and not small[0]
+                if (w.dtype == "bf16" and w.tile_m in (64, 128, 256) and w.tile_n == 256 and not small[0]
+                        and (w.tile_m_slack == 0 or (w.tile_m == 256 and w.tile_m_slack == 32 and args.slack < 0))
                         and w.K % 64 == 0 and w.N % 256 == 0):
                     p = Point(w, copies, order=order, launch_mode=lm, tail_split=True)
                     r = p.report(max(10, args.steps // 2), max(3, args.warmup // 2))
